@@ -1,0 +1,156 @@
+"""Seeded synthetic workload descriptions (the five benchmark configurations).
+
+This module only *describes* inputs: class primitives, sizes, prices, seeded
+hyper-parameters, and the planning targets obtained from the host LP. It contains none
+of the simulation's arithmetic; both the HIP library's binding and the test oracle's
+binding turn a `SimConfig` into their own C structs.
+
+The paper's experiments replay production traces and public datasets that are not
+available here; these synthetic classes stand in for them and keep only their shape:
+prefill-heavy versus decode-heavy classes, heavy-tailed lengths, diurnal-like arrival
+modulation (paper Sec. 6 and the EC's synthetic two-class instance).
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass, field, replace
+from typing import List, Optional
+
+import numpy as np
+
+from . import plan as _plan
+
+LAW_GEOMETRIC, LAW_LOGNORMAL, LAW_CONST, LAW_TABLE = 0, 1, 2, 3
+GATE_OCCUPANCY, GATE_PRIORITY, GATE_FCFS = 0, 1, 2
+
+
+@dataclass
+class SimClass:
+    lam: float                      # arrivals per server per unit time
+    in_law: int = LAW_GEOMETRIC
+    in_p0: float = 1.0
+    in_p1: float = 0.0
+    out_law: int = LAW_GEOMETRIC
+    out_p0: float = 1.0
+    out_p1: float = 0.0
+    price_in: float = 1.0
+    price_out: float = 1.0
+    bundled: int = 1
+    priority: float = 0.0
+    theta: float = 0.0
+    in_table: Optional[np.ndarray] = None
+    out_table: Optional[np.ndarray] = None
+
+
+@dataclass
+class SimConfig:
+    name: str
+    K: int
+    N: int
+    B: int
+    C: int
+    c0: float
+    c_pre: float
+    c_dec: float
+    classes: List[SimClass]
+    M: int = 0
+    x_star: List[float] = field(default_factory=list)
+    qp_star: List[float] = field(default_factory=list)
+    dt: float = 0.0
+    gate_mode: int = GATE_OCCUPANCY
+    route_mode: int = 0
+    mod_amp: float = 0.0
+    mod_period: int = 0
+    queue_cap: int = 4096
+    dbuf_cap: int = 4096
+    replications: int = 1
+    steps: int = 1000
+    seed: int = 1
+    notes: dict = field(default_factory=dict)
+
+
+def with_plan(cfg: SimConfig, lam_plan=None, objective="bundled", **kw) -> SimConfig:
+    """Fill x*, q_p* and M from the fluid LP solved for planning arrivals `lam_plan`."""
+    lam = [c.lam for c in cfg.classes] if lam_plan is None else lam_plan
+    p = _plan.solve_lp(cfg, lam, objective=objective, **kw)
+    out = replace(cfg, M=p.M, x_star=[float(v) for v in p.x], qp_star=[0.0] * cfg.K)
+    out.notes = dict(cfg.notes, lp_value=p.value, tau_mix=p.tau_mix, tau_solo=p.tau_solo,
+                     sum_x=float(p.x.sum()))
+    return out
+
+
+_ITER = dict(c0=0.010, c_pre=0.00005, c_dec=0.0002)
+
+
+def _two_class(lam=(0.6, 0.3), prices=(1.0, 1.0)):
+    return [SimClass(lam=lam[0], in_law=LAW_GEOMETRIC, in_p0=512.0, out_law=LAW_GEOMETRIC, out_p0=64.0,
+                     price_in=prices[0], price_out=prices[1], priority=64.0 / 512.0),
+            SimClass(lam=lam[1], in_law=LAW_GEOMETRIC, in_p0=128.0, out_law=LAW_GEOMETRIC, out_p0=256.0,
+                     price_in=prices[0], price_out=prices[1], priority=256.0 / 128.0)]
+
+
+def _scaled_to_load(cfg: SimConfig, mix, rho: float, **kw) -> SimConfig:
+    """Set class arrival rates to rho * (LP capacity along `mix`) and plan at full capacity."""
+    mix = np.asarray(mix, dtype=np.float64) / float(np.sum(mix))
+    s = _plan.capacity_scale(cfg, mix)
+    for c, m in zip(cfg.classes, mix):
+        c.lam = float(rho * s * m)
+    out = with_plan(cfg, lam_plan=[float(s * m) for m in mix], **kw)
+    out.notes.update(capacity_scale=s, rho=rho)
+    return out
+
+
+def config(n: int, **over) -> SimConfig:
+    """Benchmark configuration n in 1..5; keyword overrides replace top-level fields
+    (sizes such as N, replications, steps) before planning."""
+    if n == 1:
+        cfg = SimConfig(name="cfg1", K=2, N=8, B=32, C=256, classes=_two_class(), replications=16, steps=10_000,
+                        seed=1, queue_cap=1024, dbuf_cap=1024, **_ITER)
+        cfg = replace(cfg, **over)
+        return with_plan(cfg)
+    if n == 2:
+        cfg = SimConfig(name="cfg2", K=2, N=256, B=32, C=256, classes=_two_class(prices=(0.5, 2.0)),
+                        replications=1024, steps=100_000, seed=1, queue_cap=4096, dbuf_cap=4096, **_ITER)
+        for c in cfg.classes:
+            c.bundled = 0
+        cfg = replace(cfg, **over)
+        return with_plan(cfg)
+    if n == 3:
+        med_in = (256.0, 4096.0, 1024.0, 512.0); med_out = (256.0, 128.0, 512.0, 4096.0)
+        cls = [SimClass(lam=0.0, in_law=LAW_LOGNORMAL, in_p0=med_in[i], in_p1=0.8, out_law=LAW_LOGNORMAL,
+                        out_p0=med_out[i], out_p1=1.0, priority=med_out[i] / med_in[i]) for i in range(4)]
+        cfg = SimConfig(name="cfg3", K=4, N=1024, B=64, C=256, classes=cls, replications=2048, steps=100_000,
+                        seed=1, queue_cap=8192, dbuf_cap=8192, **_ITER)
+        cfg = replace(cfg, **over)
+        return _scaled_to_load(cfg, (0.4, 0.2, 0.25, 0.15), 0.95)
+    if n == 4:
+        rng = np.random.default_rng(20260202 + 4)
+        med_in = np.exp(rng.uniform(math.log(64), math.log(8192), 8))
+        med_out = np.exp(rng.uniform(math.log(16), math.log(4096), 8))
+        pin = rng.uniform(0.5, 4.0, 8); pout = rng.uniform(0.5, 4.0, 8)
+        cls = [SimClass(lam=0.0, in_law=LAW_LOGNORMAL, in_p0=float(med_in[i]), in_p1=0.8, out_law=LAW_LOGNORMAL,
+                        out_p0=float(med_out[i]), out_p1=1.0, price_in=float(pin[i]), price_out=float(pout[i]),
+                        bundled=0, priority=float(med_out[i] / med_in[i])) for i in range(8)]
+        cfg = SimConfig(name="cfg4", K=8, N=2048, B=64, C=256, classes=cls, replications=1024, steps=100_000,
+                        seed=1, queue_cap=8192, dbuf_cap=8192, **_ITER)
+        cfg = replace(cfg, **over)
+        # SLI rows of the plan: at most 5 % of a class's decode tokens in mixed iterations (a p95
+        # time-between-tokens bound lying between tau_solo and tau_mix), served fraction >= 0.9.
+        return _scaled_to_load(cfg, np.ones(8), 0.95, objective="separate", tbt_mixed_share=0.05,
+                               served_floor=0.9)
+    if n == 5:
+        rng = np.random.default_rng(20260202 + 5)
+        med_in = np.exp(rng.uniform(math.log(128), math.log(8192), 6))
+        med_out = np.exp(rng.uniform(math.log(128), math.log(8192), 6))
+        mix = rng.uniform(0.5, 1.5, 6)
+        cls = [SimClass(lam=0.0, in_law=LAW_LOGNORMAL, in_p0=float(med_in[i]), in_p1=0.8, out_law=LAW_LOGNORMAL,
+                        out_p0=float(med_out[i]), out_p1=1.0, price_in=0.5 if i % 2 else 1.0,
+                        price_out=2.0 if i % 2 else 1.0, bundled=1 - (i % 2),
+                        priority=float(med_out[i] / med_in[i])) for i in range(6)]
+        cfg = SimConfig(name="cfg5", K=6, N=10_000, B=128, C=256, classes=cls, replications=256, steps=1_000_000,
+                        seed=1, mod_amp=0.5, mod_period=100_000, queue_cap=1 << 21, dbuf_cap=1 << 16, **_ITER)
+        cfg = replace(cfg, **over)
+        # mean load 0.95 of capacity (the peak of the modulation overloads the system for part of
+        # every period, so prefill queues swing widely); the plan is made for full capacity
+        return _scaled_to_load(cfg, mix, 0.95)
+    raise ValueError("config index must be 1..5")
