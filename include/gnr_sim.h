@@ -1,0 +1,185 @@
+/*
+ * gnr_sim.h -- C ABI of the MI355X Monte-Carlo simulator of the multiclass many-server
+ * LLM-inference queueing network under the gate-and-route policy.
+ *
+ * The network is the one of the paper's Sec. 2.3 ("The Stochastic Model"): class prefill
+ * queues Q_p,i, prefill occupancy X_i, one decode buffer Q_d,i, mixed and solo decode
+ * occupancy Y_m,i / Y_s,i, on n servers that each host at most one prefill and B decodes.
+ * One batch iteration advances every decode of the batch by one token and the prefill by one
+ * chunk of at most C tokens (Sec. 2.2); its duration is c0 + c_pre*prefill_tokens +
+ * c_dec*n_decode, so a prefill in the batch slows the co-resident decodes.
+ * Control is the policy of Sec. 4: static partition into M mixed and n-M solo servers,
+ * occupancy-deviation prefill gate, solo-first work-conserving decode router.
+ * Revenue is recognised as in Sec. 2.3 (bundled: at request completion; separate: prompt
+ * tokens at prefill completion, output tokens at decode completion).
+ *
+ * Time advances in fixed steps of length dt. Every server keeps an exact clock (integer ns) for
+ * the end of its running iteration; in step s (boundary time T_s = (s+1)*dt) the library
+ *   1. draws per-server Poisson arrivals for the window and appends them to the class queues,
+ *   2. completes the iteration of every server whose clock is <= T_s,
+ *   3. runs the prefill gate over idle prefill slots of the mixed group, ascending server index,
+ *   4. routes the decode buffer (FIFO) to the least-loaded feasible server, solo group first,
+ *   5. restarts servers back-to-back from their own clock (idle servers start at T_s),
+ *   6. adds the end-of-step queue lengths and occupancies to their running sums.
+ * Replications are independent copies of the system with their own random streams
+ * (Philox4x32-10 keyed on the seed, counter = (step, stream, server, replication)).
+ *
+ * All functions return 0 on success or a negative sim_err; none throws, aborts or prints.
+ * Pointers are host pointers unless a comment says "device".
+ */
+#ifndef GNR_SIM_H
+#define GNR_SIM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SIM_MAXK 8      /* classes */
+#define SIM_MAXB 128    /* decode slots per server */
+#define SIM_MAXN 16384  /* servers per replication */
+#define SIM_NBIN 720    /* latency histogram bins: exact below 16 ns, then 16 bins per octave */
+
+enum sim_err { SIM_OK = 0, SIM_EINVAL = -1, SIM_ENOMEM = -2, SIM_EHIP = -3, SIM_EOVERFLOW = -4 };
+enum sim_law { SIM_GEOMETRIC = 0, SIM_LOGNORMAL = 1, SIM_CONST = 2, SIM_TABLE = 3 };
+enum sim_gate { SIM_GATE_OCCUPANCY = 0, SIM_GATE_PRIORITY = 1, SIM_GATE_FCFS = 2 };
+
+/* Per-class cumulative tallies (uint64), in this order. Counting processes as in Sec. 2.3:
+ * A arrivals, U_P admissions to prefill, S_P prefill completions, U_DM/U_DS admissions to a
+ * decode slot of a server that does / does not hold a prefill, S_DM/S_DS decode completions by the
+ * same distinction, M_SM/M_MS decodes switched solo->mixed / mixed->solo by a prefill admission /
+ * completion on their server. DROP_* count requests lost to a full ring. TOKP_PRE: prompt tokens
+ * recognised at prefill completion; TOKP_DEC/TOKD_DEC: prompt/output tokens recognised at decode
+ * completion; TOK_EMIT output tokens emitted; TOK_PREF prompt tokens processed. SUM_*: end-of-step
+ * values summed over steps. WAIT_STEPS: sum over admitted requests of (admission step - arrival
+ * step). *_SUM: latency sums in ns (TTFT over S_P, E2E over S_DM+S_DS, TBT over TOK_EMIT). */
+enum sim_tally {
+  SIM_T_A = 0, SIM_T_DROP_P, SIM_T_U_P, SIM_T_S_P, SIM_T_U_DM, SIM_T_U_DS, SIM_T_S_DM, SIM_T_S_DS,
+  SIM_T_M_SM, SIM_T_M_MS, SIM_T_DROP_D, SIM_T_TOKP_PRE, SIM_T_TOKP_DEC, SIM_T_TOKD_DEC, SIM_T_TOK_EMIT,
+  SIM_T_TOK_PREF, SIM_T_SUM_QP, SIM_T_SUM_QD, SIM_T_SUM_X, SIM_T_SUM_YM, SIM_T_SUM_YS, SIM_T_WAIT_STEPS,
+  SIM_T_TTFT_SUM, SIM_T_E2E_SUM, SIM_T_TBT_SUM, SIM_NTALLY
+};
+/* Per-replication tallies: executed iterations and busy ns by kind (a "mix" iteration holds a
+ * prefill chunk), steps run, and 1 if any ring overflowed. */
+enum sim_global { SIM_G_ITERS_MIX = 0, SIM_G_ITERS_SOLO, SIM_G_BUSY_MIX, SIM_G_BUSY_SOLO, SIM_G_STEPS,
+                  SIM_G_OVERFLOW, SIM_NGLOBAL };
+
+/* One request class (primitives of Sec. 2.3). Lengths are integers in [1, 32768] drawn by
+ * inverse-cdf lookup in a 65536-entry quantile table: entry j is the smallest k whose cdf reaches
+ * (j+0.5)/65536. GEOMETRIC: p0 = mean, Pr(X >= k) = (1-1/mean)^(k-1). LOGNORMAL: p0 = median,
+ * p1 = sigma, rounded to the nearest integer and clamped. CONST: p0. TABLE: caller's table. */
+typedef struct {
+  double lambda;                 /* arrivals per server per unit time */
+  int in_law, out_law;           /* enum sim_law */
+  double in_p0, in_p1, out_p0, out_p1;
+  const uint16_t *in_table, *out_table; /* 65536 entries each, copied; only for SIM_TABLE */
+  double price_in, price_out;    /* c_p, c_d: price per prompt / output token */
+  int bundled;                   /* 1: this class counts bundled revenue in rev_mixed, 0: separate */
+  double priority;               /* static index of the priority gate (larger first), e.g. D_i/P_i */
+  double theta;                  /* patience rate; abandonment is not simulated: must be 0 */
+} sim_class;
+
+typedef struct {
+  int K, N, B, C;                /* classes <= 8, servers <= 16384, decode cap <= 128, chunk <= 32768 */
+  double c0, c_pre, c_dec;       /* iteration time c0 + c_pre*ptok + c_dec*n_dec, rounded to ns */
+  double dt;                     /* step length, 0 < dt <= c0; 0 selects dt = c0 */
+  const sim_class *cls;          /* K entries, copied */
+  int M;                         /* mixed servers 0..M-1 (ceil(n * sum x*)); servers M..N-1 are solo */
+  const double *x_star;          /* K prefill-occupancy targets per server; 0 = never admit (occupancy gate) */
+  const double *qp_star;         /* K prefill-queue targets per server (gate tie-break) */
+  int gate_mode;                 /* enum sim_gate */
+  int route_mode;                /* 0: solo-first, least-loaded, lowest index */
+  double mod_amp;                /* arrival modulation lambda(s) = lambda*(1 + amp*sin(2*pi*(s mod period)/period)) */
+  int64_t mod_period;            /* in steps; 0 = homogeneous */
+  int64_t queue_cap, dbuf_cap;   /* ring capacities: per class prefill queue, decode buffer */
+} sim_config;
+
+/* Totals over replications plus derived fp64 figures (rates per server per unit time). */
+typedef struct {
+  int32_t K, replications;
+  int64_t steps;
+  double sim_time;
+  uint64_t tally[SIM_MAXK][SIM_NTALLY];
+  uint64_t glob[SIM_NGLOBAL];
+  double arrival_rate[SIM_MAXK], completion_rate[SIM_MAXK], served_fraction[SIM_MAXK];
+  double tok_rate_prefill[SIM_MAXK], tok_rate_decode[SIM_MAXK];
+  double rev_bundled[SIM_MAXK], rev_separate[SIM_MAXK], rev_mixed[SIM_MAXK];
+  double rev_bundled_total, rev_separate_total, rev_mixed_total;
+  double mean_qp[SIM_MAXK], mean_qd[SIM_MAXK], mean_x[SIM_MAXK], mean_ym[SIM_MAXK], mean_ys[SIM_MAXK];
+  double ttft_mean[SIM_MAXK], ttft_p50[SIM_MAXK], ttft_p95[SIM_MAXK], ttft_p99[SIM_MAXK];
+  double e2e_mean[SIM_MAXK], e2e_p50[SIM_MAXK], e2e_p95[SIM_MAXK], e2e_p99[SIM_MAXK];
+  double tbt_mean[SIM_MAXK], tbt_p50[SIM_MAXK], tbt_p95[SIM_MAXK], tbt_p99[SIM_MAXK];
+  double mean_wait[SIM_MAXK];
+  double fair_gap_x, fair_gap_ys, fair_min_served;   /* fairness SLIs of Sec. 5.2, measured */
+  double util_mix, util_solo, iter_rate;
+} sim_stats_t;
+
+/* Integer state of one replication, copied into caller-allocated host arrays (NULL = skip).
+ * A request is packed as stamp | cls<<29 | (P-1)<<32 | (D-1)<<48 (arrival step, class, prompt and
+ * output length). Slot order within a server carries no meaning. */
+typedef struct {
+  int64_t *class_state;   /* [5][K]: Qp, X, Qd, Ym, Ys */
+  int64_t *t_next;        /* [N] end of the running iteration in ns, INT64_MAX when idle */
+  uint32_t *iter;         /* [N] completed iterations */
+  int32_t *rem, *ptok;    /* [N] prompt tokens left of the prefill in service; tokens in the running chunk */
+  uint64_t *pfjob;        /* [N] request in prefill service (0 when none) */
+  uint8_t *n_cls, *n_join;/* [N][8] decodes per class; of those, joined after the running iteration started */
+  uint32_t *fin;          /* [N][B] iteration index at which the slot's request emits its last token */
+  uint64_t *job;          /* [N][B] request of the slot; slots 0..n_dec-1 are occupied */
+  int32_t *n_dec;         /* [N] */
+  uint64_t *queue[SIM_MAXK]; int64_t queue_len[SIM_MAXK]; /* arrival stamps, head first; capacity queue_cap */
+  uint64_t *dbuf; int64_t dbuf_len;                        /* decode buffer requests, head first; capacity dbuf_cap */
+} sim_state_t;
+
+typedef struct sim_t sim_t;  /* opaque; owned by the library */
+
+/* Device bytes sim_create needs for `max_replications` replications of `cfg`. */
+int sim_workspace_bytes(const sim_config *cfg, int max_replications, size_t *out_bytes);
+
+/* Validates and deep-copies the config, builds the sampler tables on the host and uploads them
+ * into `dev_workspace` (device pointer, 256-byte aligned, owned by the caller, must outlive the
+ * handle). SIM_EINVAL: bad sizes, negative target, M outside [0,N], dt > c0, theta != 0, total
+ * arrival mean per server-step above 0.05 (the per-step count is truncated at 3).
+ * SIM_ENOMEM: workspace too small. The library never allocates device memory itself. */
+int sim_create(const sim_config *cfg, int max_replications, void *dev_workspace, size_t bytes, sim_t **out);
+
+/* Advances `replications` replications by `steps` steps, asynchronously on `hip_stream`
+ * (a hipStream_t, NULL = default stream). Repeating the same (replications, seed) resumes; another
+ * pair restarts from the empty system. Results depend only on (config, replications, seed, total
+ * steps), not on how the steps were split over calls. Total steps must stay below 2^29. */
+int sim_run(sim_t *h, int64_t steps, int replications, uint64_t seed, void *hip_stream);
+
+/* Sums the tallies over replications on the device, copies them out and derives the fp64 figures.
+ * Synchronises the stream. Returns SIM_EOVERFLOW (with `out` filled) if any ring overflowed. */
+int sim_stats(sim_t *h, sim_stats_t *out, void *hip_stream);
+
+/* Per-replication read-outs for parity checks; each synchronises the stream.
+ * sim_tallies: out[K][SIM_NTALLY] then [SIM_NGLOBAL]. sim_hist: which = 0 TTFT, 1 E2E, 2 TBT,
+ * out[K][SIM_NBIN]. sim_digest: 64-bit order-independent digest of the integer state. */
+int sim_snapshot(sim_t *h, int replication, sim_state_t *out, void *hip_stream);
+int sim_tallies(sim_t *h, int replication, uint64_t *out, void *hip_stream);
+int sim_hist(sim_t *h, int replication, int which, uint64_t *out, void *hip_stream);
+int sim_digest(sim_t *h, int replication, uint64_t *out, void *hip_stream);
+
+/* Step-kernel launches and their accumulated device time (HIP events on the run's stream) since
+ * the handle was created or this was last called with reset != 0. Synchronises the stream. */
+int sim_kernel_time(sim_t *h, int64_t *launches, double *milliseconds, int reset, void *hip_stream);
+
+int sim_destroy(sim_t *h);
+const char *sim_strerror(int err);
+
+/* Host-only helpers (no device needed): the quantile table of a length law (65536 entries),
+ * one Philox4x32-10 block, the sampler thresholds a config would use
+ * (arr_thr[rows][3] for rows 0..rows-1, cls_thr[SIM_MAXK]). */
+int sim_length_table(int law, double p0, double p1, uint16_t *out);
+int sim_philox(uint64_t seed, uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t *out4);
+int sim_thresholds(const sim_config *cfg, int64_t rows, uint32_t *arr_thr, uint32_t *cls_thr);
+/* sizeof of the four ABI structs, in the order class, config, stats, state (for binding checks). */
+int sim_abi_sizes(size_t *out4);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,81 @@
+// Internal declarations shared by the host glue and the HIP kernels of the simulator.
+#ifndef GNR_INTERNAL_H
+#define GNR_INTERNAL_H
+
+#include <cstddef>
+#include <cstdint>
+
+#include "gnr_sim.h"
+
+namespace gnr {
+
+constexpr int kMaxK = SIM_MAXK;
+constexpr int kMaxB = SIM_MAXB;
+constexpr int kMaxN = SIM_MAXN;
+constexpr int kNBin = SIM_NBIN;
+constexpr int kTableSize = 65536;
+constexpr int kMaxLen = 32768;
+constexpr int kNTally = SIM_NTALLY;
+constexpr int kNGlobal = SIM_NGLOBAL;
+constexpr int kTallyWords = kMaxK * kNTally + kNGlobal;  // per replication, uint64
+constexpr int64_t kIdle = INT64_MAX;
+constexpr int kAdmChunk = 1024;   // admissions decided per gate pass
+constexpr int kMaxTbtBins = 256;  // width of the on-chip time-between-tokens histogram window
+
+// Per-replication class-level state, int32 words (persisted between launches).
+enum ClassStateWord {
+  CS_QP = 0, CS_X = 8, CS_QD = 16, CS_YM = 24, CS_YS = 32, CS_QHEAD = 40, CS_DHEAD = 48, CS_DCOUNT = 49, CS_WORDS = 64
+};
+
+// Everything a kernel needs, passed by value.
+struct Params {
+  int K, N, B, C, M, R;
+  int gate_mode;
+  int tbt_lo, tbt_w;          // first bin and width of the TBT histogram window kept in LDS
+  int nwords;                 // ceil(N/64) bitmap words
+  uint32_t key0, key1;
+  uint32_t queue_cap, dbuf_cap;
+  int64_t c0, cpre, cdec, dt;
+  int64_t mod_period;
+  double nx[kMaxK], invx[kMaxK], nq[kMaxK], prio[kMaxK];
+  uint32_t cls_thr[kMaxK];
+  // tables (device)
+  const uint32_t *arr_thr;    // [rows][3]
+  const uint16_t *len_tab;    // [K][2][65536]: in, out
+  // per-server state, [R][N]
+  int64_t *t_next;
+  uint32_t *iter;
+  uint32_t *remptok;          // prompt tokens left | tokens in the running chunk << 16
+  uint64_t *pf_job;
+  uint64_t *n_cls, *n_join;   // 8 x uint8 packed
+  // decode slots, [R][N][B]; slots 0..n_dec-1 of a server are occupied
+  uint32_t *fin;
+  uint64_t *job;
+  // rings
+  uint32_t *qring;            // [R][K][queue_cap] arrival stamps
+  uint64_t *dring;            // [R][dbuf_cap] requests
+  // class state, tallies, histograms
+  int32_t *cstate;            // [R][CS_WORDS]
+  uint64_t *tally;            // [R][kTallyWords]
+  uint64_t *hist;             // [R][3][K][kNBin]
+  uint64_t *digest;           // [R]
+  uint64_t *reduced;          // [kTallyWords + 3*K*kNBin] totals over replications
+};
+
+// host-side table builders (gnr_tables.cpp)
+int build_length_table(int law, double p0, double p1, const uint16_t *user, uint16_t *out);
+double total_rate(const sim_class *cls, int K);
+void build_arrival_row(double lam, int64_t dt_ns, double amp, int64_t period, int64_t row, uint32_t thr[3]);
+void build_class_thresholds(const sim_class *cls, int K, uint32_t *thr);
+
+// kernel launchers (gnr_kernels.hip); stream is a hipStream_t
+int launch_reset(const Params &p, int reps, void *stream);
+int launch_steps(const Params &p, int reps, int threads, size_t lds_bytes, uint32_t step_begin, uint32_t n_steps,
+                 void *stream);
+int launch_reduce(const Params &p, int reps, void *stream);
+int launch_digest(const Params &p, int reps, void *stream);
+size_t step_lds_bytes(const Params &p);
+int step_threads(int N);
+
+}  // namespace gnr
+#endif

@@ -138,8 +138,9 @@ def solve_lp(cfg, lam, objective="bundled", tbt_mixed_share=None, served_floor=N
                 tau_mix=r["tau_mix"], tau_solo=r["tau_solo"], EP=r["EP"], ED=r["ED"])
 
 
-def capacity_scale(cfg, mix, **kw) -> float:
-    """Largest s such that arrivals s*mix are served in full by the fluid LP (all classes at 100 %)."""
+def capacity_scale(cfg, mix, tbt_mixed_share=None, **kw) -> float:
+    """Largest s such that arrivals s*mix are served in full by the fluid LP (all classes at 100 %),
+    under the optional per-class bound on the share of decode tokens emitted in mixed iterations."""
     K, B = cfg.K, cfg.B
     mix = np.asarray(mix, dtype=np.float64)
     r = rates(cfg, kw.get("n_mixed_decodes"), kw.get("n_solo_decodes"))
@@ -154,6 +155,10 @@ def capacity_scale(cfg, mix, **kw) -> float:
         row = np.zeros(nv); row[i] = mu_p[i]; row[-1] = -mix[i]; A_eq.append(row); b_eq.append(0.0)
         row = np.zeros(nv); row[i] = mu_p[i]; row[K + i] = -mu_m[i]; row[2 * K + i] = -mu_s[i]
         A_eq.append(row); b_eq.append(0.0)
+        if tbt_mixed_share is not None:
+            a = tbt_mixed_share
+            row = np.zeros(nv); row[K + i] = (1 - a) / r["tau_mix"]; row[2 * K + i] = -a / r["tau_solo"]
+            A_ub.append(row); b_ub.append(0.0)
     res = linprog(cost, A_ub=np.array(A_ub), b_ub=np.array(b_ub), A_eq=np.array(A_eq), b_eq=np.array(b_eq),
                   bounds=[(0, None)] * nv, method="highs")
     if res.status != 0:

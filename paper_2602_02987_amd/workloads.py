@@ -92,7 +92,7 @@ def _two_class(lam=(0.6, 0.3), prices=(1.0, 1.0)):
 def _scaled_to_load(cfg: SimConfig, mix, rho: float, **kw) -> SimConfig:
     """Set class arrival rates to rho * (LP capacity along `mix`) and plan at full capacity."""
     mix = np.asarray(mix, dtype=np.float64) / float(np.sum(mix))
-    s = _plan.capacity_scale(cfg, mix)
+    s = _plan.capacity_scale(cfg, mix, tbt_mixed_share=kw.get("tbt_mixed_share"))
     for c, m in zip(cfg.classes, mix):
         c.lam = float(rho * s * m)
     out = with_plan(cfg, lam_plan=[float(s * m) for m in mix], **kw)

@@ -1,0 +1,100 @@
+"""GPU parity: the HIP library against the CPU oracle on the same seeded inputs, through the C ABI.
+Integer state, tallies, histograms and digests are compared bit-exactly; derived fp64 figures
+(rates, revenue, latency means) within 1e-12 relative."""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+
+from paper_2602_02987_amd import workloads as W
+from parity import assert_replication_equal, assert_stats_equal
+from test_oracle_dynamics import _heavy, _lp_instance
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2602_02987_amd import binding
+    binding.lib()
+    return binding
+
+
+def run_both(B, oracle_mod, cfg, steps, reps=None, seed=None, oracle_reps=None, checkpoints=1):
+    reps = cfg.replications if reps is None else reps
+    sim = B.Sim(cfg, max_replications=reps)
+    orc = oracle_mod.Oracle(cfg, max_reps=reps)
+    if oracle_reps is not None:
+        orc.select(oracle_reps)
+    done = 0
+    for c in range(checkpoints):
+        n = (steps * (c + 1)) // checkpoints - done
+        sim.run(n, reps, seed)
+        orc.run(n, reps, seed)
+        done += n
+        for r in (range(reps) if oracle_reps is None else oracle_reps):
+            assert_replication_equal(sim, orc, r, what=f"{cfg.name} after {done} steps")
+    return sim, orc
+
+
+def test_config1_full(B, oracle_mod):
+    cfg = W.config(1)
+    sim, orc = run_both(B, oracle_mod, cfg, cfg.steps, checkpoints=4)
+    assert_stats_equal(sim.stats(), orc.stats())
+    assert not sim.stats()["overflow"]
+
+
+@pytest.mark.parametrize("gate", [W.GATE_OCCUPANCY, W.GATE_PRIORITY, W.GATE_FCFS])
+def test_heavy_small_instances(B, oracle_mod, gate):
+    """Full slots, decode buffer in use, ring overflow, empty groups, B = 1."""
+    for cfg in (_heavy(gate), _heavy(gate, M=0), _heavy(gate, M=12), _heavy(gate, B=1, M=6),
+                _heavy(gate, name="heavy-prefill", M=1, queue_cap=8), _heavy(gate, N=1, M=1, B=3),
+                _heavy(gate, N=1, M=0, B=3)):
+        sim, orc = run_both(B, oracle_mod, cfg, 2500, checkpoints=5)
+        ss, os_ = sim.stats(), orc.stats()
+        assert_stats_equal(ss, os_)
+        assert ss["overflow"] == bool(os_["glob"][5])
+
+
+def test_several_tiles_and_ragged_tail(B, oracle_mod):
+    """N spans several 64-server ballot words and several servers per thread, with a ragged tail."""
+    for N, M, reps, steps in ((100, 30, 3, 1500), (1500, 400, 2, 800), (2500, 700, 1, 500)):
+        cfg = W.config(3, N=N, replications=reps)
+        cfg = replace(cfg, M=M)
+        run_both(B, oracle_mod, cfg, steps, checkpoints=2)
+
+
+def test_binding_capacity_instance(B, oracle_mod):
+    cfg = _lp_instance(64, 2, 6000, (1024, 3072), (400, 160))
+    sim, orc = run_both(B, oracle_mod, cfg, 6000, checkpoints=2)
+    assert_stats_equal(sim.stats(), orc.stats())
+
+
+def test_modulated_arrivals_and_many_classes(B, oracle_mod):
+    cfg = W.config(5, N=300, replications=2, mod_period=700)
+    run_both(B, oracle_mod, cfg, 2000, checkpoints=2)
+    cfg = W.config(4, N=256, replications=2)
+    sim, orc = run_both(B, oracle_mod, cfg, 1500)
+    assert_stats_equal(sim.stats(), orc.stats())
+
+
+def test_resume_and_restart(B, oracle_mod):
+    cfg = _heavy()
+    a = B.Sim(cfg); a.run(900)
+    b = B.Sim(cfg); b.run(1); b.run(499); b.run(400)
+    for r in range(cfg.replications):
+        assert a.digest(r) == b.digest(r)
+        assert np.array_equal(a.tallies(r)[0], b.tallies(r)[0])
+    b.run(300, seed=77)                       # another seed restarts from the empty system
+    orc = oracle_mod.Oracle(cfg); orc.run(300, seed=77)
+    for r in range(cfg.replications):
+        assert_replication_equal(b, orc, r, what="restart")
+
+
+def test_full_size_configs_on_sampled_replications(B, oracle_mod):
+    """Configs 2-5 at their full N and replication count, in the launch shape the benchmark times,
+    for a prefix of steps; the oracle recomputes a sample of replications (first, second, last)."""
+    for n, steps in ((2, 3000), (3, 1200), (4, 700), (5, 300)):
+        cfg = W.config(n)
+        sample = [0, 1, cfg.replications - 1]
+        run_both(B, oracle_mod, cfg, steps, oracle_reps=sample)

@@ -1,0 +1,77 @@
+"""CPU-only checks of the library's host side: it loads, exports every declared symbol, validates
+configurations, and builds the same sampler tables as the oracle (independent code, same definition)."""
+import ctypes
+import os
+import re
+from dataclasses import replace
+
+import numpy as np
+import pytest
+
+from paper_2602_02987_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2602_02987_amd import binding
+    binding.lib()
+    return binding
+
+
+def test_library_exports_every_declared_symbol(B):
+    header = open(os.path.join(ROOT, "include", "gnr_sim.h")).read()
+    names = set(re.findall(r"^(?:int|const char \*)\s*\*?(sim_[a-z_]+)\(", header, flags=re.M))
+    assert {"sim_workspace_bytes", "sim_create", "sim_run", "sim_stats", "sim_snapshot", "sim_destroy",
+            "sim_strerror", "sim_tallies", "sim_hist", "sim_digest", "sim_kernel_time"} <= names
+    L = B.lib()
+    for n in names:
+        assert hasattr(L, n), n
+    assert B.lib().sim_strerror(-4).decode().startswith("a prefill queue")
+    sizes = (ctypes.c_size_t * 4)()
+    assert L.sim_abi_sizes(sizes) == 0
+    assert list(sizes) == [ctypes.sizeof(B.SimClassC), ctypes.sizeof(B.SimConfigC), ctypes.sizeof(B.SimStatsC),
+                           ctypes.sizeof(B.SimStateC)]
+
+
+def test_tables_match_the_oracle(B, oracle_mod):
+    for law, p0, p1 in [(0, 512.0, 0.0), (0, 64.0, 0.0), (0, 1.0, 0.0), (1, 256.0, 0.8), (1, 4096.0, 1.0),
+                        (1, 8192.0, 1.0), (2, 600.0, 0.0)]:
+        assert np.array_equal(B.sim_length_table(law, p0, p1), oracle_mod.length_table(law, p0, p1)), (law, p0, p1)
+    rng = np.random.default_rng(11)
+    for _ in range(50):
+        seed = int(rng.integers(0, 2**63)); c = [int(v) for v in rng.integers(0, 2**32, 4)]
+        assert np.array_equal(B.sim_philox(seed, *c), oracle_mod.philox(seed, *c))
+    for n in (1, 3, 5):
+        cfg = W.config(n, N=64, replications=1)
+        rows = max(cfg.mod_period, 1)
+        arr, cth = B.sim_thresholds(cfg, rows)
+        o = oracle_mod.Oracle(cfg)
+        _, _, o_cth, o_arr = o.tables(0, rows=rows)
+        assert np.array_equal(arr, o_arr)
+        assert np.array_equal(cth[:cfg.K - 1], o_cth[:cfg.K - 1])
+
+
+def test_invalid_configurations_are_rejected(B):
+    good = W.config(1)
+    assert B.sim_workspace_bytes(good, 16) > 0
+    bad = [replace(good, K=9), replace(good, N=0), replace(good, N=20000), replace(good, B=129), replace(good, B=0),
+           replace(good, C=0), replace(good, M=9), replace(good, M=-1), replace(good, dt=0.02), replace(good, c0=0.0),
+           replace(good, queue_cap=0), replace(good, dbuf_cap=0), replace(good, gate_mode=7), replace(good, route_mode=1),
+           replace(good, x_star=[-0.1, 0.1]), replace(good, mod_amp=2.0)]
+    heavy = W.config(1); heavy.classes[0].lam = 6.0
+    theta = W.config(1); theta.classes[1].theta = 0.1
+    for cfg in bad + [heavy, theta]:
+        with pytest.raises(B.SimError) as e:
+            B.sim_workspace_bytes(cfg, 16)
+        assert e.value.code == -1
+    with pytest.raises(B.SimError):
+        B.sim_workspace_bytes(good, 0)
+
+
+def test_workspace_size_scales_with_replications(B):
+    cfg = W.config(2)
+    a, b = B.sim_workspace_bytes(cfg, 8), B.sim_workspace_bytes(cfg, 16)
+    per_rep = cfg.N * (8 + 4 + 4 + 8 + 8 + 8 + cfg.B * 12) + cfg.K * cfg.queue_cap * 4 + cfg.dbuf_cap * 8
+    assert b > a and (b - a) >= 8 * per_rep
