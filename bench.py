@@ -1,0 +1,156 @@
+#!/usr/bin/env python3
+"""Benchmark of the simulator's hot path on one MI355X.
+
+A bench "step" is one sim_run of `--sim-steps` simulation steps over every replication of the
+workload (config 5 at its full size: K=6, N=10000 servers, 256 replications, B=128, sinusoidal
+arrivals), state resident in HBM. Before timing, the system is brought away from the empty state
+by `--preload` untimed simulation steps. Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def algorithmic_bytes(t0, g0, t1, g1, slots):
+    """Bytes the step must move for the work done between two tally read-outs.
+
+    Every server-step slot reads the server's clock (8 B). An executed iteration reads the rest of
+    the record (24 B: iteration counter, prefill progress, per-class decode counts, joiner counts),
+    scans one 4-byte completion word per occupied decode slot, and writes the record back (32 B).
+    Every admission, prefill completion, decode placement and decode completion moves about 32 B of
+    request fields and ring entries.
+    """
+    from paper_2602_02987_amd.binding import GLOBAL, TALLY
+    ti = {n: i for i, n in enumerate(TALLY)}
+    gi = {n: i for i, n in enumerate(GLOBAL)}
+    d = (t1.astype("float64") - t0.astype("float64")).sum(axis=0)
+    iters = float(g1[gi["ITERS_MIX"]] + g1[gi["ITERS_SOLO"]]) - float(g0[gi["ITERS_MIX"]] + g0[gi["ITERS_SOLO"]])
+    scanned = d[ti["TOK_EMIT"]]
+    events = d[ti["U_P"]] + d[ti["S_P"]] + d[ti["U_DM"]] + d[ti["U_DS"]] + d[ti["S_DM"]] + d[ti["S_DS"]]
+    total = 8.0 * slots + iters * (24.0 + 32.0) + 4.0 * scanned + 32.0 * events
+    return total, dict(due_fraction=iters / slots, decodes_per_iteration=scanned / max(iters, 1.0),
+                       events_per_slot=events / slots, bytes_per_slot=total / slots)
+
+
+def _oracle_worker(args):
+    n, N, rep, steps = args
+    sys.path.insert(0, ROOT)
+    from oracle import binding as ob
+    from paper_2602_02987_amd import workloads as W
+    cfg = W.config(n, N=N)
+    o = ob.Oracle(cfg, max_reps=cfg.replications)
+    o.select([rep])
+    t = time.perf_counter()
+    o.run(steps, cfg.replications, cfg.seed)
+    return time.perf_counter() - t
+
+
+def cpu_baseline(n, N, steps):
+    """The oracle as it stands, one replication per host process, on a bounded sample."""
+    import multiprocessing as mp
+    from oracle import binding as ob
+    ob.build()
+    cores = min(16, os.cpu_count() or 1)
+    t = time.perf_counter()
+    with mp.get_context("spawn").Pool(cores) as pool:
+        pool.map(_oracle_worker, [(n, N, r, steps) for r in range(cores)])
+    wall = time.perf_counter() - t
+    return dict(value=cores * N * steps / wall, unit="server-steps/s", cores=cores, kind="oracle",
+                sample=f"replications 0..{cores - 1} of the workload, first {steps} steps from the empty system, "
+                       f"one process per replication, wall {wall:.1f} s incl. table build")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5, help="timed bench steps (sim_run calls)")
+    ap.add_argument("--warmup", type=int, default=1, help="untimed bench steps")
+    ap.add_argument("--sim-steps", type=int, default=1000, help="simulation steps per bench step")
+    ap.add_argument("--preload", type=int, default=4000, help="untimed simulation steps before anything else")
+    ap.add_argument("--config", type=int, default=5)
+    ap.add_argument("--servers", type=int, default=0, help="override N (0 = the configuration's own)")
+    ap.add_argument("--replications", type=int, default=0)
+    ap.add_argument("--oracle-steps", type=int, default=1500, help="0 skips the CPU baseline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (replications are independent and would shard "
+              "across GPUs without communication, but no multi-GPU path is built); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    # The CPU baseline starts worker processes, so it runs before this process touches the GPU.
+    from paper_2602_02987_amd import workloads as W
+    base = None
+    if args.oracle_steps > 0:
+        n_servers = args.servers if args.servers else W.config(args.config).N
+        base = cpu_baseline(args.config, n_servers, args.oracle_steps)
+
+    import torch
+    from paper_2602_02987_amd import binding
+    over = {}
+    if args.servers:
+        over["N"] = args.servers
+    if args.replications:
+        over["replications"] = args.replications
+    cfg = W.config(args.config, **over)
+    slots_per_step = cfg.N * cfg.replications * args.sim_steps
+
+    sim = binding.Sim(cfg)
+    sim.run(args.preload)
+    for _ in range(args.warmup):
+        sim.run(args.sim_steps)
+    torch.cuda.synchronize()
+    sim.kernel_time(reset=True)
+    K = cfg.K
+    import numpy as np
+    before = [sim.tallies(r) for r in (0, cfg.replications - 1)]
+    st0 = sim.stats()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        sim.run(args.sim_steps)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    launches, kernel_ms = sim.kernel_time()
+    st1 = sim.stats()
+
+    slots = float(slots_per_step) * args.steps
+    tt0 = st0["tally"][:K]; tt1 = st1["tally"][:K]
+    total_bytes, shape = algorithmic_bytes(tt0, st0["glob"], tt1, st1["glob"], slots)
+    per_launch_ms = kernel_ms / max(launches, 1)
+    achieved = total_bytes / (kernel_ms * 1e-3) / 1e9 if kernel_ms > 0 else 0.0
+    iters = float(st1["glob"][0] + st1["glob"][1]) - float(st0["glob"][0] + st0["glob"][1])
+
+    out = {
+        "metric": "simulated server-iterations/sec on 1 GPU + achieved HBM GB/s (% of peak)",
+        "value": slots / wall,
+        "unit": "server-steps/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall * 1e3 / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int64", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: K={cfg.K} N={cfg.N} R={cfg.replications} B={cfg.B} C={cfg.C} M={cfg.M}, "
+                               f"{args.sim_steps} simulation steps per bench step after {args.preload + args.warmup * args.sim_steps} untimed steps",
+                   "server_step_slots_per_bench_step": slots_per_step,
+                   "executed_iterations_per_s": iters / wall,
+                   "overflow": bool(st1["overflow"])},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "gnr_step_kernel", "launches": launches, "avg_launch_ms": per_launch_ms,
+                     "algorithmic_bytes_per_launch": total_bytes / max(launches, 1), **shape},
+    }
+    if base is not None:
+        out["cpu_baseline"] = base
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
