@@ -59,8 +59,9 @@ Layout make_layout(const sim_config &c, int R, int64_t rows)
   L.pf_job = take(RN * sizeof(uint64_t));
   L.n_cls = take(RN * sizeof(uint64_t));
   L.n_join = take(RN * sizeof(uint64_t));
-  L.fin = take(RN * c.B * sizeof(uint32_t));
-  L.job = take(RN * c.B * sizeof(uint64_t));
+  const size_t BS = (static_cast<size_t>(c.B) + 3) & ~size_t(3);
+  L.fin = take(RN * BS * sizeof(uint32_t));
+  L.job = take(RN * BS * sizeof(uint64_t));
   L.qring = take(static_cast<size_t>(R) * c.K * c.queue_cap * sizeof(uint32_t));
   L.dring = take(static_cast<size_t>(R) * c.dbuf_cap * sizeof(uint64_t));
   L.cstate = take(static_cast<size_t>(R) * CS_WORDS * sizeof(int32_t));
@@ -113,6 +114,8 @@ int validate(const sim_config *c, int max_reps, Ticks *t)
   if (lam * (static_cast<double>(t->dt) * 1e-9) * (1.0 + std::fabs(c->mod_amp)) > 0.05) return SIM_EINVAL;
   const int lo = host_hbin(t->c0), hi = host_hbin(t->c0 + t->cpre * c->C + t->cdec * c->B);
   if (hi - lo + 1 > kMaxTbtBins) return SIM_EINVAL;
+  // clocks are compared modulo 2^32 ns on the device: the longest iteration must stay far below 2^31 ns
+  if (t->c0 + t->cpre * c->C + t->cdec * c->B > 2000000000ll) return SIM_EINVAL;
   return SIM_OK;
 }
 
@@ -211,6 +214,7 @@ int sim_create(const sim_config *cfg, int max_replications, void *dev_workspace,
   Params &p = h->p;
   std::memset(&p, 0, sizeof p);
   p.K = cfg->K; p.N = cfg->N; p.B = cfg->B; p.C = cfg->C; p.M = cfg->M; p.R = max_replications;
+  p.BS = (cfg->B + 3) & ~3;
   p.gate_mode = cfg->gate_mode;
   p.tbt_lo = host_hbin(t.c0);
   p.tbt_w = host_hbin(t.c0 + t.cpre * cfg->C + t.cdec * cfg->B) - p.tbt_lo + 1;
@@ -247,7 +251,7 @@ int sim_create(const sim_config *cfg, int max_replications, void *dev_workspace,
 
   h->threads = step_threads(cfg->N);
   h->lds_bytes = step_lds_bytes(p);
-  if (h->lds_bytes > 64 * 1024) { delete h; return SIM_EINVAL; }
+  if (h->lds_bytes > 160 * 1024) { delete h; return SIM_EINVAL; }
   if (hipMemcpy(w + L.arr_thr, arr.data(), arr.size() * sizeof(uint32_t), hipMemcpyHostToDevice) != hipSuccess ||
       hipMemcpy(w + L.len_tab, tab.data(), tab.size() * sizeof(uint16_t), hipMemcpyHostToDevice) != hipSuccess) {
     delete h;
@@ -448,17 +452,18 @@ int sim_snapshot(sim_t *h, int r, sim_state_t *out, void *hip_stream)
     if (out->n_dec) out->n_dec[g] = nd;
   }
   if (out->fin || out->job) {
-    std::vector<uint32_t> f(static_cast<size_t>(N) * B);
-    std::vector<uint64_t> j(static_cast<size_t>(N) * B);
-    if ((rc = copy_out(f.data(), p.fin + base * B, f.size() * sizeof(uint32_t))) != SIM_OK) return rc;
-    if ((rc = copy_out(j.data(), p.job + base * B, j.size() * sizeof(uint64_t))) != SIM_OK) return rc;
+    const size_t BS = static_cast<size_t>(p.BS);
+    std::vector<uint32_t> f(static_cast<size_t>(N) * BS);
+    std::vector<uint64_t> j(static_cast<size_t>(N) * BS);
+    if ((rc = copy_out(f.data(), p.fin + base * BS, f.size() * sizeof(uint32_t))) != SIM_OK) return rc;
+    if ((rc = copy_out(j.data(), p.job + base * BS, j.size() * sizeof(uint64_t))) != SIM_OK) return rc;
     for (int g = 0; g < N; ++g) {
       int nd = 0;
       for (int k = 0; k < kMaxK; ++k) nd += static_cast<uint8_t>(nc[g] >> (8 * k));
       for (int s = 0; s < B; ++s) {
-        const size_t i = static_cast<size_t>(g) * B + s;
-        if (out->fin) out->fin[i] = s < nd ? f[i] : 0;
-        if (out->job) out->job[i] = s < nd ? j[i] : 0;
+        const size_t i = static_cast<size_t>(g) * B + s, d = static_cast<size_t>(g) * BS + s;
+        if (out->fin) out->fin[i] = s < nd ? f[d] : 0;
+        if (out->job) out->job[i] = s < nd ? j[d] : 0;
       }
     }
   }

@@ -30,6 +30,7 @@ enum ClassStateWord {
 // Everything a kernel needs, passed by value.
 struct Params {
   int K, N, B, C, M, R;
+  int BS;                     // slot-row stride in words: B rounded up to a multiple of 4
   int gate_mode;
   int tbt_lo, tbt_w;          // first bin and width of the TBT histogram window kept in LDS
   int nwords;                 // ceil(N/64) bitmap words
@@ -48,7 +49,7 @@ struct Params {
   uint32_t *remptok;          // prompt tokens left | tokens in the running chunk << 16
   uint64_t *pf_job;
   uint64_t *n_cls, *n_join;   // 8 x uint8 packed
-  // decode slots, [R][N][B]; slots 0..n_dec-1 of a server are occupied
+  // decode slots, [R][N][BS]; slots 0..n_dec-1 of a server are occupied
   uint32_t *fin;
   uint64_t *job;
   // rings
