@@ -39,7 +39,7 @@ extern "C" {
 
 #define SIM_MAXK 8      /* classes */
 #define SIM_MAXB 128    /* decode slots per server */
-#define SIM_MAXN 16384  /* servers per replication */
+#define SIM_MAXN 12288  /* servers per replication */
 #define SIM_NBIN 720    /* latency histogram bins: exact below 16 ns, then 16 bins per octave */
 
 enum sim_err { SIM_OK = 0, SIM_EINVAL = -1, SIM_ENOMEM = -2, SIM_EHIP = -3, SIM_EOVERFLOW = -4 };
@@ -82,7 +82,7 @@ typedef struct {
 } sim_class;
 
 typedef struct {
-  int K, N, B, C;                /* classes <= 8, servers <= 16384, decode cap <= 128, chunk <= 32768 */
+  int K, N, B, C;                /* classes <= 8, servers <= 12288, decode cap <= 128, chunk <= 8191 */
   double c0, c_pre, c_dec;       /* iteration time c0 + c_pre*ptok + c_dec*n_dec, rounded to ns */
   double dt;                     /* step length, 0 < dt <= c0; 0 selects dt = c0 */
   const sim_class *cls;          /* K entries, copied */

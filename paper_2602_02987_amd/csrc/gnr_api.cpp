@@ -40,7 +40,7 @@ constexpr uint32_t kStepsPerLaunch = 2048;
 
 struct Layout {
   size_t arr_thr, len_tab, t_next, iter, remptok, pf_job, n_cls, n_join, fin, job, qring, dring, cstate, tally, hist,
-      digest, reduced, total;
+      digest, reduced, params, total;
 };
 
 size_t align_up(size_t v) { return (v + 255) & ~size_t(255); }
@@ -69,6 +69,7 @@ Layout make_layout(const sim_config &c, int R, int64_t rows)
   L.hist = take(static_cast<size_t>(R) * 3 * c.K * kNBin * sizeof(uint64_t));
   L.digest = take(static_cast<size_t>(R) * sizeof(uint64_t));
   L.reduced = take((kTallyWords + static_cast<size_t>(3) * c.K * kNBin) * sizeof(uint64_t));
+  L.params = take(sizeof(Params));
   L.total = off;
   return L;
 }
@@ -93,7 +94,7 @@ int validate(const sim_config *c, int max_reps, Ticks *t)
 {
   if (!c || max_reps < 1 || !c->cls || !c->x_star || !c->qp_star) return SIM_EINVAL;
   if (c->K < 1 || c->K > kMaxK || c->N < 1 || c->N > kMaxN || c->B < 1 || c->B > kMaxB) return SIM_EINVAL;
-  if (c->C < 1 || c->C > kMaxLen || c->M < 0 || c->M > c->N) return SIM_EINVAL;
+  if (c->C < 1 || c->C > kMaxChunk || c->M < 0 || c->M > c->N) return SIM_EINVAL;
   if (c->queue_cap < 1 || c->queue_cap > (int64_t(1) << 30) || c->dbuf_cap < 1 || c->dbuf_cap > (int64_t(1) << 30))
     return SIM_EINVAL;
   if (c->gate_mode < SIM_GATE_OCCUPANCY || c->gate_mode > SIM_GATE_FCFS || c->route_mode != 0) return SIM_EINVAL;
@@ -249,11 +250,13 @@ int sim_create(const sim_config *cfg, int max_replications, void *dev_workspace,
   p.digest = reinterpret_cast<uint64_t *>(w + L.digest);
   p.reduced = reinterpret_cast<uint64_t *>(w + L.reduced);
 
+  p.self = reinterpret_cast<const Params *>(w + L.params);
   h->threads = step_threads(cfg->N);
   h->lds_bytes = step_lds_bytes(p);
   if (h->lds_bytes > 160 * 1024) { delete h; return SIM_EINVAL; }
   if (hipMemcpy(w + L.arr_thr, arr.data(), arr.size() * sizeof(uint32_t), hipMemcpyHostToDevice) != hipSuccess ||
-      hipMemcpy(w + L.len_tab, tab.data(), tab.size() * sizeof(uint16_t), hipMemcpyHostToDevice) != hipSuccess) {
+      hipMemcpy(w + L.len_tab, tab.data(), tab.size() * sizeof(uint16_t), hipMemcpyHostToDevice) != hipSuccess ||
+      hipMemcpy(w + L.params, &p, sizeof(Params), hipMemcpyHostToDevice) != hipSuccess) {
     delete h;
     return SIM_EHIP;
   }
@@ -440,7 +443,7 @@ int sim_snapshot(sim_t *h, int r, sim_state_t *out, void *hip_stream)
   for (int g = 0; g < N; ++g) {
     const int rem = static_cast<int>(pk[g] & 0xFFFFu);
     if (out->rem) out->rem[g] = rem;
-    if (out->ptok) out->ptok[g] = static_cast<int>(pk[g] >> 16);
+    if (out->ptok) out->ptok[g] = static_cast<int>((pk[g] >> 16) & 0x1FFFu);
     if (out->pfjob) out->pfjob[g] = rem ? pj[g] : 0;
     int nd = 0;
     for (int k = 0; k < kMaxK; ++k) {

@@ -15,6 +15,7 @@ constexpr int kMaxN = SIM_MAXN;
 constexpr int kNBin = SIM_NBIN;
 constexpr int kTableSize = 65536;
 constexpr int kMaxLen = 32768;
+constexpr int kMaxChunk = 8191;   // the running chunk is kept in 13 bits of the prefill word
 constexpr int kNTally = SIM_NTALLY;
 constexpr int kNGlobal = SIM_NGLOBAL;
 constexpr int kTallyWords = kMaxK * kNTally + kNGlobal;  // per replication, uint64
@@ -46,7 +47,7 @@ struct Params {
   // per-server state, [R][N]
   int64_t *t_next;
   uint32_t *iter;
-  uint32_t *remptok;          // prompt tokens left | tokens in the running chunk << 16
+  uint32_t *remptok;          // prompt tokens left | tokens in the running chunk << 16 | class << 29
   uint64_t *pf_job;
   uint64_t *n_cls, *n_join;   // 8 x uint8 packed
   // decode slots, [R][N][BS]; slots 0..n_dec-1 of a server are occupied
@@ -61,6 +62,7 @@ struct Params {
   uint64_t *hist;             // [R][3][K][kNBin]
   uint64_t *digest;           // [R]
   uint64_t *reduced;          // [kTallyWords + 3*K*kNBin] totals over replications
+  const Params *self;         // device copy of this struct (key0/key1 there are unused)
 };
 
 // host-side table builders (gnr_tables.cpp)

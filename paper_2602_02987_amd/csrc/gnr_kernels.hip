@@ -49,6 +49,34 @@ __device__ __forceinline__ uint32_t byte_sum(uint64_t packed)
 }
 __device__ __forceinline__ uint32_t byte_at(uint64_t packed, int k) { return static_cast<uint32_t>(packed >> (8 * k)) & 255u; }
 
+// Prefill word of a server: prompt tokens left | tokens in the running chunk << 16 | class << 29.
+__device__ __forceinline__ int pk_rem(uint32_t pk) { return static_cast<int>(pk & 0xFFFFu); }
+__device__ __forceinline__ int pk_ptok(uint32_t pk) { return static_cast<int>((pk >> 16) & 0x1FFFu); }
+__device__ __forceinline__ int pk_cls(uint32_t pk) { return static_cast<int>(pk >> 29); }
+
+// Position of the n-th set bit (n counted from 0) of a word that has more than n bits set.
+__device__ __forceinline__ int nth_set_bit(uint64_t word, int n)
+{
+  int pos = 0;
+#pragma unroll
+  for (int sh = 32; sh > 0; sh >>= 1) {
+    const int c = __popcll(word & ((1ull << sh) - 1ull));
+    if (n >= c) { n -= c; word >>= sh; pos += sh; }
+  }
+  return pos;
+}
+
+// Index of the j-th set bit of a bitmap given the exclusive prefix popcounts of its words.
+__device__ __forceinline__ int select_bit(const uint64_t *bm, const uint32_t *pre, int nwords, uint32_t j)
+{
+  int lo = 0, hi = nwords - 1;   // largest w with pre[w] <= j
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (pre[mid] <= j) lo = mid; else hi = mid - 1;
+  }
+  return lo * 64 + nth_set_bit(bm[lo], static_cast<int>(j - pre[lo]));
+}
+
 __device__ __forceinline__ uint64_t lanes_below() { return (1ull << (threadIdx.x & 63)) - 1ull; }
 
 __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v)
@@ -67,14 +95,29 @@ __device__ __forceinline__ void lds_add64(uint64_t *p, uint64_t v)
   atomicAdd(reinterpret_cast<unsigned long long *>(p), static_cast<unsigned long long>(v));
 }
 
+// Optional per-phase cycle counters (compiled out unless GNR_PROF is defined).
+#ifdef GNR_PROF
+__device__ unsigned long long g_prof[16];
+#define PROF_DECL unsigned long long prof_acc[16] = {0}; unsigned long long prof_last = clock64();
+#define PROF(i) { const unsigned long long t_ = clock64(); prof_acc[i] += t_ - prof_last; prof_last = t_; }
+#define PROF_FLUSH if ((threadIdx.x & 63) == 0) { for (int i_ = 0; i_ < 16; ++i_) atomicAdd(&g_prof[i_], prof_acc[i_]); }
+#else
+#define PROF_DECL
+#define PROF(i)
+#define PROF_FLUSH
+#endif
+
 // ------------------------------------------------------------------ LDS layout ----
 enum Scalar {
-  SC_NADM = 0, SC_NIDLE, SC_NCOMP, SC_MORE, SC_LMIN, SC_CNT, SC_JREM, SC_NEXT, SC_DHEAD0,
-  SC_TAKE = 16,  // [8] accepted arrivals this step
-  SC_TAIL = 24,  // [8] ring position of the first accepted arrival
-  SC_QH0 = 32,   // [8] ring head at the start of the gate pass
-  SC_WORDS = 40
+  SC_NIDLE = 0, SC_NCOMP,
+  SC_TAKE = 16,   // [8] accepted arrivals this step
+  SC_TAIL = 24,   // [8] ring position of the first accepted arrival
+  SC_ADMK = 40,   // [8] admissions per class in this gate pass
+  SC_WORDS = 48
 };
+constexpr int kLoadBins = kMaxB + 1;
+constexpr int kEvPerWave = 128;   // completions a wave can queue per step; any beyond are finished inline
+constexpr int kMaxWaves = 16;
 
 struct Lds {
   int32_t *cs;        // [CS_WORDS]
@@ -86,56 +129,72 @@ struct Lds {
   uint64_t *bm_comp;  // [nwords] servers whose prefill completed this step
   uint64_t *bm_lvl;   // [nwords] servers at the routing level
   uint64_t *bm_busy;  // [nwords] servers running an iteration
-  uint32_t *pre;      // [nwords] exclusive prefix popcounts of the bitmap being ranked
+  uint64_t *bm_join;  // [nwords] servers holding a decode that joined after the running iteration started
+  uint64_t *bm_due;   // [nwords] servers that completed an iteration this step
+  uint64_t *bm_touch; // [nwords] idle servers that were given work this step
+  uint32_t *pre_c;    // [nwords] exclusive prefix popcounts of bm_comp
+  uint32_t *pre;      // [nwords] exclusive prefix popcounts of bm_idle / bm_lvl
   uint32_t *adm;      // [kAdmChunk] class | sequence-in-class << 3 of each admission
+  uint32_t *lh;       // [2][kLoadBins] servers per decode count: solo group, mixed group
+  uint32_t *ev_g;     // [waves][kEvPerWave] servers with decodes leaving this step, queued per wave
+  uint32_t *ev_q;     // [waves][kEvPerWave] their slot-quad masks
   uint32_t *t32;      // [N] low 32 bits of the end time of the running iteration
+  uint32_t *iter;     // [N] completed iterations
   uint8_t *loads;     // [N] decodes per server
 };
 
-__host__ __device__ inline size_t lds_carve(const Params &p, unsigned char *base, Lds *out)
+// Carves the dynamic LDS block; 8-byte granules, 64-bit arrays first.
+__host__ __device__ __forceinline__ Lds lds_carve(const Params &p, unsigned char *base, size_t *total)
 {
+  Lds L;
   size_t off = 0;
-  auto take = [&](size_t bytes) { size_t o = off; off += (bytes + 7) & ~size_t(7); return o; };
-  const size_t o_tl = take(sizeof(uint64_t) * kTallyWords);
-  const size_t o_tb = take(sizeof(uint64_t) * p.K * p.tbt_w);
-  const size_t o_bi = take(sizeof(uint64_t) * p.nwords);
-  const size_t o_bc = take(sizeof(uint64_t) * p.nwords);
-  const size_t o_bl = take(sizeof(uint64_t) * p.nwords);
-  const size_t o_bb = take(sizeof(uint64_t) * p.nwords);
-  const size_t o_cs = take(sizeof(int32_t) * CS_WORDS);
-  const size_t o_ac = take(sizeof(uint32_t) * 8);
-  const size_t o_sc = take(sizeof(int32_t) * SC_WORDS);
-  const size_t o_pr = take(sizeof(uint32_t) * (p.nwords + 1));
-  const size_t o_ad = take(sizeof(uint32_t) * kAdmChunk);
-  const size_t o_t3 = take(sizeof(uint32_t) * p.N);
-  const size_t o_ld = take(static_cast<size_t>(p.N));
-  if (out) {
-    out->tl = reinterpret_cast<uint64_t *>(base + o_tl);
-    out->tbth = reinterpret_cast<uint64_t *>(base + o_tb);
-    out->bm_idle = reinterpret_cast<uint64_t *>(base + o_bi);
-    out->bm_comp = reinterpret_cast<uint64_t *>(base + o_bc);
-    out->bm_lvl = reinterpret_cast<uint64_t *>(base + o_bl);
-    out->bm_busy = reinterpret_cast<uint64_t *>(base + o_bb);
-    out->cs = reinterpret_cast<int32_t *>(base + o_cs);
-    out->acc = reinterpret_cast<uint32_t *>(base + o_ac);
-    out->sc = reinterpret_cast<int32_t *>(base + o_sc);
-    out->pre = reinterpret_cast<uint32_t *>(base + o_pr);
-    out->adm = reinterpret_cast<uint32_t *>(base + o_ad);
-    out->t32 = reinterpret_cast<uint32_t *>(base + o_t3);
-    out->loads = reinterpret_cast<uint8_t *>(base + o_ld);
-  }
-  return off;
+#define GNR_TAKE(field, type, count)                       \
+  L.field = reinterpret_cast<type *>(base + off);          \
+  off += (sizeof(type) * static_cast<size_t>(count) + 7) & ~size_t(7);
+  GNR_TAKE(tl, uint64_t, kTallyWords)
+  GNR_TAKE(tbth, uint64_t, p.K * p.tbt_w)
+  GNR_TAKE(bm_idle, uint64_t, p.nwords)
+  GNR_TAKE(bm_comp, uint64_t, p.nwords)
+  GNR_TAKE(bm_lvl, uint64_t, p.nwords)
+  GNR_TAKE(bm_busy, uint64_t, p.nwords)
+  GNR_TAKE(bm_join, uint64_t, p.nwords)
+  GNR_TAKE(bm_due, uint64_t, p.nwords)
+  GNR_TAKE(bm_touch, uint64_t, p.nwords)
+  GNR_TAKE(cs, int32_t, CS_WORDS)
+  GNR_TAKE(acc, uint32_t, 8)
+  GNR_TAKE(sc, int32_t, SC_WORDS)
+  GNR_TAKE(pre_c, uint32_t, p.nwords + 1)
+  GNR_TAKE(pre, uint32_t, p.nwords + 1)
+  GNR_TAKE(adm, uint32_t, kAdmChunk)
+  GNR_TAKE(lh, uint32_t, 2 * kLoadBins)
+  GNR_TAKE(ev_g, uint32_t, kMaxWaves * kEvPerWave)
+  GNR_TAKE(ev_q, uint32_t, kMaxWaves * kEvPerWave)
+  GNR_TAKE(t32, uint32_t, p.N)
+  GNR_TAKE(iter, uint32_t, p.N)
+  GNR_TAKE(loads, uint8_t, p.N)
+#undef GNR_TAKE
+  if (total) *total = off;
+  return L;
 }
 
-size_t step_lds_bytes(const Params &p) { return lds_carve(p, nullptr, nullptr); }
+size_t step_lds_bytes(const Params &p)
+{
+  size_t total = 0;
+  lds_carve(p, nullptr, &total);
+  return total;
+}
 
 int step_threads(int N)
 {
   int t = (N + 63) / 64 * 64;
+#ifdef GNR_MAX_THREADS
+  return t > GNR_MAX_THREADS ? GNR_MAX_THREADS : t;
+#else
   return t > 1024 ? 1024 : t;
+#endif
 }
 
-// Exclusive prefix popcounts of a bitmap (wave 0 only); returns the total in every lane of wave 0.
+// Exclusive prefix popcounts of a bitmap, computed by one whole wave; returns the total in every lane.
 __device__ __forceinline__ uint32_t rank_bitmap(const uint64_t *bm, uint32_t *pre, int nwords)
 {
   const int lane = threadIdx.x & 63;
@@ -153,18 +212,28 @@ __device__ __forceinline__ uint32_t rank_bitmap(const uint64_t *bm, uint32_t *pr
 __device__ __forceinline__ uint64_t wave_sum64(uint64_t v)
 {
 #pragma unroll
+  for (int d = 32; d > 0; d >>= 1) {
+    const uint32_t lo = __shfl_xor(static_cast<uint32_t>(v), d, 64);
+    const uint32_t hi = __shfl_xor(static_cast<uint32_t>(v >> 32), d, 64);
+    v += (static_cast<uint64_t>(hi) << 32) | lo;
+  }
+  return v;
+}
+__device__ __forceinline__ uint32_t wave_sum32(uint32_t v)
+{
+#pragma unroll
   for (int d = 32; d > 0; d >>= 1) v += __shfl_xor(v, d, 64);
   return v;
 }
 
-// Per-lane running sums of the tallies every executed iteration touches; they are added to the
-// workgroup's totals once per launch instead of once per iteration.
+// Per-lane sums of the tallies every executed iteration touches. The step sums are folded into
+// the workgroup's totals once per step; the time-between-tokens counts stay cached per lane for
+// the bin they fall in and are written out when the bin changes or the launch ends.
 struct LaneTallies {
-  uint32_t iters[2];            // [decode-only, with a prefill chunk]
+  uint32_t iters[2];            // this step: [decode-only, with a prefill chunk]
   uint64_t busy[2];
-  uint32_t tok_emit[kMaxK];
   uint64_t tbt_sum[kMaxK];
-  int hist_bin[2];              // time-between-tokens bin currently accumulated, by iteration kind
+  int hist_bin[2];              // across steps: time-between-tokens bin being accumulated, by iteration kind
   uint32_t hist_cnt[2][kMaxK];
 };
 
@@ -187,29 +256,78 @@ __device__ __forceinline__ void tally_iteration(LaneTallies &lt, uint64_t *tbth,
 #pragma unroll
   for (int k = 0; k < kMaxK; ++k) {
     const uint32_t em = byte_at(nc, k) - byte_at(nj, k);
-    lt.tok_emit[k] += em;
     lt.tbt_sum[k] += static_cast<uint64_t>(em) * static_cast<uint64_t>(d);
     lt.hist_cnt[KIND][k] += em;
   }
 }
 
-// ------------------------------------------------------------------ step kernel ----
-__global__ void __launch_bounds__(1024) gnr_step_kernel(const Params p, const uint32_t step_begin, const uint32_t n_steps)
+// Sort key of a gate candidate: the m-th waiting request of class k (m counted from the head).
+// Occupancy gate: (X_k + m - n x_k*)/x_k*, ties by the larger queue deviation Q_k - m - n q_k*;
+// priority gate: larger static index first; FCFS gate: older arrival stamp first.
+// Ties that remain go to the lower class. Within a class the key does not decrease with m, so the
+// gate's one-at-a-time argmin is the merge of the classes' sequences in this order.
+struct GateKey { double a, b; };
+
+__device__ __forceinline__ GateKey gate_key(const Params &p, const uint32_t *qring, const int (&xs)[kMaxK],
+                                            const int (&qp)[kMaxK], const uint32_t (&head)[kMaxK], int k, int m)
 {
+  GateKey key;
+  if (p.gate_mode == SIM_GATE_OCCUPANCY) {
+    key.a = (static_cast<double>(xs[k] + m) - p.nx[k]) * p.invx[k];
+    key.b = static_cast<double>(qp[k] - m) - p.nq[k];
+  } else if (p.gate_mode == SIM_GATE_PRIORITY) {
+    key.a = -p.prio[k];
+    key.b = 0.0;
+  } else {
+    uint32_t pos = head[k] + static_cast<uint32_t>(m);
+    if (pos >= p.queue_cap) pos -= p.queue_cap;
+    key.a = static_cast<double>(qring[static_cast<size_t>(k) * p.queue_cap + pos]);
+    key.b = 0.0;
+  }
+  return key;
+}
+
+// true if candidate (k1, key1) is admitted before candidate (k2, key2), k1 != k2
+__device__ __forceinline__ bool gate_before(const GateKey &x, int k1, const GateKey &y, int k2)
+{
+  if (x.a != y.a) return x.a < y.a;
+  if (x.b != y.b) return x.b > y.b;
+  return k1 < k2;
+}
+
+// ------------------------------------------------------------------ step kernel ----
+// What the completion pass knows about one server of the round being processed.
+struct RoundState {
+  bool due;        // the server's iteration ends within this step
+  uint32_t t32;    // low 32 bits of its end time
+  uint32_t it;     // index of the iteration that ends
+  int nd;          // decodes on the server
+  uint64_t nc, nj; // per-class decode counts; of those, late joiners
+  uint32_t pk;     // prefill word (mixed group only)
+  uint64_t due_mask, join_word;
+};
+
+template <int MAXT>
+__global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict__ params, const uint32_t key0,
+                                                        const uint32_t key1, const uint32_t step_begin,
+                                                        const uint32_t n_steps)
+{
+  const Params &p = *params;   // immutable after creation; read through the scalar cache on demand
   extern __shared__ __align__(16) unsigned char lds_raw[];
-  Lds L;
-  lds_carve(p, lds_raw, &L);
+  const Lds L = lds_carve(p, lds_raw, nullptr);
 
   const int r = blockIdx.x;
   const int tid = threadIdx.x;
   const int NT = blockDim.x;
   const int lane = tid & 63;
+  const int wave = tid >> 6;
   const int wave_base = tid & ~63;
   const int K = p.K, N = p.N, B = p.B, M = p.M, BS = p.BS;
   const int nper = (N + NT - 1) / NT;
+  const int nwords_m = (M + 63) >> 6;   // bitmap words that hold mixed-group servers
 
   int64_t *t_next = p.t_next + static_cast<size_t>(r) * N;
-  uint32_t *iter = p.iter + static_cast<size_t>(r) * N;
+  uint32_t *iter_g = p.iter + static_cast<size_t>(r) * N;
   uint32_t *remptok = p.remptok + static_cast<size_t>(r) * N;
   uint64_t *pf_job = p.pf_job + static_cast<size_t>(r) * N;
   uint64_t *n_cls = p.n_cls + static_cast<size_t>(r) * N;
@@ -219,145 +337,88 @@ __global__ void __launch_bounds__(1024) gnr_step_kernel(const Params p, const ui
   uint32_t *qring = p.qring + static_cast<size_t>(r) * K * p.queue_cap;
   uint64_t *dring = p.dring + static_cast<size_t>(r) * p.dbuf_cap;
   uint64_t *hist = p.hist + static_cast<size_t>(r) * 3 * K * kNBin;
+  uint32_t *ev_g = L.ev_g + wave * kEvPerWave;
+  uint32_t *ev_q = L.ev_q + wave * kEvPerWave;
 
   // ---- load the replication's class state and rebuild the on-chip views of the server state
   for (int i = tid; i < CS_WORDS; i += NT) L.cs[i] = p.cstate[static_cast<size_t>(r) * CS_WORDS + i];
   for (int i = tid; i < kTallyWords; i += NT) L.tl[i] = 0;
   for (int i = tid; i < K * p.tbt_w; i += NT) L.tbth[i] = 0;
   for (int i = tid; i < SC_WORDS; i += NT) L.sc[i] = 0;
+  for (int i = tid; i < 2 * kLoadBins; i += NT) L.lh[i] = 0;
+  __syncthreads();
   for (int i = 0; i < nper; ++i) {
     const int g = i * NT + tid;
     const bool valid = g < N;
-    bool busy = false;
+    bool busy = false, joined = false;
     if (valid) {
-      L.loads[g] = static_cast<uint8_t>(byte_sum(n_cls[g]));
+      const uint32_t nd = byte_sum(n_cls[g]);
+      L.loads[g] = static_cast<uint8_t>(nd);
+      atomicAdd(&L.lh[(g < M ? kLoadBins : 0) + nd], 1u);
       const int64_t tn = t_next[g];
       busy = tn != kIdle;
       L.t32[g] = static_cast<uint32_t>(tn);
+      L.iter[g] = iter_g[g];
+      joined = n_join[g] != 0;
     }
-    const bool idle_slot = valid && g < M && (remptok[g] & 0xFFFFu) == 0;
-    const uint64_t bi = __ballot(idle_slot), bb = __ballot(busy);
+    const bool idle_slot = valid && g < M && pk_rem(remptok[g]) == 0;
+    const uint64_t bi = __ballot(idle_slot), bb = __ballot(busy), bj = __ballot(joined);
     const int wi = (i * NT + wave_base) >> 6;
-    if (lane == 0 && wi < p.nwords) { L.bm_idle[wi] = bi; L.bm_busy[wi] = bb; }
+    if (lane == 0 && wi < p.nwords) { L.bm_idle[wi] = bi; L.bm_busy[wi] = bb; L.bm_join[wi] = bj; }
   }
   LaneTallies lt;
-  lt.iters[0] = lt.iters[1] = 0; lt.busy[0] = lt.busy[1] = 0;
   lt.hist_bin[0] = lt.hist_bin[1] = 0;
 #pragma unroll
-  for (int k = 0; k < kMaxK; ++k) { lt.tok_emit[k] = 0; lt.tbt_sum[k] = 0; lt.hist_cnt[0][k] = lt.hist_cnt[1][k] = 0; }
+  for (int k = 0; k < kMaxK; ++k) lt.hist_cnt[0][k] = lt.hist_cnt[1][k] = 0;
   __syncthreads();
 
   int64_t T = 0;
+  PROF_DECL
   for (uint32_t s = step_begin; s < step_begin + n_steps; ++s) {
+    PROF(0)
     T = (static_cast<int64_t>(s) + 1) * p.dt;
     const uint32_t T32 = static_cast<uint32_t>(T);
     if (tid < 8) L.acc[tid] = 0;
-
-    // ================= 1. arrivals =================
+    lt.iters[0] = lt.iters[1] = 0; lt.busy[0] = lt.busy[1] = 0;
+#pragma unroll
+    for (int k = 0; k < kMaxK; ++k) lt.tbt_sum[k] = 0;
     const uint32_t *thr = p.arr_thr + 3 * (p.mod_period > 0 ? static_cast<int64_t>(s % static_cast<uint64_t>(p.mod_period)) : 0);
     const uint32_t thr0 = thr[0], thr1 = thr[1], thr2 = thr[2];
-    uint64_t at_boundary = 0, touched = 0;
     __syncthreads();
-    for (int i = 0; i < nper; ++i) {
-      const int g = i * NT + tid;
-      if (g < N) {
-        uint32_t w[4];
-        philox4x32_10(p.key0, p.key1, s, 0u, static_cast<uint32_t>(g), static_cast<uint32_t>(r), w);
-        if (w[0] >= thr0) {
-          const int a = 1 + (w[0] >= thr1) + (w[0] >= thr2);
-          for (int j = 0; j < a; ++j) {
-            int k = 0;
-            for (int c = 0; c + 1 < K; ++c) k += (w[1 + j] >= p.cls_thr[c]);
-            atomicAdd(&L.acc[k], 1u);
-          }
-        }
-      }
-    }
 
-    // ================= 2. iteration completion on due servers =================
-    for (int i = 0; i < nper; ++i) {
-      const int gw = i * NT + wave_base;          // first server of this wave's 64-server block
-      const int wi = gw >> 6;
-      if (gw >= N) break;                         // wave-uniform
-      const int g = gw + lane;
-      const bool valid = g < N;
-      const uint64_t busy_word = L.bm_busy[wi];
-      const uint32_t t32 = valid ? L.t32[g] : 0u;
-      const bool due = valid && ((busy_word >> lane) & 1ull) && static_cast<int32_t>(t32 - T32) <= 0;
-      const uint64_t due_mask = __ballot(due);
-      if (due_mask == 0) {
-        if (lane == 0) L.bm_comp[wi] = 0;
-        continue;
-      }
-      uint32_t it = 0, pk = 0;
-      uint64_t nc = 0, nj = 0;
-      int nd = 0;
-      if (due) {
-        at_boundary |= 1ull << i;
-        it = iter[g] + 1;
-        pk = g < M ? remptok[g] : 0u;
-        nc = n_cls[g];
-        nj = n_join[g];
-        nd = static_cast<int>(byte_sum(nc));
-      }
-      // ---- cooperative scan of the slot rows: half a wave reads one server's row (4 words per lane)
-      uint32_t quads = 0;   // owner lane: bit q set <=> one of slots 4q..4q+3 finishes now
-      {
-        uint64_t todo = __ballot(due && nd > 0);
-        while (todo) {
-          int la[4], lb[4];
-          bool va[4], vb[4];
+    // ---- 1. arrivals of one server: one random block, word 0 -> count, words 1.. -> classes
+    auto arrivals = [&](int g) __attribute__((always_inline)) {
+      uint32_t w[4];
+      philox4x32_10(key0, key1, s, 0u, static_cast<uint32_t>(g), static_cast<uint32_t>(r), w);
+      if (w[0] >= thr0) {
+        const int a = 1 + (w[0] >= thr1) + (w[0] >= thr2);
 #pragma unroll
-          for (int u = 0; u < 4; ++u) {
-            va[u] = todo != 0;
-            la[u] = va[u] ? __ffsll(static_cast<long long>(todo)) - 1 : 0;
-            if (va[u]) todo &= todo - 1;
-            vb[u] = todo != 0;
-            lb[u] = vb[u] ? __ffsll(static_cast<long long>(todo)) - 1 : 0;
-            if (vb[u]) todo &= todo - 1;
-          }
-          uint4 v[4];
-          uint32_t its[4];
-          int nds[4];
-          const int q = lane & 31;
-          const bool hi = lane >= 32;
+        for (int j = 0; j < 3; ++j) {
+          if (j >= a) break;
+          int k = 0;
 #pragma unroll
-          for (int u = 0; u < 4; ++u) {
-            const uint32_t ita = __builtin_amdgcn_readlane(it, la[u]), itb = __builtin_amdgcn_readlane(it, lb[u]);
-            const int nda = __builtin_amdgcn_readlane(nd, la[u]), ndb = __builtin_amdgcn_readlane(nd, lb[u]);
-            const bool on = hi ? vb[u] : va[u];
-            its[u] = hi ? itb : ita;
-            nds[u] = on ? (hi ? ndb : nda) : 0;
-            const int gs = gw + (hi ? lb[u] : la[u]);
-            v[u] = make_uint4(0u, 0u, 0u, 0u);
-            if (4 * q < nds[u]) v[u] = *reinterpret_cast<const uint4 *>(fin + static_cast<size_t>(gs) * BS + 4 * q);
-          }
-#pragma unroll
-          for (int u = 0; u < 4; ++u) {
-            const int left = nds[u] - 4 * q;   // occupied words of this lane's quad
-            const bool m = (left > 0 && v[u].x == its[u]) || (left > 1 && v[u].y == its[u]) ||
-                           (left > 2 && v[u].z == its[u]) || (left > 3 && v[u].w == its[u]);
-            const uint64_t hit = __ballot(m);
-            if (hit) {
-              if (va[u] && lane == la[u]) quads = static_cast<uint32_t>(hit);
-              if (vb[u] && lane == lb[u]) quads = static_cast<uint32_t>(hit >> 32);
-            }
-          }
+          for (int c = 0; c + 1 < kMaxK; ++c) k += (c + 1 < K && w[1 + j] >= p.cls_thr[c]);
+          atomicAdd(&L.acc[k], 1u);
         }
       }
+    };
+
+    // ---- 2. finishing the iteration of server g: tallies, decodes that emitted their last token
+    //      (slot quads flagged in `quads`), prefill progress. Returns true if the prefill completed.
+    auto finish_iteration = [&](int g, uint32_t it, int nd, uint64_t nc, uint64_t nj, uint32_t pk, uint32_t t32,
+                                uint32_t quads) __attribute__((always_inline)) -> bool {
+      int rem = pk_rem(pk);
+      const int ptok = pk_ptok(pk);
+      const int64_t tn = T + static_cast<int64_t>(static_cast<int32_t>(t32 - T32));   // exact completion time
+      const int64_t d = p.c0 + p.cpre * ptok + p.cdec * static_cast<int64_t>(nd - static_cast<int>(byte_sum(nj)));
+      const int tb = hbin(d) - p.tbt_lo;
+      if (ptok > 0) tally_iteration<1>(lt, L.tbth, p.tbt_w, K, d, tb, nc, nj);
+      else tally_iteration<0>(lt, L.tbth, p.tbt_w, K, d, tb, nc, nj);
       bool pf_done = false;
-      if (due) {
-        int rem = static_cast<int>(pk & 0xFFFFu);
-        const int ptok = static_cast<int>(pk >> 16);
-        const int64_t tn = T + static_cast<int64_t>(static_cast<int32_t>(t32 - T32));   // exact completion time
-        const int64_t d = p.c0 + p.cpre * ptok + p.cdec * static_cast<int64_t>(nd - static_cast<int>(byte_sum(nj)));
-        const int tb = hbin(d) - p.tbt_lo;
-        if (ptok > 0) tally_iteration<1>(lt, L.tbth, p.tbt_w, K, d, tb, nc, nj);
-        else tally_iteration<0>(lt, L.tbth, p.tbt_w, K, d, tb, nc, nj);
-        // decodes that emitted their last token leave; the last occupied slot fills the hole.
+      const bool mixed_now = rem > 0;
+      const int nd_before = nd;
+      if (quads) {
         // Highest slot first, so the slot moved into a hole has already been checked.
-        const bool mixed_now = rem > 0;
-        const uint64_t nc_before = nc;
         uint32_t *frow = fin + static_cast<size_t>(g) * BS;
         uint64_t *jrow = job + static_cast<size_t>(g) * BS;
         while (quads) {
@@ -386,46 +447,193 @@ __global__ void __launch_bounds__(1024) gnr_step_kernel(const Params p, const ui
             }
           }
         }
-        // the prefill advances by the chunk frozen at the start of the iteration
-        if (ptok > 0) {
+        if (nd != nd_before) {
+          n_cls[g] = nc;
+          L.loads[g] = static_cast<uint8_t>(nd);
+          const int hb = g < M ? kLoadBins : 0;
+          atomicSub(&L.lh[hb + nd_before], 1u);
+          atomicAdd(&L.lh[hb + nd], 1u);
+        }
+      }
+      // the prefill advances by the chunk frozen at the start of the iteration
+      if (ptok > 0) {
+        const int k = pk_cls(pk);
+        lds_add64(&L.tl[k * kNTally + SIM_T_TOK_PREF], static_cast<uint64_t>(ptok));
+        rem -= ptok;
+        if (rem == 0) {
+          pf_done = true;
           const uint64_t jw = pf_job[g];
-          const int k = static_cast<int>(jw >> 29) & 7;
-          lds_add64(&L.tl[k * kNTally + SIM_T_TOK_PREF], static_cast<uint64_t>(ptok));
-          rem -= ptok;
-          if (rem == 0) {
-            pf_done = true;
-            const uint32_t stamp = static_cast<uint32_t>(jw) & 0x1FFFFFFFu;
-            const uint32_t Pl = (static_cast<uint32_t>(jw >> 32) & 0xFFFFu) + 1;
-            lds_add64(&L.tl[k * kNTally + SIM_T_S_P], 1);
-            atomicSub(&L.cs[CS_X + k], 1);
-            lds_add64(&L.tl[k * kNTally + SIM_T_TOKP_PRE], Pl);
-            const int64_t ttft = tn - (static_cast<int64_t>(stamp) + 1) * p.dt;
-            lds_add64(&L.tl[k * kNTally + SIM_T_TTFT_SUM], static_cast<uint64_t>(ttft));
-            atomicAdd(reinterpret_cast<unsigned long long *>(&hist[(0 * K + k) * kNBin + hbin(ttft)]), 1ull);
-            for (int c = 0; c < K; ++c) {   // co-resident decodes switch mixed -> solo
-              const int v = static_cast<int>(byte_at(nc, c));
-              if (v) {
-                lds_add64(&L.tl[c * kNTally + SIM_T_M_MS], static_cast<uint64_t>(v));
-                atomicSub(&L.cs[CS_YM + c], v);
-                atomicAdd(&L.cs[CS_YS + c], v);
-              }
+          const uint32_t stamp = static_cast<uint32_t>(jw) & 0x1FFFFFFFu;
+          const uint32_t Pl = (static_cast<uint32_t>(jw >> 32) & 0xFFFFu) + 1;
+          lds_add64(&L.tl[k * kNTally + SIM_T_S_P], 1);
+          atomicSub(&L.cs[CS_X + k], 1);
+          lds_add64(&L.tl[k * kNTally + SIM_T_TOKP_PRE], Pl);
+          const int64_t ttft = tn - (static_cast<int64_t>(stamp) + 1) * p.dt;
+          lds_add64(&L.tl[k * kNTally + SIM_T_TTFT_SUM], static_cast<uint64_t>(ttft));
+          atomicAdd(reinterpret_cast<unsigned long long *>(&hist[(0 * K + k) * kNBin + hbin(ttft)]), 1ull);
+          for (int c = 0; c < K; ++c) {   // co-resident decodes switch mixed -> solo
+            const int v = static_cast<int>(byte_at(nc, c));
+            if (v) {
+              lds_add64(&L.tl[c * kNTally + SIM_T_M_MS], static_cast<uint64_t>(v));
+              atomicSub(&L.cs[CS_YM + c], v);
+              atomicAdd(&L.cs[CS_YS + c], v);
             }
           }
         }
-        iter[g] = it;
-        if (g < M) remptok[g] = static_cast<uint32_t>(rem);   // running chunk cleared; set again at the restart
-        if (nc != nc_before) { n_cls[g] = nc; L.loads[g] = static_cast<uint8_t>(nd); }
-        if (nj) n_join[g] = 0;
+        // running chunk cleared; it is set again at the restart
+        remptok[g] = static_cast<uint32_t>(rem) | (static_cast<uint32_t>(k) << 29);
       }
-      const uint64_t done = __ballot(pf_done);
+      if (nj) n_join[g] = 0;
+      return pf_done;
+    };
+
+    // a server whose finishing was put off because decodes leave it: reload its record and finish it
+    auto finish_deferred = [&](int g, uint32_t quads) __attribute__((always_inline)) {
+      const uint64_t nc = n_cls[g];
+      const bool joined = (L.bm_join[g >> 6] >> (g & 63)) & 1ull;
+      const uint64_t nj = joined ? n_join[g] : 0ull;
+      const uint32_t pk = g < M ? remptok[g] : 0u;
+      const bool pf = finish_iteration(g, L.iter[g], L.loads[g], nc, nj, pk, L.t32[g], quads);
+      if (pf) {
+        atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_comp[g >> 6]), 1ull << (g & 63));
+        atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_idle[g >> 6]), 1ull << (g & 63));
+      }
+      if (joined) atomicAnd(reinterpret_cast<unsigned long long *>(&L.bm_join[g >> 6]), ~(1ull << (g & 63)));
+    };
+
+    // which servers of round i are due, and their records (global loads are issued, not waited for)
+    auto probe = [&](int i) __attribute__((always_inline)) -> RoundState {
+      RoundState st;
+      st.due = false; st.t32 = 0; st.it = 0; st.nd = 0; st.nc = 0; st.nj = 0; st.pk = 0; st.due_mask = 0; st.join_word = 0;
+      const int gw = i * NT + wave_base;
+      if (gw < N) {
+        const int g = gw + lane;
+        const bool valid = g < N;
+        const uint64_t busy_word = L.bm_busy[gw >> 6];
+        st.join_word = L.bm_join[gw >> 6];
+        st.t32 = valid ? L.t32[g] : 0u;
+        st.due = valid && ((busy_word >> lane) & 1ull) && static_cast<int32_t>(st.t32 - T32) <= 0;
+        st.due_mask = __ballot(st.due);
+        if (st.due) {
+          st.it = L.iter[g] + 1;
+          L.iter[g] = st.it;
+          st.nd = L.loads[g];
+          st.nc = n_cls[g];
+          if ((st.join_word >> lane) & 1ull) st.nj = n_join[g];
+          if (g < M) st.pk = remptok[g];
+        }
+      }
+      return st;
+    };
+
+    int nev = 0;   // completions queued by this wave (wave-uniform)
+    RoundState nx = probe(0);
+    PROF(1)
+    for (int i = 0; i < nper; ++i) {
+      const int gw = i * NT + wave_base;          // first server of this wave's 64-server block
+      if (gw >= N) break;                         // wave-uniform
+      const int wi = gw >> 6;
+      const int g = gw + lane;
+      const RoundState cur = nx;
+      if (i + 1 < nper) nx = probe(i + 1);        // next round's records travel while this round is scanned
+      PROF(2)
+      uint32_t quads = 0;   // owner lane: bit q set <=> one of slots 4q..4q+3 finishes now
+      if (cur.due_mask) {
+        // ---- cooperative scan of the slot rows: half a wave reads one server's row (4 words per lane)
+        uint64_t todo = __ballot(cur.due && cur.nd > 0);
+        const int q = lane & 31;
+        const bool hi = lane >= 32;
+        bool first_batch = true;
+        do {
+          int la[4], lb[4];
+          bool va[4], vb[4];
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            va[u] = todo != 0;
+            la[u] = va[u] ? __ffsll(static_cast<long long>(todo)) - 1 : 0;
+            if (va[u]) todo &= todo - 1;
+            vb[u] = todo != 0;
+            lb[u] = vb[u] ? __ffsll(static_cast<long long>(todo)) - 1 : 0;
+            if (vb[u]) todo &= todo - 1;
+          }
+          uint4 v[4];
+          uint32_t its[4];
+          int nds[4];
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const uint32_t ita = __builtin_amdgcn_readlane(cur.it, la[u]), itb = __builtin_amdgcn_readlane(cur.it, lb[u]);
+            const int nda = __builtin_amdgcn_readlane(cur.nd, la[u]), ndb = __builtin_amdgcn_readlane(cur.nd, lb[u]);
+            const bool on = hi ? vb[u] : va[u];
+            its[u] = hi ? itb : ita;
+            nds[u] = on ? (hi ? ndb : nda) : 0;
+            const int gs = gw + (hi ? lb[u] : la[u]);
+            v[u] = make_uint4(0u, 0u, 0u, 0u);
+            if (4 * q < nds[u]) v[u] = *reinterpret_cast<const uint4 *>(fin + static_cast<size_t>(gs) * BS + 4 * q);
+          }
+          if (first_batch) {   // the arrival draws of this round run while the first rows travel
+            if (g < N) arrivals(g);
+            first_batch = false;
+          }
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const int left = nds[u] - 4 * q;   // occupied words of this lane's quad
+            const bool m = (left > 0 && v[u].x == its[u]) || (left > 1 && v[u].y == its[u]) ||
+                           (left > 2 && v[u].z == its[u]) || (left > 3 && v[u].w == its[u]);
+            const uint64_t hit = __ballot(m);
+            if (hit) {
+              if (va[u] && lane == la[u]) quads = static_cast<uint32_t>(hit);
+              if (vb[u] && lane == lb[u]) quads = static_cast<uint32_t>(hit >> 32);
+            }
+          }
+        } while (todo);
+      } else if (g < N) {
+        arrivals(g);
+      }
+      PROF(3)
+      bool pf_done = false;
+      const bool deferred = cur.due && quads != 0;
+      if (cur.due && quads == 0) pf_done = finish_iteration(g, cur.it, cur.nd, cur.nc, cur.nj, cur.pk, cur.t32, 0u);
+      const uint64_t done = __ballot(pf_done), later = __ballot(deferred);
+      if (later) {   // queue the servers that have decodes leaving; they are finished after the pass
+        const int slot = nev + __popcll(later & lanes_below());
+        if (deferred) {
+          if (slot < kEvPerWave) { ev_g[slot] = static_cast<uint32_t>(g); ev_q[slot] = quads; }
+          else finish_deferred(g, quads);
+        }
+        nev += __popcll(later);
+        if (nev > kEvPerWave) nev = kEvPerWave;
+      }
       if (lane == 0) {
+        L.bm_due[wi] = cur.due_mask;
+        L.bm_touch[wi] = 0;
         L.bm_comp[wi] = done;
         if (done) L.bm_idle[wi] |= done;
+        const uint64_t nj_word = cur.join_word & ~(cur.due_mask & ~later);
+        if (nj_word != cur.join_word) L.bm_join[wi] = nj_word;
+      }
+      PROF(4)
+    }
+    for (int e = lane; e < nev; e += 64) finish_deferred(static_cast<int>(ev_g[e]), ev_q[e]);
+    // fold this step's per-lane sums into the workgroup tallies
+    {
+      const uint32_t i0 = wave_sum32(lt.iters[0]), i1 = wave_sum32(lt.iters[1]);
+      const uint64_t b0 = wave_sum64(lt.busy[0]), b1 = wave_sum64(lt.busy[1]);
+      if (lane == 0) {
+        if (i0) { lds_add64(&L.tl[kMaxK * kNTally + SIM_G_ITERS_SOLO], i0); lds_add64(&L.tl[kMaxK * kNTally + SIM_G_BUSY_SOLO], b0); }
+        if (i1) { lds_add64(&L.tl[kMaxK * kNTally + SIM_G_ITERS_MIX], i1); lds_add64(&L.tl[kMaxK * kNTally + SIM_G_BUSY_MIX], b1); }
+      }
+#pragma unroll
+      for (int k = 0; k < kMaxK; ++k) {
+        if (k >= K) continue;
+        const uint64_t ts = wave_sum64(lt.tbt_sum[k]);
+        if (lane == 0 && ts) lds_add64(&L.tl[k * kNTally + SIM_T_TBT_SUM], ts);
       }
     }
+    PROF(5)
     __syncthreads();
+    PROF(6)
 
-    // ================= arrivals into the class queues; order of prefill completions =================
+    // ================= arrivals into the class queues; ranks of completions and idle slots =================
     if (tid < K) {
       const int k = tid;
       const uint32_t a = L.acc[k];
@@ -441,8 +649,12 @@ __global__ void __launch_bounds__(1024) gnr_step_kernel(const Params p, const ui
       if (a > take) L.tl[kMaxK * kNTally + SIM_G_OVERFLOW] = 1;
     }
     if (tid < 64) {
-      const uint32_t ncomp = rank_bitmap(L.bm_comp, L.pre, p.nwords);
+      const uint32_t ncomp = rank_bitmap(L.bm_comp, L.pre_c, nwords_m);
       if (tid == 0) L.sc[SC_NCOMP] = static_cast<int32_t>(ncomp);
+    }
+    if (NT == 64 ? tid < 64 : (tid >= 64 && tid < 128)) {
+      const uint32_t nidle = rank_bitmap(L.bm_idle, L.pre, nwords_m);
+      if (lane == 0) L.sc[SC_NIDLE] = static_cast<int32_t>(nidle);
     }
     __syncthreads();
     for (int k = 0; k < K; ++k) {
@@ -454,18 +666,15 @@ __global__ void __launch_bounds__(1024) gnr_step_kernel(const Params p, const ui
       }
     }
     // completed prefills join the decode buffer in ascending server order
-    if (L.sc[SC_NCOMP] > 0) {
+    {
+      const uint32_t ncomp = static_cast<uint32_t>(L.sc[SC_NCOMP]);
       const uint32_t dcount = static_cast<uint32_t>(L.cs[CS_DCOUNT]), dhead = static_cast<uint32_t>(L.cs[CS_DHEAD]);
-      for (int i = 0; i < nper; ++i) {
-        const int g = i * NT + tid;
-        if (g >= M || g >= N) break;
-        const uint64_t word = L.bm_comp[g >> 6];
-        if (!((word >> (g & 63)) & 1ull)) continue;
-        const uint32_t rank = L.pre[g >> 6] + static_cast<uint32_t>(__popcll(word & lanes_below()));
+      for (uint32_t j = tid; j < ncomp; j += NT) {
+        const int g = select_bit(L.bm_comp, L.pre_c, nwords_m, j);
         const uint64_t jw = pf_job[g];
         const int k = static_cast<int>(jw >> 29) & 7;
-        if (dcount + rank < p.dbuf_cap) {
-          uint32_t pos = dhead + dcount + rank;
+        if (dcount + j < p.dbuf_cap) {
+          uint32_t pos = dhead + dcount + j;
           if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
           dring[pos] = jw;
           atomicAdd(&L.cs[CS_QD + k], 1);
@@ -475,229 +684,244 @@ __global__ void __launch_bounds__(1024) gnr_step_kernel(const Params p, const ui
         }
       }
     }
-    __syncthreads();
-    if (tid == 0) {
-      const uint32_t room = p.dbuf_cap - static_cast<uint32_t>(L.cs[CS_DCOUNT]);
-      const uint32_t ncp = static_cast<uint32_t>(L.sc[SC_NCOMP]);
-      L.cs[CS_DCOUNT] += static_cast<int32_t>(ncp < room ? ncp : room);
-    }
+    PROF(7)
 
     // ================= 3. prefill gate =================
-    for (;;) {
-      if (tid < 64) {
-        const uint32_t nidle = rank_bitmap(L.bm_idle, L.pre, p.nwords);
-        if (tid == 0) {
-          // the admission sequence is decided serially on the class counters; servers pick it up by rank
-          int nadm = 0;
-          const int limit = static_cast<int>(nidle) < kAdmChunk ? static_cast<int>(nidle) : kAdmChunk;
-          int qp[kMaxK], xs[kMaxK];
-          uint32_t popped[kMaxK], head[kMaxK];
+    // The m-th waiting request of class k is a candidate; its position in the admission sequence is
+    // the number of candidates that sort before it. Candidates are ranked in parallel; the idle
+    // prefill slot of rank j (ascending server index) takes the candidate of rank j.
+    for (bool first = true;; first = false) {
+      if (!first) {
+        if (tid < 64) {
+          const uint32_t nidle = rank_bitmap(L.bm_idle, L.pre, nwords_m);
+          if (tid == 0) L.sc[SC_NIDLE] = static_cast<int32_t>(nidle);
+        }
+        __syncthreads();
+      }
+      if (p.gate_mode == SIM_GATE_FCFS && first) __syncthreads();   // stamps written above are read below
+      const int nidle = L.sc[SC_NIDLE];
+      const int limit = nidle < kAdmChunk ? nidle : kAdmChunk;
+      int cnt[kMaxK], xs[kMaxK], qp[kMaxK], ncand = 0;
+      uint32_t head[kMaxK];
 #pragma unroll
-          for (int k = 0; k < kMaxK; ++k) {
-            qp[k] = k < K ? L.cs[CS_QP + k] : 0;
-            xs[k] = k < K ? L.cs[CS_X + k] : 0;
-            head[k] = k < K ? static_cast<uint32_t>(L.cs[CS_QHEAD + k]) : 0u;
-            popped[k] = 0;
-            if (k < K) L.sc[SC_QH0 + k] = static_cast<int32_t>(head[k]);
+      for (int k = 0; k < kMaxK; ++k) {
+        qp[k] = k < K ? L.cs[CS_QP + k] : 0;
+        xs[k] = k < K ? L.cs[CS_X + k] : 0;
+        head[k] = k < K ? static_cast<uint32_t>(L.cs[CS_QHEAD + k]) : 0u;
+        const bool eligible = k < K && qp[k] > 0 && (p.gate_mode != SIM_GATE_OCCUPANCY || p.invx[k] > 0.0);
+        cnt[k] = eligible ? (qp[k] < limit ? qp[k] : limit) : 0;
+        ncand += cnt[k];
+      }
+      const int nadm = ncand < limit ? ncand : limit;
+      for (int c = tid; c < ncand; c += NT) {
+        int k = 0, m = c;
+#pragma unroll
+        for (int kk = 0; kk < kMaxK - 1; ++kk)
+          if (k == kk && m >= cnt[kk]) { m -= cnt[kk]; k = kk + 1; }
+        GateKey key = {0.0, 0.0};
+#pragma unroll
+        for (int kk = 0; kk < kMaxK; ++kk)
+          if (k == kk) key = gate_key(p, qring, xs, qp, head, kk, m);
+        int rank = m;
+#pragma unroll
+        for (int k2 = 0; k2 < kMaxK; ++k2) {
+          if (k2 == k || cnt[k2] == 0 || rank >= nadm) continue;
+          int lo = 0, hi = cnt[k2];
+          while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (gate_before(gate_key(p, qring, xs, qp, head, k2, mid), k2, key, k)) lo = mid + 1; else hi = mid;
           }
-          while (nadm < limit) {
-            int best = -1;
-            double bkey = 0.0, bdl = 0.0;
-#pragma unroll
-            for (int k = 0; k < kMaxK; ++k) {
-              if (k >= K || qp[k] <= 0) continue;
-              if (p.gate_mode == SIM_GATE_OCCUPANCY) {
-                if (!(p.invx[k] > 0.0)) continue;
-                const double xi = (static_cast<double>(xs[k]) - p.nx[k]) * p.invx[k];
-                const double dl = static_cast<double>(qp[k]) - p.nq[k];
-                if (best < 0 || xi < bkey || (xi == bkey && dl > bdl)) { best = k; bkey = xi; bdl = dl; }
-              } else if (p.gate_mode == SIM_GATE_PRIORITY) {
-                if (best < 0 || p.prio[k] > bkey) { best = k; bkey = p.prio[k]; }
-              } else {
-                uint32_t pos = head[k] + popped[k];
-                if (pos >= p.queue_cap) pos -= p.queue_cap;
-                const double st = static_cast<double>(qring[static_cast<size_t>(k) * p.queue_cap + pos]);
-                if (best < 0 || st < bkey) { best = k; bkey = st; }
-              }
-            }
-            if (best < 0) break;
-#pragma unroll
-            for (int k = 0; k < kMaxK; ++k)
-              if (k == best) {
-                L.adm[nadm] = static_cast<uint32_t>(k) | (popped[k] << 3);
-                ++popped[k]; --qp[k]; ++xs[k];
-              }
-            ++nadm;
-          }
-          bool waiting = false;
-#pragma unroll
-          for (int k = 0; k < kMaxK; ++k) {
-            if (k >= K) continue;
-            uint32_t h = head[k] + popped[k];
-            if (h >= p.queue_cap) h -= p.queue_cap;
-            L.cs[CS_QHEAD + k] = static_cast<int32_t>(h);
-            L.cs[CS_QP + k] = qp[k];
-            L.cs[CS_X + k] = xs[k];
-            L.tl[k * kNTally + SIM_T_U_P] += popped[k];
-            if (qp[k] > 0 && (p.gate_mode != SIM_GATE_OCCUPANCY || p.invx[k] > 0.0)) waiting = true;
-          }
-          L.sc[SC_NADM] = nadm;
-          L.sc[SC_MORE] = (nadm == kAdmChunk && static_cast<int>(nidle) > kAdmChunk && waiting) ? 1 : 0;
+          rank += lo;
+        }
+        if (rank < nadm) {
+          L.adm[rank] = static_cast<uint32_t>(k) | (static_cast<uint32_t>(m) << 3);
+          atomicAdd(&L.sc[SC_ADMK + k], 1);
         }
       }
+      PROF(14)
       __syncthreads();
-      const int nadm = L.sc[SC_NADM];
-      if (nadm > 0) {
-        for (int i = 0; i < nper; ++i) {
-          const int gw = i * NT + wave_base;
-          if (gw >= M || gw >= N) break;     // wave-uniform: no mixed-group server in this block
-          const int g = gw + lane;
-          bool admitted = false;
-          const uint64_t word = L.bm_idle[gw >> 6];
-          if (g < M && g < N && ((word >> lane) & 1ull)) {
-            const uint32_t rank = L.pre[gw >> 6] + static_cast<uint32_t>(__popcll(word & lanes_below()));
-            if (rank < static_cast<uint32_t>(nadm)) {
-              admitted = true;
-              const uint32_t e = L.adm[rank];
-              const int k = static_cast<int>(e & 7u);
-              uint32_t pos = static_cast<uint32_t>(L.sc[SC_QH0 + k]) + (e >> 3);
-              if (pos >= p.queue_cap) pos -= p.queue_cap;
-              const uint32_t stamp = qring[static_cast<size_t>(k) * p.queue_cap + pos];
-              lds_add64(&L.tl[k * kNTally + SIM_T_WAIT_STEPS], static_cast<uint64_t>(s - stamp));
-              uint32_t w[4];
-              philox4x32_10(p.key0, p.key1, s, 1u, static_cast<uint32_t>(g), static_cast<uint32_t>(r), w);
-              const uint32_t Pl = p.len_tab[(static_cast<size_t>(k) * 2 + 0) * kTableSize + (w[0] >> 16)];
-              const uint32_t Dl = p.len_tab[(static_cast<size_t>(k) * 2 + 1) * kTableSize + (w[1] >> 16)];
-              pf_job[g] = static_cast<uint64_t>(stamp) | (static_cast<uint64_t>(k) << 29) |
-                          (static_cast<uint64_t>(Pl - 1) << 32) | (static_cast<uint64_t>(Dl - 1) << 48);
-              remptok[g] = Pl;   // an idle prefill slot implies that the running iteration holds no chunk
-              const uint64_t nc = n_cls[g];
-              for (int c = 0; c < K; ++c) {   // co-resident decodes switch solo -> mixed
-                const int v = static_cast<int>(byte_at(nc, c));
-                if (v) {
-                  lds_add64(&L.tl[c * kNTally + SIM_T_M_SM], static_cast<uint64_t>(v));
-                  atomicSub(&L.cs[CS_YS + c], v);
-                  atomicAdd(&L.cs[CS_YM + c], v);
-                }
-              }
-              if (!((L.bm_busy[gw >> 6] >> lane) & 1ull)) touched |= 1ull << i;
+      PROF(15)
+      if (first && tid == 0) {   // every thread has read the old count by now: completions are in the buffer
+        const uint32_t room = p.dbuf_cap - static_cast<uint32_t>(L.cs[CS_DCOUNT]);
+        const uint32_t ncp = static_cast<uint32_t>(L.sc[SC_NCOMP]);
+        L.cs[CS_DCOUNT] += static_cast<int32_t>(ncp < room ? ncp : room);
+      }
+      // admission j goes to the idle prefill slot of rank j; one thread per admission
+      for (int j = tid; j < nadm; j += NT) {
+        const int g = select_bit(L.bm_idle, L.pre, nwords_m, static_cast<uint32_t>(j));
+        const uint32_t e = L.adm[j];
+        const int k = static_cast<int>(e & 7u);
+        uint32_t pos = head[0];
+#pragma unroll
+        for (int kk = 1; kk < kMaxK; ++kk) pos = k == kk ? head[kk] : pos;
+        pos += e >> 3;
+        if (pos >= p.queue_cap) pos -= p.queue_cap;
+        const uint32_t stamp = qring[static_cast<size_t>(k) * p.queue_cap + pos];
+        lds_add64(&L.tl[k * kNTally + SIM_T_WAIT_STEPS], static_cast<uint64_t>(s - stamp));
+        uint32_t w[4];
+        philox4x32_10(key0, key1, s, 1u, static_cast<uint32_t>(g), static_cast<uint32_t>(r), w);
+        const uint32_t Pl = p.len_tab[(static_cast<size_t>(k) * 2 + 0) * kTableSize + (w[0] >> 16)];
+        const uint32_t Dl = p.len_tab[(static_cast<size_t>(k) * 2 + 1) * kTableSize + (w[1] >> 16)];
+        pf_job[g] = static_cast<uint64_t>(stamp) | (static_cast<uint64_t>(k) << 29) |
+                    (static_cast<uint64_t>(Pl - 1) << 32) | (static_cast<uint64_t>(Dl - 1) << 48);
+        // an idle prefill slot implies that the running iteration holds no chunk
+        remptok[g] = Pl | (static_cast<uint32_t>(k) << 29);
+        PROF(11)
+        if (L.loads[g]) {
+          const uint64_t nc = n_cls[g];
+          for (int c = 0; c < K; ++c) {   // co-resident decodes switch solo -> mixed
+            const int v = static_cast<int>(byte_at(nc, c));
+            if (v) {
+              lds_add64(&L.tl[c * kNTally + SIM_T_M_SM], static_cast<uint64_t>(v));
+              atomicSub(&L.cs[CS_YS + c], v);
+              atomicAdd(&L.cs[CS_YM + c], v);
             }
           }
-          const uint64_t adm_mask = __ballot(admitted);
-          if (lane == 0 && adm_mask) L.bm_idle[gw >> 6] = word & ~adm_mask;
         }
+        PROF(12)
+        const uint64_t bit = 1ull << (g & 63);
+        atomicAnd(reinterpret_cast<unsigned long long *>(&L.bm_idle[g >> 6]), ~bit);
+        if (!(L.bm_busy[g >> 6] & bit)) atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_touch[g >> 6]), bit);
+        PROF(13)
+      }
+      bool more = false;
+      if (nadm == kAdmChunk && nidle > kAdmChunk) {   // rare: more idle slots than one pass serves
+#pragma unroll
+        for (int k = 0; k < kMaxK; ++k)
+          if (k < K && cnt[k] > 0 && qp[k] - L.sc[SC_ADMK + k] > 0) more = true;
       }
       __syncthreads();
-      if (!L.sc[SC_MORE]) break;
+      if (tid < K) {   // class counters follow the admissions of this pass
+        const int k = tid, a = L.sc[SC_ADMK + k];
+        if (a) {
+          uint32_t h = static_cast<uint32_t>(L.cs[CS_QHEAD + k]) + static_cast<uint32_t>(a);
+          if (h >= p.queue_cap) h -= p.queue_cap;
+          L.cs[CS_QHEAD + k] = static_cast<int32_t>(h);
+          L.cs[CS_QP + k] -= a;
+          L.cs[CS_X + k] += a;
+          L.tl[k * kNTally + SIM_T_U_P] += static_cast<uint64_t>(a);
+          L.sc[SC_ADMK + k] = 0;
+        }
+      }
+      if (!more) break;
+      __syncthreads();
     }
+    PROF(8)
 
     // ================= 4. decode routing =================
-    if (tid == 0) { L.sc[SC_JREM] = L.cs[CS_DCOUNT]; L.sc[SC_NEXT] = 0; L.sc[SC_DHEAD0] = L.cs[CS_DHEAD]; }
-    for (int grp = 0; grp < 2; ++grp) {
-      const int lo = grp == 0 ? M : 0, hi = grp == 0 ? N : M;
-      const int capg = grp == 0 ? B : B - 1;
-      for (;;) {
-        if (tid == 0) L.sc[SC_LMIN] = 255;
-        __syncthreads();
-        if (L.sc[SC_JREM] <= 0 || lo >= hi) break;
-        int lmin = 255;
-        for (int i = 0; i < nper; ++i) {
-          const int g = i * NT + tid;
-          if (g >= lo && g < hi) { const int l = L.loads[g]; if (l < capg && l < lmin) lmin = l; }
+    // Each pass serves the servers at the lowest decode count of the group, in index order; the job
+    // of rank j in the decode buffer goes to the j-th of them. Every wave derives the pass parameters
+    // from the load histogram, so no thread has to broadcast them.
+    {
+      int jrem = L.cs[CS_DCOUNT], next = 0;
+      const uint32_t dhead0 = static_cast<uint32_t>(L.cs[CS_DHEAD]);
+      for (int grp = 0; grp < 2 && jrem > 0; ++grp) {
+        const int lo = grp == 0 ? M : 0, hi = grp == 0 ? N : M;
+        const int capg = grp == 0 ? B : B - 1;
+        if (lo >= hi) continue;
+        for (;;) {
+          if (jrem <= 0) break;
+          // lowest non-empty level below the cap, and the number of servers on it
+          int level = -1, cnt = 0;
+          for (int base = 0; base < capg && level < 0; base += 64) {
+            const int l = base + lane;
+            const uint32_t c = l < capg ? L.lh[grp * kLoadBins + l] : 0u;
+            const uint64_t nz = __ballot(c != 0);
+            if (nz) {
+              const int first = __ffsll(static_cast<long long>(nz)) - 1;
+              level = base + first;
+              cnt = static_cast<int>(__builtin_amdgcn_readlane(c, first));
+            }
+          }
+          if (level < 0) break;
+          const int take = cnt < jrem ? cnt : jrem;
+          for (int i = 0; i < nper; ++i) {
+            const int gw = i * NT + wave_base;
+            if (gw >= N) break;
+            const int g = gw + lane;
+            const bool at_level = g >= lo && g < hi && L.loads[g] == level;
+            const uint64_t b = __ballot(at_level);
+            if (lane == 0) L.bm_lvl[gw >> 6] = b;
+          }
+          __syncthreads();
+          if (tid < 64) rank_bitmap(L.bm_lvl, L.pre, p.nwords);
+          __syncthreads();
+          for (int j = tid; j < take; j += NT) {
+            const int g = select_bit(L.bm_lvl, L.pre, p.nwords, static_cast<uint32_t>(j));
+            uint32_t pos = dhead0 + static_cast<uint32_t>(next + j);
+            if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
+            if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
+            const uint64_t jw = dring[pos];
+            const int k = static_cast<int>(jw >> 29) & 7;
+            const uint32_t Dl = static_cast<uint32_t>(jw >> 48) + 1;
+            const uint64_t bit = 1ull << (g & 63);
+            const bool busy = L.bm_busy[g >> 6] & bit;
+            const bool mid = busy && !(L.bm_due[g >> 6] & bit);   // joins at the next restart
+            const int nd = level;
+            fin[static_cast<size_t>(g) * BS + nd] = L.iter[g] + Dl + (mid ? 1u : 0u);
+            job[static_cast<size_t>(g) * BS + nd] = jw;
+            n_cls[g] += 1ull << (8 * k);
+            if (mid) {
+              n_join[g] += 1ull << (8 * k);
+              atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_join[g >> 6]), bit);
+            }
+            L.loads[g] = static_cast<uint8_t>(nd + 1);
+            const bool has_prefill = g < M && pk_rem(remptok[g]) != 0;
+            lds_add64(&L.tl[k * kNTally + (has_prefill ? SIM_T_U_DM : SIM_T_U_DS)], 1);
+            atomicAdd(&L.cs[(has_prefill ? CS_YM : CS_YS) + k], 1);
+            atomicSub(&L.cs[CS_QD + k], 1);
+            if (!busy) atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_touch[g >> 6]), bit);
+          }
+          __syncthreads();
+          if (tid == 0) {   // `take` servers moved up one level
+            L.lh[grp * kLoadBins + level] -= static_cast<uint32_t>(take);
+            L.lh[grp * kLoadBins + level + 1] += static_cast<uint32_t>(take);
+          }
+          jrem -= take;
+          next += take;
+          __syncthreads();
         }
-        for (int d = 32; d > 0; d >>= 1) { const int o = __shfl_xor(lmin, d, 64); lmin = o < lmin ? o : lmin; }
-        if (lane == 0 && lmin < 255) atomicMin(&L.sc[SC_LMIN], lmin);
-        __syncthreads();
-        const int level = L.sc[SC_LMIN];
-        if (level == 255) break;
-        for (int i = 0; i < nper; ++i) {
-          const int gw = i * NT + wave_base;
-          if (gw >= N) break;
-          const int g = gw + lane;
-          const bool at_level = g >= lo && g < hi && L.loads[g] == level;
-          const uint64_t b = __ballot(at_level);
-          if (lane == 0) L.bm_lvl[gw >> 6] = b;
-        }
-        __syncthreads();
-        if (tid < 64) {
-          const uint32_t cnt = rank_bitmap(L.bm_lvl, L.pre, p.nwords);
-          if (tid == 0) L.sc[SC_CNT] = static_cast<int32_t>(cnt);
-        }
-        __syncthreads();
-        const int jrem = L.sc[SC_JREM], next = L.sc[SC_NEXT];
-        const int take = L.sc[SC_CNT] < jrem ? L.sc[SC_CNT] : jrem;
-        const uint32_t dhead0 = static_cast<uint32_t>(L.sc[SC_DHEAD0]);
-        for (int i = 0; i < nper; ++i) {
-          const int g = i * NT + tid;
-          if (g >= N) break;
-          if (g < lo || g >= hi) continue;
-          const uint64_t word = L.bm_lvl[g >> 6];
-          if (!((word >> (g & 63)) & 1ull)) continue;
-          const uint32_t rank = L.pre[g >> 6] + static_cast<uint32_t>(__popcll(word & lanes_below()));
-          if (rank >= static_cast<uint32_t>(take)) continue;
-          uint32_t pos = dhead0 + static_cast<uint32_t>(next) + rank;
-          if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
-          if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
-          const uint64_t jw = dring[pos];
-          const int k = static_cast<int>(jw >> 29) & 7;
-          const uint32_t Dl = static_cast<uint32_t>(jw >> 48) + 1;
-          const bool busy = (L.bm_busy[g >> 6] >> (g & 63)) & 1ull;
-          const bool mid = busy && !((at_boundary >> i) & 1ull);   // joins at the next restart
-          const int nd = L.loads[g];
-          fin[static_cast<size_t>(g) * BS + nd] = iter[g] + Dl + (mid ? 1u : 0u);
-          job[static_cast<size_t>(g) * BS + nd] = jw;
-          n_cls[g] += 1ull << (8 * k);
-          if (mid) n_join[g] += 1ull << (8 * k);
-          L.loads[g] = static_cast<uint8_t>(nd + 1);
-          const bool has_prefill = g < M && (remptok[g] & 0xFFFFu) != 0;
-          lds_add64(&L.tl[k * kNTally + (has_prefill ? SIM_T_U_DM : SIM_T_U_DS)], 1);
-          atomicAdd(&L.cs[(has_prefill ? CS_YM : CS_YS) + k], 1);
-          atomicSub(&L.cs[CS_QD + k], 1);
-          if (!busy) touched |= 1ull << i;
-        }
-        __syncthreads();
-        if (tid == 0) { L.sc[SC_JREM] = jrem - take; L.sc[SC_NEXT] = next + take; }
+      }
+      if (tid == 0 && next > 0) {
+        uint32_t h = dhead0 + static_cast<uint32_t>(next);
+        if (h >= p.dbuf_cap) h -= p.dbuf_cap;
+        L.cs[CS_DHEAD] = static_cast<int32_t>(h);
+        L.cs[CS_DCOUNT] -= next;
       }
     }
-    __syncthreads();
-    if (tid == 0) {
-      const uint32_t routed = static_cast<uint32_t>(L.sc[SC_NEXT]);
-      uint32_t h = static_cast<uint32_t>(L.cs[CS_DHEAD]) + routed;
-      if (h >= p.dbuf_cap) h -= p.dbuf_cap;
-      L.cs[CS_DHEAD] = static_cast<int32_t>(h);
-      L.cs[CS_DCOUNT] -= static_cast<int32_t>(routed);
-    }
+    PROF(9)
 
     // ================= 5. (re)start =================
-    {
-      const uint64_t todo = at_boundary | touched;
-      for (int i = 0; i < nper; ++i) {
-        const int gw = i * NT + wave_base;
-        if (gw >= N) break;
-        const bool mine = (todo >> i) & 1ull;
-        if (__ballot(mine) == 0) continue;
-        const int g = gw + lane;
-        const uint64_t busy_word = L.bm_busy[gw >> 6];
-        bool busy = (busy_word >> lane) & 1ull;
-        if (mine) {
-          const int rem = g < M ? static_cast<int>(remptok[g] & 0xFFFFu) : 0;
-          const int ptok = rem > 0 ? (rem < p.C ? rem : p.C) : 0;
-          const int n = L.loads[g];
-          if (ptok == 0 && n == 0) {
-            busy = false;
-          } else {
-            // back-to-back after a completion, otherwise from the step boundary
-            const int64_t base = ((at_boundary >> i) & 1ull) ? T + static_cast<int64_t>(static_cast<int32_t>(L.t32[g] - T32)) : T;
-            const int64_t tn = base + p.c0 + p.cpre * ptok + p.cdec * static_cast<int64_t>(n);
-            L.t32[g] = static_cast<uint32_t>(tn);
-            busy = true;
-            if (ptok > 0) remptok[g] = static_cast<uint32_t>(rem) | (static_cast<uint32_t>(ptok) << 16);
-          }
+    for (int i = 0; i < nper; ++i) {
+      const int gw = i * NT + wave_base;
+      if (gw >= N) break;
+      const int wi = gw >> 6;
+      const uint64_t due_word = L.bm_due[wi];
+      const uint64_t todo = due_word | L.bm_touch[wi];
+      if (todo == 0) continue;
+      const int g = gw + lane;
+      const uint64_t busy_word = L.bm_busy[wi];
+      bool busy = (busy_word >> lane) & 1ull;
+      if ((todo >> lane) & 1ull) {
+        const uint32_t pk = g < M ? remptok[g] : 0u;
+        const int rem = pk_rem(pk);
+        const int ptok = rem > 0 ? (rem < p.C ? rem : p.C) : 0;
+        const int n = L.loads[g];
+        if (ptok == 0 && n == 0) {
+          busy = false;
+        } else {
+          // back-to-back after a completion, otherwise from the step boundary
+          const int64_t base = ((due_word >> lane) & 1ull) ? T + static_cast<int64_t>(static_cast<int32_t>(L.t32[g] - T32)) : T;
+          const int64_t tn = base + p.c0 + p.cpre * ptok + p.cdec * static_cast<int64_t>(n);
+          L.t32[g] = static_cast<uint32_t>(tn);
+          busy = true;
+          if (ptok > 0) remptok[g] = pk | (static_cast<uint32_t>(ptok) << 16);
         }
-        const uint64_t nb = __ballot(busy);
-        if (lane == 0 && nb != busy_word) L.bm_busy[gw >> 6] = nb;
       }
+      const uint64_t nb = __ballot(busy);
+      if (lane == 0 && nb != busy_word) L.bm_busy[wi] = nb;
     }
+    PROF(10)
 
     // ================= 6. end-of-step occupancy integrals =================
     if (tid < K) {
@@ -710,30 +934,20 @@ __global__ void __launch_bounds__(1024) gnr_step_kernel(const Params p, const ui
     }
     if (tid == 0) L.tl[kMaxK * kNTally + SIM_G_STEPS] += 1;
   }
-  __syncthreads();
+  PROF_FLUSH
 
-  // ---- fold the per-lane sums into the workgroup's tallies
-  {
+  // ---- write out the cached time-between-tokens counts; the emitted-token tally is their total
 #pragma unroll
-    for (int kind = 0; kind < 2; ++kind) {
-      const uint64_t it = wave_sum64(lt.iters[kind]), bz = wave_sum64(lt.busy[kind]);
-      if (lane == 0) {
-        lds_add64(&L.tl[kMaxK * kNTally + (kind ? SIM_G_ITERS_MIX : SIM_G_ITERS_SOLO)], it);
-        lds_add64(&L.tl[kMaxK * kNTally + (kind ? SIM_G_BUSY_MIX : SIM_G_BUSY_SOLO)], bz);
-      }
-#pragma unroll
-      for (int k = 0; k < kMaxK; ++k)
-        if (k < K && lt.hist_cnt[kind][k]) lds_add64(&L.tbth[k * p.tbt_w + lt.hist_bin[kind]], lt.hist_cnt[kind][k]);
-    }
-#pragma unroll
-    for (int k = 0; k < kMaxK; ++k) {
-      if (k >= K) continue;
-      const uint64_t te = wave_sum64(lt.tok_emit[k]), ts = wave_sum64(lt.tbt_sum[k]);
-      if (lane == 0) {
-        lds_add64(&L.tl[k * kNTally + SIM_T_TOK_EMIT], te);
-        lds_add64(&L.tl[k * kNTally + SIM_T_TBT_SUM], ts);
-      }
-    }
+  for (int k = 0; k < kMaxK; ++k) {
+    if (k >= K) continue;
+    if (lt.hist_cnt[0][k]) lds_add64(&L.tbth[k * p.tbt_w + lt.hist_bin[0]], lt.hist_cnt[0][k]);
+    if (lt.hist_cnt[1][k]) lds_add64(&L.tbth[k * p.tbt_w + lt.hist_bin[1]], lt.hist_cnt[1][k]);
+  }
+  __syncthreads();
+  if (tid < K) {
+    uint64_t tot = 0;
+    for (int b = 0; b < p.tbt_w; ++b) tot += L.tbth[tid * p.tbt_w + b];
+    L.tl[tid * kNTally + SIM_T_TOK_EMIT] += tot;
   }
   __syncthreads();
 
@@ -743,6 +957,7 @@ __global__ void __launch_bounds__(1024) gnr_step_kernel(const Params p, const ui
     if (g >= N) break;
     const bool busy = (L.bm_busy[g >> 6] >> (g & 63)) & 1ull;
     t_next[g] = busy ? T + static_cast<int64_t>(static_cast<int32_t>(L.t32[g] - static_cast<uint32_t>(T))) : kIdle;
+    iter_g[g] = L.iter[g];
   }
   for (int i = tid; i < CS_WORDS; i += NT) p.cstate[static_cast<size_t>(r) * CS_WORDS + i] = L.cs[i];
   uint64_t *gt = p.tally + static_cast<size_t>(r) * kTallyWords;
@@ -840,11 +1055,12 @@ __global__ void gnr_digest_kernel(const Params p)
     const size_t sg = static_cast<size_t>(r) * N + g;
     const uint32_t pk = p.remptok[sg];
     const uint32_t rem = pk & 0xFFFFu;
+    const uint32_t ptok = (pk >> 16) & 0x1FFFu;
     uint64_t h = chain(4, static_cast<uint64_t>(g));
     h = chain(h, static_cast<uint64_t>(p.t_next[sg]));
     h = chain(h, p.iter[sg]);
     h = chain(h, rem);
-    h = chain(h, pk >> 16);
+    h = chain(h, ptok);
     h = chain(h, rem ? p.pf_job[sg] : 0ull);
     h = chain(h, p.n_cls[sg]);
     h = chain(h, p.n_join[sg]);
@@ -870,13 +1086,14 @@ int launch_reset(const Params &p, int reps, void *stream)
 int launch_steps(const Params &p, int reps, int threads, size_t lds_bytes, uint32_t step_begin, uint32_t n_steps,
                  void *stream)
 {
+  auto kernel = threads > 512 ? gnr_step_kernel<1024> : gnr_step_kernel<512>;
   if (lds_bytes > 64 * 1024) {   // more than the default dynamic LDS limit has to be asked for
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gnr_step_kernel),
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes));
     if (e != hipSuccess) return SIM_EHIP;
   }
-  hipLaunchKernelGGL(gnr_step_kernel, dim3(reps), dim3(threads), lds_bytes, static_cast<hipStream_t>(stream), p,
-                     step_begin, n_steps);
+  hipLaunchKernelGGL(kernel, dim3(reps), dim3(threads), lds_bytes, static_cast<hipStream_t>(stream), p.self, p.key0,
+                     p.key1, step_begin, n_steps);
   return hip_ok(hipGetLastError());
 }
 
@@ -886,6 +1103,18 @@ int launch_reduce(const Params &p, int reps, void *stream)
   hipLaunchKernelGGL(gnr_reduce_kernel, dim3((n + 255) / 256), dim3(256), 0, static_cast<hipStream_t>(stream), p, reps);
   return hip_ok(hipGetLastError());
 }
+
+#ifdef GNR_PROF
+extern "C" int gnr_prof_read(unsigned long long *out16, int reset)
+{
+  if (hipMemcpyFromSymbol(out16, HIP_SYMBOL(g_prof), sizeof(unsigned long long) * 16) != hipSuccess) return SIM_EHIP;
+  if (reset) {
+    unsigned long long z[16] = {0};
+    if (hipMemcpyToSymbol(HIP_SYMBOL(g_prof), z, sizeof z) != hipSuccess) return SIM_EHIP;
+  }
+  return SIM_OK;
+}
+#endif
 
 int launch_digest(const Params &p, int reps, void *stream)
 {
