@@ -187,10 +187,11 @@ size_t step_lds_bytes(const Params &p)
 int step_threads(int N)
 {
   int t = (N + 63) / 64 * 64;
+  // 512 threads leave each wave 256 registers; with 1024 the step kernel spills to scratch
 #ifdef GNR_MAX_THREADS
   return t > GNR_MAX_THREADS ? GNR_MAX_THREADS : t;
 #else
-  return t > 1024 ? 1024 : t;
+  return t > 512 ? 512 : t;
 #endif
 }
 
@@ -228,38 +229,83 @@ __device__ __forceinline__ uint32_t wave_sum32(uint32_t v)
 
 // Per-lane sums of the tallies every executed iteration touches. The step sums are folded into
 // the workgroup's totals once per step; the time-between-tokens counts stay cached per lane for
-// the bin they fall in and are written out when the bin changes or the launch ends.
+// the bin they fall in and are written out when the bin changes or the launch ends. Three bins are
+// cached because a lane's servers have three typical durations: solo group, mixed group without
+// and with a prefill chunk.
 struct LaneTallies {
   uint32_t iters[2];            // this step: [decode-only, with a prefill chunk]
   uint64_t busy[2];
   uint64_t tbt_sum[kMaxK];
-  int hist_bin[2];              // across steps: time-between-tokens bin being accumulated, by iteration kind
-  uint32_t hist_cnt[2][kMaxK];
+  int hist_bin[3];              // across steps: [solo group, mixed group decode-only, with a chunk]
+  uint32_t hist_cnt[3][kMaxK];
 };
 
 // One executed iteration of duration d whose batch held the decodes nc minus the late joiners nj.
-template <int KIND>
+template <int SLOT>
 __device__ __forceinline__ void tally_iteration(LaneTallies &lt, uint64_t *tbth, int tbt_w, int K, int64_t d, int tb,
                                                 uint64_t nc, uint64_t nj)
 {
+  constexpr int KIND = SLOT == 2 ? 1 : 0;
   lt.iters[KIND] += 1;
   lt.busy[KIND] += static_cast<uint64_t>(d);
-  if (tb != lt.hist_bin[KIND]) {   // the duration moved to another bin: flush the cached counts
+  if (tb != lt.hist_bin[SLOT]) {   // the duration moved to another bin: flush the cached counts
 #pragma unroll
     for (int k = 0; k < kMaxK; ++k)
-      if (k < K && lt.hist_cnt[KIND][k]) {
-        lds_add64(&tbth[k * tbt_w + lt.hist_bin[KIND]], lt.hist_cnt[KIND][k]);
-        lt.hist_cnt[KIND][k] = 0;
+      if (k < K && lt.hist_cnt[SLOT][k]) {
+        lds_add64(&tbth[k * tbt_w + lt.hist_bin[SLOT]], lt.hist_cnt[SLOT][k]);
+        lt.hist_cnt[SLOT][k] = 0;
       }
-    lt.hist_bin[KIND] = tb;
+    lt.hist_bin[SLOT] = tb;
   }
 #pragma unroll
   for (int k = 0; k < kMaxK; ++k) {
     const uint32_t em = byte_at(nc, k) - byte_at(nj, k);
     lt.tbt_sum[k] += static_cast<uint64_t>(em) * static_cast<uint64_t>(d);
-    lt.hist_cnt[KIND][k] += em;
+    lt.hist_cnt[SLOT][k] += em;
   }
 }
+
+// ---- wave-level folding of per-event class updates: lanes of one class are combined first, so that a
+// counter sees one LDS atomic per wave and class instead of one per event. All take uniform control flow.
+__device__ __forceinline__ void wave_count_by_class(bool active, int k, int K, uint64_t *base, int stride)
+{
+  for (int c = 0; c < K; ++c) {
+    const uint64_t m = __ballot(active && k == c);
+    if (m && (threadIdx.x & 63) == 0) lds_add64(&base[c * stride], static_cast<uint64_t>(__popcll(m)));
+  }
+}
+__device__ __forceinline__ void wave_count_by_class_i32(bool active, int k, int K, int32_t *base, int sign)
+{
+  for (int c = 0; c < K; ++c) {
+    const uint64_t m = __ballot(active && k == c);
+    if (m && (threadIdx.x & 63) == 0) atomicAdd(&base[c], sign * __popcll(m));
+  }
+}
+__device__ __forceinline__ void wave_sum_by_class(bool active, int k, int K, uint64_t v, uint64_t *base, int stride)
+{
+  for (int c = 0; c < K; ++c) {
+    const bool in = active && k == c;
+    if (__ballot(in)) {
+      const uint64_t t = wave_sum64(in ? v : 0ull);
+      if ((threadIdx.x & 63) == 0) lds_add64(&base[c * stride], t);
+    }
+  }
+}
+// Sum over the wave of per-class byte vectors (8 x uint8, each <= 128): 16-bit fields, even and odd classes.
+__device__ __forceinline__ void wave_sum_bytes(uint64_t v, uint64_t &even, uint64_t &odd)
+{
+  even = wave_sum64(v & 0x00FF00FF00FF00FFull);
+  odd = wave_sum64((v >> 8) & 0x00FF00FF00FF00FFull);
+}
+__device__ __forceinline__ uint32_t class_field(uint64_t even, uint64_t odd, int c)
+{
+  return static_cast<uint32_t>(((c & 1) ? odd : even) >> (16 * (c >> 1))) & 0xFFFFu;
+}
+
+// What finishing an iteration reports back for folding: the first decode that left the server and
+// the end of its prefill. Further decodes leaving in the same iteration are tallied directly.
+struct Leaving { int k; uint32_t P, D; int64_t e2e; bool mixed; };
+struct PrefillEnd { bool done; int k; uint32_t P; int64_t ttft; uint64_t nc; };
 
 // Sort key of a gate candidate: the m-th waiting request of class k (m counted from the head).
 // Occupancy gate: (X_k + m - n x_k*)/x_k*, ties by the larger queue deviation Q_k - m - n q_k*;
@@ -367,9 +413,9 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
     if (lane == 0 && wi < p.nwords) { L.bm_idle[wi] = bi; L.bm_busy[wi] = bb; L.bm_join[wi] = bj; }
   }
   LaneTallies lt;
-  lt.hist_bin[0] = lt.hist_bin[1] = 0;
+  lt.hist_bin[0] = lt.hist_bin[1] = lt.hist_bin[2] = 0;
 #pragma unroll
-  for (int k = 0; k < kMaxK; ++k) lt.hist_cnt[0][k] = lt.hist_cnt[1][k] = 0;
+  for (int k = 0; k < kMaxK; ++k) lt.hist_cnt[0][k] = lt.hist_cnt[1][k] = lt.hist_cnt[2][k] = 0;
   __syncthreads();
 
   int64_t T = 0;
@@ -404,17 +450,27 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
     };
 
     // ---- 2. finishing the iteration of server g: tallies, decodes that emitted their last token
-    //      (slot quads flagged in `quads`), prefill progress. Returns true if the prefill completed.
+    //      (slot quads flagged in `quads`), prefill progress. Class-level effects of the first decode
+    //      that leaves and of a prefill that ends are reported in lv / pe for folding by the caller.
+    auto leave_direct = [&](int k, uint32_t Pl, uint32_t Dl, int64_t e2e, bool mixed_now) __attribute__((always_inline)) {
+      lds_add64(&L.tl[k * kNTally + (mixed_now ? SIM_T_S_DM : SIM_T_S_DS)], 1);
+      atomicSub(&L.cs[(mixed_now ? CS_YM : CS_YS) + k], 1);
+      lds_add64(&L.tl[k * kNTally + SIM_T_TOKP_DEC], Pl);
+      lds_add64(&L.tl[k * kNTally + SIM_T_TOKD_DEC], Dl);
+      lds_add64(&L.tl[k * kNTally + SIM_T_E2E_SUM], static_cast<uint64_t>(e2e));
+    };
     auto finish_iteration = [&](int g, uint32_t it, int nd, uint64_t nc, uint64_t nj, uint32_t pk, uint32_t t32,
-                                uint32_t quads) __attribute__((always_inline)) -> bool {
+                                uint32_t quads, Leaving &lv, PrefillEnd &pe) __attribute__((always_inline)) {
       int rem = pk_rem(pk);
       const int ptok = pk_ptok(pk);
       const int64_t tn = T + static_cast<int64_t>(static_cast<int32_t>(t32 - T32));   // exact completion time
       const int64_t d = p.c0 + p.cpre * ptok + p.cdec * static_cast<int64_t>(nd - static_cast<int>(byte_sum(nj)));
       const int tb = hbin(d) - p.tbt_lo;
-      if (ptok > 0) tally_iteration<1>(lt, L.tbth, p.tbt_w, K, d, tb, nc, nj);
-      else tally_iteration<0>(lt, L.tbth, p.tbt_w, K, d, tb, nc, nj);
-      bool pf_done = false;
+      if (g >= M) tally_iteration<0>(lt, L.tbth, p.tbt_w, K, d, tb, nc, nj);
+      else if (ptok == 0) tally_iteration<1>(lt, L.tbth, p.tbt_w, K, d, tb, nc, nj);
+      else tally_iteration<2>(lt, L.tbth, p.tbt_w, K, d, tb, nc, nj);
+      lv.k = -1;
+      pe.done = false;
       const bool mixed_now = rem > 0;
       const int nd_before = nd;
       if (quads) {
@@ -434,12 +490,9 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
               const int k = static_cast<int>(jw >> 29) & 7;
               const uint32_t stamp = static_cast<uint32_t>(jw) & 0x1FFFFFFFu;
               const uint32_t Pl = (static_cast<uint32_t>(jw >> 32) & 0xFFFFu) + 1, Dl = static_cast<uint32_t>(jw >> 48) + 1;
-              lds_add64(&L.tl[k * kNTally + (mixed_now ? SIM_T_S_DM : SIM_T_S_DS)], 1);
-              atomicSub(&L.cs[(mixed_now ? CS_YM : CS_YS) + k], 1);
-              lds_add64(&L.tl[k * kNTally + SIM_T_TOKP_DEC], Pl);
-              lds_add64(&L.tl[k * kNTally + SIM_T_TOKD_DEC], Dl);
               const int64_t e2e = tn - (static_cast<int64_t>(stamp) + 1) * p.dt;
-              lds_add64(&L.tl[k * kNTally + SIM_T_E2E_SUM], static_cast<uint64_t>(e2e));
+              if (lv.k < 0) { lv.k = k; lv.P = Pl; lv.D = Dl; lv.e2e = e2e; lv.mixed = mixed_now; }
+              else leave_direct(k, Pl, Dl, e2e, mixed_now);
               atomicAdd(reinterpret_cast<unsigned long long *>(&hist[(1 * K + k) * kNBin + hbin(e2e)]), 1ull);
               nc -= 1ull << (8 * k);
               --nd;
@@ -458,43 +511,80 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
       // the prefill advances by the chunk frozen at the start of the iteration
       if (ptok > 0) {
         const int k = pk_cls(pk);
-        lds_add64(&L.tl[k * kNTally + SIM_T_TOK_PREF], static_cast<uint64_t>(ptok));
         rem -= ptok;
         if (rem == 0) {
-          pf_done = true;
           const uint64_t jw = pf_job[g];
           const uint32_t stamp = static_cast<uint32_t>(jw) & 0x1FFFFFFFu;
-          const uint32_t Pl = (static_cast<uint32_t>(jw >> 32) & 0xFFFFu) + 1;
-          lds_add64(&L.tl[k * kNTally + SIM_T_S_P], 1);
-          atomicSub(&L.cs[CS_X + k], 1);
-          lds_add64(&L.tl[k * kNTally + SIM_T_TOKP_PRE], Pl);
-          const int64_t ttft = tn - (static_cast<int64_t>(stamp) + 1) * p.dt;
-          lds_add64(&L.tl[k * kNTally + SIM_T_TTFT_SUM], static_cast<uint64_t>(ttft));
-          atomicAdd(reinterpret_cast<unsigned long long *>(&hist[(0 * K + k) * kNBin + hbin(ttft)]), 1ull);
-          for (int c = 0; c < K; ++c) {   // co-resident decodes switch mixed -> solo
-            const int v = static_cast<int>(byte_at(nc, c));
-            if (v) {
-              lds_add64(&L.tl[c * kNTally + SIM_T_M_MS], static_cast<uint64_t>(v));
-              atomicSub(&L.cs[CS_YM + c], v);
-              atomicAdd(&L.cs[CS_YS + c], v);
-            }
-          }
+          pe.done = true; pe.k = k; pe.nc = nc;
+          pe.P = (static_cast<uint32_t>(jw >> 32) & 0xFFFFu) + 1;
+          pe.ttft = tn - (static_cast<int64_t>(stamp) + 1) * p.dt;
+          atomicAdd(reinterpret_cast<unsigned long long *>(&hist[(0 * K + k) * kNBin + hbin(pe.ttft)]), 1ull);
         }
         // running chunk cleared; it is set again at the restart
         remptok[g] = static_cast<uint32_t>(rem) | (static_cast<uint32_t>(k) << 29);
       }
       if (nj) n_join[g] = 0;
-      return pf_done;
+    };
+    // class-level effects of the decodes that left (one per lane), folded over the wave
+    auto fold_leaving = [&](const Leaving &lv) __attribute__((always_inline)) {
+      const bool any = lv.k >= 0;
+      if (__ballot(any) == 0) return;
+      const bool am = any && lv.mixed, as = any && !lv.mixed;
+      wave_count_by_class(am, lv.k, K, &L.tl[SIM_T_S_DM], kNTally);
+      wave_count_by_class(as, lv.k, K, &L.tl[SIM_T_S_DS], kNTally);
+      wave_count_by_class_i32(am, lv.k, K, &L.cs[CS_YM], -1);
+      wave_count_by_class_i32(as, lv.k, K, &L.cs[CS_YS], -1);
+      wave_sum_by_class(any, lv.k, K, lv.P, &L.tl[SIM_T_TOKP_DEC], kNTally);
+      wave_sum_by_class(any, lv.k, K, lv.D, &L.tl[SIM_T_TOKD_DEC], kNTally);
+      wave_sum_by_class(any, lv.k, K, static_cast<uint64_t>(lv.e2e), &L.tl[SIM_T_E2E_SUM], kNTally);
+    };
+    // class-level effects of the prefills that ended: completion counts, recognised prompt tokens,
+    // time to first token; the co-resident decodes switch mixed -> solo
+    auto fold_prefill_end = [&](const PrefillEnd &pe) __attribute__((always_inline)) {
+      if (__ballot(pe.done) == 0) return;
+      wave_count_by_class(pe.done, pe.k, K, &L.tl[SIM_T_S_P], kNTally);
+      wave_count_by_class_i32(pe.done, pe.k, K, &L.cs[CS_X], -1);
+      wave_sum_by_class(pe.done, pe.k, K, pe.P, &L.tl[SIM_T_TOKP_PRE], kNTally);
+      wave_sum_by_class(pe.done, pe.k, K, static_cast<uint64_t>(pe.ttft), &L.tl[SIM_T_TTFT_SUM], kNTally);
+      uint64_t even, odd;
+      wave_sum_bytes(pe.done ? pe.nc : 0ull, even, odd);
+      if (lane == 0)
+        for (int c = 0; c < K; ++c) {
+          const int v = static_cast<int>(class_field(even, odd, c));
+          if (v) {
+            lds_add64(&L.tl[c * kNTally + SIM_T_M_MS], static_cast<uint64_t>(v));
+            atomicSub(&L.cs[CS_YM + c], v);
+            atomicAdd(&L.cs[CS_YS + c], v);
+          }
+        }
+    };
+    // the same effects for a single server, without folding (divergent callers)
+    auto commit_direct = [&](const Leaving &lv, const PrefillEnd &pe) __attribute__((always_inline)) {
+      if (lv.k >= 0) leave_direct(lv.k, lv.P, lv.D, lv.e2e, lv.mixed);
+      if (pe.done) {
+        lds_add64(&L.tl[pe.k * kNTally + SIM_T_S_P], 1);
+        atomicSub(&L.cs[CS_X + pe.k], 1);
+        lds_add64(&L.tl[pe.k * kNTally + SIM_T_TOKP_PRE], pe.P);
+        lds_add64(&L.tl[pe.k * kNTally + SIM_T_TTFT_SUM], static_cast<uint64_t>(pe.ttft));
+        for (int c = 0; c < K; ++c) {
+          const int v = static_cast<int>(byte_at(pe.nc, c));
+          if (v) {
+            lds_add64(&L.tl[c * kNTally + SIM_T_M_MS], static_cast<uint64_t>(v));
+            atomicSub(&L.cs[CS_YM + c], v);
+            atomicAdd(&L.cs[CS_YS + c], v);
+          }
+        }
+      }
     };
 
     // a server whose finishing was put off because decodes leave it: reload its record and finish it
-    auto finish_deferred = [&](int g, uint32_t quads) __attribute__((always_inline)) {
+    auto finish_deferred = [&](int g, uint32_t quads, Leaving &lv, PrefillEnd &pe) __attribute__((always_inline)) {
       const uint64_t nc = n_cls[g];
       const bool joined = (L.bm_join[g >> 6] >> (g & 63)) & 1ull;
       const uint64_t nj = joined ? n_join[g] : 0ull;
       const uint32_t pk = g < M ? remptok[g] : 0u;
-      const bool pf = finish_iteration(g, L.iter[g], L.loads[g], nc, nj, pk, L.t32[g], quads);
-      if (pf) {
+      finish_iteration(g, L.iter[g], L.loads[g], nc, nj, pk, L.t32[g], quads, lv, pe);
+      if (pe.done) {
         atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_comp[g >> 6]), 1ull << (g & 63));
         atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_idle[g >> 6]), 1ull << (g & 63));
       }
@@ -590,15 +680,17 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
         arrivals(g);
       }
       PROF(3)
-      bool pf_done = false;
       const bool deferred = cur.due && quads != 0;
-      if (cur.due && quads == 0) pf_done = finish_iteration(g, cur.it, cur.nd, cur.nc, cur.nj, cur.pk, cur.t32, 0u);
-      const uint64_t done = __ballot(pf_done), later = __ballot(deferred);
+      Leaving lv; lv.k = -1;
+      PrefillEnd pe; pe.done = false;
+      if (cur.due && quads == 0) finish_iteration(g, cur.it, cur.nd, cur.nc, cur.nj, cur.pk, cur.t32, 0u, lv, pe);
+      fold_prefill_end(pe);
+      const uint64_t done = __ballot(pe.done), later = __ballot(deferred);
       if (later) {   // queue the servers that have decodes leaving; they are finished after the pass
         const int slot = nev + __popcll(later & lanes_below());
         if (deferred) {
           if (slot < kEvPerWave) { ev_g[slot] = static_cast<uint32_t>(g); ev_q[slot] = quads; }
-          else finish_deferred(g, quads);
+          else { Leaving l2; PrefillEnd p2; finish_deferred(g, quads, l2, p2); commit_direct(l2, p2); }
         }
         nev += __popcll(later);
         if (nev > kEvPerWave) nev = kEvPerWave;
@@ -613,7 +705,14 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
       }
       PROF(4)
     }
-    for (int e = lane; e < nev; e += 64) finish_deferred(static_cast<int>(ev_g[e]), ev_q[e]);
+    for (int e0 = 0; e0 < nev; e0 += 64) {   // the queued servers, one per lane
+      const int e = e0 + lane;
+      Leaving lv; lv.k = -1;
+      PrefillEnd pe; pe.done = false;
+      if (e < nev) finish_deferred(static_cast<int>(ev_g[e]), ev_q[e], lv, pe);
+      fold_leaving(lv);
+      fold_prefill_end(pe);
+    }
     // fold this step's per-lane sums into the workgroup tallies
     {
       const uint32_t i0 = wave_sum32(lt.iters[0]), i1 = wave_sum32(lt.iters[1]);
@@ -669,18 +768,26 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
     {
       const uint32_t ncomp = static_cast<uint32_t>(L.sc[SC_NCOMP]);
       const uint32_t dcount = static_cast<uint32_t>(L.cs[CS_DCOUNT]), dhead = static_cast<uint32_t>(L.cs[CS_DHEAD]);
-      for (uint32_t j = tid; j < ncomp; j += NT) {
-        const int g = select_bit(L.bm_comp, L.pre_c, nwords_m, j);
-        const uint64_t jw = pf_job[g];
-        const int k = static_cast<int>(jw >> 29) & 7;
-        if (dcount + j < p.dbuf_cap) {
-          uint32_t pos = dhead + dcount + j;
-          if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
-          dring[pos] = jw;
-          atomicAdd(&L.cs[CS_QD + k], 1);
-        } else {
-          lds_add64(&L.tl[k * kNTally + SIM_T_DROP_D], 1);
-          L.tl[kMaxK * kNTally + SIM_G_OVERFLOW] = 1;
+      for (uint32_t j0 = wave_base; j0 < ncomp; j0 += NT) {   // wave-uniform trip count
+        const uint32_t j = j0 + lane;
+        const bool active = j < ncomp;
+        int k = 0;
+        bool kept = false;
+        if (active) {
+          const int g = select_bit(L.bm_comp, L.pre_c, nwords_m, j);
+          const uint64_t jw = pf_job[g];
+          k = static_cast<int>(jw >> 29) & 7;
+          kept = dcount + j < p.dbuf_cap;
+          if (kept) {
+            uint32_t pos = dhead + dcount + j;
+            if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
+            dring[pos] = jw;
+          }
+        }
+        wave_count_by_class_i32(active && kept, k, K, &L.cs[CS_QD], 1);
+        if (__ballot(active && !kept)) {
+          wave_count_by_class(active && !kept, k, K, &L.tl[SIM_T_DROP_D], kNTally);
+          if (lane == 0) L.tl[kMaxK * kNTally + SIM_G_OVERFLOW] = 1;
         }
       }
     }
@@ -747,42 +854,47 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
         L.cs[CS_DCOUNT] += static_cast<int32_t>(ncp < room ? ncp : room);
       }
       // admission j goes to the idle prefill slot of rank j; one thread per admission
-      for (int j = tid; j < nadm; j += NT) {
-        const int g = select_bit(L.bm_idle, L.pre, nwords_m, static_cast<uint32_t>(j));
-        const uint32_t e = L.adm[j];
-        const int k = static_cast<int>(e & 7u);
-        uint32_t pos = head[0];
+      for (int j0 = wave_base; j0 < nadm; j0 += NT) {   // wave-uniform trip count
+        const int j = j0 + lane;
+        const bool active = j < nadm;
+        int k = 0;
+        uint64_t wait = 0, nc = 0;
+        if (active) {
+          const int g = select_bit(L.bm_idle, L.pre, nwords_m, static_cast<uint32_t>(j));
+          const uint32_t e = L.adm[j];
+          k = static_cast<int>(e & 7u);
+          uint32_t pos = head[0];
 #pragma unroll
-        for (int kk = 1; kk < kMaxK; ++kk) pos = k == kk ? head[kk] : pos;
-        pos += e >> 3;
-        if (pos >= p.queue_cap) pos -= p.queue_cap;
-        const uint32_t stamp = qring[static_cast<size_t>(k) * p.queue_cap + pos];
-        lds_add64(&L.tl[k * kNTally + SIM_T_WAIT_STEPS], static_cast<uint64_t>(s - stamp));
-        uint32_t w[4];
-        philox4x32_10(key0, key1, s, 1u, static_cast<uint32_t>(g), static_cast<uint32_t>(r), w);
-        const uint32_t Pl = p.len_tab[(static_cast<size_t>(k) * 2 + 0) * kTableSize + (w[0] >> 16)];
-        const uint32_t Dl = p.len_tab[(static_cast<size_t>(k) * 2 + 1) * kTableSize + (w[1] >> 16)];
-        pf_job[g] = static_cast<uint64_t>(stamp) | (static_cast<uint64_t>(k) << 29) |
-                    (static_cast<uint64_t>(Pl - 1) << 32) | (static_cast<uint64_t>(Dl - 1) << 48);
-        // an idle prefill slot implies that the running iteration holds no chunk
-        remptok[g] = Pl | (static_cast<uint32_t>(k) << 29);
-        PROF(11)
-        if (L.loads[g]) {
-          const uint64_t nc = n_cls[g];
-          for (int c = 0; c < K; ++c) {   // co-resident decodes switch solo -> mixed
-            const int v = static_cast<int>(byte_at(nc, c));
+          for (int kk = 1; kk < kMaxK; ++kk) pos = k == kk ? head[kk] : pos;
+          pos += e >> 3;
+          if (pos >= p.queue_cap) pos -= p.queue_cap;
+          const uint32_t stamp = qring[static_cast<size_t>(k) * p.queue_cap + pos];
+          if (L.loads[g]) nc = n_cls[g];
+          wait = static_cast<uint64_t>(s - stamp);
+          uint32_t w[4];
+          philox4x32_10(key0, key1, s, 1u, static_cast<uint32_t>(g), static_cast<uint32_t>(r), w);
+          const uint32_t Pl = p.len_tab[(static_cast<size_t>(k) * 2 + 0) * kTableSize + (w[0] >> 16)];
+          const uint32_t Dl = p.len_tab[(static_cast<size_t>(k) * 2 + 1) * kTableSize + (w[1] >> 16)];
+          pf_job[g] = static_cast<uint64_t>(stamp) | (static_cast<uint64_t>(k) << 29) |
+                      (static_cast<uint64_t>(Pl - 1) << 32) | (static_cast<uint64_t>(Dl - 1) << 48);
+          // an idle prefill slot implies that the running iteration holds no chunk
+          remptok[g] = Pl | (static_cast<uint32_t>(k) << 29);
+          const uint64_t bit = 1ull << (g & 63);
+          atomicAnd(reinterpret_cast<unsigned long long *>(&L.bm_idle[g >> 6]), ~bit);
+          if (!(L.bm_busy[g >> 6] & bit)) atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_touch[g >> 6]), bit);
+        }
+        wave_sum_by_class(active, k, K, wait, &L.tl[SIM_T_WAIT_STEPS], kNTally);
+        uint64_t even, odd;   // co-resident decodes switch solo -> mixed
+        wave_sum_bytes(nc, even, odd);
+        if (lane == 0 && (even | odd))
+          for (int c = 0; c < K; ++c) {
+            const int v = static_cast<int>(class_field(even, odd, c));
             if (v) {
               lds_add64(&L.tl[c * kNTally + SIM_T_M_SM], static_cast<uint64_t>(v));
               atomicSub(&L.cs[CS_YS + c], v);
               atomicAdd(&L.cs[CS_YM + c], v);
             }
           }
-        }
-        PROF(12)
-        const uint64_t bit = 1ull << (g & 63);
-        atomicAnd(reinterpret_cast<unsigned long long *>(&L.bm_idle[g >> 6]), ~bit);
-        if (!(L.bm_busy[g >> 6] & bit)) atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_touch[g >> 6]), bit);
-        PROF(13)
       }
       bool more = false;
       if (nadm == kAdmChunk && nidle > kAdmChunk) {   // rare: more idle slots than one pass serves
@@ -846,31 +958,40 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           __syncthreads();
           if (tid < 64) rank_bitmap(L.bm_lvl, L.pre, p.nwords);
           __syncthreads();
-          for (int j = tid; j < take; j += NT) {
-            const int g = select_bit(L.bm_lvl, L.pre, p.nwords, static_cast<uint32_t>(j));
-            uint32_t pos = dhead0 + static_cast<uint32_t>(next + j);
-            if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
-            if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
-            const uint64_t jw = dring[pos];
-            const int k = static_cast<int>(jw >> 29) & 7;
-            const uint32_t Dl = static_cast<uint32_t>(jw >> 48) + 1;
-            const uint64_t bit = 1ull << (g & 63);
-            const bool busy = L.bm_busy[g >> 6] & bit;
-            const bool mid = busy && !(L.bm_due[g >> 6] & bit);   // joins at the next restart
-            const int nd = level;
-            fin[static_cast<size_t>(g) * BS + nd] = L.iter[g] + Dl + (mid ? 1u : 0u);
-            job[static_cast<size_t>(g) * BS + nd] = jw;
-            n_cls[g] += 1ull << (8 * k);
-            if (mid) {
-              n_join[g] += 1ull << (8 * k);
-              atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_join[g >> 6]), bit);
+          for (int j0 = wave_base; j0 < take; j0 += NT) {   // wave-uniform trip count
+            const int j = j0 + lane;
+            const bool active = j < take;
+            int k = 0;
+            bool has_prefill = false;
+            if (active) {
+              const int g = select_bit(L.bm_lvl, L.pre, p.nwords, static_cast<uint32_t>(j));
+              uint32_t pos = dhead0 + static_cast<uint32_t>(next + j);
+              if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
+              if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
+              const uint64_t jw = dring[pos];
+              k = static_cast<int>(jw >> 29) & 7;
+              const uint32_t Dl = static_cast<uint32_t>(jw >> 48) + 1;
+              const uint64_t bit = 1ull << (g & 63);
+              const bool busy = L.bm_busy[g >> 6] & bit;
+              const bool mid = busy && !(L.bm_due[g >> 6] & bit);   // joins at the next restart
+              const int nd = level;
+              fin[static_cast<size_t>(g) * BS + nd] = L.iter[g] + Dl + (mid ? 1u : 0u);
+              job[static_cast<size_t>(g) * BS + nd] = jw;
+              n_cls[g] += 1ull << (8 * k);
+              if (mid) {
+                n_join[g] += 1ull << (8 * k);
+                atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_join[g >> 6]), bit);
+              }
+              L.loads[g] = static_cast<uint8_t>(nd + 1);
+              has_prefill = g < M && pk_rem(remptok[g]) != 0;
+              if (!busy) atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_touch[g >> 6]), bit);
             }
-            L.loads[g] = static_cast<uint8_t>(nd + 1);
-            const bool has_prefill = g < M && pk_rem(remptok[g]) != 0;
-            lds_add64(&L.tl[k * kNTally + (has_prefill ? SIM_T_U_DM : SIM_T_U_DS)], 1);
-            atomicAdd(&L.cs[(has_prefill ? CS_YM : CS_YS) + k], 1);
-            atomicSub(&L.cs[CS_QD + k], 1);
-            if (!busy) atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_touch[g >> 6]), bit);
+            const bool am = active && has_prefill, as = active && !has_prefill;
+            wave_count_by_class(am, k, K, &L.tl[SIM_T_U_DM], kNTally);
+            wave_count_by_class(as, k, K, &L.tl[SIM_T_U_DS], kNTally);
+            wave_count_by_class_i32(am, k, K, &L.cs[CS_YM], 1);
+            wave_count_by_class_i32(as, k, K, &L.cs[CS_YS], 1);
+            wave_count_by_class_i32(active, k, K, &L.cs[CS_QD], -1);
           }
           __syncthreads();
           if (tid == 0) {   // `take` servers moved up one level
@@ -942,6 +1063,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
     if (k >= K) continue;
     if (lt.hist_cnt[0][k]) lds_add64(&L.tbth[k * p.tbt_w + lt.hist_bin[0]], lt.hist_cnt[0][k]);
     if (lt.hist_cnt[1][k]) lds_add64(&L.tbth[k * p.tbt_w + lt.hist_bin[1]], lt.hist_cnt[1][k]);
+    if (lt.hist_cnt[2][k]) lds_add64(&L.tbth[k * p.tbt_w + lt.hist_bin[2]], lt.hist_cnt[2][k]);
   }
   __syncthreads();
   if (tid < K) {
@@ -952,12 +1074,21 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
   __syncthreads();
 
   // ---- write the server clocks and the class state back; add this launch's tallies to the totals
+  if (tid < 8) L.acc[tid] = 0;
+  __syncthreads();
   for (int i = 0; i < nper; ++i) {
     const int g = i * NT + tid;
     if (g >= N) break;
     const bool busy = (L.bm_busy[g >> 6] >> (g & 63)) & 1ull;
     t_next[g] = busy ? T + static_cast<int64_t>(static_cast<int32_t>(L.t32[g] - static_cast<uint32_t>(T))) : kIdle;
     iter_g[g] = L.iter[g];
+    if (g < M) {   // prompt tokens already processed of the prefill in service
+      const uint32_t pk = remptok[g];
+      if (pk_rem(pk)) {
+        const uint32_t Pl = (static_cast<uint32_t>(pf_job[g] >> 32) & 0xFFFFu) + 1;
+        atomicAdd(&L.acc[pk_cls(pk)], Pl - static_cast<uint32_t>(pk_rem(pk)));
+      }
+    }
   }
   for (int i = tid; i < CS_WORDS; i += NT) p.cstate[static_cast<size_t>(r) * CS_WORDS + i] = L.cs[i];
   uint64_t *gt = p.tally + static_cast<size_t>(r) * kTallyWords;
@@ -968,6 +1099,9 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
     const int k = i / p.tbt_w, b = i % p.tbt_w;
     if (L.tbth[i]) hist[(2 * K + k) * kNBin + p.tbt_lo + b] += L.tbth[i];
   }
+  __syncthreads();
+  // prompt tokens processed so far = prompt tokens of completed prefills + progress of those in service
+  if (tid < K) gt[tid * kNTally + SIM_T_TOK_PREF] = gt[tid * kNTally + SIM_T_TOKP_PRE] + L.acc[tid];
 }
 
 // ------------------------------------------------------------------ reset ----
