@@ -21,22 +21,23 @@ HBM_PEAK_GBS = 8000.0
 
 
 def algorithmic_bytes(t0, g0, t1, g1, slots):
-    """Bytes the step must move for the work done between two tally read-outs.
+    """Bytes the step kernel must move for the work done between two tally read-outs.
 
-    Every server-step slot reads the server's clock (8 B). An executed iteration reads the rest of
-    the record (24 B: iteration counter, prefill progress, per-class decode counts, joiner counts),
-    scans one 4-byte completion word per occupied decode slot, and writes the record back (32 B).
-    Every admission, prefill completion, decode placement and decode completion moves about 32 B of
-    request fields and ring entries.
+    An executed iteration reads the server's per-class decode counts (8 B) and scans one 4-byte
+    completion word per occupied decode slot; an iteration that holds a prefill chunk also reads and
+    writes the prefill word (8 B). Every admission, prefill completion, decode placement and decode
+    completion moves about 32 B of request words and ring entries. Server clocks and iteration
+    counters stay in LDS during a launch and cost no HBM bytes per step.
     """
     from paper_2602_02987_amd.binding import GLOBAL, TALLY
     ti = {n: i for i, n in enumerate(TALLY)}
     gi = {n: i for i, n in enumerate(GLOBAL)}
     d = (t1.astype("float64") - t0.astype("float64")).sum(axis=0)
-    iters = float(g1[gi["ITERS_MIX"]] + g1[gi["ITERS_SOLO"]]) - float(g0[gi["ITERS_MIX"]] + g0[gi["ITERS_SOLO"]])
+    it_mix = float(g1[gi["ITERS_MIX"]]) - float(g0[gi["ITERS_MIX"]])
+    iters = it_mix + float(g1[gi["ITERS_SOLO"]]) - float(g0[gi["ITERS_SOLO"]])
     scanned = d[ti["TOK_EMIT"]]
     events = d[ti["U_P"]] + d[ti["S_P"]] + d[ti["U_DM"]] + d[ti["U_DS"]] + d[ti["S_DM"]] + d[ti["S_DS"]]
-    total = 8.0 * slots + iters * (24.0 + 32.0) + 4.0 * scanned + 32.0 * events
+    total = 8.0 * iters + 8.0 * it_mix + 4.0 * scanned + 32.0 * events
     return total, dict(due_fraction=iters / slots, decodes_per_iteration=scanned / max(iters, 1.0),
                        events_per_slot=events / slots, bytes_per_slot=total / slots)
 
@@ -75,7 +76,7 @@ def main():
     ap.add_argument("--steps", type=int, default=5, help="timed bench steps (sim_run calls)")
     ap.add_argument("--warmup", type=int, default=1, help="untimed bench steps")
     ap.add_argument("--sim-steps", type=int, default=1000, help="simulation steps per bench step")
-    ap.add_argument("--preload", type=int, default=4000, help="untimed simulation steps before anything else")
+    ap.add_argument("--preload", type=int, default=30000, help="untimed simulation steps before anything else")
     ap.add_argument("--config", type=int, default=5)
     ap.add_argument("--servers", type=int, default=0, help="override N (0 = the configuration's own)")
     ap.add_argument("--replications", type=int, default=0)
@@ -110,8 +111,6 @@ def main():
     torch.cuda.synchronize()
     sim.kernel_time(reset=True)
     K = cfg.K
-    import numpy as np
-    before = [sim.tallies(r) for r in (0, cfg.replications - 1)]
     st0 = sim.stats()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
