@@ -105,7 +105,10 @@ def main():
     slots_per_step = cfg.N * cfg.replications * args.sim_steps
 
     sim = binding.Sim(cfg)
-    sim.run(args.preload)
+    for _ in range(args.preload // args.sim_steps):   # same launch size as the timed steps
+        sim.run(args.sim_steps)
+    if args.preload % args.sim_steps:
+        sim.run(args.preload % args.sim_steps)
     for _ in range(args.warmup):
         sim.run(args.sim_steps)
     torch.cuda.synchronize()
