@@ -252,6 +252,7 @@ int sim_create(const sim_config *cfg, int max_replications, void *dev_workspace,
 
   p.self = reinterpret_cast<const Params *>(w + L.params);
   h->threads = step_threads(cfg->N);
+  p.threads = h->threads;
   h->lds_bytes = step_lds_bytes(p);
   if (h->lds_bytes > 160 * 1024) { delete h; return SIM_EINVAL; }
   if (hipMemcpy(w + L.arr_thr, arr.data(), arr.size() * sizeof(uint32_t), hipMemcpyHostToDevice) != hipSuccess ||

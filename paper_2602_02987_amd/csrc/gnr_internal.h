@@ -35,6 +35,7 @@ struct Params {
   int gate_mode;
   int tbt_lo, tbt_w;          // first bin and width of the TBT histogram window kept in LDS
   int nwords;                 // ceil(N/64) bitmap words
+  int threads;                // workgroup size of the step kernel
   uint32_t key0, key1;
   uint32_t queue_cap, dbuf_cap;
   int64_t c0, cpre, cdec, dt;

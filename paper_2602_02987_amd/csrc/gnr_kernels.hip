@@ -116,8 +116,9 @@ enum Scalar {
   SC_WORDS = 48
 };
 constexpr int kLoadBins = kMaxB + 1;
-constexpr int kEvPerWave = 128;   // completions a wave can queue per step; any beyond are finished inline
-constexpr int kMaxWaves = 16;
+constexpr int kEvPerWave = 128;   // servers a wave can queue for finishing; when full the queue is drained early
+constexpr int kRouteLevels = 8;   // load levels one routing pass fills
+constexpr int kMaxPend = 254;     // untallied iterations a server may accumulate (kept in a byte)
 
 struct Lds {
   int32_t *cs;        // [CS_WORDS]
@@ -127,20 +128,23 @@ struct Lds {
   uint64_t *tbth;     // [K][tbt_w]
   uint64_t *bm_idle;  // [nwords] mixed-group servers whose prefill slot is idle
   uint64_t *bm_comp;  // [nwords] servers whose prefill completed this step
-  uint64_t *bm_lvl;   // [nwords] servers at the routing level
   uint64_t *bm_busy;  // [nwords] servers running an iteration
-  uint64_t *bm_join;  // [nwords] servers holding a decode that joined after the running iteration started
+  uint64_t *bm_join;  // [nwords] servers holding decodes that are not part of their untallied iterations
   uint64_t *bm_due;   // [nwords] servers that completed an iteration this step
   uint64_t *bm_touch; // [nwords] idle servers that were given work this step
+  uint64_t *bm_flush; // [nwords] servers whose untallied iterations must be tallied at the restart
+  uint64_t *bm_lvl;   // [kRouteLevels][nwords] servers of the routed group with at most (level) decodes
+  uint32_t *pre_lvl;  // [kRouteLevels][nwords] exclusive prefix popcounts of bm_lvl
   uint32_t *pre_c;    // [nwords] exclusive prefix popcounts of bm_comp
-  uint32_t *pre;      // [nwords] exclusive prefix popcounts of bm_idle / bm_lvl
+  uint32_t *pre;      // [nwords] exclusive prefix popcounts of bm_idle
   uint32_t *adm;      // [kAdmChunk] class | sequence-in-class << 3 of each admission
   uint32_t *lh;       // [2][kLoadBins] servers per decode count: solo group, mixed group
-  uint32_t *ev_g;     // [waves][kEvPerWave] servers with decodes leaving this step, queued per wave
+  uint32_t *ev_g;     // [waves][kEvPerWave] servers queued for finishing, per wave
   uint32_t *ev_q;     // [waves][kEvPerWave] their slot-quad masks
   uint32_t *t32;      // [N] low 32 bits of the end time of the running iteration
   uint32_t *iter;     // [N] completed iterations
   uint8_t *loads;     // [N] decodes per server
+  uint8_t *pend;      // [N] completed iterations not yet tallied (all with the server's current batch)
 };
 
 // Carves the dynamic LDS block; 8-byte granules, 64-bit arrays first.
@@ -155,23 +159,26 @@ __host__ __device__ __forceinline__ Lds lds_carve(const Params &p, unsigned char
   GNR_TAKE(tbth, uint64_t, p.K * p.tbt_w)
   GNR_TAKE(bm_idle, uint64_t, p.nwords)
   GNR_TAKE(bm_comp, uint64_t, p.nwords)
-  GNR_TAKE(bm_lvl, uint64_t, p.nwords)
   GNR_TAKE(bm_busy, uint64_t, p.nwords)
   GNR_TAKE(bm_join, uint64_t, p.nwords)
   GNR_TAKE(bm_due, uint64_t, p.nwords)
   GNR_TAKE(bm_touch, uint64_t, p.nwords)
+  GNR_TAKE(bm_flush, uint64_t, p.nwords)
+  GNR_TAKE(bm_lvl, uint64_t, kRouteLevels * p.nwords)
   GNR_TAKE(cs, int32_t, CS_WORDS)
   GNR_TAKE(acc, uint32_t, 8)
   GNR_TAKE(sc, int32_t, SC_WORDS)
+  GNR_TAKE(pre_lvl, uint32_t, kRouteLevels * p.nwords)
   GNR_TAKE(pre_c, uint32_t, p.nwords + 1)
   GNR_TAKE(pre, uint32_t, p.nwords + 1)
   GNR_TAKE(adm, uint32_t, kAdmChunk)
   GNR_TAKE(lh, uint32_t, 2 * kLoadBins)
-  GNR_TAKE(ev_g, uint32_t, kMaxWaves * kEvPerWave)
-  GNR_TAKE(ev_q, uint32_t, kMaxWaves * kEvPerWave)
+  GNR_TAKE(ev_g, uint32_t, (p.threads / 64) * kEvPerWave)
+  GNR_TAKE(ev_q, uint32_t, (p.threads / 64) * kEvPerWave)
   GNR_TAKE(t32, uint32_t, p.N)
   GNR_TAKE(iter, uint32_t, p.N)
   GNR_TAKE(loads, uint8_t, p.N)
+  GNR_TAKE(pend, uint8_t, p.N)
 #undef GNR_TAKE
   if (total) *total = off;
   return L;
@@ -227,44 +234,6 @@ __device__ __forceinline__ uint32_t wave_sum32(uint32_t v)
   return v;
 }
 
-// Per-lane sums of the tallies every executed iteration touches. The step sums are folded into
-// the workgroup's totals once per step; the time-between-tokens counts stay cached per lane for
-// the bin they fall in and are written out when the bin changes or the launch ends. Three bins are
-// cached because a lane's servers have three typical durations: solo group, mixed group without
-// and with a prefill chunk.
-struct LaneTallies {
-  uint32_t iters[2];            // this step: [decode-only, with a prefill chunk]
-  uint64_t busy[2];
-  uint64_t tbt_sum[kMaxK];
-  int hist_bin[3];              // across steps: [solo group, mixed group decode-only, with a chunk]
-  uint32_t hist_cnt[3][kMaxK];
-};
-
-// One executed iteration of duration d whose batch held the decodes nc minus the late joiners nj.
-template <int SLOT>
-__device__ __forceinline__ void tally_iteration(LaneTallies &lt, uint64_t *tbth, int tbt_w, int K, int64_t d, int tb,
-                                                uint64_t nc, uint64_t nj)
-{
-  constexpr int KIND = SLOT == 2 ? 1 : 0;
-  lt.iters[KIND] += 1;
-  lt.busy[KIND] += static_cast<uint64_t>(d);
-  if (tb != lt.hist_bin[SLOT]) {   // the duration moved to another bin: flush the cached counts
-#pragma unroll
-    for (int k = 0; k < kMaxK; ++k)
-      if (k < K && lt.hist_cnt[SLOT][k]) {
-        lds_add64(&tbth[k * tbt_w + lt.hist_bin[SLOT]], lt.hist_cnt[SLOT][k]);
-        lt.hist_cnt[SLOT][k] = 0;
-      }
-    lt.hist_bin[SLOT] = tb;
-  }
-#pragma unroll
-  for (int k = 0; k < kMaxK; ++k) {
-    const uint32_t em = byte_at(nc, k) - byte_at(nj, k);
-    lt.tbt_sum[k] += static_cast<uint64_t>(em) * static_cast<uint64_t>(d);
-    lt.hist_cnt[SLOT][k] += em;
-  }
-}
-
 // ---- wave-level folding of per-event class updates: lanes of one class are combined first, so that a
 // counter sees one LDS atomic per wave and class instead of one per event. All take uniform control flow.
 __device__ __forceinline__ void wave_count_by_class(bool active, int k, int K, uint64_t *base, int stride)
@@ -302,10 +271,44 @@ __device__ __forceinline__ uint32_t class_field(uint64_t even, uint64_t odd, int
   return static_cast<uint32_t>(((c & 1) ? odd : even) >> (16 * (c >> 1))) & 0xFFFFu;
 }
 
-// What finishing an iteration reports back for folding: the first decode that left the server and
-// the end of its prefill. Further decodes leaving in the same iteration are tallied directly.
-struct Leaving { int k; uint32_t P, D; int64_t e2e; bool mixed; };
-struct PrefillEnd { bool done; int k; uint32_t P; int64_t ttft; uint64_t nc; };
+// Per-lane sums of this step's iteration tallies; folded into the workgroup's totals once per step.
+struct LaneTallies {
+  uint32_t iters[2];   // [decode-only, with a prefill chunk]
+  uint64_t busy[2];
+  uint64_t tbt_sum[kMaxK];
+};
+
+// m executed iterations of duration d whose batch held the per-class decode counts `comp`.
+// The time-between-tokens histogram gets m*comp_k tokens in the bin of d: lanes that share a bin are
+// summed over the wave first. Uniform control flow; lanes without anything to tally pass m = 0.
+__device__ __forceinline__ void tally_iterations(LaneTallies &lt, uint64_t *tbth, int tbt_w, int tbt_lo, int K, uint32_t m,
+                                                 int64_t d, bool chunk, uint64_t comp)
+{
+  if (__ballot(m != 0) == 0) return;
+  const int lane = threadIdx.x & 63;
+  if (m) {
+    if (chunk) { lt.iters[1] += m; lt.busy[1] += static_cast<uint64_t>(m) * static_cast<uint64_t>(d); }
+    else { lt.iters[0] += m; lt.busy[0] += static_cast<uint64_t>(m) * static_cast<uint64_t>(d); }
+  }
+  const uint64_t md = static_cast<uint64_t>(m) * static_cast<uint64_t>(d);
+#pragma unroll
+  for (int k = 0; k < kMaxK; ++k) lt.tbt_sum[k] += static_cast<uint64_t>(byte_at(comp, k)) * md;
+  const int tb = m ? hbin(d) - tbt_lo : -1;
+  uint64_t todo = __ballot(m != 0);
+  while (todo) {
+    const int leader = __ffsll(static_cast<long long>(todo)) - 1;
+    const int b = __builtin_amdgcn_readlane(tb, leader);
+    const bool in = tb == b;
+    todo &= ~__ballot(in);
+    for (int k = 0; k < K; ++k) {
+      const uint32_t t = wave_sum32(in ? m * byte_at(comp, k) : 0u);
+      if (lane == 0 && t) lds_add64(&tbth[k * tbt_w + b], t);
+    }
+  }
+}
+
+// bytewise a - b for per-class count vectors with b_k <= a_k
+__device__ __forceinline__ uint64_t bytes_sub(uint64_t a, uint64_t b) { return a - b; }
 
 // Sort key of a gate candidate: the m-th waiting request of class k (m counted from the head).
 // Occupancy gate: (X_k + m - n x_k*)/x_k*, ties by the larger queue deviation Q_k - m - n q_k*;
@@ -341,18 +344,16 @@ __device__ __forceinline__ bool gate_before(const GateKey &x, int k1, const Gate
   return k1 < k2;
 }
 
-// ------------------------------------------------------------------ step kernel ----
-// What the completion pass knows about one server of the round being processed.
-struct RoundState {
-  bool due;        // the server's iteration ends within this step
-  uint32_t t32;    // low 32 bits of its end time
-  uint32_t it;     // index of the iteration that ends
-  int nd;          // decodes on the server
-  uint64_t nc, nj; // per-class decode counts; of those, late joiners
-  uint32_t pk;     // prefill word (mixed group only)
-  uint64_t due_mask, join_word;
-};
+// What finishing an iteration reports back for folding: the first decode that left the server and
+// the end of its prefill. Further decodes leaving in the same iteration are tallied directly.
+struct Leaving { int k; uint32_t P, D; int64_t e2e; bool mixed; };
+struct PrefillEnd { bool done; int k; uint32_t P; int64_t ttft; uint64_t nc; };
 
+// ------------------------------------------------------------------ step kernel ----
+// Iteration tallies are lazy. A server whose batch does not change runs identical iterations, so the
+// completion pass only counts them (`pend`); they are tallied, with their multiplicity, when the batch is
+// about to change: a decode leaves, a decode that joined mid-iteration becomes part of the batch, a prefill
+// is present, work is placed on a server that is at an iteration boundary, or the launch ends.
 template <int MAXT>
 __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict__ params, const uint32_t key0,
                                                         const uint32_t key1, const uint32_t step_begin,
@@ -367,9 +368,11 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
   const int NT = blockDim.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
+  const int nwaves = NT >> 6;
   const int wave_base = tid & ~63;
   const int K = p.K, N = p.N, B = p.B, M = p.M, BS = p.BS;
   const int nper = (N + NT - 1) / NT;
+  const int nwords = p.nwords;
   const int nwords_m = (M + 63) >> 6;   // bitmap words that hold mixed-group servers
 
   int64_t *t_next = p.t_next + static_cast<size_t>(r) * N;
@@ -400,6 +403,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
     if (valid) {
       const uint32_t nd = byte_sum(n_cls[g]);
       L.loads[g] = static_cast<uint8_t>(nd);
+      L.pend[g] = 0;
       atomicAdd(&L.lh[(g < M ? kLoadBins : 0) + nd], 1u);
       const int64_t tn = t_next[g];
       busy = tn != kIdle;
@@ -410,18 +414,16 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
     const bool idle_slot = valid && g < M && pk_rem(remptok[g]) == 0;
     const uint64_t bi = __ballot(idle_slot), bb = __ballot(busy), bj = __ballot(joined);
     const int wi = (i * NT + wave_base) >> 6;
-    if (lane == 0 && wi < p.nwords) { L.bm_idle[wi] = bi; L.bm_busy[wi] = bb; L.bm_join[wi] = bj; }
+    if (lane == 0 && wi < nwords) { L.bm_idle[wi] = bi; L.bm_busy[wi] = bb; L.bm_join[wi] = bj; L.bm_flush[wi] = 0; }
   }
   LaneTallies lt;
-  lt.hist_bin[0] = lt.hist_bin[1] = lt.hist_bin[2] = 0;
-#pragma unroll
-  for (int k = 0; k < kMaxK; ++k) lt.hist_cnt[0][k] = lt.hist_cnt[1][k] = lt.hist_cnt[2][k] = 0;
   __syncthreads();
 
   int64_t T = 0;
   PROF_DECL
   for (uint32_t s = step_begin; s < step_begin + n_steps; ++s) {
     PROF(0)
+    const bool last_step = s + 1 == step_begin + n_steps;
     T = (static_cast<int64_t>(s) + 1) * p.dt;
     const uint32_t T32 = static_cast<uint32_t>(T);
     if (tid < 8) L.acc[tid] = 0;
@@ -449,196 +451,174 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
       }
     };
 
-    // ---- 2. finishing the iteration of server g: tallies, decodes that emitted their last token
-    //      (slot quads flagged in `quads`), prefill progress. Class-level effects of the first decode
-    //      that leaves and of a prefill that ends are reported in lv / pe for folding by the caller.
-    auto leave_direct = [&](int k, uint32_t Pl, uint32_t Dl, int64_t e2e, bool mixed_now) __attribute__((always_inline)) {
-      lds_add64(&L.tl[k * kNTally + (mixed_now ? SIM_T_S_DM : SIM_T_S_DS)], 1);
-      atomicSub(&L.cs[(mixed_now ? CS_YM : CS_YS) + k], 1);
-      lds_add64(&L.tl[k * kNTally + SIM_T_TOKP_DEC], Pl);
-      lds_add64(&L.tl[k * kNTally + SIM_T_TOKD_DEC], Dl);
-      lds_add64(&L.tl[k * kNTally + SIM_T_E2E_SUM], static_cast<uint64_t>(e2e));
-    };
-    auto finish_iteration = [&](int g, uint32_t it, int nd, uint64_t nc, uint64_t nj, uint32_t pk, uint32_t t32,
-                                uint32_t quads, Leaving &lv, PrefillEnd &pe) __attribute__((always_inline)) {
-      int rem = pk_rem(pk);
-      const int ptok = pk_ptok(pk);
-      const int64_t tn = T + static_cast<int64_t>(static_cast<int32_t>(t32 - T32));   // exact completion time
-      const int64_t d = p.c0 + p.cpre * ptok + p.cdec * static_cast<int64_t>(nd - static_cast<int>(byte_sum(nj)));
-      const int tb = hbin(d) - p.tbt_lo;
-      if (g >= M) tally_iteration<0>(lt, L.tbth, p.tbt_w, K, d, tb, nc, nj);
-      else if (ptok == 0) tally_iteration<1>(lt, L.tbth, p.tbt_w, K, d, tb, nc, nj);
-      else tally_iteration<2>(lt, L.tbth, p.tbt_w, K, d, tb, nc, nj);
-      lv.k = -1;
-      pe.done = false;
-      const bool mixed_now = rem > 0;
-      const int nd_before = nd;
-      if (quads) {
-        // Highest slot first, so the slot moved into a hole has already been checked.
-        uint32_t *frow = fin + static_cast<size_t>(g) * BS;
-        uint64_t *jrow = job + static_cast<size_t>(g) * BS;
-        while (quads) {
-          const int q = 31 - __clz(quads);
-          quads &= ~(1u << q);
-          const uint4 v = *reinterpret_cast<const uint4 *>(frow + 4 * q);
-          const uint32_t wv[4] = {v.x, v.y, v.z, v.w};
+    // ---- 2. finishing queued servers, one per lane (uniform control flow; lanes beyond the queue idle).
+    //      Tallies the server's untallied iterations and the one that just ended, removes the decodes
+    //      that emitted their last token (slot quads flagged in the queue entry), advances the prefill.
+    auto drain_events = [&](int nev) __attribute__((always_inline)) {
+      for (int e0 = 0; e0 < nev; e0 += 64) {
+        const int e = e0 + lane;
+        const bool active = e < nev;
+        uint32_t m = 0;
+        int64_t d = 0;
+        bool chunk = false;
+        uint64_t comp = 0;
+        Leaving lv; lv.k = -1; lv.P = lv.D = 0; lv.e2e = 0; lv.mixed = false;
+        PrefillEnd pe; pe.done = false; pe.k = 0; pe.P = 0; pe.ttft = 0; pe.nc = 0;
+        if (active) {
+          const int g = static_cast<int>(ev_g[e]);
+          uint32_t quads = ev_q[e];
+          uint64_t nc = n_cls[g];
+          const uint64_t bit = 1ull << (g & 63);
+          const bool joined = L.bm_join[g >> 6] & bit;
+          const uint64_t nj = joined ? n_join[g] : 0ull;
+          const uint32_t pk = g < M ? remptok[g] : 0u;
+          const uint32_t it = L.iter[g];
+          int nd = L.loads[g];
+          int rem = pk_rem(pk);
+          const int ptok = pk_ptok(pk);
+          const int64_t tn = T + static_cast<int64_t>(static_cast<int32_t>(L.t32[g] - T32));   // exact completion time
+          comp = bytes_sub(nc, nj);
+          d = p.c0 + p.cpre * ptok + p.cdec * static_cast<int64_t>(byte_sum(comp));
+          chunk = ptok > 0;
+          m = static_cast<uint32_t>(L.pend[g]) + 1u;
+          L.pend[g] = 0;
+          const bool mixed_now = rem > 0;
+          const int nd_before = nd;
+          if (quads) {
+            // Highest slot first, so the slot moved into a hole has already been checked.
+            uint32_t *frow = fin + static_cast<size_t>(g) * BS;
+            uint64_t *jrow = job + static_cast<size_t>(g) * BS;
+            while (quads) {
+              const int q = 31 - __clz(quads);
+              quads &= ~(1u << q);
+              const uint4 v = *reinterpret_cast<const uint4 *>(frow + 4 * q);
+              const uint32_t wv[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-          for (int w = 3; w >= 0; --w) {
-            const int j = 4 * q + w;
-            if (j < nd && wv[w] == it) {
-              const uint64_t jw = jrow[j];
-              const int k = static_cast<int>(jw >> 29) & 7;
-              const uint32_t stamp = static_cast<uint32_t>(jw) & 0x1FFFFFFFu;
-              const uint32_t Pl = (static_cast<uint32_t>(jw >> 32) & 0xFFFFu) + 1, Dl = static_cast<uint32_t>(jw >> 48) + 1;
-              const int64_t e2e = tn - (static_cast<int64_t>(stamp) + 1) * p.dt;
-              if (lv.k < 0) { lv.k = k; lv.P = Pl; lv.D = Dl; lv.e2e = e2e; lv.mixed = mixed_now; }
-              else leave_direct(k, Pl, Dl, e2e, mixed_now);
-              atomicAdd(reinterpret_cast<unsigned long long *>(&hist[(1 * K + k) * kNBin + hbin(e2e)]), 1ull);
-              nc -= 1ull << (8 * k);
-              --nd;
-              if (j < nd) { frow[j] = frow[nd]; jrow[j] = jrow[nd]; }
+              for (int w = 3; w >= 0; --w) {
+                const int j = 4 * q + w;
+                if (j < nd && wv[w] == it) {
+                  const uint64_t jw = jrow[j];
+                  const int k = static_cast<int>(jw >> 29) & 7;
+                  const uint32_t stamp = static_cast<uint32_t>(jw) & 0x1FFFFFFFu;
+                  const uint32_t Pl = (static_cast<uint32_t>(jw >> 32) & 0xFFFFu) + 1, Dl = static_cast<uint32_t>(jw >> 48) + 1;
+                  const int64_t e2e = tn - (static_cast<int64_t>(stamp) + 1) * p.dt;
+                  if (lv.k < 0) { lv.k = k; lv.P = Pl; lv.D = Dl; lv.e2e = e2e; lv.mixed = mixed_now; }
+                  else {   // a second decode leaving the same server in the same iteration: rare, tallied directly
+                    lds_add64(&L.tl[k * kNTally + (mixed_now ? SIM_T_S_DM : SIM_T_S_DS)], 1);
+                    atomicSub(&L.cs[(mixed_now ? CS_YM : CS_YS) + k], 1);
+                    lds_add64(&L.tl[k * kNTally + SIM_T_TOKP_DEC], Pl);
+                    lds_add64(&L.tl[k * kNTally + SIM_T_TOKD_DEC], Dl);
+                    lds_add64(&L.tl[k * kNTally + SIM_T_E2E_SUM], static_cast<uint64_t>(e2e));
+                  }
+                  atomicAdd(reinterpret_cast<unsigned long long *>(&hist[(1 * K + k) * kNBin + hbin(e2e)]), 1ull);
+                  nc -= 1ull << (8 * k);
+                  --nd;
+                  if (j < nd) { frow[j] = frow[nd]; jrow[j] = jrow[nd]; }
+                }
+              }
+            }
+            if (nd != nd_before) {
+              n_cls[g] = nc;
+              L.loads[g] = static_cast<uint8_t>(nd);
+              const int hb = g < M ? kLoadBins : 0;
+              atomicSub(&L.lh[hb + nd_before], 1u);
+              atomicAdd(&L.lh[hb + nd], 1u);
             }
           }
-        }
-        if (nd != nd_before) {
-          n_cls[g] = nc;
-          L.loads[g] = static_cast<uint8_t>(nd);
-          const int hb = g < M ? kLoadBins : 0;
-          atomicSub(&L.lh[hb + nd_before], 1u);
-          atomicAdd(&L.lh[hb + nd], 1u);
-        }
-      }
-      // the prefill advances by the chunk frozen at the start of the iteration
-      if (ptok > 0) {
-        const int k = pk_cls(pk);
-        rem -= ptok;
-        if (rem == 0) {
-          const uint64_t jw = pf_job[g];
-          const uint32_t stamp = static_cast<uint32_t>(jw) & 0x1FFFFFFFu;
-          pe.done = true; pe.k = k; pe.nc = nc;
-          pe.P = (static_cast<uint32_t>(jw >> 32) & 0xFFFFu) + 1;
-          pe.ttft = tn - (static_cast<int64_t>(stamp) + 1) * p.dt;
-          atomicAdd(reinterpret_cast<unsigned long long *>(&hist[(0 * K + k) * kNBin + hbin(pe.ttft)]), 1ull);
-        }
-        // running chunk cleared; it is set again at the restart
-        remptok[g] = static_cast<uint32_t>(rem) | (static_cast<uint32_t>(k) << 29);
-      }
-      if (nj) n_join[g] = 0;
-    };
-    // class-level effects of the decodes that left (one per lane), folded over the wave
-    auto fold_leaving = [&](const Leaving &lv) __attribute__((always_inline)) {
-      const bool any = lv.k >= 0;
-      if (__ballot(any) == 0) return;
-      const bool am = any && lv.mixed, as = any && !lv.mixed;
-      wave_count_by_class(am, lv.k, K, &L.tl[SIM_T_S_DM], kNTally);
-      wave_count_by_class(as, lv.k, K, &L.tl[SIM_T_S_DS], kNTally);
-      wave_count_by_class_i32(am, lv.k, K, &L.cs[CS_YM], -1);
-      wave_count_by_class_i32(as, lv.k, K, &L.cs[CS_YS], -1);
-      wave_sum_by_class(any, lv.k, K, lv.P, &L.tl[SIM_T_TOKP_DEC], kNTally);
-      wave_sum_by_class(any, lv.k, K, lv.D, &L.tl[SIM_T_TOKD_DEC], kNTally);
-      wave_sum_by_class(any, lv.k, K, static_cast<uint64_t>(lv.e2e), &L.tl[SIM_T_E2E_SUM], kNTally);
-    };
-    // class-level effects of the prefills that ended: completion counts, recognised prompt tokens,
-    // time to first token; the co-resident decodes switch mixed -> solo
-    auto fold_prefill_end = [&](const PrefillEnd &pe) __attribute__((always_inline)) {
-      if (__ballot(pe.done) == 0) return;
-      wave_count_by_class(pe.done, pe.k, K, &L.tl[SIM_T_S_P], kNTally);
-      wave_count_by_class_i32(pe.done, pe.k, K, &L.cs[CS_X], -1);
-      wave_sum_by_class(pe.done, pe.k, K, pe.P, &L.tl[SIM_T_TOKP_PRE], kNTally);
-      wave_sum_by_class(pe.done, pe.k, K, static_cast<uint64_t>(pe.ttft), &L.tl[SIM_T_TTFT_SUM], kNTally);
-      uint64_t even, odd;
-      wave_sum_bytes(pe.done ? pe.nc : 0ull, even, odd);
-      if (lane == 0)
-        for (int c = 0; c < K; ++c) {
-          const int v = static_cast<int>(class_field(even, odd, c));
-          if (v) {
-            lds_add64(&L.tl[c * kNTally + SIM_T_M_MS], static_cast<uint64_t>(v));
-            atomicSub(&L.cs[CS_YM + c], v);
-            atomicAdd(&L.cs[CS_YS + c], v);
+          // the prefill advances by the chunk frozen at the start of the iteration
+          if (ptok > 0) {
+            const int k = pk_cls(pk);
+            rem -= ptok;
+            if (rem == 0) {
+              const uint64_t jw = pf_job[g];
+              const uint32_t stamp = static_cast<uint32_t>(jw) & 0x1FFFFFFFu;
+              pe.done = true; pe.k = k; pe.nc = nc;
+              pe.P = (static_cast<uint32_t>(jw >> 32) & 0xFFFFu) + 1;
+              pe.ttft = tn - (static_cast<int64_t>(stamp) + 1) * p.dt;
+              atomicAdd(reinterpret_cast<unsigned long long *>(&hist[(0 * K + k) * kNBin + hbin(pe.ttft)]), 1ull);
+              atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_comp[g >> 6]), bit);
+              atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_idle[g >> 6]), bit);
+            }
+            // running chunk cleared; it is set again at the restart
+            remptok[g] = static_cast<uint32_t>(rem) | (static_cast<uint32_t>(k) << 29);
+          }
+          if (joined) {
+            n_join[g] = 0;
+            atomicAnd(reinterpret_cast<unsigned long long *>(&L.bm_join[g >> 6]), ~bit);
           }
         }
-    };
-    // the same effects for a single server, without folding (divergent callers)
-    auto commit_direct = [&](const Leaving &lv, const PrefillEnd &pe) __attribute__((always_inline)) {
-      if (lv.k >= 0) leave_direct(lv.k, lv.P, lv.D, lv.e2e, lv.mixed);
-      if (pe.done) {
-        lds_add64(&L.tl[pe.k * kNTally + SIM_T_S_P], 1);
-        atomicSub(&L.cs[CS_X + pe.k], 1);
-        lds_add64(&L.tl[pe.k * kNTally + SIM_T_TOKP_PRE], pe.P);
-        lds_add64(&L.tl[pe.k * kNTally + SIM_T_TTFT_SUM], static_cast<uint64_t>(pe.ttft));
-        for (int c = 0; c < K; ++c) {
-          const int v = static_cast<int>(byte_at(pe.nc, c));
-          if (v) {
-            lds_add64(&L.tl[c * kNTally + SIM_T_M_MS], static_cast<uint64_t>(v));
-            atomicSub(&L.cs[CS_YM + c], v);
-            atomicAdd(&L.cs[CS_YS + c], v);
+        tally_iterations(lt, L.tbth, p.tbt_w, p.tbt_lo, K, m, d, chunk, comp);
+        // class-level effects of the decodes that left (at most one per lane here), folded over the wave
+        {
+          const bool any = lv.k >= 0;
+          if (__ballot(any)) {
+            const bool am = any && lv.mixed, as = any && !lv.mixed;
+            wave_count_by_class(am, lv.k, K, &L.tl[SIM_T_S_DM], kNTally);
+            wave_count_by_class(as, lv.k, K, &L.tl[SIM_T_S_DS], kNTally);
+            wave_count_by_class_i32(am, lv.k, K, &L.cs[CS_YM], -1);
+            wave_count_by_class_i32(as, lv.k, K, &L.cs[CS_YS], -1);
+            wave_sum_by_class(any, lv.k, K, lv.P, &L.tl[SIM_T_TOKP_DEC], kNTally);
+            wave_sum_by_class(any, lv.k, K, lv.D, &L.tl[SIM_T_TOKD_DEC], kNTally);
+            wave_sum_by_class(any, lv.k, K, static_cast<uint64_t>(lv.e2e), &L.tl[SIM_T_E2E_SUM], kNTally);
           }
         }
-      }
-    };
-
-    // a server whose finishing was put off because decodes leave it: reload its record and finish it
-    auto finish_deferred = [&](int g, uint32_t quads, Leaving &lv, PrefillEnd &pe) __attribute__((always_inline)) {
-      const uint64_t nc = n_cls[g];
-      const bool joined = (L.bm_join[g >> 6] >> (g & 63)) & 1ull;
-      const uint64_t nj = joined ? n_join[g] : 0ull;
-      const uint32_t pk = g < M ? remptok[g] : 0u;
-      finish_iteration(g, L.iter[g], L.loads[g], nc, nj, pk, L.t32[g], quads, lv, pe);
-      if (pe.done) {
-        atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_comp[g >> 6]), 1ull << (g & 63));
-        atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_idle[g >> 6]), 1ull << (g & 63));
-      }
-      if (joined) atomicAnd(reinterpret_cast<unsigned long long *>(&L.bm_join[g >> 6]), ~(1ull << (g & 63)));
-    };
-
-    // which servers of round i are due, and their records (global loads are issued, not waited for)
-    auto probe = [&](int i) __attribute__((always_inline)) -> RoundState {
-      RoundState st;
-      st.due = false; st.t32 = 0; st.it = 0; st.nd = 0; st.nc = 0; st.nj = 0; st.pk = 0; st.due_mask = 0; st.join_word = 0;
-      const int gw = i * NT + wave_base;
-      if (gw < N) {
-        const int g = gw + lane;
-        const bool valid = g < N;
-        const uint64_t busy_word = L.bm_busy[gw >> 6];
-        st.join_word = L.bm_join[gw >> 6];
-        st.t32 = valid ? L.t32[g] : 0u;
-        st.due = valid && ((busy_word >> lane) & 1ull) && static_cast<int32_t>(st.t32 - T32) <= 0;
-        st.due_mask = __ballot(st.due);
-        if (st.due) {
-          st.it = L.iter[g] + 1;
-          L.iter[g] = st.it;
-          st.nd = L.loads[g];
-          st.nc = n_cls[g];
-          if ((st.join_word >> lane) & 1ull) st.nj = n_join[g];
-          if (g < M) st.pk = remptok[g];
+        // prefills that ended: completion counts, recognised prompt tokens, time to first token;
+        // the co-resident decodes switch mixed -> solo
+        if (__ballot(pe.done)) {
+          wave_count_by_class(pe.done, pe.k, K, &L.tl[SIM_T_S_P], kNTally);
+          wave_count_by_class_i32(pe.done, pe.k, K, &L.cs[CS_X], -1);
+          wave_sum_by_class(pe.done, pe.k, K, pe.P, &L.tl[SIM_T_TOKP_PRE], kNTally);
+          wave_sum_by_class(pe.done, pe.k, K, static_cast<uint64_t>(pe.ttft), &L.tl[SIM_T_TTFT_SUM], kNTally);
+          uint64_t even, odd;
+          wave_sum_bytes(pe.done ? pe.nc : 0ull, even, odd);
+          if (lane == 0)
+            for (int c = 0; c < K; ++c) {
+              const int v = static_cast<int>(class_field(even, odd, c));
+              if (v) {
+                lds_add64(&L.tl[c * kNTally + SIM_T_M_MS], static_cast<uint64_t>(v));
+                atomicSub(&L.cs[CS_YM + c], v);
+                atomicAdd(&L.cs[CS_YS + c], v);
+              }
+            }
         }
       }
-      return st;
     };
 
-    int nev = 0;   // completions queued by this wave (wave-uniform)
-    RoundState nx = probe(0);
+    // ---- completion pass over this wave's rounds of 64 servers
+    int nev = 0;   // servers queued by this wave (wave-uniform)
     PROF(1)
-    for (int i = 0; i < nper; ++i) {
+    for (int i = 0;; ++i) {
       const int gw = i * NT + wave_base;          // first server of this wave's 64-server block
-      if (gw >= N) break;                         // wave-uniform
-      const int wi = gw >> 6;
+      const bool tail = i >= nper || gw >= N;     // wave-uniform: one extra trip finishes what is still queued
+      const int wi = tail ? 0 : gw >> 6;
       const int g = gw + lane;
-      const RoundState cur = nx;
-      if (i + 1 < nper) nx = probe(i + 1);        // next round's records travel while this round is scanned
+      const bool valid = !tail && g < N;
+      const uint64_t busy_word = tail ? 0ull : L.bm_busy[wi], join_word = tail ? 0ull : L.bm_join[wi];
+      const uint64_t idle_word = tail ? 0ull : L.bm_idle[wi];
+      const uint32_t t32 = valid ? L.t32[g] : 0u;
+      const bool due = valid && ((busy_word >> lane) & 1ull) && static_cast<int32_t>(t32 - T32) <= 0;
+      const uint64_t due_mask = __ballot(due);
+      uint32_t it = 0;
+      int nd = 0, pend = 0;
+      if (due) {
+        it = L.iter[g] + 1;
+        L.iter[g] = it;
+        nd = L.loads[g];
+        pend = L.pend[g];
+      }
       PROF(2)
       uint32_t quads = 0;   // owner lane: bit q set <=> one of slots 4q..4q+3 finishes now
-      if (cur.due_mask) {
+      if (due_mask) {
         // ---- cooperative scan of the slot rows: half a wave reads one server's row (4 words per lane)
-        uint64_t todo = __ballot(cur.due && cur.nd > 0);
+        uint64_t todo = __ballot(due && nd > 0);
         const int q = lane & 31;
         const bool hi = lane >= 32;
         bool first_batch = true;
         do {
-          int la[4], lb[4];
-          bool va[4], vb[4];
+          int la[8], lb[8];
+          bool va[8], vb[8];
 #pragma unroll
-          for (int u = 0; u < 4; ++u) {
+          for (int u = 0; u < 8; ++u) {
             va[u] = todo != 0;
             la[u] = va[u] ? __ffsll(static_cast<long long>(todo)) - 1 : 0;
             if (va[u]) todo &= todo - 1;
@@ -646,13 +626,13 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
             lb[u] = vb[u] ? __ffsll(static_cast<long long>(todo)) - 1 : 0;
             if (vb[u]) todo &= todo - 1;
           }
-          uint4 v[4];
-          uint32_t its[4];
-          int nds[4];
+          uint4 v[8];
+          uint32_t its[8];
+          int nds[8];
 #pragma unroll
-          for (int u = 0; u < 4; ++u) {
-            const uint32_t ita = __builtin_amdgcn_readlane(cur.it, la[u]), itb = __builtin_amdgcn_readlane(cur.it, lb[u]);
-            const int nda = __builtin_amdgcn_readlane(cur.nd, la[u]), ndb = __builtin_amdgcn_readlane(cur.nd, lb[u]);
+          for (int u = 0; u < 8; ++u) {
+            const uint32_t ita = __builtin_amdgcn_readlane(it, la[u]), itb = __builtin_amdgcn_readlane(it, lb[u]);
+            const int nda = __builtin_amdgcn_readlane(nd, la[u]), ndb = __builtin_amdgcn_readlane(nd, lb[u]);
             const bool on = hi ? vb[u] : va[u];
             its[u] = hi ? itb : ita;
             nds[u] = on ? (hi ? ndb : nda) : 0;
@@ -661,11 +641,11 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
             if (4 * q < nds[u]) v[u] = *reinterpret_cast<const uint4 *>(fin + static_cast<size_t>(gs) * BS + 4 * q);
           }
           if (first_batch) {   // the arrival draws of this round run while the first rows travel
-            if (g < N) arrivals(g);
+            if (valid) arrivals(g);
             first_batch = false;
           }
 #pragma unroll
-          for (int u = 0; u < 4; ++u) {
+          for (int u = 0; u < 8; ++u) {
             const int left = nds[u] - 4 * q;   // occupied words of this lane's quad
             const bool m = (left > 0 && v[u].x == its[u]) || (left > 1 && v[u].y == its[u]) ||
                            (left > 2 && v[u].z == its[u]) || (left > 3 && v[u].w == its[u]);
@@ -676,57 +656,31 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
             }
           }
         } while (todo);
-      } else if (g < N) {
+      } else if (valid) {
         arrivals(g);
       }
       PROF(3)
-      const bool deferred = cur.due && quads != 0;
-      Leaving lv; lv.k = -1;
-      PrefillEnd pe; pe.done = false;
-      if (cur.due && quads == 0) finish_iteration(g, cur.it, cur.nd, cur.nc, cur.nj, cur.pk, cur.t32, 0u, lv, pe);
-      fold_prefill_end(pe);
-      const uint64_t done = __ballot(pe.done), later = __ballot(deferred);
-      if (later) {   // queue the servers that have decodes leaving; they are finished after the pass
-        const int slot = nev + __popcll(later & lanes_below());
-        if (deferred) {
-          if (slot < kEvPerWave) { ev_g[slot] = static_cast<uint32_t>(g); ev_q[slot] = quads; }
-          else { Leaving l2; PrefillEnd p2; finish_deferred(g, quads, l2, p2); commit_direct(l2, p2); }
-        }
-        nev += __popcll(later);
-        if (nev > kEvPerWave) nev = kEvPerWave;
-      }
-      if (lane == 0) {
-        L.bm_due[wi] = cur.due_mask;
+      // a due server is finished now (queued) if its batch changes or carries a prefill; otherwise the
+      // iteration is only counted
+      const bool prefill_here = g < M && !((idle_word >> lane) & 1ull);
+      const bool event = due && (quads != 0 || ((join_word >> lane) & 1ull) || prefill_here || pend >= kMaxPend);
+      if (due && !event) L.pend[g] = static_cast<uint8_t>(pend + 1);
+      const uint64_t ev_mask = __ballot(event);
+      if (lane == 0 && !tail) {
+        L.bm_due[wi] = due_mask;
         L.bm_touch[wi] = 0;
-        L.bm_comp[wi] = done;
-        if (done) L.bm_idle[wi] |= done;
-        const uint64_t nj_word = cur.join_word & ~(cur.due_mask & ~later);
-        if (nj_word != cur.join_word) L.bm_join[wi] = nj_word;
+        L.bm_comp[wi] = 0;
       }
+      const int cnt = __popcll(ev_mask);
+      if (tail || nev + cnt > kEvPerWave) { drain_events(nev); nev = 0; }
+      if (tail) break;
+      if (event) {
+        const int slot = nev + __popcll(ev_mask & lanes_below());
+        ev_g[slot] = static_cast<uint32_t>(g);
+        ev_q[slot] = quads;
+      }
+      nev += cnt;
       PROF(4)
-    }
-    for (int e0 = 0; e0 < nev; e0 += 64) {   // the queued servers, one per lane
-      const int e = e0 + lane;
-      Leaving lv; lv.k = -1;
-      PrefillEnd pe; pe.done = false;
-      if (e < nev) finish_deferred(static_cast<int>(ev_g[e]), ev_q[e], lv, pe);
-      fold_leaving(lv);
-      fold_prefill_end(pe);
-    }
-    // fold this step's per-lane sums into the workgroup tallies
-    {
-      const uint32_t i0 = wave_sum32(lt.iters[0]), i1 = wave_sum32(lt.iters[1]);
-      const uint64_t b0 = wave_sum64(lt.busy[0]), b1 = wave_sum64(lt.busy[1]);
-      if (lane == 0) {
-        if (i0) { lds_add64(&L.tl[kMaxK * kNTally + SIM_G_ITERS_SOLO], i0); lds_add64(&L.tl[kMaxK * kNTally + SIM_G_BUSY_SOLO], b0); }
-        if (i1) { lds_add64(&L.tl[kMaxK * kNTally + SIM_G_ITERS_MIX], i1); lds_add64(&L.tl[kMaxK * kNTally + SIM_G_BUSY_MIX], b1); }
-      }
-#pragma unroll
-      for (int k = 0; k < kMaxK; ++k) {
-        if (k >= K) continue;
-        const uint64_t ts = wave_sum64(lt.tbt_sum[k]);
-        if (lane == 0 && ts) lds_add64(&L.tl[k * kNTally + SIM_T_TBT_SUM], ts);
-      }
     }
     PROF(5)
     __syncthreads();
@@ -882,6 +836,8 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           const uint64_t bit = 1ull << (g & 63);
           atomicAnd(reinterpret_cast<unsigned long long *>(&L.bm_idle[g >> 6]), ~bit);
           if (!(L.bm_busy[g >> 6] & bit)) atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_touch[g >> 6]), bit);
+          // at an iteration boundary the next iteration carries a chunk: tally the untallied ones first
+          else if ((L.bm_due[g >> 6] & bit) && L.pend[g]) atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_flush[g >> 6]), bit);
         }
         wave_sum_by_class(active, k, K, wait, &L.tl[SIM_T_WAIT_STEPS], kNTally);
         uint64_t even, odd;   // co-resident decodes switch solo -> mixed
@@ -921,9 +877,11 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
     PROF(8)
 
     // ================= 4. decode routing =================
-    // Each pass serves the servers at the lowest decode count of the group, in index order; the job
-    // of rank j in the decode buffer goes to the j-th of them. Every wave derives the pass parameters
-    // from the load histogram, so no thread has to broadcast them.
+    // Sequentially every job goes to the least-loaded feasible server, lowest index first: all servers with
+    // the lowest decode count l get one job in index order, then all servers with at most l+1, and so on.
+    // One pass here fills up to kRouteLevels such levels at once: job j falls into level t and has a rank
+    // there; it goes to the server of that rank among those with at most Lmin+t decodes, into slot Lmin+t.
+    // Every wave derives the pass parameters from the load histogram, so no thread has to broadcast them.
     {
       int jrem = L.cs[CS_DCOUNT], next = 0;
       const uint32_t dhead0 = static_cast<uint32_t>(L.cs[CS_DHEAD]);
@@ -933,38 +891,61 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
         if (lo >= hi) continue;
         for (;;) {
           if (jrem <= 0) break;
-          // lowest non-empty level below the cap, and the number of servers on it
-          int level = -1, cnt = 0;
-          for (int base = 0; base < capg && level < 0; base += 64) {
+          int lmin = -1;
+          for (int base = 0; base < capg && lmin < 0; base += 64) {
             const int l = base + lane;
-            const uint32_t c = l < capg ? L.lh[grp * kLoadBins + l] : 0u;
-            const uint64_t nz = __ballot(c != 0);
-            if (nz) {
-              const int first = __ffsll(static_cast<long long>(nz)) - 1;
-              level = base + first;
-              cnt = static_cast<int>(__builtin_amdgcn_readlane(c, first));
+            const uint64_t nz = __ballot(l < capg && L.lh[grp * kLoadBins + l] != 0);
+            if (nz) lmin = base + __ffsll(static_cast<long long>(nz)) - 1;
+          }
+          if (lmin < 0) break;
+          // levels of this pass: servers with at most lmin+t decodes, jobs taken and jobs before it
+          int nl = 0, csum = 0, rem_jobs = jrem;
+          int take_t[kRouteLevels], w_t[kRouteLevels];
+#pragma unroll
+          for (int t = 0; t < kRouteLevels; ++t) {
+            take_t[t] = 0; w_t[t] = 0;
+            if (nl == t && rem_jobs > 0 && lmin + t < capg) {
+              csum += static_cast<int>(L.lh[grp * kLoadBins + lmin + t]);
+              take_t[t] = csum < rem_jobs ? csum : rem_jobs;
+              w_t[t] = jrem - rem_jobs;
+              rem_jobs -= take_t[t];
+              nl = t + 1;
             }
           }
-          if (level < 0) break;
-          const int take = cnt < jrem ? cnt : jrem;
+          const int total = jrem - rem_jobs;
+          const int lmax = lmin + nl - 1;
+          int take_last = 0;
+#pragma unroll
+          for (int t = 0; t < kRouteLevels; ++t) if (t == nl - 1) take_last = take_t[t];
           for (int i = 0; i < nper; ++i) {
             const int gw = i * NT + wave_base;
             if (gw >= N) break;
             const int g = gw + lane;
-            const bool at_level = g >= lo && g < hi && L.loads[g] == level;
-            const uint64_t b = __ballot(at_level);
-            if (lane == 0) L.bm_lvl[gw >> 6] = b;
+            const int load = (g >= lo && g < hi) ? static_cast<int>(L.loads[g]) : 1 << 20;
+#pragma unroll
+            for (int t = 0; t < kRouteLevels; ++t) {
+              if (t < nl) {
+                const uint64_t b = __ballot(load <= lmin + t);
+                if (lane == 0) L.bm_lvl[t * nwords + (gw >> 6)] = b;
+              }
+            }
           }
           __syncthreads();
-          if (tid < 64) rank_bitmap(L.bm_lvl, L.pre, p.nwords);
+          for (int t = wave; t < nl; t += nwaves) rank_bitmap(L.bm_lvl + t * nwords, L.pre_lvl + t * nwords, nwords);
           __syncthreads();
-          for (int j0 = wave_base; j0 < take; j0 += NT) {   // wave-uniform trip count
+          for (int j0 = wave_base; j0 < total; j0 += NT) {   // wave-uniform trip count
             const int j = j0 + lane;
-            const bool active = j < take;
+            const bool active = j < total;
             int k = 0;
             bool has_prefill = false;
             if (active) {
-              const int g = select_bit(L.bm_lvl, L.pre, p.nwords, static_cast<uint32_t>(j));
+              int t = 0;
+#pragma unroll
+              for (int u = 1; u < kRouteLevels; ++u) if (u < nl && j >= w_t[u]) t = u;
+              int wt = w_t[0];
+#pragma unroll
+              for (int u = 1; u < kRouteLevels; ++u) wt = t == u ? w_t[u] : wt;
+              const int g = select_bit(L.bm_lvl + t * nwords, L.pre_lvl + t * nwords, nwords, static_cast<uint32_t>(j - wt));
               uint32_t pos = dhead0 + static_cast<uint32_t>(next + j);
               if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
               if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
@@ -973,17 +954,20 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
               const uint32_t Dl = static_cast<uint32_t>(jw >> 48) + 1;
               const uint64_t bit = 1ull << (g & 63);
               const bool busy = L.bm_busy[g >> 6] & bit;
-              const bool mid = busy && !(L.bm_due[g >> 6] & bit);   // joins at the next restart
-              const int nd = level;
+              const bool at_boundary = L.bm_due[g >> 6] & bit;
+              const bool mid = busy && !at_boundary;   // joins at the next restart
+              const int nd = lmin + t;                 // the server holds exactly this many decodes by now
               fin[static_cast<size_t>(g) * BS + nd] = L.iter[g] + Dl + (mid ? 1u : 0u);
               job[static_cast<size_t>(g) * BS + nd] = jw;
-              n_cls[g] += 1ull << (8 * k);
-              if (mid) {
-                n_join[g] += 1ull << (8 * k);
+              // several levels can reach the same server in one pass: its counts are updated atomically
+              atomicAdd(reinterpret_cast<unsigned long long *>(&n_cls[g]), 1ull << (8 * k));
+              // the new decode is not part of the iterations still to be tallied for this server
+              if (mid || (at_boundary && L.pend[g])) {
+                atomicAdd(reinterpret_cast<unsigned long long *>(&n_join[g]), 1ull << (8 * k));
                 atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_join[g >> 6]), bit);
+                if (!mid) atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_flush[g >> 6]), bit);
               }
-              L.loads[g] = static_cast<uint8_t>(nd + 1);
-              has_prefill = g < M && pk_rem(remptok[g]) != 0;
+              has_prefill = g < M && !(L.bm_idle[g >> 6] & bit);
               if (!busy) atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_touch[g >> 6]), bit);
             }
             const bool am = active && has_prefill, as = active && !has_prefill;
@@ -994,12 +978,24 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
             wave_count_by_class_i32(active, k, K, &L.cs[CS_QD], -1);
           }
           __syncthreads();
-          if (tid == 0) {   // `take` servers moved up one level
-            L.lh[grp * kLoadBins + level] -= static_cast<uint32_t>(take);
-            L.lh[grp * kLoadBins + level + 1] += static_cast<uint32_t>(take);
+          // every server with at most lmax decodes now holds lmax, plus one if the last level reached it
+          for (int i = 0; i < nper; ++i) {
+            const int gw = i * NT + wave_base;
+            if (gw >= N) break;
+            const int g = gw + lane;
+            const uint64_t word = L.bm_lvl[(nl - 1) * nwords + (gw >> 6)];
+            if ((word >> lane) & 1ull) {
+              const uint32_t rank = L.pre_lvl[(nl - 1) * nwords + (gw >> 6)] + static_cast<uint32_t>(__popcll(word & lanes_below()));
+              L.loads[g] = static_cast<uint8_t>(lmax + (rank < static_cast<uint32_t>(take_last) ? 1 : 0));
+            }
           }
-          jrem -= take;
-          next += take;
+          if (tid == 0) {
+            for (int t = 0; t + 1 < nl; ++t) L.lh[grp * kLoadBins + lmin + t] = 0;
+            L.lh[grp * kLoadBins + lmax] = static_cast<uint32_t>(csum - take_last);
+            L.lh[grp * kLoadBins + lmax + 1] += static_cast<uint32_t>(take_last);
+          }
+          jrem -= total;
+          next += total;
           __syncthreads();
         }
       }
@@ -1017,10 +1013,35 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
       const int gw = i * NT + wave_base;
       if (gw >= N) break;
       const int wi = gw >> 6;
-      const uint64_t due_word = L.bm_due[wi];
-      const uint64_t todo = due_word | L.bm_touch[wi];
-      if (todo == 0) continue;
       const int g = gw + lane;
+      const bool valid = g < N;
+      const uint64_t due_word = L.bm_due[wi], flush_word = L.bm_flush[wi];
+      const uint64_t todo = due_word | L.bm_touch[wi];
+      // untallied iterations are tallied before the batch changes, and all of them when the launch ends
+      const bool flush = valid && (((flush_word >> lane) & 1ull) || (last_step && L.pend[g] != 0));
+      const uint64_t flush_mask = __ballot(flush);
+      if (flush_mask) {
+        uint32_t m = 0;
+        int64_t d = 0;
+        uint64_t comp = 0;
+        if (flush) {
+          const uint64_t bit = 1ull << lane;
+          const uint64_t nc = n_cls[g];
+          const bool joined = L.bm_join[wi] & bit;
+          const uint64_t nj = joined ? n_join[g] : 0ull;
+          comp = bytes_sub(nc, nj);
+          d = p.c0 + p.cdec * static_cast<int64_t>(byte_sum(comp));   // untallied iterations never hold a chunk
+          m = L.pend[g];
+          L.pend[g] = 0;
+          if ((flush_word & bit) && joined) {   // the decodes placed at this boundary join the batch now
+            n_join[g] = 0;
+            atomicAnd(reinterpret_cast<unsigned long long *>(&L.bm_join[wi]), ~bit);
+          }
+        }
+        tally_iterations(lt, L.tbth, p.tbt_w, p.tbt_lo, K, m, d, false, comp);
+        if (lane == 0 && flush_word) L.bm_flush[wi] = 0;
+      }
+      if (todo == 0) continue;
       const uint64_t busy_word = L.bm_busy[wi];
       bool busy = (busy_word >> lane) & 1ull;
       if ((todo >> lane) & 1ull) {
@@ -1044,7 +1065,24 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
     }
     PROF(10)
 
-    // ================= 6. end-of-step occupancy integrals =================
+    // ================= 6. end-of-step sums =================
+    {
+      const uint32_t i0 = wave_sum32(lt.iters[0]), i1 = wave_sum32(lt.iters[1]);
+      const uint64_t b0 = wave_sum64(lt.busy[0]), b1 = wave_sum64(lt.busy[1]);
+      if (lane == 0) {
+        if (i0) { lds_add64(&L.tl[kMaxK * kNTally + SIM_G_ITERS_SOLO], i0); lds_add64(&L.tl[kMaxK * kNTally + SIM_G_BUSY_SOLO], b0); }
+        if (i1) { lds_add64(&L.tl[kMaxK * kNTally + SIM_G_ITERS_MIX], i1); lds_add64(&L.tl[kMaxK * kNTally + SIM_G_BUSY_MIX], b1); }
+      }
+      for (int k = 0; k < K; ++k) {
+        uint64_t v = 0;
+#pragma unroll
+        for (int kk = 0; kk < kMaxK; ++kk) v = k == kk ? lt.tbt_sum[kk] : v;
+        if (__ballot(v != 0)) {
+          const uint64_t ts = wave_sum64(v);
+          if (lane == 0) lds_add64(&L.tl[k * kNTally + SIM_T_TBT_SUM], ts);
+        }
+      }
+    }
     if (tid < K) {
       const int k = tid;
       L.tl[k * kNTally + SIM_T_SUM_QP] += static_cast<uint64_t>(L.cs[CS_QP + k]);
@@ -1056,26 +1094,18 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
     if (tid == 0) L.tl[kMaxK * kNTally + SIM_G_STEPS] += 1;
   }
   PROF_FLUSH
-
-  // ---- write out the cached time-between-tokens counts; the emitted-token tally is their total
-#pragma unroll
-  for (int k = 0; k < kMaxK; ++k) {
-    if (k >= K) continue;
-    if (lt.hist_cnt[0][k]) lds_add64(&L.tbth[k * p.tbt_w + lt.hist_bin[0]], lt.hist_cnt[0][k]);
-    if (lt.hist_cnt[1][k]) lds_add64(&L.tbth[k * p.tbt_w + lt.hist_bin[1]], lt.hist_cnt[1][k]);
-    if (lt.hist_cnt[2][k]) lds_add64(&L.tbth[k * p.tbt_w + lt.hist_bin[2]], lt.hist_cnt[2][k]);
-  }
   __syncthreads();
+
+  // ---- the emitted-token tally is the total of the time-between-tokens counts of this launch
   if (tid < K) {
     uint64_t tot = 0;
     for (int b = 0; b < p.tbt_w; ++b) tot += L.tbth[tid * p.tbt_w + b];
     L.tl[tid * kNTally + SIM_T_TOK_EMIT] += tot;
   }
+  if (tid < 8) L.acc[tid] = 0;
   __syncthreads();
 
   // ---- write the server clocks and the class state back; add this launch's tallies to the totals
-  if (tid < 8) L.acc[tid] = 0;
-  __syncthreads();
   for (int i = 0; i < nper; ++i) {
     const int g = i * NT + tid;
     if (g >= N) break;
