@@ -141,6 +141,7 @@ struct Lds {
   uint32_t *lh;       // [2][kLoadBins] servers per decode count: solo group, mixed group
   uint32_t *ev_g;     // [waves][kEvPerWave] servers queued for finishing, per wave
   uint32_t *ev_q;     // [waves][kEvPerWave] their slot-quad masks
+  uint8_t *stage;     // [waves][64] lanes of the due servers with decodes, of the round a wave has open
   uint32_t *t32;      // [N] low 32 bits of the end time of the running iteration
   uint32_t *iter;     // [N] completed iterations
   uint8_t *loads;     // [N] decodes per server
@@ -179,6 +180,7 @@ __host__ __device__ __forceinline__ Lds lds_carve(const Params &p, unsigned char
   GNR_TAKE(iter, uint32_t, p.N)
   GNR_TAKE(loads, uint8_t, p.N)
   GNR_TAKE(pend, uint8_t, p.N)
+  GNR_TAKE(stage, uint8_t, p.threads)
 #undef GNR_TAKE
   if (total) *total = off;
   return L;
@@ -194,11 +196,12 @@ size_t step_lds_bytes(const Params &p)
 int step_threads(int N)
 {
   int t = (N + 63) / 64 * 64;
-  // 512 threads leave each wave 256 registers; with 1024 the step kernel spills to scratch
+  // Sixteen waves per compute unit hide the most latency; the kernel is also built for 768 and 512 threads
+  // (more registers per lane), which measured slower on the large configurations.
 #ifdef GNR_MAX_THREADS
   return t > GNR_MAX_THREADS ? GNR_MAX_THREADS : t;
 #else
-  return t > 512 ? 512 : t;
+  return t > 1024 ? 1024 : t;
 #endif
 }
 
@@ -217,21 +220,31 @@ __device__ __forceinline__ uint32_t rank_bitmap(const uint64_t *bm, uint32_t *pr
   return running;
 }
 
-__device__ __forceinline__ uint64_t wave_sum64(uint64_t v)
+// Wave totals with data-parallel-primitive adds: four steps inside each row of 16 lanes, then the row
+// totals are passed on (row 0 -> 1, 2 -> 3, then 1 -> 2 and 3); lane 63 ends with the total, which is
+// returned as a wave-uniform value. All 64 lanes must be active.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_add(uint32_t v)
 {
-#pragma unroll
-  for (int d = 32; d > 0; d >>= 1) {
-    const uint32_t lo = __shfl_xor(static_cast<uint32_t>(v), d, 64);
-    const uint32_t hi = __shfl_xor(static_cast<uint32_t>(v >> 32), d, 64);
-    v += (static_cast<uint64_t>(hi) << 32) | lo;
-  }
-  return v;
+  return v + static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), CTRL, ROW_MASK, 0xF, false));
 }
 __device__ __forceinline__ uint32_t wave_sum32(uint32_t v)
 {
-#pragma unroll
-  for (int d = 32; d > 0; d >>= 1) v += __shfl_xor(v, d, 64);
-  return v;
+  v = dpp_add<0xB1, 0xF>(v);    // quad_perm [1,0,3,2]
+  v = dpp_add<0x4E, 0xF>(v);    // quad_perm [2,3,0,1]
+  v = dpp_add<0x141, 0xF>(v);   // row_half_mirror
+  v = dpp_add<0x140, 0xF>(v);   // row_mirror
+  v = dpp_add<0x142, 0xA>(v);   // row_bcast 15 into rows 1 and 3
+  v = dpp_add<0x143, 0xC>(v);   // row_bcast 31 into rows 2 and 3
+  return static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(v), 63));
+}
+// 64-bit total of values below 2^58: three 32-bit totals of 16-, 16- and 26-bit pieces.
+__device__ __forceinline__ uint64_t wave_sum64(uint64_t v)
+{
+  const uint64_t s0 = wave_sum32(static_cast<uint32_t>(v) & 0xFFFFu);
+  const uint64_t s1 = wave_sum32(static_cast<uint32_t>(v >> 16) & 0xFFFFu);
+  const uint64_t s2 = wave_sum32(static_cast<uint32_t>(v >> 32));
+  return s0 + (s1 << 16) + (s2 << 32);
 }
 
 // ---- wave-level folding of per-event class updates: lanes of one class are combined first, so that a
@@ -272,37 +285,30 @@ __device__ __forceinline__ uint32_t class_field(uint64_t even, uint64_t odd, int
 }
 
 // Per-lane sums of this step's iteration tallies; folded into the workgroup's totals once per step.
-struct LaneTallies {
-  uint32_t iters[2];   // [decode-only, with a prefill chunk]
-  uint64_t busy[2];
-  uint64_t tbt_sum[kMaxK];
-};
-
-// m executed iterations of duration d whose batch held the per-class decode counts `comp`.
-// The time-between-tokens histogram gets m*comp_k tokens in the bin of d: lanes that share a bin are
-// summed over the wave first. Uniform control flow; lanes without anything to tally pass m = 0.
-__device__ __forceinline__ void tally_iterations(LaneTallies &lt, uint64_t *tbth, int tbt_w, int tbt_lo, int K, uint32_t m,
+// m executed iterations of duration d whose batch held the per-class decode counts `comp`; lanes with
+// nothing to tally pass m = 0. Uniform control flow (all 64 lanes). The tallies every lane shares are summed
+// over the wave first (same-address LDS atomics serialise); the time-between-tokens histogram, whose bins
+// differ from lane to lane, gets m*comp_k tokens in the bin of d by LDS atomics directly.
+__device__ __forceinline__ void tally_iterations(uint64_t *tl, uint64_t *tbth, int tbt_w, int tbt_lo, int K, uint32_t m,
                                                  int64_t d, bool chunk, uint64_t comp)
 {
   if (__ballot(m != 0) == 0) return;
   const int lane = threadIdx.x & 63;
-  if (m) {
-    if (chunk) { lt.iters[1] += m; lt.busy[1] += static_cast<uint64_t>(m) * static_cast<uint64_t>(d); }
-    else { lt.iters[0] += m; lt.busy[0] += static_cast<uint64_t>(m) * static_cast<uint64_t>(d); }
+  const uint64_t md = static_cast<uint64_t>(m) * static_cast<uint64_t>(d);   // < 2^8 * 2^31
+  const uint32_t its = wave_sum32(chunk ? m << 16 : m);                      // m <= 255: both totals fit 16 bits
+  const uint64_t busy_solo = wave_sum64(chunk ? 0ull : md), busy_mix = wave_sum64(chunk ? md : 0ull);
+  if (lane == 0) {
+    if (its & 0xFFFFu) { lds_add64(&tl[kMaxK * kNTally + SIM_G_ITERS_SOLO], its & 0xFFFFu); lds_add64(&tl[kMaxK * kNTally + SIM_G_BUSY_SOLO], busy_solo); }
+    if (its >> 16) { lds_add64(&tl[kMaxK * kNTally + SIM_G_ITERS_MIX], its >> 16); lds_add64(&tl[kMaxK * kNTally + SIM_G_BUSY_MIX], busy_mix); }
   }
-  const uint64_t md = static_cast<uint64_t>(m) * static_cast<uint64_t>(d);
+  const int b = hbin(d) - tbt_lo;
 #pragma unroll
-  for (int k = 0; k < kMaxK; ++k) lt.tbt_sum[k] += static_cast<uint64_t>(byte_at(comp, k)) * md;
-  const int tb = m ? hbin(d) - tbt_lo : -1;
-  uint64_t todo = __ballot(m != 0);
-  while (todo) {
-    const int leader = __ffsll(static_cast<long long>(todo)) - 1;
-    const int b = __builtin_amdgcn_readlane(tb, leader);
-    const bool in = tb == b;
-    todo &= ~__ballot(in);
-    for (int k = 0; k < K; ++k) {
-      const uint32_t t = wave_sum32(in ? m * byte_at(comp, k) : 0u);
-      if (lane == 0 && t) lds_add64(&tbth[k * tbt_w + b], t);
+  for (int k = 0; k < kMaxK; ++k) {
+    if (k < K) {   // wave-uniform
+      const uint32_t c = m ? byte_at(comp, k) : 0u;
+      const uint64_t t = wave_sum64(static_cast<uint64_t>(c) * md);   // < 2^7 * 2^39
+      if (lane == 0 && t) lds_add64(&tl[k * kNTally + SIM_T_TBT_SUM], t);
+      if (c) lds_add64(&tbth[k * tbt_w + b], static_cast<uint64_t>(m) * c);
     }
   }
 }
@@ -346,7 +352,6 @@ __device__ __forceinline__ bool gate_before(const GateKey &x, int k1, const Gate
 
 // What finishing an iteration reports back for folding: the first decode that left the server and
 // the end of its prefill. Further decodes leaving in the same iteration are tallied directly.
-struct Leaving { int k; uint32_t P, D; int64_t e2e; bool mixed; };
 struct PrefillEnd { bool done; int k; uint32_t P; int64_t ttft; uint64_t nc; };
 
 // ------------------------------------------------------------------ step kernel ----
@@ -354,10 +359,27 @@ struct PrefillEnd { bool done; int k; uint32_t P; int64_t ttft; uint64_t nc; };
 // completion pass only counts them (`pend`); they are tallied, with their multiplicity, when the batch is
 // about to change: a decode leaves, a decode that joined mid-iteration becomes part of the batch, a prefill
 // is present, work is placed on a server that is at an iteration boundary, or the launch ends.
+// The arrays of the simulation state, handed to the step kernel by value: pointers that arrive as kernel
+// arguments are known to point to global memory, so their loads and stores are plain global accesses
+// (counted apart from LDS traffic) instead of generic ones that a wait on LDS would also wait for.
+struct StepArrays {
+  const uint32_t *arr_thr;
+  const uint16_t *len_tab;
+  int64_t *t_next;
+  uint32_t *iter, *remptok;
+  uint64_t *pf_job, *n_cls, *n_join;
+  uint32_t *fin;
+  uint64_t *job;
+  uint32_t *qring;
+  uint64_t *dring;
+  int32_t *cstate;
+  uint64_t *tally, *hist;
+};
+
 template <int MAXT>
-__global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict__ params, const uint32_t key0,
-                                                        const uint32_t key1, const uint32_t step_begin,
-                                                        const uint32_t n_steps)
+__global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict__ params, const StepArrays a,
+                                                        const uint32_t key0, const uint32_t key1,
+                                                        const uint32_t step_begin, const uint32_t n_steps)
 {
   const Params &p = *params;   // immutable after creation; read through the scalar cache on demand
   extern __shared__ __align__(16) unsigned char lds_raw[];
@@ -367,30 +389,31 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
   const int tid = threadIdx.x;
   const int NT = blockDim.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  // wave-uniform values are made scalar explicitly, so that loops and branches on them are scalar too
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int nwaves = NT >> 6;
-  const int wave_base = tid & ~63;
+  const int wave_base = wave << 6;
   const int K = p.K, N = p.N, B = p.B, M = p.M, BS = p.BS;
   const int nper = (N + NT - 1) / NT;
   const int nwords = p.nwords;
   const int nwords_m = (M + 63) >> 6;   // bitmap words that hold mixed-group servers
 
-  int64_t *t_next = p.t_next + static_cast<size_t>(r) * N;
-  uint32_t *iter_g = p.iter + static_cast<size_t>(r) * N;
-  uint32_t *remptok = p.remptok + static_cast<size_t>(r) * N;
-  uint64_t *pf_job = p.pf_job + static_cast<size_t>(r) * N;
-  uint64_t *n_cls = p.n_cls + static_cast<size_t>(r) * N;
-  uint64_t *n_join = p.n_join + static_cast<size_t>(r) * N;
-  uint32_t *fin = p.fin + static_cast<size_t>(r) * N * BS;
-  uint64_t *job = p.job + static_cast<size_t>(r) * N * BS;
-  uint32_t *qring = p.qring + static_cast<size_t>(r) * K * p.queue_cap;
-  uint64_t *dring = p.dring + static_cast<size_t>(r) * p.dbuf_cap;
-  uint64_t *hist = p.hist + static_cast<size_t>(r) * 3 * K * kNBin;
+  int64_t *t_next = a.t_next + static_cast<size_t>(r) * N;
+  uint32_t *iter_g = a.iter + static_cast<size_t>(r) * N;
+  uint32_t *remptok = a.remptok + static_cast<size_t>(r) * N;
+  uint64_t *pf_job = a.pf_job + static_cast<size_t>(r) * N;
+  uint64_t *n_cls = a.n_cls + static_cast<size_t>(r) * N;
+  uint64_t *n_join = a.n_join + static_cast<size_t>(r) * N;
+  uint32_t *fin = a.fin + static_cast<size_t>(r) * N * BS;
+  uint64_t *job = a.job + static_cast<size_t>(r) * N * BS;
+  uint32_t *qring = a.qring + static_cast<size_t>(r) * K * p.queue_cap;
+  uint64_t *dring = a.dring + static_cast<size_t>(r) * p.dbuf_cap;
+  uint64_t *hist = a.hist + static_cast<size_t>(r) * 3 * K * kNBin;
   uint32_t *ev_g = L.ev_g + wave * kEvPerWave;
   uint32_t *ev_q = L.ev_q + wave * kEvPerWave;
 
   // ---- load the replication's class state and rebuild the on-chip views of the server state
-  for (int i = tid; i < CS_WORDS; i += NT) L.cs[i] = p.cstate[static_cast<size_t>(r) * CS_WORDS + i];
+  for (int i = tid; i < CS_WORDS; i += NT) L.cs[i] = a.cstate[static_cast<size_t>(r) * CS_WORDS + i];
   for (int i = tid; i < kTallyWords; i += NT) L.tl[i] = 0;
   for (int i = tid; i < K * p.tbt_w; i += NT) L.tbth[i] = 0;
   for (int i = tid; i < SC_WORDS; i += NT) L.sc[i] = 0;
@@ -416,7 +439,6 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
     const int wi = (i * NT + wave_base) >> 6;
     if (lane == 0 && wi < nwords) { L.bm_idle[wi] = bi; L.bm_busy[wi] = bb; L.bm_join[wi] = bj; L.bm_flush[wi] = 0; }
   }
-  LaneTallies lt;
   __syncthreads();
 
   int64_t T = 0;
@@ -427,10 +449,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
     T = (static_cast<int64_t>(s) + 1) * p.dt;
     const uint32_t T32 = static_cast<uint32_t>(T);
     if (tid < 8) L.acc[tid] = 0;
-    lt.iters[0] = lt.iters[1] = 0; lt.busy[0] = lt.busy[1] = 0;
-#pragma unroll
-    for (int k = 0; k < kMaxK; ++k) lt.tbt_sum[k] = 0;
-    const uint32_t *thr = p.arr_thr + 3 * (p.mod_period > 0 ? static_cast<int64_t>(s % static_cast<uint64_t>(p.mod_period)) : 0);
+    const uint32_t *thr = a.arr_thr + 3 * (p.mod_period > 0 ? static_cast<int64_t>(s % static_cast<uint64_t>(p.mod_period)) : 0);
     const uint32_t thr0 = thr[0], thr1 = thr[1], thr2 = thr[2];
     __syncthreads();
 
@@ -456,13 +475,13 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
     //      that emitted their last token (slot quads flagged in the queue entry), advances the prefill.
     auto drain_events = [&](int nev) __attribute__((always_inline)) {
       for (int e0 = 0; e0 < nev; e0 += 64) {
+        PROF(4)
         const int e = e0 + lane;
         const bool active = e < nev;
         uint32_t m = 0;
         int64_t d = 0;
         bool chunk = false;
         uint64_t comp = 0;
-        Leaving lv; lv.k = -1; lv.P = lv.D = 0; lv.e2e = 0; lv.mixed = false;
         PrefillEnd pe; pe.done = false; pe.k = 0; pe.P = 0; pe.ttft = 0; pe.nc = 0;
         if (active) {
           const int g = static_cast<int>(ev_g[e]);
@@ -502,18 +521,16 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
                   const uint32_t stamp = static_cast<uint32_t>(jw) & 0x1FFFFFFFu;
                   const uint32_t Pl = (static_cast<uint32_t>(jw >> 32) & 0xFFFFu) + 1, Dl = static_cast<uint32_t>(jw >> 48) + 1;
                   const int64_t e2e = tn - (static_cast<int64_t>(stamp) + 1) * p.dt;
-                  if (lv.k < 0) { lv.k = k; lv.P = Pl; lv.D = Dl; lv.e2e = e2e; lv.mixed = mixed_now; }
-                  else {   // a second decode leaving the same server in the same iteration: rare, tallied directly
-                    lds_add64(&L.tl[k * kNTally + (mixed_now ? SIM_T_S_DM : SIM_T_S_DS)], 1);
-                    atomicSub(&L.cs[(mixed_now ? CS_YM : CS_YS) + k], 1);
-                    lds_add64(&L.tl[k * kNTally + SIM_T_TOKP_DEC], Pl);
-                    lds_add64(&L.tl[k * kNTally + SIM_T_TOKD_DEC], Dl);
-                    lds_add64(&L.tl[k * kNTally + SIM_T_E2E_SUM], static_cast<uint64_t>(e2e));
-                  }
+                  lds_add64(&L.tl[k * kNTally + (mixed_now ? SIM_T_S_DM : SIM_T_S_DS)], 1);
+                  atomicSub(&L.cs[(mixed_now ? CS_YM : CS_YS) + k], 1);
+                  lds_add64(&L.tl[k * kNTally + SIM_T_TOKP_DEC], Pl);
+                  lds_add64(&L.tl[k * kNTally + SIM_T_TOKD_DEC], Dl);
+                  lds_add64(&L.tl[k * kNTally + SIM_T_E2E_SUM], static_cast<uint64_t>(e2e));
                   atomicAdd(reinterpret_cast<unsigned long long *>(&hist[(1 * K + k) * kNBin + hbin(e2e)]), 1ull);
                   nc -= 1ull << (8 * k);
                   --nd;
                   if (j < nd) { frow[j] = frow[nd]; jrow[j] = jrow[nd]; }
+                  frow[nd] = 0;   // a vacated slot must never match a later iteration index
                 }
               }
             }
@@ -547,140 +564,163 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
             atomicAnd(reinterpret_cast<unsigned long long *>(&L.bm_join[g >> 6]), ~bit);
           }
         }
-        tally_iterations(lt, L.tbth, p.tbt_w, p.tbt_lo, K, m, d, chunk, comp);
-        // class-level effects of the decodes that left (at most one per lane here), folded over the wave
-        {
-          const bool any = lv.k >= 0;
-          if (__ballot(any)) {
-            const bool am = any && lv.mixed, as = any && !lv.mixed;
-            wave_count_by_class(am, lv.k, K, &L.tl[SIM_T_S_DM], kNTally);
-            wave_count_by_class(as, lv.k, K, &L.tl[SIM_T_S_DS], kNTally);
-            wave_count_by_class_i32(am, lv.k, K, &L.cs[CS_YM], -1);
-            wave_count_by_class_i32(as, lv.k, K, &L.cs[CS_YS], -1);
-            wave_sum_by_class(any, lv.k, K, lv.P, &L.tl[SIM_T_TOKP_DEC], kNTally);
-            wave_sum_by_class(any, lv.k, K, lv.D, &L.tl[SIM_T_TOKD_DEC], kNTally);
-            wave_sum_by_class(any, lv.k, K, static_cast<uint64_t>(lv.e2e), &L.tl[SIM_T_E2E_SUM], kNTally);
-          }
-        }
-        // prefills that ended: completion counts, recognised prompt tokens, time to first token;
-        // the co-resident decodes switch mixed -> solo
-        if (__ballot(pe.done)) {
-          wave_count_by_class(pe.done, pe.k, K, &L.tl[SIM_T_S_P], kNTally);
-          wave_count_by_class_i32(pe.done, pe.k, K, &L.cs[CS_X], -1);
-          wave_sum_by_class(pe.done, pe.k, K, pe.P, &L.tl[SIM_T_TOKP_PRE], kNTally);
-          wave_sum_by_class(pe.done, pe.k, K, static_cast<uint64_t>(pe.ttft), &L.tl[SIM_T_TTFT_SUM], kNTally);
-          uint64_t even, odd;
-          wave_sum_bytes(pe.done ? pe.nc : 0ull, even, odd);
-          if (lane == 0)
-            for (int c = 0; c < K; ++c) {
-              const int v = static_cast<int>(class_field(even, odd, c));
-              if (v) {
-                lds_add64(&L.tl[c * kNTally + SIM_T_M_MS], static_cast<uint64_t>(v));
-                atomicSub(&L.cs[CS_YM + c], v);
-                atomicAdd(&L.cs[CS_YS + c], v);
-              }
+        PROF(11)
+        tally_iterations(L.tl, L.tbth, p.tbt_w, p.tbt_lo, K, m, d, chunk, comp);
+        PROF(12)
+        // a prefill that ended: completion count, recognised prompt tokens, time to first token; the
+        // co-resident decodes switch mixed -> solo
+        if (pe.done) {
+          lds_add64(&L.tl[pe.k * kNTally + SIM_T_S_P], 1);
+          atomicSub(&L.cs[CS_X + pe.k], 1);
+          lds_add64(&L.tl[pe.k * kNTally + SIM_T_TOKP_PRE], pe.P);
+          lds_add64(&L.tl[pe.k * kNTally + SIM_T_TTFT_SUM], static_cast<uint64_t>(pe.ttft));
+#pragma unroll
+          for (int c = 0; c < kMaxK; ++c) {
+            const int v = static_cast<int>(byte_at(pe.nc, c));
+            if (v) {
+              lds_add64(&L.tl[c * kNTally + SIM_T_M_MS], static_cast<uint64_t>(v));
+              atomicSub(&L.cs[CS_YM + c], v);
+              atomicAdd(&L.cs[CS_YS + c], v);
             }
+          }
         }
       }
     };
 
-    // ---- completion pass over this wave's rounds of 64 servers
-    int nev = 0;   // servers queued by this wave (wave-uniform)
-    PROF(1)
-    for (int i = 0;; ++i) {
-      const int gw = i * NT + wave_base;          // first server of this wave's 64-server block
-      const bool tail = i >= nper || gw >= N;     // wave-uniform: one extra trip finishes what is still queued
-      const int wi = tail ? 0 : gw >> 6;
-      const int g = gw + lane;
-      const bool valid = !tail && g < N;
-      const uint64_t busy_word = tail ? 0ull : L.bm_busy[wi], join_word = tail ? 0ull : L.bm_join[wi];
-      const uint64_t idle_word = tail ? 0ull : L.bm_idle[wi];
-      const uint32_t t32 = valid ? L.t32[g] : 0u;
-      const bool due = valid && ((busy_word >> lane) & 1ull) && static_cast<int32_t>(t32 - T32) <= 0;
-      const uint64_t due_mask = __ballot(due);
-      uint32_t it = 0;
-      int nd = 0, pend = 0;
-      if (due) {
-        it = L.iter[g] + 1;
-        L.iter[g] = it;
-        nd = L.loads[g];
-        pend = L.pend[g];
-      }
-      PROF(2)
-      uint32_t quads = 0;   // owner lane: bit q set <=> one of slots 4q..4q+3 finishes now
-      if (due_mask) {
-        // ---- cooperative scan of the slot rows: half a wave reads one server's row (4 words per lane)
-        uint64_t todo = __ballot(due && nd > 0);
-        const int q = lane & 31;
-        const bool hi = lane >= 32;
-        bool first_batch = true;
-        do {
-          int la[8], lb[8];
-          bool va[8], vb[8];
+    // ---- completion pass, one round of 64 servers (one per lane) at a time.
+    //      open_round: due test; the due servers that hold decodes are listed in `stage`.
+    //      issue: eight lanes read one server's slot row, 16 bytes per lane and load, the first 64 slots in
+    //      two loads (rows with more decodes take a second pass for slots 64..127).
+    //      process: the finish words are compared with the server's iteration index; the hit masks travel back
+    //      to the owning lanes. finalize: a server whose batch changes, or that carries a prefill, is queued for
+    //      finishing; for any other the iteration is only counted. The loads of the next round travel while
+    //      the queue is drained and the next round's arrivals are drawn.
+    //      Slots beyond a server's decode count never hold a future iteration index (they are cleared when
+    //      vacated), so the comparison needs no occupancy mask.
+    {
+      constexpr int Q = 4;   // groups of eight servers per batch
+      const int l8 = lane & 7, grp = lane >> 3;
+      const uint64_t below = lanes_below();
+      uint8_t *stage = L.stage + wave * 64;
+      const int nrounds = wave_base < N ? (N - wave_base + NT - 1) / NT : 0;   // wave-uniform
+      int nev = 0;          // servers queued by this wave (wave-uniform)
+      int ne = 0;           // servers listed for the open round (wave-uniform)
+      bool wide = false;    // a listed server holds more than 64 decodes (wave-uniform)
+      bool o_due = false, o_must = false, o_scan = false;   // owner-lane state of the open round
+      int o_rank = 0, o_nd = 0, o_pend = 0;
+      uint32_t o_it = 0, o_q = 0;
+      uint4 v[Q][2];
+      uint32_t vit[Q];
+
+      auto open_round = [&](int i) __attribute__((always_inline)) {
+        const int gw = i * NT + wave_base;
+        const int wi = gw >> 6;
+        const int g = gw + lane;
+        const uint64_t lbit = 1ull << lane;
+        const bool busy = g < N && (L.bm_busy[wi] & lbit);
+        o_due = busy && static_cast<int32_t>(L.t32[g] - T32) <= 0;
+        o_it = 0; o_nd = 0; o_pend = 0; o_q = 0;
+        if (o_due) {
+          o_it = L.iter[g] + 1;
+          L.iter[g] = o_it;
+          o_nd = L.loads[g];
+          o_pend = L.pend[g];
+        }
+        const bool prefill_here = g < M && !(L.bm_idle[wi] & lbit);
+        o_must = o_due && ((L.bm_join[wi] & lbit) || prefill_here || o_pend >= kMaxPend);
+        o_scan = o_due && o_nd > 0;
+        const uint64_t dm = __ballot(o_due), sm = __ballot(o_scan);
+        wide = __ballot(o_nd > 64) != 0;
+        o_rank = __popcll(sm & below);
+        ne = __popcll(sm);
+        if (o_scan) stage[o_rank] = static_cast<uint8_t>(lane);
+        if (lane == 0) {
+          L.bm_due[wi] = dm;
+          L.bm_touch[wi] = 0;
+          L.bm_comp[wi] = 0;
+        }
+      };
+      // half 0: slots 0..63 of each listed row, half 1: slots 64..127
+      auto issue = [&](int i, int b, int half) __attribute__((always_inline)) {
+        const uint32_t gw = static_cast<uint32_t>(i * NT + wave_base);
 #pragma unroll
-          for (int u = 0; u < 8; ++u) {
-            va[u] = todo != 0;
-            la[u] = va[u] ? __ffsll(static_cast<long long>(todo)) - 1 : 0;
-            if (va[u]) todo &= todo - 1;
-            vb[u] = todo != 0;
-            lb[u] = vb[u] ? __ffsll(static_cast<long long>(todo)) - 1 : 0;
-            if (vb[u]) todo &= todo - 1;
-          }
-          uint4 v[8];
-          uint32_t its[8];
-          int nds[8];
-#pragma unroll
-          for (int u = 0; u < 8; ++u) {
-            const uint32_t ita = __builtin_amdgcn_readlane(it, la[u]), itb = __builtin_amdgcn_readlane(it, lb[u]);
-            const int nda = __builtin_amdgcn_readlane(nd, la[u]), ndb = __builtin_amdgcn_readlane(nd, lb[u]);
-            const bool on = hi ? vb[u] : va[u];
-            its[u] = hi ? itb : ita;
-            nds[u] = on ? (hi ? ndb : nda) : 0;
-            const int gs = gw + (hi ? lb[u] : la[u]);
-            v[u] = make_uint4(0u, 0u, 0u, 0u);
-            if (4 * q < nds[u]) v[u] = *reinterpret_cast<const uint4 *>(fin + static_cast<size_t>(gs) * BS + 4 * q);
-          }
-          if (first_batch) {   // the arrival draws of this round run while the first rows travel
-            if (valid) arrivals(g);
-            first_batch = false;
-          }
-#pragma unroll
-          for (int u = 0; u < 8; ++u) {
-            const int left = nds[u] - 4 * q;   // occupied words of this lane's quad
-            const bool m = (left > 0 && v[u].x == its[u]) || (left > 1 && v[u].y == its[u]) ||
-                           (left > 2 && v[u].z == its[u]) || (left > 3 && v[u].w == its[u]);
-            const uint64_t hit = __ballot(m);
-            if (hit) {
-              if (va[u] && lane == la[u]) quads = static_cast<uint32_t>(hit);
-              if (vb[u] && lane == lb[u]) quads = static_cast<uint32_t>(hit >> 32);
+        for (int t = 0; t < Q; ++t) {
+          v[t][0] = v[t][1] = make_uint4(0u, 0u, 0u, 0u);
+          vit[t] = 0xFFFFFFFFu;
+          const int p0 = 8 * (b * Q + t);
+          if (p0 < ne) {   // wave-uniform
+            const int pidx = p0 + grp;
+            const bool ok = pidx < ne;
+            const int sid = ok ? stage[pidx] : 0;
+            const uint32_t its = __shfl(o_it, sid, 64);
+            const int nds = __shfl(o_nd, sid, 64);
+            if (ok) {
+              vit[t] = its;
+              const int q0 = 16 * half + l8;   // this lane's quads of the row: q0 and q0 + 8
+              const uint32_t off = (gw + static_cast<uint32_t>(sid)) * static_cast<uint32_t>(BS) + 4u * q0;
+              if (4 * q0 < nds) v[t][0] = *reinterpret_cast<const uint4 *>(fin + off);
+              if (4 * q0 + 32 < nds) v[t][1] = *reinterpret_cast<const uint4 *>(fin + off + 32u);
             }
           }
-        } while (todo);
-      } else if (valid) {
-        arrivals(g);
+        }
+      };
+      auto process = [&](int b, int half) __attribute__((always_inline)) {
+#pragma unroll
+        for (int t = 0; t < Q; ++t) {
+          const int p0 = 8 * (b * Q + t);
+          if (p0 < ne) {   // wave-uniform
+            const uint32_t it = vit[t];
+            const bool m0 = v[t][0].x == it || v[t][0].y == it || v[t][0].z == it || v[t][0].w == it;
+            const bool m1 = v[t][1].x == it || v[t][1].y == it || v[t][1].z == it || v[t][1].w == it;
+            if (__ballot(m0 || m1)) {   // a decode emits its last token: rare
+              const uint64_t bal0 = __ballot(m0), bal1 = __ballot(m1);
+              const int d = o_rank - p0;
+              if (o_scan && static_cast<unsigned>(d) < 8u) {
+                const uint32_t h = (static_cast<uint32_t>(bal0 >> (8 * d)) & 0xFFu) |
+                                   ((static_cast<uint32_t>(bal1 >> (8 * d)) & 0xFFu) << 8);
+                o_q |= h << (16 * half);
+              }
+            }
+          }
+        }
+      };
+      auto finalize = [&](int i) __attribute__((always_inline)) {
+        const int g = i * NT + wave_base + lane;
+        const bool event = o_due && (o_must || o_q != 0);
+        if (o_due && !event) L.pend[g] = static_cast<uint8_t>(o_pend + 1);
+        const uint64_t evm = __ballot(event);
+        if (evm) {
+          if (event) {
+            const int slot = nev + __popcll(evm & below);
+            ev_g[slot] = static_cast<uint32_t>(g);
+            ev_q[slot] = o_q;
+          }
+          nev += __popcll(evm);
+        }
+      };
+
+      PROF(1)
+      if (nrounds > 0) { open_round(0); issue(0, 0, 0); }
+      for (int i = 0; i < nrounds; ++i) {
+        PROF(2)
+        {
+          const int g = i * NT + wave_base + lane;
+          if (g < N) arrivals(g);
+        }
+        PROF(3)
+        process(0, 0);
+        for (int b = 1; 8 * Q * b < ne; ++b) { issue(i, b, 0); process(b, 0); }
+        if (wide)
+          for (int b = 0; 8 * Q * b < ne; ++b) { issue(i, b, 1); process(b, 1); }
+        finalize(i);
+        if (i + 1 < nrounds) { open_round(i + 1); issue(i + 1, 0, 0); }
+        PROF(2)
+        if (nev > kEvPerWave - 64 || i + 1 == nrounds) {
+          drain_events(nev);
+          nev = 0;
+        }
+        PROF(4)
       }
-      PROF(3)
-      // a due server is finished now (queued) if its batch changes or carries a prefill; otherwise the
-      // iteration is only counted
-      const bool prefill_here = g < M && !((idle_word >> lane) & 1ull);
-      const bool event = due && (quads != 0 || ((join_word >> lane) & 1ull) || prefill_here || pend >= kMaxPend);
-      if (due && !event) L.pend[g] = static_cast<uint8_t>(pend + 1);
-      const uint64_t ev_mask = __ballot(event);
-      if (lane == 0 && !tail) {
-        L.bm_due[wi] = due_mask;
-        L.bm_touch[wi] = 0;
-        L.bm_comp[wi] = 0;
-      }
-      const int cnt = __popcll(ev_mask);
-      if (tail || nev + cnt > kEvPerWave) { drain_events(nev); nev = 0; }
-      if (tail) break;
-      if (event) {
-        const int slot = nev + __popcll(ev_mask & lanes_below());
-        ev_g[slot] = static_cast<uint32_t>(g);
-        ev_q[slot] = quads;
-      }
-      nev += cnt;
-      PROF(4)
     }
     PROF(5)
     __syncthreads();
@@ -827,8 +867,8 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           wait = static_cast<uint64_t>(s - stamp);
           uint32_t w[4];
           philox4x32_10(key0, key1, s, 1u, static_cast<uint32_t>(g), static_cast<uint32_t>(r), w);
-          const uint32_t Pl = p.len_tab[(static_cast<size_t>(k) * 2 + 0) * kTableSize + (w[0] >> 16)];
-          const uint32_t Dl = p.len_tab[(static_cast<size_t>(k) * 2 + 1) * kTableSize + (w[1] >> 16)];
+          const uint32_t Pl = a.len_tab[(static_cast<size_t>(k) * 2 + 0) * kTableSize + (w[0] >> 16)];
+          const uint32_t Dl = a.len_tab[(static_cast<size_t>(k) * 2 + 1) * kTableSize + (w[1] >> 16)];
           pf_job[g] = static_cast<uint64_t>(stamp) | (static_cast<uint64_t>(k) << 29) |
                       (static_cast<uint64_t>(Pl - 1) << 32) | (static_cast<uint64_t>(Dl - 1) << 48);
           // an idle prefill slot implies that the running iteration holds no chunk
@@ -1038,7 +1078,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
             atomicAnd(reinterpret_cast<unsigned long long *>(&L.bm_join[wi]), ~bit);
           }
         }
-        tally_iterations(lt, L.tbth, p.tbt_w, p.tbt_lo, K, m, d, false, comp);
+        tally_iterations(L.tl, L.tbth, p.tbt_w, p.tbt_lo, K, m, d, false, comp);
         if (lane == 0 && flush_word) L.bm_flush[wi] = 0;
       }
       if (todo == 0) continue;
@@ -1066,23 +1106,6 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
     PROF(10)
 
     // ================= 6. end-of-step sums =================
-    {
-      const uint32_t i0 = wave_sum32(lt.iters[0]), i1 = wave_sum32(lt.iters[1]);
-      const uint64_t b0 = wave_sum64(lt.busy[0]), b1 = wave_sum64(lt.busy[1]);
-      if (lane == 0) {
-        if (i0) { lds_add64(&L.tl[kMaxK * kNTally + SIM_G_ITERS_SOLO], i0); lds_add64(&L.tl[kMaxK * kNTally + SIM_G_BUSY_SOLO], b0); }
-        if (i1) { lds_add64(&L.tl[kMaxK * kNTally + SIM_G_ITERS_MIX], i1); lds_add64(&L.tl[kMaxK * kNTally + SIM_G_BUSY_MIX], b1); }
-      }
-      for (int k = 0; k < K; ++k) {
-        uint64_t v = 0;
-#pragma unroll
-        for (int kk = 0; kk < kMaxK; ++kk) v = k == kk ? lt.tbt_sum[kk] : v;
-        if (__ballot(v != 0)) {
-          const uint64_t ts = wave_sum64(v);
-          if (lane == 0) lds_add64(&L.tl[k * kNTally + SIM_T_TBT_SUM], ts);
-        }
-      }
-    }
     if (tid < K) {
       const int k = tid;
       L.tl[k * kNTally + SIM_T_SUM_QP] += static_cast<uint64_t>(L.cs[CS_QP + k]);
@@ -1120,8 +1143,8 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
       }
     }
   }
-  for (int i = tid; i < CS_WORDS; i += NT) p.cstate[static_cast<size_t>(r) * CS_WORDS + i] = L.cs[i];
-  uint64_t *gt = p.tally + static_cast<size_t>(r) * kTallyWords;
+  for (int i = tid; i < CS_WORDS; i += NT) a.cstate[static_cast<size_t>(r) * CS_WORDS + i] = L.cs[i];
+  uint64_t *gt = a.tally + static_cast<size_t>(r) * kTallyWords;
   for (int i = tid; i < kTallyWords; i += NT) {
     if (i == kMaxK * kNTally + SIM_G_OVERFLOW) gt[i] |= L.tl[i]; else gt[i] += L.tl[i];
   }
@@ -1143,6 +1166,7 @@ __global__ void gnr_reset_kernel(const Params p, const int reps)
   for (size_t i = t0; i < n_srv; i += stride) {
     p.t_next[i] = kIdle; p.iter[i] = 0; p.remptok[i] = 0; p.pf_job[i] = 0; p.n_cls[i] = 0; p.n_join[i] = 0;
   }
+  for (size_t i = t0; i < n_srv * p.BS; i += stride) p.fin[i] = 0;   // free slots never match an iteration index
   for (size_t i = t0; i < static_cast<size_t>(reps) * CS_WORDS; i += stride) p.cstate[i] = 0;
   for (size_t i = t0; i < static_cast<size_t>(reps) * kTallyWords; i += stride) p.tally[i] = 0;
   for (size_t i = t0; i < static_cast<size_t>(reps) * 3 * p.K * kNBin; i += stride) p.hist[i] = 0;
@@ -1250,13 +1274,15 @@ int launch_reset(const Params &p, int reps, void *stream)
 int launch_steps(const Params &p, int reps, int threads, size_t lds_bytes, uint32_t step_begin, uint32_t n_steps,
                  void *stream)
 {
-  auto kernel = threads > 512 ? gnr_step_kernel<1024> : gnr_step_kernel<512>;
+  auto kernel = threads > 768 ? gnr_step_kernel<1024> : threads > 512 ? gnr_step_kernel<768> : gnr_step_kernel<512>;
   if (lds_bytes > 64 * 1024) {   // more than the default dynamic LDS limit has to be asked for
     const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes));
     if (e != hipSuccess) return SIM_EHIP;
   }
-  hipLaunchKernelGGL(kernel, dim3(reps), dim3(threads), lds_bytes, static_cast<hipStream_t>(stream), p.self, p.key0,
+  const StepArrays a = {p.arr_thr, p.len_tab, p.t_next, p.iter, p.remptok, p.pf_job, p.n_cls, p.n_join,
+                        p.fin,     p.job,     p.qring,  p.dring, p.cstate, p.tally,  p.hist};
+  hipLaunchKernelGGL(kernel, dim3(reps), dim3(threads), lds_bytes, static_cast<hipStream_t>(stream), p.self, a, p.key0,
                      p.key1, step_begin, n_steps);
   return hip_ok(hipGetLastError());
 }
