@@ -20,14 +20,24 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 
 
-def algorithmic_bytes(t0, g0, t1, g1, slots):
-    """Bytes the step kernel must move for the work done between two tally read-outs.
+# HBM traffic of one step-kernel launch of the default run, from hardware counters (FETCH_SIZE + WRITE_SIZE,
+# each scaled by what the same counter reads for a device copy of known size). Valid only for the kernel source
+# it was measured on: the hash below is compared with the current source and the figure dropped on a mismatch.
+TRAFFIC = {"kernel_sha256": None, "bytes_per_launch": None}
 
-    An executed iteration reads the server's per-class decode counts (8 B) and scans one 4-byte
-    completion word per occupied decode slot; an iteration that holds a prefill chunk also reads and
-    writes the prefill word (8 B). Every admission, prefill completion, decode placement and decode
-    completion moves about 32 B of request words and ring entries. Server clocks and iteration
-    counters stay in LDS during a launch and cost no HBM bytes per step.
+
+def algorithmic_bytes(t0, g0, t1, g1, slots):
+    """Bytes the method moves for the work done between two tally read-outs.
+
+    Per server-step slot: 8 B to read the server's clock (is it due?); for a due server 24 B for the
+    rest of its record plus one 4-byte finish word per occupied decode slot, and 32 B to write the
+    record back; about 32 B of request words and ring entries per admission, placement and completion.
+    With f = executed iterations per slot, n = occupied decode slots per executed iteration and
+    e = events per slot this is 8 + f*(24 + 4n) + f*32 + e*32 bytes per slot.
+
+    The second figure is what this kernel has to move given that server clocks, iteration counters and
+    decode counts stay in LDS for a whole launch: the finish words of the due servers, the prefill
+    word of iterations that carry a chunk, and the event traffic.
     """
     from paper_2602_02987_amd.binding import GLOBAL, TALLY
     ti = {n: i for i, n in enumerate(TALLY)}
@@ -35,11 +45,21 @@ def algorithmic_bytes(t0, g0, t1, g1, slots):
     d = (t1.astype("float64") - t0.astype("float64")).sum(axis=0)
     it_mix = float(g1[gi["ITERS_MIX"]]) - float(g0[gi["ITERS_MIX"]])
     iters = it_mix + float(g1[gi["ITERS_SOLO"]]) - float(g0[gi["ITERS_SOLO"]])
-    scanned = d[ti["TOK_EMIT"]]
+    scanned = d[ti["TOK_EMIT"]]   # every occupied decode slot of an executed iteration emits one token
     events = d[ti["U_P"]] + d[ti["S_P"]] + d[ti["U_DM"]] + d[ti["U_DS"]] + d[ti["S_DM"]] + d[ti["S_DS"]]
-    total = 8.0 * iters + 8.0 * it_mix + 4.0 * scanned + 32.0 * events
+    total = 8.0 * slots + (24.0 + 32.0) * iters + 4.0 * scanned + 32.0 * events
+    on_chip_records = 4.0 * scanned + 16.0 * it_mix + 32.0 * events
     return total, dict(due_fraction=iters / slots, decodes_per_iteration=scanned / max(iters, 1.0),
-                       events_per_slot=events / slots, bytes_per_slot=total / slots)
+                       events_per_slot=events / slots, bytes_per_slot=total / slots,
+                       bytes_per_slot_with_records_in_lds=on_chip_records / slots)
+
+
+def measured_traffic():
+    import hashlib
+    src = os.path.join(ROOT, "paper_2602_02987_amd", "csrc", "gnr_kernels.hip")
+    with open(src, "rb") as fh:
+        sha = hashlib.sha256(fh.read()).hexdigest()
+    return TRAFFIC["bytes_per_launch"] if TRAFFIC["kernel_sha256"] == sha else None
 
 
 def _oracle_worker(args):
@@ -81,6 +101,9 @@ def main():
     ap.add_argument("--servers", type=int, default=0, help="override N (0 = the configuration's own)")
     ap.add_argument("--replications", type=int, default=0)
     ap.add_argument("--oracle-steps", type=int, default=1500, help="0 skips the CPU baseline")
+    ap.add_argument("--calibration-copy-mib", type=int, default=0,
+                    help="also run one device-to-device copy of this size before the timed region "
+                         "(a kernel of known traffic to scale hardware counters with)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (replications are independent and would shard "
@@ -111,6 +134,12 @@ def main():
         sim.run(args.preload % args.sim_steps)
     for _ in range(args.warmup):
         sim.run(args.sim_steps)
+    if args.calibration_copy_mib:
+        src = torch.zeros(args.calibration_copy_mib << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     torch.cuda.synchronize()
     sim.kernel_time(reset=True)
     K = cfg.K
@@ -145,7 +174,7 @@ def main():
                    "executed_iterations_per_s": iters / wall,
                    "overflow": bool(st1["overflow"])},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(),
                      "kernel": "gnr_step_kernel", "launches": launches, "avg_launch_ms": per_launch_ms,
                      "algorithmic_bytes_per_launch": total_bytes / max(launches, 1), **shape},
     }

@@ -227,6 +227,7 @@ int sim_create(const sim_config *cfg, int max_replications, void *dev_workspace,
   for (int k = 0; k < cfg->K; ++k) {
     p.nx[k] = static_cast<double>(cfg->N) * cfg->x_star[k];
     p.invx[k] = cfg->x_star[k] > 0.0 ? 1.0 / cfg->x_star[k] : 0.0;
+    p.xstar[k] = cfg->x_star[k];
     p.nq[k] = static_cast<double>(cfg->N) * cfg->qp_star[k];
     p.prio[k] = cfg->cls[k].priority;
   }

@@ -40,7 +40,7 @@ struct Params {
   uint32_t queue_cap, dbuf_cap;
   int64_t c0, cpre, cdec, dt;
   int64_t mod_period;
-  double nx[kMaxK], invx[kMaxK], nq[kMaxK], prio[kMaxK];
+  double nx[kMaxK], invx[kMaxK], xstar[kMaxK], nq[kMaxK], prio[kMaxK];   // n x*, 1/x*, x*, n q*, priority index
   uint32_t cls_thr[kMaxK];
   // tables (device)
   const uint32_t *arr_thr;    // [rows][3]

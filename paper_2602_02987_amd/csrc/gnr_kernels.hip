@@ -79,14 +79,22 @@ __device__ __forceinline__ int select_bit(const uint64_t *bm, const uint32_t *pr
 
 __device__ __forceinline__ uint64_t lanes_below() { return (1ull << (threadIdx.x & 63)) - 1ull; }
 
+// Inclusive prefix sum over the wave with data-parallel-primitive adds: shifts by 1, 2, 4 and 8 inside each
+// row of 16 lanes, then the row totals are passed on (row 0 -> 1, 2 -> 3, then 1 -> 2 and 3). All 64 lanes
+// must be active.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_add(uint32_t v)
+{
+  return v + static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), CTRL, ROW_MASK, 0xF, false));
+}
 __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v)
 {
-  const int lane = threadIdx.x & 63;
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    const uint32_t o = __shfl_up(v, d, 64);
-    if (lane >= d) v += o;
-  }
+  v = dpp_add<0x111, 0xF>(v);   // row_shr 1
+  v = dpp_add<0x112, 0xF>(v);   // row_shr 2
+  v = dpp_add<0x114, 0xF>(v);   // row_shr 4
+  v = dpp_add<0x118, 0xF>(v);   // row_shr 8
+  v = dpp_add<0x142, 0xA>(v);   // row_bcast 15 into rows 1 and 3
+  v = dpp_add<0x143, 0xC>(v);   // row_bcast 31 into rows 2 and 3
   return v;
 }
 
@@ -97,10 +105,10 @@ __device__ __forceinline__ void lds_add64(uint64_t *p, uint64_t v)
 
 // Optional per-phase cycle counters (compiled out unless GNR_PROF is defined).
 #ifdef GNR_PROF
-__device__ unsigned long long g_prof[16];
-#define PROF_DECL unsigned long long prof_acc[16] = {0}; unsigned long long prof_last = clock64();
+__device__ unsigned long long g_prof[32];
+#define PROF_DECL unsigned long long prof_acc[32] = {0}; unsigned long long prof_last = clock64();
 #define PROF(i) { const unsigned long long t_ = clock64(); prof_acc[i] += t_ - prof_last; prof_last = t_; }
-#define PROF_FLUSH if ((threadIdx.x & 63) == 0) { for (int i_ = 0; i_ < 16; ++i_) atomicAdd(&g_prof[i_], prof_acc[i_]); }
+#define PROF_FLUSH if ((threadIdx.x & 63) == 0) { for (int i_ = 0; i_ < 32; ++i_) atomicAdd(&g_prof[i_], prof_acc[i_]); }
 #else
 #define PROF_DECL
 #define PROF(i)
@@ -113,11 +121,14 @@ enum Scalar {
   SC_TAKE = 16,   // [8] accepted arrivals this step
   SC_TAIL = 24,   // [8] ring position of the first accepted arrival
   SC_ADMK = 40,   // [8] admissions per class in this gate pass
-  SC_WORDS = 48
+  SC_TAKE_T = 48, // [kRouteLevels] jobs each level of the routing pass takes
+  SC_W_T = 56,    // [kRouteLevels] jobs of the pass that come before each level
+  SC_WORDS = 64
 };
 constexpr int kLoadBins = kMaxB + 1;
 constexpr int kEvPerWave = 128;   // servers a wave can queue for finishing; when full the queue is drained early
-constexpr int kRouteLevels = 8;   // load levels one routing pass fills
+constexpr int kRouteLevels = 4;
+constexpr int kJobsLds = 512;      // requests of a routing pass staged in LDS; later ones are read from the buffer   // load levels one routing pass fills
 constexpr int kMaxPend = 254;     // untallied iterations a server may accumulate (kept in a byte)
 
 struct Lds {
@@ -133,8 +144,9 @@ struct Lds {
   uint64_t *bm_due;   // [nwords] servers that completed an iteration this step
   uint64_t *bm_touch; // [nwords] idle servers that were given work this step
   uint64_t *bm_flush; // [nwords] servers whose untallied iterations must be tallied at the restart
-  uint64_t *bm_lvl;   // [kRouteLevels][nwords] servers of the routed group with at most (level) decodes
-  uint32_t *pre_lvl;  // [kRouteLevels][nwords] exclusive prefix popcounts of bm_lvl
+  uint64_t *bm_chunk; // [nwords] mixed-group servers whose running iteration carries a prefill chunk
+  uint64_t *jobs;     // [kJobsLds] the first requests a routing pass places, copied from the decode buffer
+  uint32_t *pre_lvl;  // [kRouteLevels][nwords] servers of the routed group with at most (level) decodes: per word, then ranks
   uint32_t *pre_c;    // [nwords] exclusive prefix popcounts of bm_comp
   uint32_t *pre;      // [nwords] exclusive prefix popcounts of bm_idle
   uint32_t *adm;      // [kAdmChunk] class | sequence-in-class << 3 of each admission
@@ -146,6 +158,7 @@ struct Lds {
   uint32_t *iter;     // [N] completed iterations
   uint8_t *loads;     // [N] decodes per server
   uint8_t *pend;      // [N] completed iterations not yet tallied (all with the server's current batch)
+  uint16_t *rem;      // [M] prompt tokens left of the prefill a mixed-group server has in service (0: slot idle)
 };
 
 // Carves the dynamic LDS block; 8-byte granules, 64-bit arrays first.
@@ -165,7 +178,8 @@ __host__ __device__ __forceinline__ Lds lds_carve(const Params &p, unsigned char
   GNR_TAKE(bm_due, uint64_t, p.nwords)
   GNR_TAKE(bm_touch, uint64_t, p.nwords)
   GNR_TAKE(bm_flush, uint64_t, p.nwords)
-  GNR_TAKE(bm_lvl, uint64_t, kRouteLevels * p.nwords)
+  GNR_TAKE(bm_chunk, uint64_t, p.nwords)
+  GNR_TAKE(jobs, uint64_t, kJobsLds)
   GNR_TAKE(cs, int32_t, CS_WORDS)
   GNR_TAKE(acc, uint32_t, 8)
   GNR_TAKE(sc, int32_t, SC_WORDS)
@@ -180,6 +194,7 @@ __host__ __device__ __forceinline__ Lds lds_carve(const Params &p, unsigned char
   GNR_TAKE(iter, uint32_t, p.N)
   GNR_TAKE(loads, uint8_t, p.N)
   GNR_TAKE(pend, uint8_t, p.N)
+  GNR_TAKE(rem, uint16_t, p.M)
   GNR_TAKE(stage, uint8_t, p.threads)
 #undef GNR_TAKE
   if (total) *total = off;
@@ -215,7 +230,7 @@ __device__ __forceinline__ uint32_t rank_bitmap(const uint64_t *bm, uint32_t *pr
     const uint32_t v = w < nwords ? static_cast<uint32_t>(__popcll(bm[w])) : 0u;
     const uint32_t inc = wave_incl_scan(v);
     if (w < nwords) pre[w] = running + inc - v;
-    running += __shfl(inc, 63, 64);
+    running += static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(inc), 63));
   }
   return running;
 }
@@ -223,11 +238,6 @@ __device__ __forceinline__ uint32_t rank_bitmap(const uint64_t *bm, uint32_t *pr
 // Wave totals with data-parallel-primitive adds: four steps inside each row of 16 lanes, then the row
 // totals are passed on (row 0 -> 1, 2 -> 3, then 1 -> 2 and 3); lane 63 ends with the total, which is
 // returned as a wave-uniform value. All 64 lanes must be active.
-template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ uint32_t dpp_add(uint32_t v)
-{
-  return v + static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), CTRL, ROW_MASK, 0xF, false));
-}
 __device__ __forceinline__ uint32_t wave_sum32(uint32_t v)
 {
   v = dpp_add<0xB1, 0xF>(v);    // quad_perm [1,0,3,2]
@@ -434,10 +444,18 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
       L.iter[g] = iter_g[g];
       joined = n_join[g] != 0;
     }
-    const bool idle_slot = valid && g < M && pk_rem(remptok[g]) == 0;
-    const uint64_t bi = __ballot(idle_slot), bb = __ballot(busy), bj = __ballot(joined);
+    bool idle_slot = false, chunk = false;
+    if (valid && g < M) {   // the prefill word stays in LDS during the launch: tokens left, and whether a chunk runs
+      const uint32_t pk = remptok[g];
+      L.rem[g] = static_cast<uint16_t>(pk_rem(pk));
+      idle_slot = pk_rem(pk) == 0;
+      chunk = pk_ptok(pk) > 0;
+    }
+    const uint64_t bi = __ballot(idle_slot), bb = __ballot(busy), bj = __ballot(joined), bc = __ballot(chunk);
     const int wi = (i * NT + wave_base) >> 6;
-    if (lane == 0 && wi < nwords) { L.bm_idle[wi] = bi; L.bm_busy[wi] = bb; L.bm_join[wi] = bj; L.bm_flush[wi] = 0; }
+    if (lane == 0 && wi < nwords) {
+      L.bm_idle[wi] = bi; L.bm_busy[wi] = bb; L.bm_join[wi] = bj; L.bm_flush[wi] = 0; L.bm_chunk[wi] = bc;
+    }
   }
   __syncthreads();
 
@@ -490,11 +508,11 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           const uint64_t bit = 1ull << (g & 63);
           const bool joined = L.bm_join[g >> 6] & bit;
           const uint64_t nj = joined ? n_join[g] : 0ull;
-          const uint32_t pk = g < M ? remptok[g] : 0u;
+          const bool has_chunk = g < M && (L.bm_chunk[g >> 6] & bit);
           const uint32_t it = L.iter[g];
           int nd = L.loads[g];
-          int rem = pk_rem(pk);
-          const int ptok = pk_ptok(pk);
+          int rem = g < M ? static_cast<int>(L.rem[g]) : 0;
+          const int ptok = has_chunk ? (rem < p.C ? rem : p.C) : 0;   // the chunk frozen at the start of the iteration
           const int64_t tn = T + static_cast<int64_t>(static_cast<int32_t>(L.t32[g] - T32));   // exact completion time
           comp = bytes_sub(nc, nj);
           d = p.c0 + p.cpre * ptok + p.cdec * static_cast<int64_t>(byte_sum(comp));
@@ -544,10 +562,12 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           }
           // the prefill advances by the chunk frozen at the start of the iteration
           if (ptok > 0) {
-            const int k = pk_cls(pk);
             rem -= ptok;
+            L.rem[g] = static_cast<uint16_t>(rem);
+            atomicAnd(reinterpret_cast<unsigned long long *>(&L.bm_chunk[g >> 6]), ~bit);   // set again at the restart
             if (rem == 0) {
               const uint64_t jw = pf_job[g];
+              const int k = static_cast<int>(jw >> 29) & 7;
               const uint32_t stamp = static_cast<uint32_t>(jw) & 0x1FFFFFFFu;
               pe.done = true; pe.k = k; pe.nc = nc;
               pe.P = (static_cast<uint32_t>(jw >> 32) & 0xFFFFu) + 1;
@@ -556,8 +576,6 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
               atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_comp[g >> 6]), bit);
               atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_idle[g >> 6]), bit);
             }
-            // running chunk cleared; it is set again at the restart
-            remptok[g] = static_cast<uint32_t>(rem) | (static_cast<uint32_t>(k) << 29);
           }
           if (joined) {
             n_join[g] = 0;
@@ -602,7 +620,6 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
       const int l8 = lane & 7, grp = lane >> 3;
       const uint64_t below = lanes_below();
       uint8_t *stage = L.stage + wave * 64;
-      const int nrounds = wave_base < N ? (N - wave_base + NT - 1) / NT : 0;   // wave-uniform
       int nev = 0;          // servers queued by this wave (wave-uniform)
       int ne = 0;           // servers listed for the open round (wave-uniform)
       bool wide = false;    // a listed server holds more than 64 decodes (wave-uniform)
@@ -612,9 +629,8 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
       uint4 v[Q][2];
       uint32_t vit[Q];
 
-      auto open_round = [&](int i) __attribute__((always_inline)) {
-        const int gw = i * NT + wave_base;
-        const int wi = gw >> 6;
+      auto open_round = [&](int wi) __attribute__((always_inline)) {
+        const int gw = wi << 6;
         const int g = gw + lane;
         const uint64_t lbit = 1ull << lane;
         const bool busy = g < N && (L.bm_busy[wi] & lbit);
@@ -641,8 +657,8 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
         }
       };
       // half 0: slots 0..63 of each listed row, half 1: slots 64..127
-      auto issue = [&](int i, int b, int half) __attribute__((always_inline)) {
-        const uint32_t gw = static_cast<uint32_t>(i * NT + wave_base);
+      auto issue = [&](int wi, int b, int half) __attribute__((always_inline)) {
+        const uint32_t gw = static_cast<uint32_t>(wi) << 6;
 #pragma unroll
         for (int t = 0; t < Q; ++t) {
           v[t][0] = v[t][1] = make_uint4(0u, 0u, 0u, 0u);
@@ -684,8 +700,8 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           }
         }
       };
-      auto finalize = [&](int i) __attribute__((always_inline)) {
-        const int g = i * NT + wave_base + lane;
+      auto finalize = [&](int wi) __attribute__((always_inline)) {
+        const int g = (wi << 6) + lane;
         const bool event = o_due && (o_must || o_q != 0);
         if (o_due && !event) L.pend[g] = static_cast<uint8_t>(o_pend + 1);
         const uint64_t evm = __ballot(event);
@@ -699,27 +715,31 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
         }
       };
 
+      // wave w owns the 64-server blocks w, w + nwaves, w + 2 nwaves, ...
       PROF(1)
-      if (nrounds > 0) { open_round(0); issue(0, 0, 0); }
-      for (int i = 0; i < nrounds; ++i) {
+      int blk = wave;
+      if (blk < nwords) { open_round(blk); issue(blk, 0, 0); }
+      while (blk < nwords) {
         PROF(2)
+        const int nblk = blk + nwaves;
         {
-          const int g = i * NT + wave_base + lane;
+          const int g = (blk << 6) + lane;
           if (g < N) arrivals(g);
         }
         PROF(3)
         process(0, 0);
-        for (int b = 1; 8 * Q * b < ne; ++b) { issue(i, b, 0); process(b, 0); }
+        for (int b = 1; 8 * Q * b < ne; ++b) { issue(blk, b, 0); process(b, 0); }
         if (wide)
-          for (int b = 0; 8 * Q * b < ne; ++b) { issue(i, b, 1); process(b, 1); }
-        finalize(i);
-        if (i + 1 < nrounds) { open_round(i + 1); issue(i + 1, 0, 0); }
+          for (int b = 0; 8 * Q * b < ne; ++b) { issue(blk, b, 1); process(b, 1); }
+        finalize(blk);
+        if (nblk < nwords) { open_round(nblk); issue(nblk, 0, 0); }
         PROF(2)
-        if (nev > kEvPerWave - 64 || i + 1 == nrounds) {
+        if (nev > kEvPerWave - 64 || nblk >= nwords) {
           drain_events(nev);
           nev = 0;
         }
         PROF(4)
+        blk = nblk;
       }
     }
     PROF(5)
@@ -787,248 +807,353 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
     }
     PROF(7)
 
-    // ================= 3. prefill gate =================
-    // The m-th waiting request of class k is a candidate; its position in the admission sequence is
-    // the number of candidates that sort before it. Candidates are ranked in parallel; the idle
-    // prefill slot of rank j (ascending server index) takes the candidate of rank j.
-    for (bool first = true;; first = false) {
-      if (!first) {
-        if (tid < 64) {
-          const uint32_t nidle = rank_bitmap(L.bm_idle, L.pre, nwords_m);
-          if (tid == 0) L.sc[SC_NIDLE] = static_cast<int32_t>(nidle);
-        }
-        __syncthreads();
+    // ================= 3.-5. prefill gate, decode routing and restart =================
+    // Gate: the m-th waiting request of class k is a candidate; its position in the admission sequence is
+    // the number of candidates that sort before it. Candidates are ranked in parallel; the idle prefill slot
+    // of rank j (ascending server index) takes the candidate of rank j.
+    // Routing: sequentially every job goes to the least-loaded feasible server, lowest index first: all
+    // servers with the lowest decode count l get one job in index order, then all servers with at most l+1,
+    // and so on. One pass fills up to kRouteLevels such levels at once. Level t takes take_t jobs, the first
+    // of them job w_t of the pass; the server of rank q among those with at most lmin+t decodes takes job
+    // w_t + q into slot lmin+t. Every lane places the jobs of its own server.
+    // Both run side by side in passes of three segments with a barrier after each:
+    //   A  gate: rank the candidates          routing: pass parameters from the load histogram, then the
+    //                                          servers of each level are counted per 64-server word
+    //   B  gate: admissions take their slots  routing: one wave per level turns the counts into ranks
+    //   C  gate: class counters               routing: placement; in the last pass every lane then restarts
+    //                                          its servers
+    // One pass is the rule; more follow only when more than kAdmChunk slots are idle or the jobs reach past
+    // kRouteLevels levels or into the mixed group.
+    {
+      const int dcount0 = L.cs[CS_DCOUNT];
+      int jrem, next = 0, grp = 0;
+      {
+        const int ncp = L.sc[SC_NCOMP], room = static_cast<int>(p.dbuf_cap) - dcount0;
+        jrem = dcount0 + (ncp < room ? ncp : room);
       }
-      if (p.gate_mode == SIM_GATE_FCFS && first) __syncthreads();   // stamps written above are read below
-      const int nidle = L.sc[SC_NIDLE];
-      const int limit = nidle < kAdmChunk ? nidle : kAdmChunk;
-      int cnt[kMaxK], xs[kMaxK], qp[kMaxK], ncand = 0;
-      uint32_t head[kMaxK];
-#pragma unroll
-      for (int k = 0; k < kMaxK; ++k) {
-        qp[k] = k < K ? L.cs[CS_QP + k] : 0;
-        xs[k] = k < K ? L.cs[CS_X + k] : 0;
-        head[k] = k < K ? static_cast<uint32_t>(L.cs[CS_QHEAD + k]) : 0u;
-        const bool eligible = k < K && qp[k] > 0 && (p.gate_mode != SIM_GATE_OCCUPANCY || p.invx[k] > 0.0);
-        cnt[k] = eligible ? (qp[k] < limit ? qp[k] : limit) : 0;
-        ncand += cnt[k];
-      }
-      const int nadm = ncand < limit ? ncand : limit;
-      for (int c = tid; c < ncand; c += NT) {
-        int k = 0, m = c;
-#pragma unroll
-        for (int kk = 0; kk < kMaxK - 1; ++kk)
-          if (k == kk && m >= cnt[kk]) { m -= cnt[kk]; k = kk + 1; }
-        GateKey key = {0.0, 0.0};
-#pragma unroll
-        for (int kk = 0; kk < kMaxK; ++kk)
-          if (k == kk) key = gate_key(p, qring, xs, qp, head, kk, m);
-        int rank = m;
-#pragma unroll
-        for (int k2 = 0; k2 < kMaxK; ++k2) {
-          if (k2 == k || cnt[k2] == 0 || rank >= nadm) continue;
-          int lo = 0, hi = cnt[k2];
-          while (lo < hi) {
-            const int mid = (lo + hi) >> 1;
-            if (gate_before(gate_key(p, qring, xs, qp, head, k2, mid), k2, key, k)) lo = mid + 1; else hi = mid;
+      const uint32_t dhead0 = static_cast<uint32_t>(L.cs[CS_DHEAD]);
+      bool gate_on = true, route_on = jrem > 0, started = false;
+      for (int pass = 0; !started; ++pass) {
+        if (gate_on && pass > 0) {
+          if (tid < 64) {
+            const uint32_t nidle = rank_bitmap(L.bm_idle, L.pre, nwords_m);
+            if (tid == 0) L.sc[SC_NIDLE] = static_cast<int32_t>(nidle);
           }
-          rank += lo;
+          __syncthreads();
         }
-        if (rank < nadm) {
-          L.adm[rank] = static_cast<uint32_t>(k) | (static_cast<uint32_t>(m) << 3);
-          atomicAdd(&L.sc[SC_ADMK + k], 1);
-        }
-      }
-      PROF(14)
-      __syncthreads();
-      PROF(15)
-      if (first && tid == 0) {   // every thread has read the old count by now: completions are in the buffer
-        const uint32_t room = p.dbuf_cap - static_cast<uint32_t>(L.cs[CS_DCOUNT]);
-        const uint32_t ncp = static_cast<uint32_t>(L.sc[SC_NCOMP]);
-        L.cs[CS_DCOUNT] += static_cast<int32_t>(ncp < room ? ncp : room);
-      }
-      // admission j goes to the idle prefill slot of rank j; one thread per admission
-      for (int j0 = wave_base; j0 < nadm; j0 += NT) {   // wave-uniform trip count
-        const int j = j0 + lane;
-        const bool active = j < nadm;
-        int k = 0;
-        uint64_t wait = 0, nc = 0;
-        if (active) {
-          const int g = select_bit(L.bm_idle, L.pre, nwords_m, static_cast<uint32_t>(j));
-          const uint32_t e = L.adm[j];
-          k = static_cast<int>(e & 7u);
-          uint32_t pos = head[0];
+        if (p.gate_mode == SIM_GATE_FCFS && pass == 0) __syncthreads();   // stamps written above are read below
+
+        // ---------------- segment A ----------------
+        int nadm = 0, nidle = 0;
+        if (gate_on) {
+          nidle = L.sc[SC_NIDLE];
+          const int limit = nidle < kAdmChunk ? nidle : kAdmChunk;
+          int cnt[kMaxK], qp[kMaxK], xs[kMaxK], ncand = 0;
+          uint32_t head[kMaxK];
 #pragma unroll
-          for (int kk = 1; kk < kMaxK; ++kk) pos = k == kk ? head[kk] : pos;
-          pos += e >> 3;
-          if (pos >= p.queue_cap) pos -= p.queue_cap;
-          const uint32_t stamp = qring[static_cast<size_t>(k) * p.queue_cap + pos];
-          if (L.loads[g]) nc = n_cls[g];
-          wait = static_cast<uint64_t>(s - stamp);
-          uint32_t w[4];
-          philox4x32_10(key0, key1, s, 1u, static_cast<uint32_t>(g), static_cast<uint32_t>(r), w);
-          const uint32_t Pl = a.len_tab[(static_cast<size_t>(k) * 2 + 0) * kTableSize + (w[0] >> 16)];
-          const uint32_t Dl = a.len_tab[(static_cast<size_t>(k) * 2 + 1) * kTableSize + (w[1] >> 16)];
-          pf_job[g] = static_cast<uint64_t>(stamp) | (static_cast<uint64_t>(k) << 29) |
-                      (static_cast<uint64_t>(Pl - 1) << 32) | (static_cast<uint64_t>(Dl - 1) << 48);
-          // an idle prefill slot implies that the running iteration holds no chunk
-          remptok[g] = Pl | (static_cast<uint32_t>(k) << 29);
-          const uint64_t bit = 1ull << (g & 63);
-          atomicAnd(reinterpret_cast<unsigned long long *>(&L.bm_idle[g >> 6]), ~bit);
-          if (!(L.bm_busy[g >> 6] & bit)) atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_touch[g >> 6]), bit);
-          // at an iteration boundary the next iteration carries a chunk: tally the untallied ones first
-          else if ((L.bm_due[g >> 6] & bit) && L.pend[g]) atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_flush[g >> 6]), bit);
-        }
-        wave_sum_by_class(active, k, K, wait, &L.tl[SIM_T_WAIT_STEPS], kNTally);
-        uint64_t even, odd;   // co-resident decodes switch solo -> mixed
-        wave_sum_bytes(nc, even, odd);
-        if (lane == 0 && (even | odd))
-          for (int c = 0; c < K; ++c) {
-            const int v = static_cast<int>(class_field(even, odd, c));
-            if (v) {
-              lds_add64(&L.tl[c * kNTally + SIM_T_M_SM], static_cast<uint64_t>(v));
-              atomicSub(&L.cs[CS_YS + c], v);
-              atomicAdd(&L.cs[CS_YM + c], v);
+          for (int k = 0; k < kMaxK; ++k) {
+            qp[k] = k < K ? L.cs[CS_QP + k] : 0;
+            xs[k] = k < K ? L.cs[CS_X + k] : 0;
+            head[k] = k < K ? static_cast<uint32_t>(L.cs[CS_QHEAD + k]) : 0u;
+            const bool eligible = k < K && qp[k] > 0 && (p.gate_mode != SIM_GATE_OCCUPANCY || p.invx[k] > 0.0);
+            cnt[k] = eligible ? (qp[k] < limit ? qp[k] : limit) : 0;
+            ncand += cnt[k];
+          }
+          nadm = ncand < limit ? ncand : limit;
+          for (int c = tid; c < ncand; c += NT) {
+            int k = 0, m = c;
+#pragma unroll
+            for (int kk = 0; kk < kMaxK - 1; ++kk)
+              if (k == kk && m >= cnt[kk]) { m -= cnt[kk]; k = kk + 1; }
+            GateKey key = {0.0, 0.0};
+#pragma unroll
+            for (int kk = 0; kk < kMaxK; ++kk)
+              if (k == kk) key = gate_key(p, qring, xs, qp, head, kk, m);
+            int rank = m;
+#pragma unroll
+            for (int k2 = 0; k2 < kMaxK; ++k2) {
+              if (k2 == k || cnt[k2] == 0 || rank >= nadm) continue;
+              // number of candidates of class k2 that sort before this one: they form a prefix of the class
+              int lo = 0, hi = cnt[k2];
+              if (p.gate_mode == SIM_GATE_OCCUPANCY) {
+                // the key is linear in the sequence number: bracket the crossing next to its estimate with two
+                // exact comparisons, so the search below runs over a few candidates only (or, if the
+                // estimate is off, over the side the comparisons point to)
+                const double est = key.a * p.xstar[k2] - (static_cast<double>(xs[k2]) - p.nx[k2]);
+                const int g0 = est > 0.0 ? (est < static_cast<double>(hi) ? static_cast<int>(est) : hi) : 0;
+                const int l2 = g0 > 1 ? g0 - 1 : 0, h2 = g0 + 2 < hi ? g0 + 2 : hi;
+                if (l2 > 0) {
+                  if (gate_before(gate_key(p, qring, xs, qp, head, k2, l2 - 1), k2, key, k)) lo = l2; else hi = l2 - 1;
+                }
+                if (h2 < hi) {
+                  if (gate_before(gate_key(p, qring, xs, qp, head, k2, h2), k2, key, k)) lo = h2 + 1; else hi = h2;
+                }
+              }
+              while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (gate_before(gate_key(p, qring, xs, qp, head, k2, mid), k2, key, k)) lo = mid + 1; else hi = mid;
+              }
+              rank += lo;
+            }
+            if (rank < nadm) {
+              L.adm[rank] = static_cast<uint32_t>(k) | (static_cast<uint32_t>(m) << 3);
+              atomicAdd(&L.sc[SC_ADMK + k], 1);
             }
           }
-      }
-      bool more = false;
-      if (nadm == kAdmChunk && nidle > kAdmChunk) {   // rare: more idle slots than one pass serves
-#pragma unroll
-        for (int k = 0; k < kMaxK; ++k)
-          if (k < K && cnt[k] > 0 && qp[k] - L.sc[SC_ADMK + k] > 0) more = true;
-      }
-      __syncthreads();
-      if (tid < K) {   // class counters follow the admissions of this pass
-        const int k = tid, a = L.sc[SC_ADMK + k];
-        if (a) {
-          uint32_t h = static_cast<uint32_t>(L.cs[CS_QHEAD + k]) + static_cast<uint32_t>(a);
-          if (h >= p.queue_cap) h -= p.queue_cap;
-          L.cs[CS_QHEAD + k] = static_cast<int32_t>(h);
-          L.cs[CS_QP + k] -= a;
-          L.cs[CS_X + k] += a;
-          L.tl[k * kNTally + SIM_T_U_P] += static_cast<uint64_t>(a);
-          L.sc[SC_ADMK + k] = 0;
         }
-      }
-      if (!more) break;
-      __syncthreads();
-    }
-    PROF(8)
-
-    // ================= 4. decode routing =================
-    // Sequentially every job goes to the least-loaded feasible server, lowest index first: all servers with
-    // the lowest decode count l get one job in index order, then all servers with at most l+1, and so on.
-    // One pass here fills up to kRouteLevels such levels at once: job j falls into level t and has a rank
-    // there; it goes to the server of that rank among those with at most Lmin+t decodes, into slot Lmin+t.
-    // Every wave derives the pass parameters from the load histogram, so no thread has to broadcast them.
-    {
-      int jrem = L.cs[CS_DCOUNT], next = 0;
-      const uint32_t dhead0 = static_cast<uint32_t>(L.cs[CS_DHEAD]);
-      for (int grp = 0; grp < 2 && jrem > 0; ++grp) {
-        const int lo = grp == 0 ? M : 0, hi = grp == 0 ? N : M;
-        const int capg = grp == 0 ? B : B - 1;
-        if (lo >= hi) continue;
-        for (;;) {
-          if (jrem <= 0) break;
-          int lmin = -1;
-          for (int base = 0; base < capg && lmin < 0; base += 64) {
-            const int l = base + lane;
-            const uint64_t nz = __ballot(l < capg && L.lh[grp * kLoadBins + l] != 0);
-            if (nz) lmin = base + __ffsll(static_cast<long long>(nz)) - 1;
+        PROF(8)
+        int lmin = -1, nl = 0, csum = 0, total = 0, lmax = 0, take_last = 0, lo = 0, hi = 0;
+        if (route_on) {
+          int capg = 0;
+          for (; grp < 2; ++grp) {   // solo group first; a group without a free slot is skipped
+            lo = grp == 0 ? M : 0; hi = grp == 0 ? N : M;
+            capg = grp == 0 ? B : B - 1;
+            if (lo >= hi) continue;
+            for (int base = 0; base < capg && lmin < 0; base += 64) {
+              const int l = base + lane;
+              const uint64_t nz = __ballot(l < capg && L.lh[grp * kLoadBins + l] != 0);
+              if (nz) lmin = base + __ffsll(static_cast<long long>(nz)) - 1;
+            }
+            if (lmin >= 0) break;
           }
-          if (lmin < 0) break;
-          // levels of this pass: servers with at most lmin+t decodes, jobs taken and jobs before it
-          int nl = 0, csum = 0, rem_jobs = jrem;
-          int take_t[kRouteLevels], w_t[kRouteLevels];
-#pragma unroll
-          for (int t = 0; t < kRouteLevels; ++t) {
-            take_t[t] = 0; w_t[t] = 0;
-            if (nl == t && rem_jobs > 0 && lmin + t < capg) {
+          if (lmin < 0) {
+            route_on = false;   // every slot is taken: the jobs stay in the buffer
+          } else {
+            // levels of this pass: servers with at most lmin+t decodes, jobs taken and jobs before it
+            // (every wave computes the same values and stores them: no broadcast, no barrier)
+            int rem_jobs = jrem;
+            for (int t = 0; t < kRouteLevels && rem_jobs > 0 && lmin + t < capg; ++t) {
               csum += static_cast<int>(L.lh[grp * kLoadBins + lmin + t]);
-              take_t[t] = csum < rem_jobs ? csum : rem_jobs;
-              w_t[t] = jrem - rem_jobs;
-              rem_jobs -= take_t[t];
+              take_last = csum < rem_jobs ? csum : rem_jobs;
+              if (lane == 0) { L.sc[SC_TAKE_T + t] = take_last; L.sc[SC_W_T + t] = jrem - rem_jobs; }
+              rem_jobs -= take_last;
               nl = t + 1;
             }
-          }
-          const int total = jrem - rem_jobs;
-          const int lmax = lmin + nl - 1;
-          int take_last = 0;
+            total = jrem - rem_jobs;
+            lmax = lmin + nl - 1;
+            for (int wi = wave; wi < nwords; wi += nwaves) {
+              const int g = (wi << 6) + lane;
+              const int load = (g >= lo && g < hi) ? static_cast<int>(L.loads[g]) : 1 << 20;
 #pragma unroll
-          for (int t = 0; t < kRouteLevels; ++t) if (t == nl - 1) take_last = take_t[t];
-          for (int i = 0; i < nper; ++i) {
-            const int gw = i * NT + wave_base;
-            if (gw >= N) break;
-            const int g = gw + lane;
-            const int load = (g >= lo && g < hi) ? static_cast<int>(L.loads[g]) : 1 << 20;
-#pragma unroll
-            for (int t = 0; t < kRouteLevels; ++t) {
-              if (t < nl) {
-                const uint64_t b = __ballot(load <= lmin + t);
-                if (lane == 0) L.bm_lvl[t * nwords + (gw >> 6)] = b;
+              for (int t = 0; t < kRouteLevels; ++t) {
+                if (t < nl) {
+                  const uint64_t bal = __ballot(load <= lmin + t);
+                  if (lane == 0) L.pre_lvl[t * nwords + wi] = static_cast<uint32_t>(__popcll(bal));
+                }
               }
             }
           }
-          __syncthreads();
-          for (int t = wave; t < nl; t += nwaves) rank_bitmap(L.bm_lvl + t * nwords, L.pre_lvl + t * nwords, nwords);
-          __syncthreads();
-          for (int j0 = wave_base; j0 < total; j0 += NT) {   // wave-uniform trip count
+        }
+        PROF(9)
+        __syncthreads();
+        PROF(14)
+
+        // ---------------- segment B ----------------
+        bool gate_more = false;
+        if (gate_on) {
+          if (pass == 0 && tid == 0) L.cs[CS_DCOUNT] = jrem;   // the completions of this step are in the buffer
+          // admission j goes to the idle prefill slot of rank j; one thread per admission
+          for (int j0 = wave_base; j0 < nadm; j0 += NT) {   // wave-uniform trip count
             const int j = j0 + lane;
-            const bool active = j < total;
+            const bool active = j < nadm;
             int k = 0;
-            bool has_prefill = false;
+            uint64_t wait = 0, nc = 0;
             if (active) {
-              int t = 0;
-#pragma unroll
-              for (int u = 1; u < kRouteLevels; ++u) if (u < nl && j >= w_t[u]) t = u;
-              int wt = w_t[0];
-#pragma unroll
-              for (int u = 1; u < kRouteLevels; ++u) wt = t == u ? w_t[u] : wt;
-              const int g = select_bit(L.bm_lvl + t * nwords, L.pre_lvl + t * nwords, nwords, static_cast<uint32_t>(j - wt));
-              uint32_t pos = dhead0 + static_cast<uint32_t>(next + j);
-              if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
-              if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
-              const uint64_t jw = dring[pos];
-              k = static_cast<int>(jw >> 29) & 7;
-              const uint32_t Dl = static_cast<uint32_t>(jw >> 48) + 1;
+              const int g = select_bit(L.bm_idle, L.pre, nwords_m, static_cast<uint32_t>(j));
+              const uint32_t e = L.adm[j];
+              k = static_cast<int>(e & 7u);
+              uint32_t pos = static_cast<uint32_t>(L.cs[CS_QHEAD + k]) + (e >> 3);
+              if (pos >= p.queue_cap) pos -= p.queue_cap;
+              const uint32_t stamp = qring[static_cast<size_t>(k) * p.queue_cap + pos];
+              if (L.loads[g]) nc = n_cls[g];
+              wait = static_cast<uint64_t>(s - stamp);
+              uint32_t w[4];
+              philox4x32_10(key0, key1, s, 1u, static_cast<uint32_t>(g), static_cast<uint32_t>(r), w);
+              const uint32_t Pl = a.len_tab[(static_cast<size_t>(k) * 2 + 0) * kTableSize + (w[0] >> 16)];
+              const uint32_t Dl = a.len_tab[(static_cast<size_t>(k) * 2 + 1) * kTableSize + (w[1] >> 16)];
+              pf_job[g] = static_cast<uint64_t>(stamp) | (static_cast<uint64_t>(k) << 29) |
+                          (static_cast<uint64_t>(Pl - 1) << 32) | (static_cast<uint64_t>(Dl - 1) << 48);
+              // an idle prefill slot implies that the running iteration holds no chunk
+              L.rem[g] = static_cast<uint16_t>(Pl);
               const uint64_t bit = 1ull << (g & 63);
-              const bool busy = L.bm_busy[g >> 6] & bit;
-              const bool at_boundary = L.bm_due[g >> 6] & bit;
-              const bool mid = busy && !at_boundary;   // joins at the next restart
-              const int nd = lmin + t;                 // the server holds exactly this many decodes by now
-              fin[static_cast<size_t>(g) * BS + nd] = L.iter[g] + Dl + (mid ? 1u : 0u);
-              job[static_cast<size_t>(g) * BS + nd] = jw;
-              // several levels can reach the same server in one pass: its counts are updated atomically
-              atomicAdd(reinterpret_cast<unsigned long long *>(&n_cls[g]), 1ull << (8 * k));
-              // the new decode is not part of the iterations still to be tallied for this server
-              if (mid || (at_boundary && L.pend[g])) {
-                atomicAdd(reinterpret_cast<unsigned long long *>(&n_join[g]), 1ull << (8 * k));
-                atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_join[g >> 6]), bit);
-                if (!mid) atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_flush[g >> 6]), bit);
+              atomicAnd(reinterpret_cast<unsigned long long *>(&L.bm_idle[g >> 6]), ~bit);
+              if (!(L.bm_busy[g >> 6] & bit)) atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_touch[g >> 6]), bit);
+              // at an iteration boundary the next iteration carries a chunk: tally the untallied ones first
+              else if ((L.bm_due[g >> 6] & bit) && L.pend[g]) atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_flush[g >> 6]), bit);
+            }
+            wave_sum_by_class(active, k, K, wait, &L.tl[SIM_T_WAIT_STEPS], kNTally);
+            uint64_t even, odd;   // co-resident decodes switch solo -> mixed
+            wave_sum_bytes(nc, even, odd);
+            if (lane == 0 && (even | odd))
+              for (int c = 0; c < K; ++c) {
+                const int v = static_cast<int>(class_field(even, odd, c));
+                if (v) {
+                  lds_add64(&L.tl[c * kNTally + SIM_T_M_SM], static_cast<uint64_t>(v));
+                  atomicSub(&L.cs[CS_YS + c], v);
+                  atomicAdd(&L.cs[CS_YM + c], v);
+                }
               }
-              has_prefill = g < M && !(L.bm_idle[g >> 6] & bit);
-              if (!busy) atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_touch[g >> 6]), bit);
-            }
-            const bool am = active && has_prefill, as = active && !has_prefill;
-            wave_count_by_class(am, k, K, &L.tl[SIM_T_U_DM], kNTally);
-            wave_count_by_class(as, k, K, &L.tl[SIM_T_U_DS], kNTally);
-            wave_count_by_class_i32(am, k, K, &L.cs[CS_YM], 1);
-            wave_count_by_class_i32(as, k, K, &L.cs[CS_YS], 1);
-            wave_count_by_class_i32(active, k, K, &L.cs[CS_QD], -1);
           }
-          __syncthreads();
-          // every server with at most lmax decodes now holds lmax, plus one if the last level reached it
-          for (int i = 0; i < nper; ++i) {
-            const int gw = i * NT + wave_base;
-            if (gw >= N) break;
-            const int g = gw + lane;
-            const uint64_t word = L.bm_lvl[(nl - 1) * nwords + (gw >> 6)];
-            if ((word >> lane) & 1ull) {
-              const uint32_t rank = L.pre_lvl[(nl - 1) * nwords + (gw >> 6)] + static_cast<uint32_t>(__popcll(word & lanes_below()));
-              L.loads[g] = static_cast<uint8_t>(lmax + (rank < static_cast<uint32_t>(take_last) ? 1 : 0));
+          if (nadm == kAdmChunk && nidle > kAdmChunk) {   // rare: more idle slots than one pass serves
+            for (int k = 0; k < K; ++k) {
+              const bool eligible = p.gate_mode != SIM_GATE_OCCUPANCY || p.invx[k] > 0.0;
+              if (eligible && L.cs[CS_QP + k] - L.sc[SC_ADMK + k] > 0) gate_more = true;
             }
           }
+        }
+        if (route_on) {
+          // the requests this pass places are staged in LDS
+          const int nstage = total < kJobsLds ? total : kJobsLds;
+          for (int j = tid; j < nstage; j += NT) {
+            uint32_t pos = dhead0 + static_cast<uint32_t>(next + j);
+            if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
+            if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
+            L.jobs[j] = dring[pos];
+          }
+          // counts -> exclusive prefix over the words; the last waves take this
+          for (int t = nwaves - 1 - wave; t < nl; t += nwaves) {
+            uint32_t *pre = L.pre_lvl + t * nwords;
+            uint32_t running = 0;
+            for (int base = 0; base < nwords; base += 64) {
+              const int w = base + lane;
+              const uint32_t v = w < nwords ? pre[w] : 0u;
+              const uint32_t inc = wave_incl_scan(v);
+              if (w < nwords) pre[w] = running + inc - v;
+              running += static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(inc), 63));
+            }
+          }
+        }
+        PROF(15)
+        __syncthreads();
+        PROF(16)
+
+        // ---------------- segment C ----------------
+        if (gate_on && tid < K) {   // class counters follow the admissions of this pass
+          const int k = tid, adm_k = L.sc[SC_ADMK + k];
+          if (adm_k) {
+            uint32_t h = static_cast<uint32_t>(L.cs[CS_QHEAD + k]) + static_cast<uint32_t>(adm_k);
+            if (h >= p.queue_cap) h -= p.queue_cap;
+            L.cs[CS_QHEAD + k] = static_cast<int32_t>(h);
+            L.cs[CS_QP + k] -= adm_k;
+            L.cs[CS_X + k] += adm_k;
+            L.tl[k * kNTally + SIM_T_U_P] += static_cast<uint64_t>(adm_k);
+            L.sc[SC_ADMK + k] = 0;
+          }
+        }
+        const bool last_pass = !gate_more && (!route_on || total == jrem);
+        for (int wi = wave; wi < nwords; wi += nwaves) {
+          const int gw = wi << 6;
+          const int g = gw + lane;
+          const uint64_t bit = 1ull << lane;
+          if (route_on) {
+            const int load = (g >= lo && g < hi) ? static_cast<int>(L.loads[g]) : 1 << 20;
+            if (__ballot(load <= lmax)) {   // wave-uniform
+              const bool busy = L.bm_busy[wi] & bit;
+              const bool at_boundary = L.bm_due[wi] & bit;
+              const bool mid = busy && !at_boundary;   // a job placed now joins at the next restart
+              const bool has_prefill = g < M && !(L.bm_idle[wi] & bit);
+              bool got = false, got_last = false;
+#pragma unroll
+              for (int t = 0; t < kRouteLevels; ++t) {
+                if (t < nl) {   // wave-uniform
+                  const bool in = load <= lmin + t;
+                  const uint64_t bal = __ballot(in);
+                  if (bal) {
+                    const int q = static_cast<int>(L.pre_lvl[t * nwords + wi]) + __popcll(bal & lanes_below());
+                    if (in && q < L.sc[SC_TAKE_T + t]) {
+                      got = true;
+                      got_last = t == nl - 1;
+                      const int j = L.sc[SC_W_T + t] + q;   // position in this pass
+                      uint64_t jw;
+                      if (j < kJobsLds) {
+                        jw = L.jobs[j];
+                      } else {
+                        uint32_t pos = dhead0 + static_cast<uint32_t>(next + j);
+                        if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
+                        if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
+                        jw = dring[pos];
+                      }
+                      const int k = static_cast<int>(jw >> 29) & 7;
+                      const uint32_t Dl = static_cast<uint32_t>(jw >> 48) + 1;
+                      const int nd = lmin + t;   // the server holds exactly this many decodes by now
+                      fin[static_cast<size_t>(g) * BS + nd] = L.iter[g] + Dl + (mid ? 1u : 0u);
+                      job[static_cast<size_t>(g) * BS + nd] = jw;
+                      atomicAdd(reinterpret_cast<unsigned long long *>(&n_cls[g]), 1ull << (8 * k));
+                      // the new decode is not part of the iterations still to be tallied for this server
+                      if (mid || (at_boundary && L.pend[g]))
+                        atomicAdd(reinterpret_cast<unsigned long long *>(&n_join[g]), 1ull << (8 * k));
+                      lds_add64(&L.tl[k * kNTally + (has_prefill ? SIM_T_U_DM : SIM_T_U_DS)], 1);
+                      atomicAdd(&L.cs[(has_prefill ? CS_YM : CS_YS) + k], 1);
+                      atomicSub(&L.cs[CS_QD + k], 1);
+                    }
+                  }
+                }
+              }
+              if (got) {
+                if (mid || (at_boundary && L.pend[g])) {
+                  atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_join[wi]), bit);
+                  if (!mid) atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_flush[wi]), bit);
+                }
+                if (!busy) atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_touch[wi]), bit);
+              }
+              // every server with at most lmax decodes now holds lmax, plus one if the last level reached it
+              if (load <= lmax) L.loads[g] = static_cast<uint8_t>(lmax + (got_last ? 1 : 0));
+            }
+          }
+          if (last_pass) {
+            // ---- (re)start of the servers that completed an iteration or were given work in this step
+            const bool valid = g < N;
+            const uint64_t due_word = L.bm_due[wi], flush_word = L.bm_flush[wi];
+            const uint64_t todo = due_word | L.bm_touch[wi];
+            // untallied iterations are tallied before the batch changes, and all of them when the launch ends
+            const bool flush = valid && ((flush_word & bit) || (last_step && L.pend[g] != 0));
+            if (__ballot(flush)) {
+              uint32_t m = 0;
+              int64_t d = 0;
+              uint64_t comp = 0;
+              if (flush) {
+                const uint64_t nc = n_cls[g];
+                const bool joined = L.bm_join[wi] & bit;
+                const uint64_t nj = joined ? n_join[g] : 0ull;
+                comp = bytes_sub(nc, nj);
+                d = p.c0 + p.cdec * static_cast<int64_t>(byte_sum(comp));   // untallied iterations never hold a chunk
+                m = L.pend[g];
+                L.pend[g] = 0;
+                if ((flush_word & bit) && joined) {   // the decodes placed at this boundary join the batch now
+                  n_join[g] = 0;
+                  atomicAnd(reinterpret_cast<unsigned long long *>(&L.bm_join[wi]), ~bit);
+                }
+              }
+              tally_iterations(L.tl, L.tbth, p.tbt_w, p.tbt_lo, K, m, d, false, comp);
+              if (lane == 0 && flush_word) L.bm_flush[wi] = 0;
+            }
+            if (todo) {
+              const uint64_t busy_word = L.bm_busy[wi];
+              bool busy = busy_word & bit, chunk_now = false;
+              if (todo & bit) {
+                const int rem = g < M ? static_cast<int>(L.rem[g]) : 0;
+                const int ptok = rem > 0 ? (rem < p.C ? rem : p.C) : 0;
+                chunk_now = ptok > 0;
+                const int n = L.loads[g];
+                if (ptok == 0 && n == 0) {
+                  busy = false;
+                } else {
+                  // back-to-back after a completion, otherwise from the step boundary
+                  const int64_t base = (due_word & bit) ? T + static_cast<int64_t>(static_cast<int32_t>(L.t32[g] - T32)) : T;
+                  const int64_t tn = base + p.c0 + p.cpre * ptok + p.cdec * static_cast<int64_t>(n);
+                  L.t32[g] = static_cast<uint32_t>(tn);
+                  busy = true;
+                }
+              }
+              const uint64_t nb = __ballot(busy), nchunk = __ballot(chunk_now);
+              if (lane == 0) {
+                if (nb != busy_word) L.bm_busy[wi] = nb;
+                if (gw < M) L.bm_chunk[wi] = (L.bm_chunk[wi] & ~todo) | nchunk;
+              }
+            }
+          }
+        }
+        if (route_on) {
           if (tid == 0) {
             for (int t = 0; t + 1 < nl; ++t) L.lh[grp * kLoadBins + lmin + t] = 0;
             L.lh[grp * kLoadBins + lmax] = static_cast<uint32_t>(csum - take_last);
@@ -1036,8 +1161,13 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           }
           jrem -= total;
           next += total;
-          __syncthreads();
+          route_on = jrem > 0;
         }
+        gate_on = gate_more;
+        started = last_pass;
+        PROF(10)
+        __syncthreads();
+        PROF(17)
       }
       if (tid == 0 && next > 0) {
         uint32_t h = dhead0 + static_cast<uint32_t>(next);
@@ -1046,64 +1176,6 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
         L.cs[CS_DCOUNT] -= next;
       }
     }
-    PROF(9)
-
-    // ================= 5. (re)start =================
-    for (int i = 0; i < nper; ++i) {
-      const int gw = i * NT + wave_base;
-      if (gw >= N) break;
-      const int wi = gw >> 6;
-      const int g = gw + lane;
-      const bool valid = g < N;
-      const uint64_t due_word = L.bm_due[wi], flush_word = L.bm_flush[wi];
-      const uint64_t todo = due_word | L.bm_touch[wi];
-      // untallied iterations are tallied before the batch changes, and all of them when the launch ends
-      const bool flush = valid && (((flush_word >> lane) & 1ull) || (last_step && L.pend[g] != 0));
-      const uint64_t flush_mask = __ballot(flush);
-      if (flush_mask) {
-        uint32_t m = 0;
-        int64_t d = 0;
-        uint64_t comp = 0;
-        if (flush) {
-          const uint64_t bit = 1ull << lane;
-          const uint64_t nc = n_cls[g];
-          const bool joined = L.bm_join[wi] & bit;
-          const uint64_t nj = joined ? n_join[g] : 0ull;
-          comp = bytes_sub(nc, nj);
-          d = p.c0 + p.cdec * static_cast<int64_t>(byte_sum(comp));   // untallied iterations never hold a chunk
-          m = L.pend[g];
-          L.pend[g] = 0;
-          if ((flush_word & bit) && joined) {   // the decodes placed at this boundary join the batch now
-            n_join[g] = 0;
-            atomicAnd(reinterpret_cast<unsigned long long *>(&L.bm_join[wi]), ~bit);
-          }
-        }
-        tally_iterations(L.tl, L.tbth, p.tbt_w, p.tbt_lo, K, m, d, false, comp);
-        if (lane == 0 && flush_word) L.bm_flush[wi] = 0;
-      }
-      if (todo == 0) continue;
-      const uint64_t busy_word = L.bm_busy[wi];
-      bool busy = (busy_word >> lane) & 1ull;
-      if ((todo >> lane) & 1ull) {
-        const uint32_t pk = g < M ? remptok[g] : 0u;
-        const int rem = pk_rem(pk);
-        const int ptok = rem > 0 ? (rem < p.C ? rem : p.C) : 0;
-        const int n = L.loads[g];
-        if (ptok == 0 && n == 0) {
-          busy = false;
-        } else {
-          // back-to-back after a completion, otherwise from the step boundary
-          const int64_t base = ((due_word >> lane) & 1ull) ? T + static_cast<int64_t>(static_cast<int32_t>(L.t32[g] - T32)) : T;
-          const int64_t tn = base + p.c0 + p.cpre * ptok + p.cdec * static_cast<int64_t>(n);
-          L.t32[g] = static_cast<uint32_t>(tn);
-          busy = true;
-          if (ptok > 0) remptok[g] = pk | (static_cast<uint32_t>(ptok) << 16);
-        }
-      }
-      const uint64_t nb = __ballot(busy);
-      if (lane == 0 && nb != busy_word) L.bm_busy[wi] = nb;
-    }
-    PROF(10)
 
     // ================= 6. end-of-step sums =================
     if (tid < K) {
@@ -1136,11 +1208,17 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
     t_next[g] = busy ? T + static_cast<int64_t>(static_cast<int32_t>(L.t32[g] - static_cast<uint32_t>(T))) : kIdle;
     iter_g[g] = L.iter[g];
     if (g < M) {   // prompt tokens already processed of the prefill in service
-      const uint32_t pk = remptok[g];
-      if (pk_rem(pk)) {
-        const uint32_t Pl = (static_cast<uint32_t>(pf_job[g] >> 32) & 0xFFFFu) + 1;
-        atomicAdd(&L.acc[pk_cls(pk)], Pl - static_cast<uint32_t>(pk_rem(pk)));
+      const uint32_t rem = L.rem[g];
+      uint32_t pk = 0;
+      if (rem) {
+        const uint64_t jw = pf_job[g];
+        const uint32_t Pl = (static_cast<uint32_t>(jw >> 32) & 0xFFFFu) + 1, k = static_cast<uint32_t>(jw >> 29) & 7u;
+        atomicAdd(&L.acc[k], Pl - rem);
+        const bool chunk = (L.bm_chunk[g >> 6] >> (g & 63)) & 1ull;
+        const uint32_t cmax = static_cast<uint32_t>(p.C);
+        pk = rem | ((chunk ? (rem < cmax ? rem : cmax) : 0u) << 16) | (k << 29);
       }
+      remptok[g] = pk;
     }
   }
   for (int i = tid; i < CS_WORDS; i += NT) a.cstate[static_cast<size_t>(r) * CS_WORDS + i] = L.cs[i];
@@ -1297,9 +1375,9 @@ int launch_reduce(const Params &p, int reps, void *stream)
 #ifdef GNR_PROF
 extern "C" int gnr_prof_read(unsigned long long *out16, int reset)
 {
-  if (hipMemcpyFromSymbol(out16, HIP_SYMBOL(g_prof), sizeof(unsigned long long) * 16) != hipSuccess) return SIM_EHIP;
+  if (hipMemcpyFromSymbol(out16, HIP_SYMBOL(g_prof), sizeof(unsigned long long) * 32) != hipSuccess) return SIM_EHIP;
   if (reset) {
-    unsigned long long z[16] = {0};
+    unsigned long long z[32] = {0};
     if (hipMemcpyToSymbol(HIP_SYMBOL(g_prof), z, sizeof z) != hipSuccess) return SIM_EHIP;
   }
   return SIM_OK;
