@@ -11,7 +11,10 @@ LIB = os.path.join(HERE, "libgnr_sim.so")
 SOURCES = ["gnr_kernels.hip", "gnr_api.cpp", "gnr_tables.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared", "-ffp-contract=off",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function",
+         # the kernels combine the lanes of a wave themselves before they touch a shared counter; the
+         # compiler's own rewrite of atomics into wave-wide scans only adds code around them
+         "-mllvm", "-amdgpu-atomic-optimizer-strategy=None"]
 
 
 def build(verbose: bool = False) -> str:

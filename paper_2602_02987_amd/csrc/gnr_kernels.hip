@@ -455,17 +455,23 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
     const int wi = (i * NT + wave_base) >> 6;
     if (lane == 0 && wi < nwords) {
       L.bm_idle[wi] = bi; L.bm_busy[wi] = bb; L.bm_join[wi] = bj; L.bm_flush[wi] = 0; L.bm_chunk[wi] = bc;
+      L.bm_due[wi] = 0; L.bm_touch[wi] = 0;   // nothing waits for a restart when a launch begins
     }
   }
   __syncthreads();
 
   int64_t T = 0;
   PROF_DECL
-  for (uint32_t s = step_begin; s < step_begin + n_steps; ++s) {
+  // A server that completed an iteration, or was given work while idle, is restarted lazily: when its block
+  // is opened in the next step's completion pass (same lane, no extra sweep). After the last step of the launch
+  // one more pass over the blocks does only that, and tallies every iteration still untallied.
+  for (uint32_t s = step_begin; s <= step_begin + n_steps; ++s) {
     PROF(0)
-    const bool last_step = s + 1 == step_begin + n_steps;
+    const bool final_pass = s == step_begin + n_steps;
     T = (static_cast<int64_t>(s) + 1) * p.dt;
     const uint32_t T32 = static_cast<uint32_t>(T);
+    const int64_t Tp = T - p.dt;   // the boundary of the previous step: restarts refer to it
+    const uint32_t Tp32 = static_cast<uint32_t>(Tp);
     if (tid < 8) L.acc[tid] = 0;
     const uint32_t *thr = a.arr_thr + 3 * (p.mod_period > 0 ? static_cast<int64_t>(s % static_cast<uint64_t>(p.mod_period)) : 0);
     const uint32_t thr0 = thr[0], thr1 = thr[1], thr2 = thr[2];
@@ -633,14 +639,75 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
         const int gw = wi << 6;
         const int g = gw + lane;
         const uint64_t lbit = 1ull << lane;
-        const bool busy = g < N && (L.bm_busy[wi] & lbit);
-        o_due = busy && static_cast<int32_t>(L.t32[g] - T32) <= 0;
-        o_it = 0; o_nd = 0; o_pend = 0; o_q = 0;
+        const bool valid = g < N;
+        const uint64_t busy_word = L.bm_busy[wi], due_prev = L.bm_due[wi], touch_prev = L.bm_touch[wi];
+        const uint64_t flush_prev = L.bm_flush[wi];
+        uint32_t t32v = valid ? L.t32[g] : 0u;
+        const int nd = valid ? static_cast<int>(L.loads[g]) : 0;
+        int pend = valid ? static_cast<int>(L.pend[g]) : 0;
+        bool busy = busy_word & lbit;
+        // ---- (re)start of the servers that completed an iteration or were given work in the previous step.
+        //      Untallied iterations are tallied before the batch changes, and all of them when the launch ends.
+        const bool flush = valid && ((flush_prev & lbit) || (final_pass && pend != 0));
+        if (__ballot(flush)) {
+          uint32_t m = 0;
+          int64_t d = 0;
+          uint64_t comp = 0;
+          if (flush) {
+            const uint64_t nc = n_cls[g];
+            const bool joined = L.bm_join[wi] & lbit;
+            const uint64_t nj = joined ? n_join[g] : 0ull;
+            comp = bytes_sub(nc, nj);
+            d = p.c0 + p.cdec * static_cast<int64_t>(byte_sum(comp));   // untallied iterations never hold a chunk
+            m = static_cast<uint32_t>(pend);
+            pend = 0;
+            L.pend[g] = 0;
+            if ((flush_prev & lbit) && joined) {   // the decodes placed at the boundary joined the batch there
+              n_join[g] = 0;
+              atomicAnd(reinterpret_cast<unsigned long long *>(&L.bm_join[wi]), ~lbit);
+            }
+          }
+          tally_iterations(L.tl, L.tbth, p.tbt_w, p.tbt_lo, K, m, d, false, comp);
+          if (lane == 0 && flush_prev) L.bm_flush[wi] = 0;
+        }
+        const uint64_t todo = due_prev | touch_prev;
+        if (todo) {
+          bool chunk_now = false;
+          if (todo & lbit) {
+            const int rem = g < M ? static_cast<int>(L.rem[g]) : 0;
+            const int ptok = rem > 0 ? (rem < p.C ? rem : p.C) : 0;
+            chunk_now = ptok > 0;
+            if (ptok == 0 && nd == 0) {
+              busy = false;
+            } else {
+              // back-to-back after a completion, otherwise from the step boundary
+              const int64_t base = (due_prev & lbit) ? Tp + static_cast<int64_t>(static_cast<int32_t>(t32v - Tp32)) : Tp;
+              const int64_t tn = base + p.c0 + p.cpre * ptok + p.cdec * static_cast<int64_t>(nd);
+              t32v = static_cast<uint32_t>(tn);
+              L.t32[g] = t32v;
+              busy = true;
+            }
+          }
+          const uint64_t nb = __ballot(busy), nchunk = __ballot(chunk_now);
+          if (lane == 0) {
+            if (nb != busy_word) L.bm_busy[wi] = nb;
+            if (gw < M) L.bm_chunk[wi] = (L.bm_chunk[wi] & ~todo) | nchunk;
+          }
+        }
+        o_due = false; o_it = 0; o_nd = 0; o_pend = 0; o_q = 0;
+        if (final_pass) {   // only the restarts: the launch ends here
+          if (lane == 0) { L.bm_due[wi] = 0; L.bm_touch[wi] = 0; }
+          o_must = o_scan = false;
+          ne = 0; wide = false;
+          return;
+        }
+        // ---- which servers complete an iteration in this step
+        o_due = busy && static_cast<int32_t>(t32v - T32) <= 0;
         if (o_due) {
           o_it = L.iter[g] + 1;
           L.iter[g] = o_it;
-          o_nd = L.loads[g];
-          o_pend = L.pend[g];
+          o_nd = nd;
+          o_pend = pend;
         }
         const bool prefill_here = g < M && !(L.bm_idle[wi] & lbit);
         o_must = o_due && ((L.bm_join[wi] & lbit) || prefill_here || o_pend >= kMaxPend);
@@ -722,7 +789,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
       while (blk < nwords) {
         PROF(2)
         const int nblk = blk + nwaves;
-        {
+        if (!final_pass) {
           const int g = (blk << 6) + lane;
           if (g < N) arrivals(g);
         }
@@ -743,6 +810,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
       }
     }
     PROF(5)
+    if (final_pass) break;   // wave-uniform; the barrier after the loop follows
     __syncthreads();
     PROF(6)
 
@@ -832,8 +900,8 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
         jrem = dcount0 + (ncp < room ? ncp : room);
       }
       const uint32_t dhead0 = static_cast<uint32_t>(L.cs[CS_DHEAD]);
-      bool gate_on = true, route_on = jrem > 0, started = false;
-      for (int pass = 0; !started; ++pass) {
+      bool gate_on = true, route_on = jrem > 0;
+      for (int pass = 0; gate_on || route_on; ++pass) {
         if (gate_on && pass > 0) {
           if (tid < 64) {
             const uint32_t nidle = rank_bitmap(L.bm_idle, L.pre, nwords_m);
@@ -931,14 +999,19 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
             }
             total = jrem - rem_jobs;
             lmax = lmin + nl - 1;
-            for (int wi = wave; wi < nwords; wi += nwaves) {
-              const int g = (wi << 6) + lane;
-              const int load = (g >= lo && g < hi) ? static_cast<int>(L.loads[g]) : 1 << 20;
+            {
+              const int g0 = (wave << 6) + lane;
+              int load_next = (wave < nwords && g0 >= lo && g0 < hi) ? static_cast<int>(L.loads[g0]) : 1 << 20;
+              for (int wi = wave; wi < nwords; wi += nwaves) {
+                const int load = load_next;
+                const int gn = ((wi + nwaves) << 6) + lane;   // the next block's counts are read ahead
+                load_next = (wi + nwaves < nwords && gn >= lo && gn < hi) ? static_cast<int>(L.loads[gn]) : 1 << 20;
 #pragma unroll
-              for (int t = 0; t < kRouteLevels; ++t) {
-                if (t < nl) {
-                  const uint64_t bal = __ballot(load <= lmin + t);
-                  if (lane == 0) L.pre_lvl[t * nwords + wi] = static_cast<uint32_t>(__popcll(bal));
+                for (int t = 0; t < kRouteLevels; ++t) {
+                  if (t < nl) {
+                    const uint64_t bal = __ballot(load <= lmin + t);
+                    if (lane == 0) L.pre_lvl[t * nwords + wi] = static_cast<uint32_t>(__popcll(bal));
+                  }
                 }
               }
             }
@@ -1040,117 +1113,67 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
             L.sc[SC_ADMK + k] = 0;
           }
         }
-        const bool last_pass = !gate_more && (!route_on || total == jrem);
-        for (int wi = wave; wi < nwords; wi += nwaves) {
-          const int gw = wi << 6;
-          const int g = gw + lane;
-          const uint64_t bit = 1ull << lane;
-          if (route_on) {
-            const int load = (g >= lo && g < hi) ? static_cast<int>(L.loads[g]) : 1 << 20;
-            if (__ballot(load <= lmax)) {   // wave-uniform
-              const bool busy = L.bm_busy[wi] & bit;
-              const bool at_boundary = L.bm_due[wi] & bit;
-              const bool mid = busy && !at_boundary;   // a job placed now joins at the next restart
-              const bool has_prefill = g < M && !(L.bm_idle[wi] & bit);
-              bool got = false, got_last = false;
+        if (route_on) {
+          for (int wi = wave; wi < nwords; wi += nwaves) {
+            const int gw = wi << 6;
+            const int g = gw + lane;
+            const uint64_t bit = 1ull << lane;
+            const int n_own = g < N ? static_cast<int>(L.loads[g]) : 0;   // decodes of this lane's server
+            const int load = (g >= lo && g < hi) ? n_own : 1 << 20;
+            if (__ballot(load <= lmax) == 0) continue;   // wave-uniform
+            const uint64_t busy_word = L.bm_busy[wi], due_word = L.bm_due[wi], idle_word = L.bm_idle[wi];
+            const int pend_own = g < N ? static_cast<int>(L.pend[g]) : 0;
+            const bool busy0 = busy_word & bit, at_boundary = due_word & bit;
+            const bool mid = busy0 && !at_boundary;   // a job placed now joins at the next restart
+            const bool has_prefill = g < M && !(idle_word & bit);
+            // the new decode is not part of the iterations still to be tallied for this server
+            const bool joins = mid || (at_boundary && pend_own != 0);
+            bool got = false, got_last = false;
 #pragma unroll
-              for (int t = 0; t < kRouteLevels; ++t) {
-                if (t < nl) {   // wave-uniform
-                  const bool in = load <= lmin + t;
-                  const uint64_t bal = __ballot(in);
-                  if (bal) {
-                    const int q = static_cast<int>(L.pre_lvl[t * nwords + wi]) + __popcll(bal & lanes_below());
-                    if (in && q < L.sc[SC_TAKE_T + t]) {
-                      got = true;
-                      got_last = t == nl - 1;
-                      const int j = L.sc[SC_W_T + t] + q;   // position in this pass
-                      uint64_t jw;
-                      if (j < kJobsLds) {
-                        jw = L.jobs[j];
-                      } else {
-                        uint32_t pos = dhead0 + static_cast<uint32_t>(next + j);
-                        if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
-                        if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
-                        jw = dring[pos];
-                      }
-                      const int k = static_cast<int>(jw >> 29) & 7;
-                      const uint32_t Dl = static_cast<uint32_t>(jw >> 48) + 1;
-                      const int nd = lmin + t;   // the server holds exactly this many decodes by now
-                      fin[static_cast<size_t>(g) * BS + nd] = L.iter[g] + Dl + (mid ? 1u : 0u);
-                      job[static_cast<size_t>(g) * BS + nd] = jw;
-                      atomicAdd(reinterpret_cast<unsigned long long *>(&n_cls[g]), 1ull << (8 * k));
-                      // the new decode is not part of the iterations still to be tallied for this server
-                      if (mid || (at_boundary && L.pend[g]))
-                        atomicAdd(reinterpret_cast<unsigned long long *>(&n_join[g]), 1ull << (8 * k));
-                      lds_add64(&L.tl[k * kNTally + (has_prefill ? SIM_T_U_DM : SIM_T_U_DS)], 1);
-                      atomicAdd(&L.cs[(has_prefill ? CS_YM : CS_YS) + k], 1);
-                      atomicSub(&L.cs[CS_QD + k], 1);
+            for (int t = 0; t < kRouteLevels; ++t) {
+              if (t < nl) {   // wave-uniform
+                const bool in = load <= lmin + t;
+                const uint64_t bal = __ballot(in);
+                if (bal) {
+                  const int q = static_cast<int>(L.pre_lvl[t * nwords + wi]) + __popcll(bal & lanes_below());
+                  if (in && q < L.sc[SC_TAKE_T + t]) {
+                    got = true;
+                    got_last = t == nl - 1;
+                    const int j = L.sc[SC_W_T + t] + q;   // position in this pass
+                    uint64_t jw;
+                    if (j < kJobsLds) {
+                      jw = L.jobs[j];
+                    } else {
+                      uint32_t pos = dhead0 + static_cast<uint32_t>(next + j);
+                      if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
+                      if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
+                      jw = dring[pos];
                     }
+                    const int k = static_cast<int>(jw >> 29) & 7;
+                    const uint32_t Dl = static_cast<uint32_t>(jw >> 48) + 1;
+                    const int nd = lmin + t;   // the server holds exactly this many decodes by now
+                    fin[static_cast<size_t>(g) * BS + nd] = L.iter[g] + Dl + (mid ? 1u : 0u);
+                    job[static_cast<size_t>(g) * BS + nd] = jw;
+                    atomicAdd(reinterpret_cast<unsigned long long *>(&n_cls[g]), 1ull << (8 * k));
+                    if (joins) atomicAdd(reinterpret_cast<unsigned long long *>(&n_join[g]), 1ull << (8 * k));
+                    lds_add64(&L.tl[k * kNTally + (has_prefill ? SIM_T_U_DM : SIM_T_U_DS)], 1);
+                    atomicAdd(&L.cs[(has_prefill ? CS_YM : CS_YS) + k], 1);
+                    atomicSub(&L.cs[CS_QD + k], 1);
                   }
                 }
               }
-              if (got) {
-                if (mid || (at_boundary && L.pend[g])) {
-                  atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_join[wi]), bit);
-                  if (!mid) atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_flush[wi]), bit);
-                }
-                if (!busy) atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_touch[wi]), bit);
-              }
-              // every server with at most lmax decodes now holds lmax, plus one if the last level reached it
-              if (load <= lmax) L.loads[g] = static_cast<uint8_t>(lmax + (got_last ? 1 : 0));
             }
-          }
-          if (last_pass) {
-            // ---- (re)start of the servers that completed an iteration or were given work in this step
-            const bool valid = g < N;
-            const uint64_t due_word = L.bm_due[wi], flush_word = L.bm_flush[wi];
-            const uint64_t todo = due_word | L.bm_touch[wi];
-            // untallied iterations are tallied before the batch changes, and all of them when the launch ends
-            const bool flush = valid && ((flush_word & bit) || (last_step && L.pend[g] != 0));
-            if (__ballot(flush)) {
-              uint32_t m = 0;
-              int64_t d = 0;
-              uint64_t comp = 0;
-              if (flush) {
-                const uint64_t nc = n_cls[g];
-                const bool joined = L.bm_join[wi] & bit;
-                const uint64_t nj = joined ? n_join[g] : 0ull;
-                comp = bytes_sub(nc, nj);
-                d = p.c0 + p.cdec * static_cast<int64_t>(byte_sum(comp));   // untallied iterations never hold a chunk
-                m = L.pend[g];
-                L.pend[g] = 0;
-                if ((flush_word & bit) && joined) {   // the decodes placed at this boundary join the batch now
-                  n_join[g] = 0;
-                  atomicAnd(reinterpret_cast<unsigned long long *>(&L.bm_join[wi]), ~bit);
-                }
-              }
-              tally_iterations(L.tl, L.tbth, p.tbt_w, p.tbt_lo, K, m, d, false, comp);
-              if (lane == 0 && flush_word) L.bm_flush[wi] = 0;
+            // marks for the next completion pass: decodes that are not part of the untallied iterations;
+            // untallied iterations to tally before the restart; idle servers that now hold work
+            const uint64_t join_m = __ballot(got && joins), flush_m = __ballot(got && joins && !mid);
+            const uint64_t touch_m = __ballot(got && !busy0);
+            if (lane == 0) {
+              if (join_m) L.bm_join[wi] |= join_m;
+              if (flush_m) L.bm_flush[wi] |= flush_m;
+              if (touch_m) L.bm_touch[wi] |= touch_m;
             }
-            if (todo) {
-              const uint64_t busy_word = L.bm_busy[wi];
-              bool busy = busy_word & bit, chunk_now = false;
-              if (todo & bit) {
-                const int rem = g < M ? static_cast<int>(L.rem[g]) : 0;
-                const int ptok = rem > 0 ? (rem < p.C ? rem : p.C) : 0;
-                chunk_now = ptok > 0;
-                const int n = L.loads[g];
-                if (ptok == 0 && n == 0) {
-                  busy = false;
-                } else {
-                  // back-to-back after a completion, otherwise from the step boundary
-                  const int64_t base = (due_word & bit) ? T + static_cast<int64_t>(static_cast<int32_t>(L.t32[g] - T32)) : T;
-                  const int64_t tn = base + p.c0 + p.cpre * ptok + p.cdec * static_cast<int64_t>(n);
-                  L.t32[g] = static_cast<uint32_t>(tn);
-                  busy = true;
-                }
-              }
-              const uint64_t nb = __ballot(busy), nchunk = __ballot(chunk_now);
-              if (lane == 0) {
-                if (nb != busy_word) L.bm_busy[wi] = nb;
-                if (gw < M) L.bm_chunk[wi] = (L.bm_chunk[wi] & ~todo) | nchunk;
-              }
-            }
+            // every server with at most lmax decodes now holds lmax, plus one if the last level reached it
+            if (load <= lmax) L.loads[g] = static_cast<uint8_t>(lmax + (got_last ? 1 : 0));
           }
         }
         if (route_on) {
@@ -1164,7 +1187,6 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           route_on = jrem > 0;
         }
         gate_on = gate_more;
-        started = last_pass;
         PROF(10)
         __syncthreads();
         PROF(17)
