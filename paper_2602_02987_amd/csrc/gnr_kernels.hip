@@ -145,6 +145,7 @@ struct Lds {
   uint64_t *bm_touch; // [nwords] idle servers that were given work this step
   uint64_t *bm_flush; // [nwords] servers whose untallied iterations must be tallied at the restart
   uint64_t *bm_chunk; // [nwords] mixed-group servers whose running iteration carries a prefill chunk
+  uint64_t *bm_adm;   // [nwords] prefill slots that take an admission in this gate pass
   uint64_t *jobs;     // [kJobsLds] the first requests a routing pass places, copied from the decode buffer
   uint32_t *pre_lvl;  // [kRouteLevels][nwords] servers of the routed group with at most (level) decodes: per word, then ranks
   uint32_t *pre_c;    // [nwords] exclusive prefix popcounts of bm_comp
@@ -179,6 +180,7 @@ __host__ __device__ __forceinline__ Lds lds_carve(const Params &p, unsigned char
   GNR_TAKE(bm_touch, uint64_t, p.nwords)
   GNR_TAKE(bm_flush, uint64_t, p.nwords)
   GNR_TAKE(bm_chunk, uint64_t, p.nwords)
+  GNR_TAKE(bm_adm, uint64_t, p.nwords)
   GNR_TAKE(jobs, uint64_t, kJobsLds)
   GNR_TAKE(cs, int32_t, CS_WORDS)
   GNR_TAKE(acc, uint32_t, 8)
@@ -894,7 +896,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
     // kRouteLevels levels or into the mixed group.
     {
       const int dcount0 = L.cs[CS_DCOUNT];
-      int jrem, next = 0, grp = 0;
+      int jrem, next = 0;
       {
         const int ncp = L.sc[SC_NCOMP], room = static_cast<int>(p.dbuf_cap) - dcount0;
         jrem = dcount0 + (ncp < room ? ncp : room);
@@ -928,8 +930,25 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
             ncand += cnt[k];
           }
           nadm = ncand < limit ? ncand : limit;
-          for (int c = tid; c < ncand; c += NT) {
+          // The admissions take the first nadm idle prefill slots, whatever their order: the slot bitmaps are
+          // updated here a word at a time (no atomics); bm_adm keeps the slots for the admissions to find.
+          for (int w = tid; w < nwords_m; w += NT) {
+            const uint64_t idle = L.bm_idle[w];
+            const int before = static_cast<int>(L.pre[w]);   // idle slots in the words before this one
+            uint64_t adm = 0;
+            if (before < nadm)
+              adm = before + __popcll(idle) <= nadm ? idle : idle & ((1ull << nth_set_bit(idle, nadm - before)) - 1ull);
+            L.bm_adm[w] = adm;
+            if (adm) {
+              L.bm_idle[w] = idle & ~adm;
+              L.bm_touch[w] |= adm & ~L.bm_busy[w];   // an idle server is given work
+            }
+          }
+          for (int c0 = wave_base; c0 < ncand; c0 += NT) {   // wave-uniform trip count
+            const int c = c0 + lane;
+            bool admitted = false;
             int k = 0, m = c;
+            if (c < ncand) {
 #pragma unroll
             for (int kk = 0; kk < kMaxK - 1; ++kk)
               if (k == kk && m >= cnt[kk]) { m -= cnt[kk]; k = kk + 1; }
@@ -963,54 +982,79 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
               }
               rank += lo;
             }
-            if (rank < nadm) {
-              L.adm[rank] = static_cast<uint32_t>(k) | (static_cast<uint32_t>(m) << 3);
-              atomicAdd(&L.sc[SC_ADMK + k], 1);
+            admitted = rank < nadm;
+            if (admitted) L.adm[rank] = static_cast<uint32_t>(k) | (static_cast<uint32_t>(m) << 3);
+            }
+            // admissions per class: counted over the wave first (candidates of a class sit in neighbouring lanes)
+            for (int c = 0; c < K; ++c) {
+              const uint64_t mk = __ballot(admitted && k == c);
+              if (mk && lane == 0) atomicAdd(&L.sc[SC_ADMK + c], __popcll(mk));
             }
           }
         }
-        PROF(8)
-        int lmin = -1, nl = 0, csum = 0, total = 0, lmax = 0, take_last = 0, lo = 0, hi = 0;
+        // routing pass: up to kRouteLevels levels, first of the solo group (servers M..N-1), then, if that group
+        // is full by then, of the mixed group (servers 0..M-1, one slot less). Level t of group G holds the
+        // servers of G with at most lminG + (t - firstG) decodes.
+        int nl = 0, total = 0;
+        int lminG[2] = {0, 0}, nG[2] = {0, 0}, csumG[2] = {0, 0}, tlastG[2] = {0, 0};
         if (route_on) {
-          int capg = 0;
-          for (; grp < 2; ++grp) {   // solo group first; a group without a free slot is skipped
-            lo = grp == 0 ? M : 0; hi = grp == 0 ? N : M;
-            capg = grp == 0 ? B : B - 1;
-            if (lo >= hi) continue;
-            for (int base = 0; base < capg && lmin < 0; base += 64) {
+          // (every wave computes the same values and stores them: no broadcast, no barrier)
+          int rem_jobs = jrem;
+#pragma unroll
+          for (int gi = 0; gi < 2; ++gi) {
+            const int glo = gi == 0 ? M : 0, ghi = gi == 0 ? N : M;
+            const int capg = gi == 0 ? B : B - 1;
+            if (glo >= ghi || nl >= kRouteLevels || rem_jobs <= 0) continue;   // wave-uniform
+            int lm = -1;
+            for (int base = 0; base < capg && lm < 0; base += 64) {
               const int l = base + lane;
-              const uint64_t nz = __ballot(l < capg && L.lh[grp * kLoadBins + l] != 0);
-              if (nz) lmin = base + __ffsll(static_cast<long long>(nz)) - 1;
+              const uint64_t nz = __ballot(l < capg && L.lh[gi * kLoadBins + l] != 0);
+              if (nz) lm = base + __ffsll(static_cast<long long>(nz)) - 1;
             }
-            if (lmin >= 0) break;
+            if (lm < 0) continue;   // no free slot in this group
+            lminG[gi] = lm;
+            for (int u = 0; nl < kRouteLevels && rem_jobs > 0 && lm + u < capg; ++u) {
+              csumG[gi] += static_cast<int>(L.lh[gi * kLoadBins + lm + u]);
+              const int tk = csumG[gi] < rem_jobs ? csumG[gi] : rem_jobs;
+              if (lane == 0) { L.sc[SC_TAKE_T + nl] = tk; L.sc[SC_W_T + nl] = jrem - rem_jobs; }
+              rem_jobs -= tk;
+              tlastG[gi] = tk;
+              ++nG[gi];
+              ++nl;
+            }
           }
-          if (lmin < 0) {
+          PROF(24)
+          total = jrem - rem_jobs;
+          if (nl == 0) {
             route_on = false;   // every slot is taken: the jobs stay in the buffer
           } else {
-            // levels of this pass: servers with at most lmin+t decodes, jobs taken and jobs before it
-            // (every wave computes the same values and stores them: no broadcast, no barrier)
-            int rem_jobs = jrem;
-            for (int t = 0; t < kRouteLevels && rem_jobs > 0 && lmin + t < capg; ++t) {
-              csum += static_cast<int>(L.lh[grp * kLoadBins + lmin + t]);
-              take_last = csum < rem_jobs ? csum : rem_jobs;
-              if (lane == 0) { L.sc[SC_TAKE_T + t] = take_last; L.sc[SC_W_T + t] = jrem - rem_jobs; }
-              rem_jobs -= take_last;
-              nl = t + 1;
-            }
-            total = jrem - rem_jobs;
-            lmax = lmin + nl - 1;
-            {
-              const int g0 = (wave << 6) + lane;
-              int load_next = (wave < nwords && g0 >= lo && g0 < hi) ? static_cast<int>(L.loads[g0]) : 1 << 20;
-              for (int wi = wave; wi < nwords; wi += nwaves) {
-                const int load = load_next;
-                const int gn = ((wi + nwaves) << 6) + lane;   // the next block's counts are read ahead
-                load_next = (wi + nwaves < nwords && gn >= lo && gn < hi) ? static_cast<int>(L.loads[gn]) : 1 << 20;
+            PROF(25)
+            // four blocks per round: their decode counts are read together, then compared level by level
+            for (int w0 = wave; w0 < nwords; w0 += 4 * nwaves) {
+              int tmin4[4], tend4[4];
 #pragma unroll
-                for (int t = 0; t < kRouteLevels; ++t) {
-                  if (t < nl) {
-                    const uint64_t bal = __ballot(load <= lmin + t);
-                    if (lane == 0) L.pre_lvl[t * nwords + wi] = static_cast<uint32_t>(__popcll(bal));
+              for (int u = 0; u < 4; ++u) {
+                const int wi = w0 + u * nwaves;
+                const int g = (wi << 6) + lane;
+                tmin4[u] = 0; tend4[u] = 0;
+                if (wi < nwords && g < N) {
+                  const int gi = g >= M ? 0 : 1;
+                  const int first = gi == 0 ? 0 : nG[0];
+                  const int d = static_cast<int>(L.loads[g]) - (gi == 0 ? lminG[0] : lminG[1]);
+                  tmin4[u] = first + (d > 0 ? d : 0);
+                  tend4[u] = first + (gi == 0 ? nG[0] : nG[1]);
+                }
+              }
+#pragma unroll
+              for (int u = 0; u < 4; ++u) {
+                const int wi = w0 + u * nwaves;
+                if (wi < nwords) {   // wave-uniform
+#pragma unroll
+                  for (int t = 0; t < kRouteLevels; ++t) {
+                    if (t < nl) {
+                      const uint64_t bal = __ballot(t >= tmin4[u] && t < tend4[u]);
+                      if (lane == 0) L.pre_lvl[t * nwords + wi] = static_cast<uint32_t>(__popcll(bal));
+                    }
                   }
                 }
               }
@@ -1032,7 +1076,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
             int k = 0;
             uint64_t wait = 0, nc = 0;
             if (active) {
-              const int g = select_bit(L.bm_idle, L.pre, nwords_m, static_cast<uint32_t>(j));
+              const int g = select_bit(L.bm_adm, L.pre, nwords_m, static_cast<uint32_t>(j));
               const uint32_t e = L.adm[j];
               k = static_cast<int>(e & 7u);
               uint32_t pos = static_cast<uint32_t>(L.cs[CS_QHEAD + k]) + (e >> 3);
@@ -1049,10 +1093,9 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
               // an idle prefill slot implies that the running iteration holds no chunk
               L.rem[g] = static_cast<uint16_t>(Pl);
               const uint64_t bit = 1ull << (g & 63);
-              atomicAnd(reinterpret_cast<unsigned long long *>(&L.bm_idle[g >> 6]), ~bit);
-              if (!(L.bm_busy[g >> 6] & bit)) atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_touch[g >> 6]), bit);
               // at an iteration boundary the next iteration carries a chunk: tally the untallied ones first
-              else if ((L.bm_due[g >> 6] & bit) && L.pend[g]) atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_flush[g >> 6]), bit);
+              if ((L.bm_busy[g >> 6] & bit) && (L.bm_due[g >> 6] & bit) && L.pend[g])
+                atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_flush[g >> 6]), bit);
             }
             wave_sum_by_class(active, k, K, wait, &L.tl[SIM_T_WAIT_STEPS], kNTally);
             uint64_t even, odd;   // co-resident decodes switch solo -> mixed
@@ -1114,15 +1157,26 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           }
         }
         if (route_on) {
+          int take_r[kRouteLevels], w_r[kRouteLevels];
+#pragma unroll
+          for (int t = 0; t < kRouteLevels; ++t) { take_r[t] = L.sc[SC_TAKE_T + t]; w_r[t] = L.sc[SC_W_T + t]; }
           for (int wi = wave; wi < nwords; wi += nwaves) {
             const int gw = wi << 6;
             const int g = gw + lane;
             const uint64_t bit = 1ull << lane;
+            // what the block needs from LDS is read in one go
             const int n_own = g < N ? static_cast<int>(L.loads[g]) : 0;   // decodes of this lane's server
-            const int load = (g >= lo && g < hi) ? n_own : 1 << 20;
-            if (__ballot(load <= lmax) == 0) continue;   // wave-uniform
-            const uint64_t busy_word = L.bm_busy[wi], due_word = L.bm_due[wi], idle_word = L.bm_idle[wi];
             const int pend_own = g < N ? static_cast<int>(L.pend[g]) : 0;
+            const uint64_t busy_word = L.bm_busy[wi], due_word = L.bm_due[wi], idle_word = L.bm_idle[wi];
+            int pre_r[kRouteLevels];
+#pragma unroll
+            for (int t = 0; t < kRouteLevels; ++t) pre_r[t] = static_cast<int>(L.pre_lvl[(t < nl ? t : 0) * nwords + wi]);
+            // levels tmin..tend-1 of the pass hold this lane's server
+            const int gi = g >= M ? 0 : 1;
+            const int first = gi == 0 ? 0 : nG[0], my_n = gi == 0 ? nG[0] : nG[1], my_lmin = gi == 0 ? lminG[0] : lminG[1];
+            const int tend = g < N ? first + my_n : 0;
+            const int tmin = first + (n_own > my_lmin ? n_own - my_lmin : 0);
+            if (__ballot(tmin < tend) == 0) continue;   // wave-uniform
             const bool busy0 = busy_word & bit, at_boundary = due_word & bit;
             const bool mid = busy0 && !at_boundary;   // a job placed now joins at the next restart
             const bool has_prefill = g < M && !(idle_word & bit);
@@ -1132,14 +1186,14 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
 #pragma unroll
             for (int t = 0; t < kRouteLevels; ++t) {
               if (t < nl) {   // wave-uniform
-                const bool in = load <= lmin + t;
+                const bool in = t >= tmin && t < tend;
                 const uint64_t bal = __ballot(in);
                 if (bal) {
-                  const int q = static_cast<int>(L.pre_lvl[t * nwords + wi]) + __popcll(bal & lanes_below());
-                  if (in && q < L.sc[SC_TAKE_T + t]) {
+                  const int q = pre_r[t] + __popcll(bal & lanes_below());
+                  if (in && q < take_r[t]) {
                     got = true;
-                    got_last = t == nl - 1;
-                    const int j = L.sc[SC_W_T + t] + q;   // position in this pass
+                    got_last = t == tend - 1;
+                    const int j = w_r[t] + q;   // position in this pass
                     uint64_t jw;
                     if (j < kJobsLds) {
                       jw = L.jobs[j];
@@ -1151,7 +1205,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
                     }
                     const int k = static_cast<int>(jw >> 29) & 7;
                     const uint32_t Dl = static_cast<uint32_t>(jw >> 48) + 1;
-                    const int nd = lmin + t;   // the server holds exactly this many decodes by now
+                    const int nd = my_lmin + (t - first);   // the server holds exactly this many decodes by now
                     fin[static_cast<size_t>(g) * BS + nd] = L.iter[g] + Dl + (mid ? 1u : 0u);
                     job[static_cast<size_t>(g) * BS + nd] = jw;
                     atomicAdd(reinterpret_cast<unsigned long long *>(&n_cls[g]), 1ull << (8 * k));
@@ -1167,20 +1221,24 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
             // untallied iterations to tally before the restart; idle servers that now hold work
             const uint64_t join_m = __ballot(got && joins), flush_m = __ballot(got && joins && !mid);
             const uint64_t touch_m = __ballot(got && !busy0);
-            if (lane == 0) {
-              if (join_m) L.bm_join[wi] |= join_m;
-              if (flush_m) L.bm_flush[wi] |= flush_m;
-              if (touch_m) L.bm_touch[wi] |= touch_m;
+            if (lane == 0) {   // fire and forget: nothing here waits for the old words
+              if (join_m) atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_join[wi]), join_m);
+              if (flush_m) atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_flush[wi]), flush_m);
+              if (touch_m) atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_touch[wi]), touch_m);
             }
-            // every server with at most lmax decodes now holds lmax, plus one if the last level reached it
-            if (load <= lmax) L.loads[g] = static_cast<uint8_t>(lmax + (got_last ? 1 : 0));
+            // every server below the last level of its group now holds that level, plus one if that level reached it
+            if (tmin < tend) L.loads[g] = static_cast<uint8_t>(my_lmin + my_n - 1 + (got_last ? 1 : 0));
           }
-        }
-        if (route_on) {
           if (tid == 0) {
-            for (int t = 0; t + 1 < nl; ++t) L.lh[grp * kLoadBins + lmin + t] = 0;
-            L.lh[grp * kLoadBins + lmax] = static_cast<uint32_t>(csum - take_last);
-            L.lh[grp * kLoadBins + lmax + 1] += static_cast<uint32_t>(take_last);
+#pragma unroll
+            for (int gi = 0; gi < 2; ++gi) {
+              if (nG[gi] > 0) {
+                const int lmaxg = lminG[gi] + nG[gi] - 1;
+                for (int t = 0; t + 1 < nG[gi]; ++t) L.lh[gi * kLoadBins + lminG[gi] + t] = 0;
+                L.lh[gi * kLoadBins + lmaxg] = static_cast<uint32_t>(csumG[gi] - tlastG[gi]);
+                L.lh[gi * kLoadBins + lmaxg + 1] += static_cast<uint32_t>(tlastG[gi]);
+              }
+            }
           }
           jrem -= total;
           next += total;
