@@ -20,7 +20,7 @@ constexpr int kNTally = SIM_NTALLY;
 constexpr int kNGlobal = SIM_NGLOBAL;
 constexpr int kTallyWords = kMaxK * kNTally + kNGlobal;  // per replication, uint64
 constexpr int64_t kIdle = INT64_MAX;
-constexpr int kAdmChunk = 1024;   // admissions decided per gate pass
+constexpr int kAdmChunk = 256;    // admissions decided per gate pass
 constexpr int kMaxTbtBins = 256;  // width of the on-chip time-between-tokens histogram window
 
 // Per-replication class-level state, int32 words (persisted between launches).

@@ -128,7 +128,7 @@ enum Scalar {
 constexpr int kLoadBins = kMaxB + 1;
 constexpr int kEvPerWave = 128;   // servers a wave can queue for finishing; when full the queue is drained early
 constexpr int kRouteLevels = 4;
-constexpr int kJobsLds = 512;      // requests of a routing pass staged in LDS; later ones are read from the buffer   // load levels one routing pass fills
+constexpr int kJobsLds = 256;      // requests of a routing pass staged in LDS; later ones are read from the buffer
 constexpr int kMaxPend = 254;     // untallied iterations a server may accumulate (kept in a byte)
 
 struct Lds {
@@ -154,7 +154,7 @@ struct Lds {
   uint32_t *lh;       // [2][kLoadBins] servers per decode count: solo group, mixed group
   uint32_t *ev_g;     // [waves][kEvPerWave] servers queued for finishing, per wave
   uint32_t *ev_q;     // [waves][kEvPerWave] their slot-quad masks
-  uint8_t *stage;     // [waves][64] lanes of the due servers with decodes, of the round a wave has open
+  uint8_t *stage;     // [waves][128] row halves to scan of the block a wave has open: lane | half << 6
   uint32_t *t32;      // [N] low 32 bits of the end time of the running iteration
   uint32_t *iter;     // [N] completed iterations
   uint8_t *loads;     // [N] decodes per server
@@ -197,7 +197,7 @@ __host__ __device__ __forceinline__ Lds lds_carve(const Params &p, unsigned char
   GNR_TAKE(loads, uint8_t, p.N)
   GNR_TAKE(pend, uint8_t, p.N)
   GNR_TAKE(rem, uint16_t, p.M)
-  GNR_TAKE(stage, uint8_t, p.threads)
+  GNR_TAKE(stage, uint8_t, 2 * p.threads)
 #undef GNR_TAKE
   if (total) *total = off;
   return L;
@@ -614,24 +614,23 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
     };
 
     // ---- completion pass, one round of 64 servers (one per lane) at a time.
-    //      open_round: due test; the due servers that hold decodes are listed in `stage`.
-    //      issue: eight lanes read one server's slot row, 16 bytes per lane and load, the first 64 slots in
-    //      two loads (rows with more decodes take a second pass for slots 64..127).
-    //      process: the finish words are compared with the server's iteration index; the hit masks travel back
-    //      to the owning lanes. finalize: a server whose batch changes, or that carries a prefill, is queued for
-    //      finishing; for any other the iteration is only counted. The loads of the next round travel while
-    //      the queue is drained and the next round's arrivals are drawn.
+    //      open_round: due test; the slot rows of the due servers are listed in `stage`, 64 slots (half a row)
+    //      per entry. issue_group: eight lanes read one entry, 16 bytes per lane and load; a group is eight
+    //      entries. process_group: the finish words are compared with the server's iteration index; the hit masks
+    //      travel back to the owning lanes. Four groups are in flight: as soon as one is compared its registers
+    //      take the next group of the block, and the first four groups of a block are issued before the arrivals
+    //      of the block are drawn. finalize: a server whose batch changes, or that carries a prefill, is queued
+    //      for finishing; for any other the iteration is only counted.
     //      Slots beyond a server's decode count never hold a future iteration index (they are cleared when
     //      vacated), so the comparison needs no occupancy mask.
     {
-      constexpr int Q = 4;   // groups of eight servers per batch
+      constexpr int Q = 4;   // groups of eight row halves in flight
       const int l8 = lane & 7, grp = lane >> 3;
       const uint64_t below = lanes_below();
-      uint8_t *stage = L.stage + wave * 64;
+      uint8_t *stage = L.stage + wave * 128;
       int nev = 0;          // servers queued by this wave (wave-uniform)
-      int ne = 0;           // servers listed for the open round (wave-uniform)
-      bool wide = false;    // a listed server holds more than 64 decodes (wave-uniform)
-      bool o_due = false, o_must = false, o_scan = false;   // owner-lane state of the open round
+      int ne = 0;           // row halves listed for the open block (wave-uniform)
+      bool o_due = false, o_must = false, o_scan = false, o_big = false;   // owner-lane state of the open round
       int o_rank = 0, o_nd = 0, o_pend = 0;
       uint32_t o_it = 0, o_q = 0;
       uint4 v[Q][2];
@@ -682,10 +681,11 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
             if (ptok == 0 && nd == 0) {
               busy = false;
             } else {
-              // back-to-back after a completion, otherwise from the step boundary
-              const int64_t base = (due_prev & lbit) ? Tp + static_cast<int64_t>(static_cast<int32_t>(t32v - Tp32)) : Tp;
-              const int64_t tn = base + p.c0 + p.cpre * ptok + p.cdec * static_cast<int64_t>(nd);
-              t32v = static_cast<uint32_t>(tn);
+              // back-to-back after a completion, otherwise from the step boundary; only the low 32 bits of the
+              // clock are kept and an iteration lasts less than 2^31 ns, so 32-bit arithmetic is exact here
+              const uint32_t dur = static_cast<uint32_t>(p.c0) + static_cast<uint32_t>(p.cpre) * static_cast<uint32_t>(ptok) +
+                                   static_cast<uint32_t>(p.cdec) * static_cast<uint32_t>(nd);
+              t32v = ((due_prev & lbit) ? t32v : Tp32) + dur;
               L.t32[g] = t32v;
               busy = true;
             }
@@ -699,8 +699,8 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
         o_due = false; o_it = 0; o_nd = 0; o_pend = 0; o_q = 0;
         if (final_pass) {   // only the restarts: the launch ends here
           if (lane == 0) { L.bm_due[wi] = 0; L.bm_touch[wi] = 0; }
-          o_must = o_scan = false;
-          ne = 0; wide = false;
+          o_must = o_scan = o_big = false;
+          ne = 0;
           return;
         }
         // ---- which servers complete an iteration in this step
@@ -714,60 +714,55 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
         const bool prefill_here = g < M && !(L.bm_idle[wi] & lbit);
         o_must = o_due && ((L.bm_join[wi] & lbit) || prefill_here || o_pend >= kMaxPend);
         o_scan = o_due && o_nd > 0;
-        const uint64_t dm = __ballot(o_due), sm = __ballot(o_scan);
-        wide = __ballot(o_nd > 64) != 0;
-        o_rank = __popcll(sm & below);
-        ne = __popcll(sm);
-        if (o_scan) stage[o_rank] = static_cast<uint8_t>(lane);
+        o_big = o_scan && o_nd > 64;   // the row's second half holds decodes too
+        const uint64_t dm = __ballot(o_due), sm = __ballot(o_scan), bg = __ballot(o_big);
+        o_rank = __popcll(sm & below) + __popcll(bg & below);
+        ne = __popcll(sm) + __popcll(bg);
+        if (o_scan) {
+          stage[o_rank] = static_cast<uint8_t>(lane);
+          if (o_big) stage[o_rank + 1] = static_cast<uint8_t>(lane | 64);
+        }
         if (lane == 0) {
           L.bm_due[wi] = dm;
           L.bm_touch[wi] = 0;
           L.bm_comp[wi] = 0;
         }
       };
-      // half 0: slots 0..63 of each listed row, half 1: slots 64..127
-      auto issue = [&](int wi, int b, int half) __attribute__((always_inline)) {
+      // group gi of the open block goes into register set t
+      auto issue_group = [&](int wi, int t, int gi) __attribute__((always_inline)) {
         const uint32_t gw = static_cast<uint32_t>(wi) << 6;
-#pragma unroll
-        for (int t = 0; t < Q; ++t) {
-          v[t][0] = v[t][1] = make_uint4(0u, 0u, 0u, 0u);
-          vit[t] = 0xFFFFFFFFu;
-          const int p0 = 8 * (b * Q + t);
-          if (p0 < ne) {   // wave-uniform
-            const int pidx = p0 + grp;
-            const bool ok = pidx < ne;
-            const int sid = ok ? stage[pidx] : 0;
-            const uint32_t its = __shfl(o_it, sid, 64);
-            const int nds = __shfl(o_nd, sid, 64);
-            if (ok) {
-              vit[t] = its;
-              const int q0 = 16 * half + l8;   // this lane's quads of the row: q0 and q0 + 8
-              const uint32_t off = (gw + static_cast<uint32_t>(sid)) * static_cast<uint32_t>(BS) + 4u * q0;
-              if (4 * q0 < nds) v[t][0] = *reinterpret_cast<const uint4 *>(fin + off);
-              if (4 * q0 + 32 < nds) v[t][1] = *reinterpret_cast<const uint4 *>(fin + off + 32u);
-            }
-          }
+        const int pidx = 8 * gi + grp;
+        const bool ok = pidx < ne;
+        const int e = ok ? stage[pidx] : 0;
+        const int sid = e & 63, half = e >> 6;
+        const uint32_t its = __shfl(o_it, sid, 64);
+        const int nds_all = __shfl(o_nd, sid, 64);   // every lane takes part: the owner may sit in a lane without an entry
+        const int nds = ok ? nds_all : 0;
+        const int q0 = 16 * half + l8;   // this lane's quads of the row: q0 and q0 + 8
+        const uint32_t off = (gw + static_cast<uint32_t>(sid)) * static_cast<uint32_t>(BS) + 4u * q0;
+        // a register that is not loaded holds zeros, which no iteration index equals (the first is 1)
+        vit[t] = its;
+        v[t][0] = v[t][1] = make_uint4(0u, 0u, 0u, 0u);
+        if (4 * q0 < nds) v[t][0] = *reinterpret_cast<const uint4 *>(fin + off);
+        if (4 * q0 + 32 < nds) v[t][1] = *reinterpret_cast<const uint4 *>(fin + off + 32u);
+      };
+      auto process_group = [&](int t, int gi) __attribute__((always_inline)) {
+        const uint32_t it = vit[t];
+        const bool m0 = v[t][0].x == it || v[t][0].y == it || v[t][0].z == it || v[t][0].w == it;
+        const bool m1 = v[t][1].x == it || v[t][1].y == it || v[t][1].z == it || v[t][1].w == it;
+        if (__ballot(m0 || m1)) {   // a decode emits its last token: rare
+          const uint64_t bal0 = __ballot(m0), bal1 = __ballot(m1);
+          const int d0 = o_rank - 8 * gi, d1 = d0 + 1;   // this owner's entries, counted within the group
+          if (o_scan && static_cast<unsigned>(d0) < 8u)
+            o_q |= (static_cast<uint32_t>(bal0 >> (8 * d0)) & 0xFFu) | ((static_cast<uint32_t>(bal1 >> (8 * d0)) & 0xFFu) << 8);
+          if (o_big && static_cast<unsigned>(d1) < 8u)
+            o_q |= ((static_cast<uint32_t>(bal0 >> (8 * d1)) & 0xFFu) | ((static_cast<uint32_t>(bal1 >> (8 * d1)) & 0xFFu) << 8)) << 16;
         }
       };
-      auto process = [&](int b, int half) __attribute__((always_inline)) {
+      auto prefetch = [&](int wi) __attribute__((always_inline)) {   // the first groups of a block just opened
 #pragma unroll
-        for (int t = 0; t < Q; ++t) {
-          const int p0 = 8 * (b * Q + t);
-          if (p0 < ne) {   // wave-uniform
-            const uint32_t it = vit[t];
-            const bool m0 = v[t][0].x == it || v[t][0].y == it || v[t][0].z == it || v[t][0].w == it;
-            const bool m1 = v[t][1].x == it || v[t][1].y == it || v[t][1].z == it || v[t][1].w == it;
-            if (__ballot(m0 || m1)) {   // a decode emits its last token: rare
-              const uint64_t bal0 = __ballot(m0), bal1 = __ballot(m1);
-              const int d = o_rank - p0;
-              if (o_scan && static_cast<unsigned>(d) < 8u) {
-                const uint32_t h = (static_cast<uint32_t>(bal0 >> (8 * d)) & 0xFFu) |
-                                   ((static_cast<uint32_t>(bal1 >> (8 * d)) & 0xFFu) << 8);
-                o_q |= h << (16 * half);
-              }
-            }
-          }
-        }
+        for (int t = 0; t < Q; ++t)
+          if (8 * t < ne) issue_group(wi, t, t);   // wave-uniform
       };
       auto finalize = [&](int wi) __attribute__((always_inline)) {
         const int g = (wi << 6) + lane;
@@ -787,7 +782,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
       // wave w owns the 64-server blocks w, w + nwaves, w + 2 nwaves, ...
       PROF(1)
       int blk = wave;
-      if (blk < nwords) { open_round(blk); issue(blk, 0, 0); }
+      if (blk < nwords) { open_round(blk); prefetch(blk); }
       while (blk < nwords) {
         PROF(2)
         const int nblk = blk + nwaves;
@@ -796,18 +791,24 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           if (g < N) arrivals(g);
         }
         PROF(3)
-        process(0, 0);
-        for (int b = 1; 8 * Q * b < ne; ++b) { issue(blk, b, 0); process(b, 0); }
-        if (wide)
-          for (int b = 0; 8 * Q * b < ne; ++b) { issue(blk, b, 1); process(b, 1); }
+        for (int g0 = 0; 8 * g0 < ne; g0 += Q) {
+#pragma unroll
+          for (int t = 0; t < Q; ++t) {
+            const int gi = g0 + t;
+            if (8 * gi < ne) {   // wave-uniform
+              process_group(t, gi);
+              if (8 * (gi + Q) < ne) issue_group(blk, t, gi + Q);   // the freed registers take the next group
+            }
+          }
+        }
         finalize(blk);
-        if (nblk < nwords) { open_round(nblk); issue(nblk, 0, 0); }
         PROF(2)
-        if (nev > kEvPerWave - 64 || nblk >= nwords) {
+        if (nev > kEvPerWave - 64 || nblk >= nwords) {   // before the next block is opened: fewer live registers
           drain_events(nev);
           nev = 0;
         }
         PROF(4)
+        if (nblk < nwords) { open_round(nblk); prefetch(nblk); }   // its loads travel while the arrivals are drawn
         blk = nblk;
       }
     }
@@ -916,15 +917,16 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
         // ---------------- segment A ----------------
         int nadm = 0, nidle = 0;
         if (gate_on) {
-          nidle = L.sc[SC_NIDLE];
+          nidle = __builtin_amdgcn_readfirstlane(L.sc[SC_NIDLE]);
           const int limit = nidle < kAdmChunk ? nidle : kAdmChunk;
           int cnt[kMaxK], qp[kMaxK], xs[kMaxK], ncand = 0;
           uint32_t head[kMaxK];
 #pragma unroll
           for (int k = 0; k < kMaxK; ++k) {
-            qp[k] = k < K ? L.cs[CS_QP + k] : 0;
-            xs[k] = k < K ? L.cs[CS_X + k] : 0;
-            head[k] = k < K ? static_cast<uint32_t>(L.cs[CS_QHEAD + k]) : 0u;
+            // wave-uniform values, kept in scalar registers
+            qp[k] = k < K ? __builtin_amdgcn_readfirstlane(L.cs[CS_QP + k]) : 0;
+            xs[k] = k < K ? __builtin_amdgcn_readfirstlane(L.cs[CS_X + k]) : 0;
+            head[k] = k < K ? static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(L.cs[CS_QHEAD + k])) : 0u;
             const bool eligible = k < K && qp[k] > 0 && (p.gate_mode != SIM_GATE_OCCUPANCY || p.invx[k] > 0.0);
             cnt[k] = eligible ? (qp[k] < limit ? qp[k] : limit) : 0;
             ncand += cnt[k];
@@ -1159,7 +1161,10 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
         if (route_on) {
           int take_r[kRouteLevels], w_r[kRouteLevels];
 #pragma unroll
-          for (int t = 0; t < kRouteLevels; ++t) { take_r[t] = L.sc[SC_TAKE_T + t]; w_r[t] = L.sc[SC_W_T + t]; }
+          for (int t = 0; t < kRouteLevels; ++t) {
+            take_r[t] = __builtin_amdgcn_readfirstlane(L.sc[SC_TAKE_T + t]);
+            w_r[t] = __builtin_amdgcn_readfirstlane(L.sc[SC_W_T + t]);
+          }
           for (int wi = wave; wi < nwords; wi += nwaves) {
             const int gw = wi << 6;
             const int g = gw + lane;
@@ -1170,7 +1175,8 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
             const uint64_t busy_word = L.bm_busy[wi], due_word = L.bm_due[wi], idle_word = L.bm_idle[wi];
             int pre_r[kRouteLevels];
 #pragma unroll
-            for (int t = 0; t < kRouteLevels; ++t) pre_r[t] = static_cast<int>(L.pre_lvl[(t < nl ? t : 0) * nwords + wi]);
+            for (int t = 0; t < kRouteLevels; ++t)
+              pre_r[t] = __builtin_amdgcn_readfirstlane(static_cast<int>(L.pre_lvl[(t < nl ? t : 0) * nwords + wi]));
             // levels tmin..tend-1 of the pass hold this lane's server
             const int gi = g >= M ? 0 : 1;
             const int first = gi == 0 ? 0 : nG[0], my_n = gi == 0 ? nG[0] : nG[1], my_lmin = gi == 0 ? lminG[0] : lminG[1];

@@ -98,3 +98,61 @@ def test_full_size_configs_on_sampled_replications(B, oracle_mod):
         cfg = W.config(n)
         sample = [0, 1, cfg.replications - 1]
         run_both(B, oracle_mod, cfg, steps, oracle_reps=sample)
+
+
+def _limits_class(**kw):
+    base = dict(lam=1.0, in_law=W.LAW_CONST, in_p0=64.0, out_law=W.LAW_GEOMETRIC, out_p0=4.0)
+    base.update(kw)
+    return W.SimClass(**base)
+
+
+def _limits_cfg(name, classes, N, M, B, steps, x_star=None, **kw):
+    K = len(classes)
+    return W.SimConfig(name=name, K=K, N=N, B=B, C=256, c0=0.010, c_pre=0.00005, c_dec=0.0002, classes=classes, M=M,
+                       x_star=x_star or [0.3 / K] * K, qp_star=[0.0] * K, queue_cap=kw.pop("queue_cap", 4096),
+                       dbuf_cap=kw.pop("dbuf_cap", 4096), replications=kw.pop("replications", 2), steps=steps,
+                       seed=kw.pop("seed", 5), **kw)
+
+
+def test_rows_with_more_than_64_decodes(B, oracle_mod):
+    """B = 128 and an overloaded decode side: slot rows fill past 64 and up to the cap, so both halves of a row
+    are scanned, decodes leave from either half, and the last slot of a full row is reused."""
+    cls = [_limits_class(lam=2.4, in_p0=200.0, out_p0=3000.0), _limits_class(lam=1.6, in_p0=90.0, out_p0=1500.0)]
+    cfg = _limits_cfg("wide-rows", cls, N=48, M=16, B=128, steps=5000)
+    sim, orc = run_both(B, oracle_mod, cfg, 5000, checkpoints=2)
+    assert_stats_equal(sim.stats(), orc.stats())
+    loads = orc.slots(0)["n_dec"]
+    assert loads.max() == 128 and (loads > 64).sum() > 20
+
+
+def test_more_admissions_and_placements_than_one_pass_stages(B, oracle_mod):
+    """Several hundred admissions and placements in one step: more than one gate pass decides (256) and more
+    requests than a routing pass stages on chip (256)."""
+    cls = [_limits_class(lam=2.5), _limits_class(lam=2.0, in_p0=40.0, out_p0=6.0)]
+    cfg = _limits_cfg("bursts", cls, N=8192, M=5000, B=8, steps=40, replications=1)
+    sim, orc = run_both(B, oracle_mod, cfg, 40, checkpoints=2)
+    t, _ = orc.tallies(0)
+    from paper_2602_02987_amd.binding import TALLY
+    ti = {n: i for i, n in enumerate(TALLY)}
+    assert t[:, ti["U_P"]].sum() / 40 > 300 and (t[:, ti["U_DM"]].sum() + t[:, ti["U_DS"]].sum()) / 40 > 280
+
+
+def test_jobs_spread_over_many_load_levels(B, oracle_mod):
+    """Three solo servers with unequal loads take several jobs per step: more load levels than one routing
+    pass fills (4), then the mixed group once the solo group is full."""
+    cls = [_limits_class(lam=1.0, out_p0=2.0)]
+    cfg = _limits_cfg("levels", cls, N=1000, M=997, B=128, steps=1500, x_star=[0.5])
+    sim, orc = run_both(B, oracle_mod, cfg, 1500, checkpoints=2)
+    assert_stats_equal(sim.stats(), orc.stats())
+    cls = [_limits_class(lam=4.5, out_p0=40.0)]   # the solo group saturates: the rest goes to the mixed group
+    cfg = _limits_cfg("levels-full", cls, N=200, M=197, B=128, steps=1500, x_star=[0.5])
+    run_both(B, oracle_mod, cfg, 1500, checkpoints=2)
+
+
+def test_long_runs_of_identical_iterations(B, oracle_mod):
+    """A lone decode of thousands of tokens: its server repeats the same iteration far more often than the
+    untallied-iteration counter holds (254), and launches end in the middle of such runs."""
+    cls = [_limits_class(lam=0.25, in_p0=100.0, out_law=W.LAW_CONST, out_p0=2000.0)]
+    cfg = _limits_cfg("runs", cls, N=8, M=2, B=4, steps=7000, x_star=[0.1])
+    sim, orc = run_both(B, oracle_mod, cfg, 7000, checkpoints=3)
+    assert_stats_equal(sim.stats(), orc.stats())
