@@ -1,12 +1,13 @@
 // HIP kernels of the gate-and-route network simulator (gfx950, wave64).
 //
-// One workgroup owns one replication for a whole launch and loops over the steps itself.
-// Server g is owned by thread g % blockDim of its replication's workgroup: only the owner ever
-// touches that server's record and slot row, so per-server updates need no synchronisation.
-// Class-level counters (queue lengths, occupancies, tallies) live in LDS and are updated with
-// integer atomics, which commute; everything that the policy defines sequentially (order of
-// simultaneous prefill completions, of gate admissions, of routed requests) is reproduced with
-// 64-server ballot words in LDS and prefix popcounts over them.
+// One workgroup owns one replication for a whole launch and loops over the steps itself. The servers are
+// handled in blocks of 64 (one per lane); wave w takes the blocks w, w + nwaves, ... in every sweep, and the
+// servers a wave queues for finishing are finished by that wave, so a server's record and slot row are
+// touched by one wave at a time. Class-level counters (queue lengths, occupancies, tallies) live in LDS and
+// are updated with integer atomics, which commute; the lanes of a wave are combined first, because atomics of
+// several lanes on one LDS address serialise. Everything that the policy defines sequentially (order of
+// simultaneous prefill completions, of gate admissions, of routed requests) is reproduced with 64-server
+// ballot words in LDS and prefix popcounts over them.
 #include <hip/hip_runtime.h>
 
 #include "gnr_internal.h"
@@ -52,7 +53,6 @@ __device__ __forceinline__ uint32_t byte_at(uint64_t packed, int k) { return sta
 // Prefill word of a server: prompt tokens left | tokens in the running chunk << 16 | class << 29.
 __device__ __forceinline__ int pk_rem(uint32_t pk) { return static_cast<int>(pk & 0xFFFFu); }
 __device__ __forceinline__ int pk_ptok(uint32_t pk) { return static_cast<int>((pk >> 16) & 0x1FFFu); }
-__device__ __forceinline__ int pk_cls(uint32_t pk) { return static_cast<int>(pk >> 29); }
 
 // Position of the n-th set bit (n counted from 0) of a word that has more than n bits set.
 __device__ __forceinline__ int nth_set_bit(uint64_t word, int n)
@@ -325,8 +325,6 @@ __device__ __forceinline__ void tally_iterations(uint64_t *tl, uint64_t *tbth, i
   }
 }
 
-// bytewise a - b for per-class count vectors with b_k <= a_k
-__device__ __forceinline__ uint64_t bytes_sub(uint64_t a, uint64_t b) { return a - b; }
 
 // Sort key of a gate candidate: the m-th waiting request of class k (m counted from the head).
 // Occupancy gate: (X_k + m - n x_k*)/x_k*, ties by the larger queue deviation Q_k - m - n q_k*;
@@ -362,8 +360,7 @@ __device__ __forceinline__ bool gate_before(const GateKey &x, int k1, const Gate
   return k1 < k2;
 }
 
-// What finishing an iteration reports back for folding: the first decode that left the server and
-// the end of its prefill. Further decodes leaving in the same iteration are tallied directly.
+// The end of a server's prefill, kept until the lane has left the divergent part of the finishing code.
 struct PrefillEnd { bool done; int k; uint32_t P; int64_t ttft; uint64_t nc; };
 
 // ------------------------------------------------------------------ step kernel ----
@@ -522,7 +519,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           int rem = g < M ? static_cast<int>(L.rem[g]) : 0;
           const int ptok = has_chunk ? (rem < p.C ? rem : p.C) : 0;   // the chunk frozen at the start of the iteration
           const int64_t tn = T + static_cast<int64_t>(static_cast<int32_t>(L.t32[g] - T32));   // exact completion time
-          comp = bytes_sub(nc, nj);
+          comp = nc - nj;   // bytewise: no class joins more decodes than it holds
           d = p.c0 + p.cpre * ptok + p.cdec * static_cast<int64_t>(byte_sum(comp));
           chunk = ptok > 0;
           m = static_cast<uint32_t>(L.pend[g]) + 1u;
@@ -658,7 +655,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
             const uint64_t nc = n_cls[g];
             const bool joined = L.bm_join[wi] & lbit;
             const uint64_t nj = joined ? n_join[g] : 0ull;
-            comp = bytes_sub(nc, nj);
+            comp = nc - nj;   // bytewise: no class joins more decodes than it holds
             d = p.c0 + p.cdec * static_cast<int64_t>(byte_sum(comp));   // untallied iterations never hold a chunk
             m = static_cast<uint32_t>(pend);
             pend = 0;

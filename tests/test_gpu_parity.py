@@ -156,3 +156,11 @@ def test_long_runs_of_identical_iterations(B, oracle_mod):
     cfg = _limits_cfg("runs", cls, N=8, M=2, B=4, steps=7000, x_star=[0.1])
     sim, orc = run_both(B, oracle_mod, cfg, 7000, checkpoints=3)
     assert_stats_equal(sim.stats(), orc.stats())
+
+
+def test_config5_width_through_a_load_peak(B, oracle_mod):
+    """Config 5 at its full N (157 blocks of 64 servers, 16 waves) with a short modulation period, so that the
+    load peak falls inside the run: every solo server then holds more than 64 decodes."""
+    cfg = W.config(5, replications=2, mod_period=20000)
+    sim, orc = run_both(B, oracle_mod, cfg, 10000, oracle_reps=[0], checkpoints=2)
+    assert (orc.slots(0)["n_dec"] > 64).sum() > 5000
