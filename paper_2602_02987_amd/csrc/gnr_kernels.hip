@@ -106,9 +106,10 @@ __device__ __forceinline__ void lds_add64(uint64_t *p, uint64_t v)
 // Optional per-phase cycle counters (compiled out unless GNR_PROF is defined).
 #ifdef GNR_PROF
 __device__ unsigned long long g_prof[32];
-#define PROF_DECL unsigned long long prof_acc[32] = {0}; unsigned long long prof_last = clock64();
-#define PROF(i) { const unsigned long long t_ = clock64(); prof_acc[i] += t_ - prof_last; prof_last = t_; }
-#define PROF_FLUSH if ((threadIdx.x & 63) == 0) { for (int i_ = 0; i_ < 32; ++i_) atomicAdd(&g_prof[i_], prof_acc[i_]); }
+// The time since the wave's previous mark goes to bucket i of a per-workgroup table in LDS.
+#define PROF_DECL unsigned long long prof_last = clock64();
+#define PROF(i) { const unsigned long long t_ = clock64(); if ((threadIdx.x & 63) == 0) atomicAdd(reinterpret_cast<unsigned long long *>(&L.prof[i]), t_ - prof_last); prof_last = t_; }
+#define PROF_FLUSH __syncthreads(); if (threadIdx.x < 32) atomicAdd(&g_prof[threadIdx.x], static_cast<unsigned long long>(L.prof[threadIdx.x]));
 #else
 #define PROF_DECL
 #define PROF(i)
@@ -136,6 +137,9 @@ struct Lds {
   uint32_t *acc;      // [8]
   int32_t *sc;        // [SC_WORDS]
   uint64_t *tl;       // [kTallyWords]
+#ifdef GNR_PROF
+  uint64_t *prof;     // [32] cycle buckets of the optional phase profile
+#endif
   uint64_t *tbth;     // [K][tbt_w]
   uint64_t *bm_idle;  // [nwords] mixed-group servers whose prefill slot is idle
   uint64_t *bm_comp;  // [nwords] servers whose prefill completed this step
@@ -154,7 +158,7 @@ struct Lds {
   uint32_t *lh;       // [2][kLoadBins] servers per decode count: solo group, mixed group
   uint32_t *ev_g;     // [waves][kEvPerWave] servers queued for finishing, per wave
   uint32_t *ev_q;     // [waves][kEvPerWave] their slot-quad masks
-  uint8_t *stage;     // [waves][128] row halves to scan of the block a wave has open: lane | half << 6
+  uint16_t *stage;    // [waves][128] row halves to scan of the block a wave has open: lane | half << 6 | decodes << 8
   uint32_t *t32;      // [N] low 32 bits of the end time of the running iteration
   uint32_t *iter;     // [N] completed iterations
   uint8_t *loads;     // [N] decodes per server
@@ -171,6 +175,9 @@ __host__ __device__ __forceinline__ Lds lds_carve(const Params &p, unsigned char
   L.field = reinterpret_cast<type *>(base + off);          \
   off += (sizeof(type) * static_cast<size_t>(count) + 7) & ~size_t(7);
   GNR_TAKE(tl, uint64_t, kTallyWords)
+#ifdef GNR_PROF
+  GNR_TAKE(prof, uint64_t, 32)
+#endif
   GNR_TAKE(tbth, uint64_t, p.K * p.tbt_w)
   GNR_TAKE(bm_idle, uint64_t, p.nwords)
   GNR_TAKE(bm_comp, uint64_t, p.nwords)
@@ -197,7 +204,7 @@ __host__ __device__ __forceinline__ Lds lds_carve(const Params &p, unsigned char
   GNR_TAKE(loads, uint8_t, p.N)
   GNR_TAKE(pend, uint8_t, p.N)
   GNR_TAKE(rem, uint16_t, p.M)
-  GNR_TAKE(stage, uint8_t, 2 * p.threads)
+  GNR_TAKE(stage, uint16_t, 2 * p.threads)
 #undef GNR_TAKE
   if (total) *total = off;
   return L;
@@ -424,6 +431,9 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
   // ---- load the replication's class state and rebuild the on-chip views of the server state
   for (int i = tid; i < CS_WORDS; i += NT) L.cs[i] = a.cstate[static_cast<size_t>(r) * CS_WORDS + i];
   for (int i = tid; i < kTallyWords; i += NT) L.tl[i] = 0;
+#ifdef GNR_PROF
+  if (tid < 32) L.prof[tid] = 0;
+#endif
   for (int i = tid; i < K * p.tbt_w; i += NT) L.tbth[i] = 0;
   for (int i = tid; i < SC_WORDS; i += NT) L.sc[i] = 0;
   for (int i = tid; i < 2 * kLoadBins; i += NT) L.lh[i] = 0;
@@ -612,19 +622,18 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
 
     // ---- completion pass, one round of 64 servers (one per lane) at a time.
     //      open_round: due test; the slot rows of the due servers are listed in `stage`, 64 slots (half a row)
-    //      per entry. issue_group: eight lanes read one entry, 16 bytes per lane and load; a group is eight
-    //      entries. process_group: the finish words are compared with the server's iteration index; the hit masks
-    //      travel back to the owning lanes. Four groups are in flight: as soon as one is compared its registers
-    //      take the next group of the block, and the first four groups of a block are issued before the arrivals
-    //      of the block are drawn. finalize: a server whose batch changes, or that carries a prefill, is queued
-    //      for finishing; for any other the iteration is only counted.
+    //      per entry. issue_batch: eight lanes read one entry, 16 bytes per lane and load; a group is eight
+    //      entries, a batch four groups. process_group: the finish words are compared with the server's iteration
+    //      index; the hit masks travel back to the owning lanes. The first batch of a block is issued when the
+    //      block is opened, before the arrivals of the block are drawn. finalize: a server whose batch changes,
+    //      or that carries a prefill, is queued for finishing; for any other the iteration is only counted.
     //      Slots beyond a server's decode count never hold a future iteration index (they are cleared when
     //      vacated), so the comparison needs no occupancy mask.
     {
       constexpr int Q = 4;   // groups of eight row halves in flight
       const int l8 = lane & 7, grp = lane >> 3;
       const uint64_t below = lanes_below();
-      uint8_t *stage = L.stage + wave * 128;
+      uint16_t *stage = L.stage + wave * 128;
       int nev = 0;          // servers queued by this wave (wave-uniform)
       int ne = 0;           // row halves listed for the open block (wave-uniform)
       bool o_due = false, o_must = false, o_scan = false, o_big = false;   // owner-lane state of the open round
@@ -638,11 +647,16 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
         const int g = gw + lane;
         const uint64_t lbit = 1ull << lane;
         const bool valid = g < N;
+        // everything the block needs from LDS is read here in one go: a chain of dependent LDS round trips
+        // costs far more than a few reads that turn out unused
         const uint64_t busy_word = L.bm_busy[wi], due_prev = L.bm_due[wi], touch_prev = L.bm_touch[wi];
-        const uint64_t flush_prev = L.bm_flush[wi];
+        const uint64_t flush_prev = L.bm_flush[wi], idle_word = L.bm_idle[wi], chunk_word = L.bm_chunk[wi];
+        uint64_t join_word = L.bm_join[wi];
         uint32_t t32v = valid ? L.t32[g] : 0u;
+        const uint32_t iter_v = valid ? L.iter[g] : 0u;
         const int nd = valid ? static_cast<int>(L.loads[g]) : 0;
         int pend = valid ? static_cast<int>(L.pend[g]) : 0;
+        const int rem_v = g < M ? static_cast<int>(L.rem[g]) : 0;
         bool busy = busy_word & lbit;
         // ---- (re)start of the servers that completed an iteration or were given work in the previous step.
         //      Untallied iterations are tallied before the batch changes, and all of them when the launch ends.
@@ -651,29 +665,33 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           uint32_t m = 0;
           int64_t d = 0;
           uint64_t comp = 0;
+          bool unjoin = false;
           if (flush) {
             const uint64_t nc = n_cls[g];
-            const bool joined = L.bm_join[wi] & lbit;
+            const bool joined = join_word & lbit;
             const uint64_t nj = joined ? n_join[g] : 0ull;
             comp = nc - nj;   // bytewise: no class joins more decodes than it holds
             d = p.c0 + p.cdec * static_cast<int64_t>(byte_sum(comp));   // untallied iterations never hold a chunk
             m = static_cast<uint32_t>(pend);
             pend = 0;
             L.pend[g] = 0;
-            if ((flush_prev & lbit) && joined) {   // the decodes placed at the boundary joined the batch there
-              n_join[g] = 0;
-              atomicAnd(reinterpret_cast<unsigned long long *>(&L.bm_join[wi]), ~lbit);
-            }
+            unjoin = (flush_prev & lbit) && joined;   // the decodes placed at the boundary joined the batch there
+            if (unjoin) n_join[g] = 0;
           }
           tally_iterations(L.tl, L.tbth, p.tbt_w, p.tbt_lo, K, m, d, false, comp);
+          const uint64_t unjoin_m = __ballot(unjoin);
+          if (unjoin_m) {   // this wave alone works on the block's words
+            join_word &= ~unjoin_m;
+            if (lane == 0) L.bm_join[wi] = join_word;
+          }
           if (lane == 0 && flush_prev) L.bm_flush[wi] = 0;
         }
+        PROF(18)
         const uint64_t todo = due_prev | touch_prev;
         if (todo) {
           bool chunk_now = false;
           if (todo & lbit) {
-            const int rem = g < M ? static_cast<int>(L.rem[g]) : 0;
-            const int ptok = rem > 0 ? (rem < p.C ? rem : p.C) : 0;
+            const int ptok = rem_v > 0 ? (rem_v < p.C ? rem_v : p.C) : 0;
             chunk_now = ptok > 0;
             if (ptok == 0 && nd == 0) {
               busy = false;
@@ -690,7 +708,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           const uint64_t nb = __ballot(busy), nchunk = __ballot(chunk_now);
           if (lane == 0) {
             if (nb != busy_word) L.bm_busy[wi] = nb;
-            if (gw < M) L.bm_chunk[wi] = (L.bm_chunk[wi] & ~todo) | nchunk;
+            if (gw < M) L.bm_chunk[wi] = (chunk_word & ~todo) | nchunk;
           }
         }
         o_due = false; o_it = 0; o_nd = 0; o_pend = 0; o_q = 0;
@@ -700,48 +718,61 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           ne = 0;
           return;
         }
+        PROF(19)
         // ---- which servers complete an iteration in this step
         o_due = busy && static_cast<int32_t>(t32v - T32) <= 0;
         if (o_due) {
-          o_it = L.iter[g] + 1;
+          o_it = iter_v + 1;
           L.iter[g] = o_it;
           o_nd = nd;
           o_pend = pend;
         }
-        const bool prefill_here = g < M && !(L.bm_idle[wi] & lbit);
-        o_must = o_due && ((L.bm_join[wi] & lbit) || prefill_here || o_pend >= kMaxPend);
+        const bool prefill_here = g < M && !(idle_word & lbit);
+        o_must = o_due && ((join_word & lbit) || prefill_here || o_pend >= kMaxPend);
         o_scan = o_due && o_nd > 0;
         o_big = o_scan && o_nd > 64;   // the row's second half holds decodes too
         const uint64_t dm = __ballot(o_due), sm = __ballot(o_scan), bg = __ballot(o_big);
         o_rank = __popcll(sm & below) + __popcll(bg & below);
         ne = __popcll(sm) + __popcll(bg);
-        if (o_scan) {
-          stage[o_rank] = static_cast<uint8_t>(lane);
-          if (o_big) stage[o_rank + 1] = static_cast<uint8_t>(lane | 64);
+        if (o_scan) {   // entry: lane | second half << 6 | decode count << 8
+          const uint32_t e = static_cast<uint32_t>(lane) | (static_cast<uint32_t>(o_nd) << 8);
+          stage[o_rank] = static_cast<uint16_t>(e);
+          if (o_big) stage[o_rank + 1] = static_cast<uint16_t>(e | 64u);
         }
         if (lane == 0) {
           L.bm_due[wi] = dm;
           L.bm_touch[wi] = 0;
           L.bm_comp[wi] = 0;
         }
+        PROF(20)
       };
-      // group gi of the open block goes into register set t
-      auto issue_group = [&](int wi, int t, int gi) __attribute__((always_inline)) {
+      // Groups g0 .. g0+Q-1 of the open block go into the Q register sets. The LDS reads of all of them are
+      // issued together, then the loads, then the shuffles that fetch the iteration indices (needed only when
+      // the words are compared): two LDS round trips per batch instead of two per group.
+      auto issue_batch = [&](int wi, int g0) __attribute__((always_inline)) {
         const uint32_t gw = static_cast<uint32_t>(wi) << 6;
-        const int pidx = 8 * gi + grp;
-        const bool ok = pidx < ne;
-        const int e = ok ? stage[pidx] : 0;
-        const int sid = e & 63, half = e >> 6;
-        const uint32_t its = __shfl(o_it, sid, 64);
-        const int nds_all = __shfl(o_nd, sid, 64);   // every lane takes part: the owner may sit in a lane without an entry
-        const int nds = ok ? nds_all : 0;
-        const int q0 = 16 * half + l8;   // this lane's quads of the row: q0 and q0 + 8
-        const uint32_t off = (gw + static_cast<uint32_t>(sid)) * static_cast<uint32_t>(BS) + 4u * q0;
-        // a register that is not loaded holds zeros, which no iteration index equals (the first is 1)
-        vit[t] = its;
-        v[t][0] = v[t][1] = make_uint4(0u, 0u, 0u, 0u);
-        if (4 * q0 < nds) v[t][0] = *reinterpret_cast<const uint4 *>(fin + off);
-        if (4 * q0 + 32 < nds) v[t][1] = *reinterpret_cast<const uint4 *>(fin + off + 32u);
+        uint32_t e[Q];
+#pragma unroll
+        for (int t = 0; t < Q; ++t) {
+          const int pidx = 8 * (g0 + t) + grp;
+          e[t] = pidx < ne ? stage[pidx] : 0u;   // no entry: decode count 0, nothing is loaded
+        }
+#pragma unroll
+        for (int t = 0; t < Q; ++t) {
+          const uint32_t sid = e[t] & 63u, half = (e[t] >> 6) & 1u;
+          const int nds = static_cast<int>(e[t] >> 8);
+          const int q0 = 16 * static_cast<int>(half) + l8;   // this lane's quads of the row: q0 and q0 + 8
+          const uint32_t off = (gw + sid) * static_cast<uint32_t>(BS) + 4u * q0;
+          // a register that is not loaded holds zeros, which no iteration index equals (the first is 1)
+          v[t][0] = v[t][1] = make_uint4(0u, 0u, 0u, 0u);
+          if (4 * q0 < nds) v[t][0] = *reinterpret_cast<const uint4 *>(fin + off);
+          if (4 * q0 + 32 < nds) v[t][1] = *reinterpret_cast<const uint4 *>(fin + off + 32u);
+        }
+#pragma unroll
+        for (int t = 0; t < Q; ++t) {
+          const uint32_t it_owner = __shfl(o_it, static_cast<int>(e[t] & 63u), 64);   // every lane takes part
+          vit[t] = 8 * (g0 + t) + grp < ne ? it_owner : 0xFFFFFFFFu;                  // no entry: matches nothing
+        }
       };
       auto process_group = [&](int t, int gi) __attribute__((always_inline)) {
         const uint32_t it = vit[t];
@@ -755,11 +786,6 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           if (o_big && static_cast<unsigned>(d1) < 8u)
             o_q |= ((static_cast<uint32_t>(bal0 >> (8 * d1)) & 0xFFu) | ((static_cast<uint32_t>(bal1 >> (8 * d1)) & 0xFFu) << 8)) << 16;
         }
-      };
-      auto prefetch = [&](int wi) __attribute__((always_inline)) {   // the first groups of a block just opened
-#pragma unroll
-        for (int t = 0; t < Q; ++t)
-          if (8 * t < ne) issue_group(wi, t, t);   // wave-uniform
       };
       auto finalize = [&](int wi) __attribute__((always_inline)) {
         const int g = (wi << 6) + lane;
@@ -779,7 +805,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
       // wave w owns the 64-server blocks w, w + nwaves, w + 2 nwaves, ...
       PROF(1)
       int blk = wave;
-      if (blk < nwords) { open_round(blk); prefetch(blk); }
+      if (blk < nwords) { open_round(blk); issue_batch(blk, 0); }
       while (blk < nwords) {
         PROF(2)
         const int nblk = blk + nwaves;
@@ -789,15 +815,12 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
         }
         PROF(3)
         for (int g0 = 0; 8 * g0 < ne; g0 += Q) {
+          if (g0 > 0) issue_batch(blk, g0);   // the first batch of a block was issued when the block was opened
 #pragma unroll
-          for (int t = 0; t < Q; ++t) {
-            const int gi = g0 + t;
-            if (8 * gi < ne) {   // wave-uniform
-              process_group(t, gi);
-              if (8 * (gi + Q) < ne) issue_group(blk, t, gi + Q);   // the freed registers take the next group
-            }
-          }
+          for (int t = 0; t < Q; ++t)
+            if (8 * (g0 + t) < ne) process_group(t, g0 + t);   // wave-uniform
         }
+        PROF(22)
         finalize(blk);
         PROF(2)
         if (nev > kEvPerWave - 64 || nblk >= nwords) {   // before the next block is opened: fewer live registers
@@ -805,7 +828,9 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           nev = 0;
         }
         PROF(4)
-        if (nblk < nwords) { open_round(nblk); prefetch(nblk); }   // its loads travel while the arrivals are drawn
+        PROF(23)
+        if (nblk < nwords) { open_round(nblk); issue_batch(nblk, 0); }   // its loads travel while the arrivals are drawn
+        PROF(21)
         blk = nblk;
       }
     }
