@@ -149,12 +149,12 @@ struct Lds {
   uint64_t *bm_touch; // [nwords] idle servers that were given work this step
   uint64_t *bm_flush; // [nwords] servers whose untallied iterations must be tallied at the restart
   uint64_t *bm_chunk; // [nwords] mixed-group servers whose running iteration carries a prefill chunk
-  uint64_t *bm_adm;   // [nwords] prefill slots that take an admission in this gate pass
   uint64_t *jobs;     // [kJobsLds] the first requests a routing pass places, copied from the decode buffer
   uint32_t *pre_lvl;  // [kRouteLevels][nwords] servers of the routed group with at most (level) decodes: per word, then ranks
   uint32_t *pre_c;    // [nwords] exclusive prefix popcounts of bm_comp
   uint32_t *pre;      // [nwords] exclusive prefix popcounts of bm_idle
   uint32_t *adm;      // [kAdmChunk] class | sequence-in-class << 3 of each admission
+  uint16_t *adm_slot; // [kAdmChunk] prefill slot (server) that takes the admission of each rank
   uint32_t *lh;       // [2][kLoadBins] servers per decode count: solo group, mixed group
   uint32_t *ev_g;     // [waves][kEvPerWave] servers queued for finishing, per wave
   uint32_t *ev_q;     // [waves][kEvPerWave] their slot-quad masks
@@ -187,7 +187,6 @@ __host__ __device__ __forceinline__ Lds lds_carve(const Params &p, unsigned char
   GNR_TAKE(bm_touch, uint64_t, p.nwords)
   GNR_TAKE(bm_flush, uint64_t, p.nwords)
   GNR_TAKE(bm_chunk, uint64_t, p.nwords)
-  GNR_TAKE(bm_adm, uint64_t, p.nwords)
   GNR_TAKE(jobs, uint64_t, kJobsLds)
   GNR_TAKE(cs, int32_t, CS_WORDS)
   GNR_TAKE(acc, uint32_t, 8)
@@ -196,6 +195,7 @@ __host__ __device__ __forceinline__ Lds lds_carve(const Params &p, unsigned char
   GNR_TAKE(pre_c, uint32_t, p.nwords + 1)
   GNR_TAKE(pre, uint32_t, p.nwords + 1)
   GNR_TAKE(adm, uint32_t, kAdmChunk)
+  GNR_TAKE(adm_slot, uint16_t, kAdmChunk)
   GNR_TAKE(lh, uint32_t, 2 * kLoadBins)
   GNR_TAKE(ev_g, uint32_t, (p.threads / 64) * kEvPerWave)
   GNR_TAKE(ev_q, uint32_t, (p.threads / 64) * kEvPerWave)
@@ -623,14 +623,14 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
     // ---- completion pass, one round of 64 servers (one per lane) at a time.
     //      open_round: due test; the slot rows of the due servers are listed in `stage`, 64 slots (half a row)
     //      per entry. issue_batch: eight lanes read one entry, 16 bytes per lane and load; a group is eight
-    //      entries, a batch four groups. process_group: the finish words are compared with the server's iteration
+    //      entries, a batch Q groups. process_group: the finish words are compared with the server's iteration
     //      index; the hit masks travel back to the owning lanes. The first batch of a block is issued when the
     //      block is opened, before the arrivals of the block are drawn. finalize: a server whose batch changes,
     //      or that carries a prefill, is queued for finishing; for any other the iteration is only counted.
     //      Slots beyond a server's decode count never hold a future iteration index (they are cleared when
     //      vacated), so the comparison needs no occupancy mask.
     {
-      constexpr int Q = 4;   // groups of eight row halves in flight
+      constexpr int Q = 5;   // groups of eight row halves in flight
       const int l8 = lane & 7, grp = lane >> 3;
       const uint64_t below = lanes_below();
       uint16_t *stage = L.stage + wave * 128;
@@ -955,17 +955,21 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           }
           nadm = ncand < limit ? ncand : limit;
           // The admissions take the first nadm idle prefill slots, whatever their order: the slot bitmaps are
-          // updated here a word at a time (no atomics); bm_adm keeps the slots for the admissions to find.
-          for (int w = tid; w < nwords_m; w += NT) {
-            const uint64_t idle = L.bm_idle[w];
+          // updated here a word at a time (no atomics).
+          // A wave takes a word, a lane a slot; the slot of every admission rank goes into a table.
+          for (int w = wave; w < nwords_m; w += nwaves) {   // wave-uniform
+            const uint64_t idle = L.bm_idle[w], busy_w = L.bm_busy[w], touch_w = L.bm_touch[w];
             const int before = static_cast<int>(L.pre[w]);   // idle slots in the words before this one
             uint64_t adm = 0;
             if (before < nadm)
               adm = before + __popcll(idle) <= nadm ? idle : idle & ((1ull << nth_set_bit(idle, nadm - before)) - 1ull);
-            L.bm_adm[w] = adm;
             if (adm) {
-              L.bm_idle[w] = idle & ~adm;
-              L.bm_touch[w] |= adm & ~L.bm_busy[w];   // an idle server is given work
+              if ((adm >> lane) & 1ull)
+                L.adm_slot[before + __popcll(adm & lanes_below())] = static_cast<uint16_t>((w << 6) + lane);
+              if (lane == 0) {
+                L.bm_idle[w] = idle & ~adm;
+                L.bm_touch[w] = touch_w | (adm & ~busy_w);   // an idle server is given work
+              }
             }
           }
           for (int c0 = wave_base; c0 < ncand; c0 += NT) {   // wave-uniform trip count
@@ -1100,7 +1104,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
             int k = 0;
             uint64_t wait = 0, nc = 0;
             if (active) {
-              const int g = select_bit(L.bm_adm, L.pre, nwords_m, static_cast<uint32_t>(j));
+              const int g = L.adm_slot[j];
               const uint32_t e = L.adm[j];
               k = static_cast<int>(e & 7u);
               uint32_t pos = static_cast<uint32_t>(L.cs[CS_QHEAD + k]) + (e >> 3);
