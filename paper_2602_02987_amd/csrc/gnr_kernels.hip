@@ -219,14 +219,15 @@ size_t step_lds_bytes(const Params &p)
 
 int step_threads(int N)
 {
-  int t = (N + 63) / 64 * 64;
-  // Sixteen waves per compute unit hide the most latency; the kernel is also built for 768 and 512 threads
-  // (more registers per lane), which measured slower on the large configurations.
+  // A replication with many servers fills the LDS of a compute unit, runs alone there and wants all sixteen
+  // waves to hide latency. Small replications run several workgroups per compute unit, which hide each
+  // other's barriers better than more waves in one workgroup would: two waves measured best there (N = 256,
+  // 1024, 2048), one wave and four or more waves slower.
+  int t = N <= 64 ? 64 : N <= 2560 ? 128 : N <= 5120 ? 512 : 1024;
 #ifdef GNR_MAX_THREADS
-  return t > GNR_MAX_THREADS ? GNR_MAX_THREADS : t;
-#else
-  return t > 1024 ? 1024 : t;
+  if (t > GNR_MAX_THREADS) t = GNR_MAX_THREADS;
 #endif
+  return t;
 }
 
 // Exclusive prefix popcounts of a bitmap, computed by one whole wave; returns the total in every lane.
