@@ -151,6 +151,16 @@ int sim_create(const sim_config *cfg, int max_replications, void *dev_workspace,
  * steps), not on how the steps were split over calls. Total steps must stay below 2^29. */
 int sim_run(sim_t *h, int64_t steps, int replications, uint64_t seed, void *hip_stream);
 
+/* Replaces the gate's targets x*_i (prefill occupancy per server) and q*_p,i (prefill backlog per server)
+ * between two sim_run calls; the run goes on from its current state. This is the hook of the paper's online
+ * adaptive algorithm (trace-driven online policy evaluation: the controller re-estimates the class arrival
+ * rates from a rolling window, Eq. main-online-arrival-estimate, re-solves the fluid LP at every replanning
+ * epoch, and the gate then ranks by the deviation from the current targets). Only the targets move: the
+ * mixed/solo split M keeps the value given to sim_create (moving M*(t_k), Eq. main-online-mixed-target, is not
+ * built). x_star, qp_star: host arrays of K doubles. SIM_EINVAL: a negative or non-finite target.
+ * The new values are copied to the device asynchronously on `hip_stream`, ordered after earlier runs. */
+int sim_set_targets(sim_t *h, const double *x_star, const double *qp_star, void *hip_stream);
+
 /* Sums the tallies over replications on the device, copies them out and derives the fp64 figures.
  * Synchronises the stream. Returns SIM_EOVERFLOW (with `out` filled) if any ring overflowed. */
 int sim_stats(sim_t *h, sim_stats_t *out, void *hip_stream);

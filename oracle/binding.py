@@ -56,6 +56,7 @@ def lib():
         _lib.oracle_philox.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, C.c_void_p]
         _lib.oracle_length_table.argtypes = [C.c_int, C.c_double, C.c_double, C.c_void_p]
         _lib.oracle_run.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_uint64]
+        _lib.oracle_set_targets.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
     return _lib
 
 
@@ -173,6 +174,13 @@ class Oracle:
         rc = self.L.oracle_run(self.h, int(steps), int(reps), int(seed))
         if rc:
             raise RuntimeError(f"oracle_run failed ({rc})")
+
+    def set_targets(self, x_star, qp_star):
+        """New gate targets from here on; the state is kept."""
+        x = np.ascontiguousarray(x_star, dtype=np.float64); q = np.ascontiguousarray(qp_star, dtype=np.float64)
+        assert x.size == self.cfg.K and q.size == self.cfg.K
+        if self.L.oracle_set_targets(self.h, x.ctypes.data, q.ctypes.data):
+            raise RuntimeError("oracle_set_targets failed")
 
     def violations(self):
         return int(self.L.oracle_violations(self.h)), int(self.L.oracle_first_violation(self.h))

@@ -639,6 +639,23 @@ static void step_rep(oracle_t *o, int r, uint32_t s)
   R->glob[G_STEPS]++;
 }
 
+/* Replaces the gate's targets between runs; the state is kept (the hook of the paper's online adaptive
+ * algorithm, trace-driven online policy evaluation: only x* and q_p* move here, the split M stays). */
+int oracle_set_targets(oracle_t *o, const double *x_star, const double *qp_star)
+{
+  if (!o || !x_star || !qp_star) return -1;
+  for (int k = 0; k < o->cfg.K; k++)
+    if (!(x_star[k] >= 0.0) || !isfinite(x_star[k]) || !isfinite(qp_star[k])) return -1;
+  for (int k = 0; k < o->cfg.K; k++) {
+    o->x_star[k] = x_star[k];
+    o->qp_star[k] = qp_star[k];
+    o->nx[k] = (double)o->cfg.N * x_star[k];
+    o->invx[k] = x_star[k] > 0.0 ? 1.0 / x_star[k] : 0.0;
+    o->nq[k] = (double)o->cfg.N * qp_star[k];
+  }
+  return 0;
+}
+
 /* run `steps` more steps; a different (replications, seed) pair restarts from the empty system */
 int oracle_run(oracle_t *o, int64_t steps, int replications, uint64_t seed)
 {

@@ -83,6 +83,7 @@ def lib():
         L.sim_tallies.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
         L.sim_hist.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
         L.sim_digest.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_uint64), C.c_void_p]
+        L.sim_set_targets.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.sim_kernel_time.argtypes = [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.c_int, C.c_void_p]
         L.sim_destroy.argtypes = [C.c_void_p]
         L.sim_length_table.argtypes = [C.c_int, C.c_double, C.c_double, C.c_void_p]
@@ -216,6 +217,14 @@ class Sim:
         seed = self.cfg.seed if seed is None else seed
         with self.torch.cuda.device(self.device):
             _check(lib().sim_run(self.h, int(steps), int(reps), int(seed), self._stream()), "sim_run")
+
+    def set_targets(self, x_star, qp_star):
+        """New gate targets x*, q_p* (per server, K values each) for the steps still to run."""
+        x = np.ascontiguousarray(x_star, dtype=np.float64); q = np.ascontiguousarray(qp_star, dtype=np.float64)
+        if x.size != self.cfg.K or q.size != self.cfg.K:
+            raise ValueError("set_targets wants K values each")
+        with self.torch.cuda.device(self.device):
+            _check(lib().sim_set_targets(self.h, x.ctypes.data, q.ctypes.data, self._stream()), "sim_set_targets")
 
     def stats(self):
         st = SimStatsC()

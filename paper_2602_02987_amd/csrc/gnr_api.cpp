@@ -298,6 +298,25 @@ int sim_run(sim_t *h, int64_t steps, int replications, uint64_t seed, void *hip_
   return SIM_OK;
 }
 
+int sim_set_targets(sim_t *h, const double *x_star, const double *qp_star, void *hip_stream)
+{
+  if (!h || !x_star || !qp_star) return SIM_EINVAL;
+  for (int k = 0; k < h->p.K; ++k)
+    if (!(x_star[k] >= 0.0) || !std::isfinite(x_star[k]) || !std::isfinite(qp_star[k])) return SIM_EINVAL;
+  for (int k = 0; k < h->p.K; ++k) {
+    h->p.nx[k] = static_cast<double>(h->p.N) * x_star[k];
+    h->p.invx[k] = x_star[k] > 0.0 ? 1.0 / x_star[k] : 0.0;
+    h->p.xstar[k] = x_star[k];
+    h->p.nq[k] = static_cast<double>(h->p.N) * qp_star[k];
+  }
+  // the step kernel reads its parameters from the device copy; stream order puts the update after earlier runs
+  // (the source is pageable host memory: the call returns once the bytes have been staged)
+  if (hipMemcpyAsync(const_cast<Params *>(h->p.self), &h->p, sizeof(Params), hipMemcpyHostToDevice,
+                     static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+    return SIM_EHIP;
+  return SIM_OK;
+}
+
 int sim_kernel_time(sim_t *h, int64_t *launches, double *milliseconds, int reset, void *hip_stream)
 {
   if (!h) return SIM_EINVAL;

@@ -89,7 +89,7 @@ def rates(cfg, n_mixed_decodes=None, n_solo_decodes=None):
 
 
 def solve_lp(cfg, lam, objective="bundled", tbt_mixed_share=None, served_floor=None,
-             n_mixed_decodes=None, n_solo_decodes=None) -> Plan:
+             n_mixed_decodes=None, n_solo_decodes=None, max_mixed_fraction=None) -> Plan:
     """Steady-state fluid LP with theta = 0 and q_d = 0 (decode-buffer elimination, Prop. 1).
 
     Variables per class: x_i, y_m,i, y_s,i. The prefill flow balance is relaxed to
@@ -98,6 +98,7 @@ def solve_lp(cfg, lam, objective="bundled", tbt_mixed_share=None, served_floor=N
     Optional SLI rows (paper Sec. 5.2): `tbt_mixed_share` bounds, per class, the share of
     decode tokens emitted in mixed iterations; `served_floor` is a lower bound on every
     class's served fraction mu_p,i x_i / lambda_i (max-min fairness floor).
+    `max_mixed_fraction` caps sum_i x_i (replanning with the mixed/solo split held where it is).
     """
     K, B = cfg.K, cfg.B
     lam = np.asarray(lam, dtype=np.float64)
@@ -115,7 +116,7 @@ def solve_lp(cfg, lam, objective="bundled", tbt_mixed_share=None, served_floor=N
             cost[ix(i)] -= pin[i] * r["EP"][i] * mu_p[i]
             cost[im(i)] -= pout[i] * r["ED"][i] * mu_m[i]; cost[isx(i)] -= pout[i] * r["ED"][i] * mu_s[i]
     A_ub, b_ub, A_eq, b_eq = [], [], [], []
-    row = np.zeros(nv); row[:K] = 1; A_ub.append(row); b_ub.append(1.0)
+    row = np.zeros(nv); row[:K] = 1; A_ub.append(row); b_ub.append(1.0 if max_mixed_fraction is None else float(max_mixed_fraction))
     row = np.zeros(nv); row[K:2 * K] = 1; row[:K] = -(B - 1); A_ub.append(row); b_ub.append(0.0)
     row = np.zeros(nv); row[2 * K:] = 1; row[:K] = B; A_ub.append(row); b_ub.append(float(B))
     for i in range(K):
@@ -164,6 +165,23 @@ def capacity_scale(cfg, mix, tbt_mixed_share=None, **kw) -> float:
     if res.status != 0:
         raise RuntimeError(f"capacity LP failed: {res.message}")
     return float(res.x[-1])
+
+
+def estimate_rates(arrivals_now, arrivals_before, n_servers, t_now, window, rho=3.0, lam_min=1e-6, eps=1e-9):
+    """Conservative per-server class arrival rates from a rolling window (paper, online adaptive algorithm,
+    Eq. main-online-arrival-estimate): N_i = A_i(t) - A_i((t - W)^+), W_eff = min{W, max{t, eps}},
+    lambda_i = max{rho * N_i / (n * W_eff), lam_min}. `arrivals_*` are cumulative counts per class at t and at
+    (t - W)^+; times in seconds."""
+    n_i = np.asarray(arrivals_now, dtype=np.float64) - np.asarray(arrivals_before, dtype=np.float64)
+    w_eff = min(float(window), max(float(t_now), float(eps)))
+    return np.maximum(float(rho) * n_i / (float(n_servers) * w_eff), float(lam_min))
+
+
+def replan(cfg, lam_hat, **kw) -> Plan:
+    """Re-solves the fluid LP for new rate estimates with the mixed/solo split held at cfg.M servers
+    (sum_i x_i <= M/N); the plan's x are the gate's new occupancy targets (paper, online adaptive algorithm:
+    the LP is re-solved with the estimates in place of lambda_i)."""
+    return solve_lp(cfg, lam_hat, max_mixed_fraction=cfg.M / cfg.N, **kw)
 
 
 def erlang_c(c: int, a: float) -> float:

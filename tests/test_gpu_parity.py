@@ -164,3 +164,22 @@ def test_config5_width_through_a_load_peak(B, oracle_mod):
     cfg = W.config(5, replications=2, mod_period=20000)
     sim, orc = run_both(B, oracle_mod, cfg, 10000, oracle_reps=[0], checkpoints=2)
     assert (orc.slots(0)["n_dec"] > 64).sum() > 5000
+
+
+def test_targets_moved_between_runs(B, oracle_mod):
+    """sim_set_targets between two runs: the gate follows the new targets from the next step on."""
+    for cfg, new_x, new_q in ((_heavy(), [0.02, 0.4, 0.3], [0.0, 2.0, 0.0]),
+                              (_heavy(name="heavy-prefill", M=1, queue_cap=8), [0.02, 0.4, 0.3], [0.0, 2.0, 0.0]),
+                              (W.config(3, N=300, replications=2), [0.3, 0.02, 0.05, 0.1], [0.0, 0.0, 0.5, 0.0])):
+        sim = B.Sim(cfg); orc = oracle_mod.Oracle(cfg)
+        sim.run(700); orc.run(700)
+        sim.set_targets(new_x, new_q); orc.set_targets(new_x, new_q)
+        sim.run(900); orc.run(900)
+        for r in range(cfg.replications):
+            assert_replication_equal(sim, orc, r, what=f"{cfg.name} after new targets")
+        sim.set_targets(cfg.x_star, cfg.qp_star); orc.set_targets(cfg.x_star, cfg.qp_star)
+        sim.run(400); orc.run(400)
+        for r in range(cfg.replications):
+            assert_replication_equal(sim, orc, r, what=f"{cfg.name} after the old targets again")
+    with pytest.raises(B.SimError):
+        sim.set_targets([-1.0] * cfg.K, [0.0] * cfg.K)

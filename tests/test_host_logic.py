@@ -24,7 +24,7 @@ def test_library_exports_every_declared_symbol(B):
     header = open(os.path.join(ROOT, "include", "gnr_sim.h")).read()
     names = set(re.findall(r"^(?:int|const char \*)\s*\*?(sim_[a-z_]+)\(", header, flags=re.M))
     assert {"sim_workspace_bytes", "sim_create", "sim_run", "sim_stats", "sim_snapshot", "sim_destroy",
-            "sim_strerror", "sim_tallies", "sim_hist", "sim_digest", "sim_kernel_time"} <= names
+            "sim_strerror", "sim_tallies", "sim_hist", "sim_digest", "sim_kernel_time", "sim_set_targets"} <= names
     L = B.lib()
     for n in names:
         assert hasattr(L, n), n

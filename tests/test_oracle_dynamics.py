@@ -299,3 +299,39 @@ def test_percentiles_from_histogram(oracle_mod):
         b95 = int(np.searchsorted(cum, -(-95 * n // 100)))
         assert st["tbt_p95"][k] == pytest.approx(oracle_mod.hedge(b95) * 1e-9, rel=1e-12)
         assert oracle_mod.hedge(oracle_mod.hbin(10_000_000)) * 1e-9 <= st["tbt_p50"][k] <= st["tbt_p95"][k] <= st["tbt_p99"][k] <= 0.0492
+
+
+def test_rate_estimate_and_replanning():
+    """Rolling-window estimate (Eq. main-online-arrival-estimate) by hand, and the re-solved LP keeps the
+    prefill occupancy inside the split it was given."""
+    from paper_2602_02987_amd import plan
+    lam = plan.estimate_rates([130, 40], [10, 40], n_servers=20, t_now=12.0, window=30.0, rho=3.0, lam_min=1e-6)
+    assert lam[0] == 3.0 * 120 / (20 * 12.0) and lam[1] == 1e-6      # window cut at t, floor for a silent class
+    lam = plan.estimate_rates([130, 40], [100, 10], n_servers=20, t_now=100.0, window=30.0)
+    assert np.allclose(lam, [3.0 * 30 / 600.0, 3.0 * 30 / 600.0])
+    cfg = W.config(3, N=64, replications=1)
+    base = np.array([c.lam for c in cfg.classes])
+    p = plan.replan(cfg, 3.0 * base)
+    assert p.x.sum() <= cfg.M / cfg.N + 1e-9 and p.x.sum() > 0.5 * cfg.M / cfg.N
+    q = plan.replan(cfg, 0.1 * base)
+    assert q.x.sum() < p.x.sum() and np.all(q.x > 0)                 # light load: every class served, little prefill occupancy
+    assert np.allclose(q.served, 0.1 * base, rtol=1e-6)
+
+
+def test_targets_can_move_between_runs(oracle_mod):
+    """New targets change the gate's order from then on and nothing else: the state carries over, the
+    invariants hold, and a run whose targets are set to the values it already has is unchanged."""
+    cfg = _heavy()
+    a = oracle_mod.Oracle(cfg); a.set_check(1); a.run(600); a.set_targets(cfg.x_star, cfg.qp_star); a.run(600)
+    b = oracle_mod.Oracle(cfg); b.run(1200)
+    assert a.violations() == (0, 0)
+    assert all(a.digest(r) == b.digest(r) for r in range(cfg.replications))
+    # where the prefill slots are the bottleneck the admission mix follows the targets
+    cfg = _heavy(name="heavy-prefill", M=1, queue_cap=8)
+    a = oracle_mod.Oracle(cfg); a.run(2000)
+    c = oracle_mod.Oracle(cfg); c.set_check(1); c.run(600); c.set_targets([0.02, 0.4, 0.3], [0.0, 2.0, 0.0]); c.run(1400)
+    assert c.violations() == (0, 0)
+    ta, tc = a.tallies(0)[0], c.tallies(0)[0]
+    assert np.array_equal(ta[:, TI["A"]] + ta[:, TI["DROP_P"]], tc[:, TI["A"]] + tc[:, TI["DROP_P"]])   # same arrivals
+    assert not np.array_equal(ta[:, TI["U_P"]], tc[:, TI["U_P"]])                                       # another admission mix
+    assert tc[1, TI["U_P"]] > 10 * ta[1, TI["U_P"]]                                                     # the class whose target was raised
