@@ -57,12 +57,13 @@ def lib():
         _lib.oracle_length_table.argtypes = [C.c_int, C.c_double, C.c_double, C.c_void_p]
         _lib.oracle_run.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_uint64]
         _lib.oracle_set_targets.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+        _lib.oracle_patience_table.argtypes = [C.c_double, C.c_double, C.c_void_p]
     return _lib
 
 
 TALLY = ["A", "DROP_P", "U_P", "S_P", "U_DM", "U_DS", "S_DM", "S_DS", "M_SM", "M_MS", "DROP_D", "TOKP_PRE",
          "TOKP_DEC", "TOKD_DEC", "TOK_EMIT", "TOK_PREF", "SUM_QP", "SUM_QD", "SUM_X", "SUM_YM", "SUM_YS",
-         "WAIT_STEPS", "TTFT_SUM", "E2E_SUM", "TBT_SUM"]
+         "WAIT_STEPS", "TTFT_SUM", "E2E_SUM", "TBT_SUM", "AB_P", "AB_D"]
 GLOBAL = ["ITERS_MIX", "ITERS_SOLO", "BUSY_MIX", "BUSY_SOLO", "STEPS", "OVERFLOW"]
 NBIN = 720
 
@@ -82,7 +83,7 @@ class Stats(C.Structure):
                 ("tbt_mean", _D8), ("tbt_p50", _D8), ("tbt_p95", _D8), ("tbt_p99", _D8),
                 ("mean_wait", _D8), ("fair_gap_x", C.c_double), ("fair_gap_ys", C.c_double),
                 ("fair_min_served", C.c_double), ("util_mix", C.c_double), ("util_solo", C.c_double),
-                ("iter_rate", C.c_double)]
+                ("iter_rate", C.c_double), ("abandon_rate_p", _D8), ("abandon_rate_d", _D8)]
 
 
 def stats_to_dict(st) -> dict:
@@ -109,6 +110,13 @@ def length_table(law, p0, p1=0.0):
     rc = lib().oracle_length_table(law, float(p0), float(p1), out.ctypes.data)
     if rc:
         raise ValueError("bad length law")
+    return out
+
+
+def patience_table(theta, dt):
+    out = np.zeros(65536, dtype=np.uint16)
+    if lib().oracle_patience_table(float(theta), float(dt), out.ctypes.data):
+        raise ValueError("bad patience rate")
     return out
 
 
@@ -219,6 +227,15 @@ class Oracle:
         cap = int(max(self.cfg.queue_cap, self.cfg.dbuf_cap))
         out = np.zeros(cap, np.uint64)
         assert self.L.oracle_get_queue(self.h, r, k, out.ctypes.data_as(C.c_void_p), C.c_int64(cap), C.byref(ln)) == 0
+        return out[:ln.value].copy()
+
+    def queue_deadlines(self, r, k):
+        """Steps at which the entries of queue(r, k) abandon if still waiting (0xFFFFFFFF: never)."""
+        ln = C.c_int64(0)
+        cap = int(max(self.cfg.queue_cap, self.cfg.dbuf_cap))
+        out = np.zeros(cap, np.uint64)
+        assert self.L.oracle_get_queue_deadlines(self.h, r, k, out.ctypes.data_as(C.c_void_p), C.c_int64(cap),
+                                                 C.byref(ln)) == 0
         return out[:ln.value].copy()
 
     def tallies(self, r):

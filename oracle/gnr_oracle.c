@@ -21,6 +21,10 @@
  *  - router: solo group first, then mixed group, else the decode buffer, FCFS
  *    (Sec. 4, decode routing);
  *  - revenue recognition events (Sec. 2.3, bundled and separate charging);
+ *  - abandonment (Sec. 2.3): a job waiting in a prefill queue or in the decode
+ *    buffer leaves when its exponential patience, rate theta of its class, ends;
+ *  - abandonment (Sec. 2.3): a job waiting in a prefill queue or in the decode buffer leaves when its
+ *    exponential patience, rate theta of its class, runs out;
  *  - balance equations and capacity constraints (Sec. 2.3) are checked by
  *    oracle_check(), recomputing every aggregate from the per-server state.
  *  Readings (time stepping, tie orders, samplers) are listed where they occur.
@@ -29,7 +33,10 @@
  * sampler tables against closed-form pmfs, a hand-traced worked example,
  * flow-balance / capacity / token-conservation invariants, Little's law as an
  * exact integer identity, the exact stationary law of the discrete M/Geo/c
- * chain and its Erlang-C limit, convergence of revenue to the fluid-LP optimum.
+ * chain and its Erlang-C limit, convergence of revenue to the fluid-LP optimum;
+ * abandonment: the patience table against the geometric law, queues that nobody
+ * leaves by service rebuilt job by job from the patience blocks, the exact
+ * stationary law of the discrete chain with abandonment (Erlang-A).
  *
  * Build: gcc -O2 -ffp-contract=off -fPIC -shared gnr_oracle.c -o libgnr_oracle.so -lm
  */
@@ -51,7 +58,7 @@ enum {
   T_A = 0, T_DROP_P, T_U_P, T_S_P, T_U_DM, T_U_DS, T_S_DM, T_S_DS, T_M_SM, T_M_MS,
   T_DROP_D, T_TOKP_PRE, T_TOKP_DEC, T_TOKD_DEC, T_TOK_EMIT, T_TOK_PREF,
   T_SUM_QP, T_SUM_QD, T_SUM_X, T_SUM_YM, T_SUM_YS, T_WAIT_STEPS,
-  T_TTFT_SUM, T_E2E_SUM, T_TBT_SUM, NTALLY
+  T_TTFT_SUM, T_E2E_SUM, T_TBT_SUM, T_AB_P, T_AB_D, NTALLY
 };
 /* per-replication global tally indices */
 enum { G_ITERS_MIX = 0, G_ITERS_SOLO, G_BUSY_MIX, G_BUSY_SOLO, G_STEPS, G_OVERFLOW, NGLOBAL };
@@ -64,7 +71,7 @@ typedef struct {
   double price_in, price_out; /* c_p, c_d per token (Sec. 2.3 revenue models) */
   int bundled;                /* which recognition rule the "mixed" revenue uses */
   double priority;            /* static index of the Prioritize-and-Route gate (Sec. 5.1) */
-  double theta;               /* patience rate; must be 0 */
+  double theta;               /* patience rate of a waiting job (Sec. 2.3); 0 = never abandons */
 } oracle_class;
 
 typedef struct {
@@ -93,15 +100,18 @@ typedef struct {
   slot_t slot[MAXB];
 } server_t;
 
-typedef struct { int cls, P, D; uint32_t stamp; } job_t;
+#define DL_NEVER 0xFFFFFFFFu
+/* dl: the step at whose start a job that is still waiting abandons (DL_NEVER: it never does) */
+typedef struct { int cls, P, D; uint32_t stamp, dl; } job_t;
+typedef struct { uint32_t stamp, dl; } qent_t;
 
-typedef struct { uint32_t *v; int64_t head, len, alloc; } fifo32;
+typedef struct { qent_t *v; int64_t head, len, alloc; } fifoq;
 typedef struct { job_t *v; int64_t head, len, alloc; } fifojob;
 
 typedef struct {
   int inited;
   int64_t Qp[MAXK], X[MAXK], Qd[MAXK], Ym[MAXK], Ys[MAXK];
-  fifo32 q[MAXK];
+  fifoq q[MAXK];
   fifojob dbuf;
   server_t *sv;
   uint64_t tally[MAXK][NTALLY];
@@ -119,6 +129,8 @@ typedef struct oracle_t {
   int64_t rows;
   uint32_t cls_thr[MAXK];
   uint16_t *tab_in[MAXK], *tab_out[MAXK];
+  uint16_t *tab_pat[MAXK]; /* patience in steps, NULL for a class that never abandons */
+  int any_theta;
   int max_reps, reps;
   uint64_t seed;
   int64_t steps_done;
@@ -204,6 +216,17 @@ int oracle_length_table(int law, double p0, double p1, uint16_t *out)
   return 0;
 }
 
+/* Patience of a waiting job, in steps (Sec. 2.3: exponential patience with rate theta). A job is asked at the
+ * start of every step after the one it joined the queue in; an exponential patience seen at those instants is
+ * geometric on {1,2,...}: Pr(patience >= m) = exp(-theta*dt*(m-1)). Same quantile-table form as the lengths
+ * (so clamped at 32768 steps). */
+int oracle_patience_table(double theta, double dt, uint16_t *out)
+{
+  if (!(theta > 0.0) || !(dt > 0.0)) return -1;
+  double p = -expm1(-theta * dt);
+  return oracle_length_table(LAW_GEOMETRIC, 1.0 / p, 0.0, out);
+}
+
 static double total_rate(const oracle_t *o)
 {
   double lam = 0.0;
@@ -233,7 +256,7 @@ static void arrival_row(const oracle_t *o, int64_t row, uint32_t thr[3])
 }
 
 /* ---------------------------------------------------------------- fifos ---- */
-static void f32_push(fifo32 *f, uint32_t v)
+static void fq_push(fifoq *f, qent_t v)
 {
   if (f->head + f->len == f->alloc) {
     if (f->head > 0) { memmove(f->v, f->v + f->head, (size_t)f->len * sizeof *f->v); f->head = 0; }
@@ -244,7 +267,7 @@ static void f32_push(fifo32 *f, uint32_t v)
   }
   f->v[f->head + f->len++] = v;
 }
-static uint32_t f32_pop(fifo32 *f) { uint32_t v = f->v[f->head++]; f->len--; if (!f->len) f->head = 0; return v; }
+static qent_t fq_pop(fifoq *f) { qent_t v = f->v[f->head++]; f->len--; if (!f->len) f->head = 0; return v; }
 
 static void fj_push(fifojob *f, job_t v)
 {
@@ -288,7 +311,8 @@ int oracle_create(const oracle_config *cfg, int max_reps, oracle_t **out)
     o->cls[k] = cfg->cls[k];
     o->x_star[k] = cfg->x_star[k];
     o->qp_star[k] = cfg->qp_star[k];
-    if (cfg->cls[k].theta != 0.0 || !(cfg->cls[k].lambda >= 0.0) || cfg->x_star[k] < 0.0) { free(o); return -1; }
+    if (!(cfg->cls[k].theta >= 0.0) || !isfinite(cfg->cls[k].theta) || !(cfg->cls[k].lambda >= 0.0) ||
+        cfg->x_star[k] < 0.0) { free(o); return -1; }
   }
   o->cfg.cls = o->cls; o->cfg.x_star = o->x_star; o->cfg.qp_star = o->qp_star;
   o->c0_ns = llround(cfg->c0 * 1e9);
@@ -320,6 +344,11 @@ int oracle_create(const oracle_config *cfg, int max_reps, oracle_t **out)
     if (o->cls[k].out_law == LAW_TABLE) { memcpy(o->tab_out[k], o->cls[k].out_table, 65536 * 2); e2 = 0; }
     else e2 = oracle_length_table(o->cls[k].out_law, o->cls[k].out_p0, o->cls[k].out_p1, o->tab_out[k]);
     o->cls[k].in_table = o->cls[k].out_table = NULL;
+    if (o->cls[k].theta > 0.0) {
+      o->tab_pat[k] = malloc(65536 * sizeof(uint16_t));
+      if (oracle_patience_table(o->cls[k].theta, (double)o->dt_ns * 1e-9, o->tab_pat[k])) e1 = 1;
+      o->any_theta = 1;
+    }
     if (e1 || e2) { o->max_reps = 0; oracle_destroy(o); return -1; }
     for (int j = 0; j < 65536; j++)
       if (o->tab_in[k][j] < 1 || o->tab_in[k][j] > 32768 || o->tab_out[k][j] < 1 || o->tab_out[k][j] > 32768) {
@@ -345,7 +374,7 @@ int oracle_destroy(oracle_t *o)
 {
   if (!o) return -1;
   for (int r = 0; r < o->max_reps; r++) rep_free(&o->rep[r]);
-  for (int k = 0; k < MAXK; k++) { free(o->tab_in[k]); free(o->tab_out[k]); }
+  for (int k = 0; k < MAXK; k++) { free(o->tab_in[k]); free(o->tab_out[k]); free(o->tab_pat[k]); }
   free(o->arr_thr); free(o->rep); free(o->sel); free(o);
   return 0;
 }
@@ -435,22 +464,26 @@ static int64_t check_rep(oracle_t *o, int r)
     if (Qd[k] != R->Qd[k]) viol(o, 133);
     if (R->q[k].len != R->Qp[k]) viol(o, 134);
     if (R->Qp[k] > o->cfg.queue_cap) viol(o, 135);
-    /* balance equations, empty initial state, no abandonment */
-    if (R->Qp[k] != (int64_t)(t[T_A] - t[T_U_P])) viol(o, 140);
+    /* balance equations of Sec. 2.3 from the empty initial state (B_p, B_d: abandonments) */
+    if (R->Qp[k] != (int64_t)(t[T_A] - t[T_U_P] - t[T_AB_P])) viol(o, 140);
     if (R->X[k] != (int64_t)(t[T_U_P] - t[T_S_P])) viol(o, 141);
-    if (R->Qd[k] != (int64_t)(t[T_S_P] - t[T_DROP_D] - t[T_U_DM] - t[T_U_DS])) viol(o, 142);
+    if (R->Qd[k] != (int64_t)(t[T_S_P] - t[T_DROP_D] - t[T_U_DM] - t[T_U_DS] - t[T_AB_D])) viol(o, 142);
     if (R->Ym[k] != (int64_t)(t[T_U_DM] - t[T_S_DM] + t[T_M_SM] - t[T_M_MS])) viol(o, 143);
     if (R->Ys[k] != (int64_t)(t[T_U_DS] - t[T_S_DS] + t[T_M_MS] - t[T_M_SM])) viol(o, 144);
     /* token conservation */
     if ((int64_t)t[T_TOK_EMIT] != (int64_t)t[T_TOKD_DEC] + prog_dec[k]) viol(o, 150);
     if ((int64_t)t[T_TOK_PREF] != (int64_t)t[T_TOKP_PRE] + prog_pre[k]) viol(o, 151);
-    /* FIFO stamps are non-decreasing and not in the future */
+    /* FIFO stamps are non-decreasing and not in the future; nobody waits past the end of their patience */
     for (int64_t i = 0; i < R->q[k].len; i++) {
-      uint32_t st = R->q[k].v[R->q[k].head + i];
+      uint32_t st = R->q[k].v[R->q[k].head + i].stamp;
       if (st >= (uint64_t)o->steps_done) viol(o, 152);
-      if (i && st < R->q[k].v[R->q[k].head + i - 1]) viol(o, 153);
+      if (i && st < R->q[k].v[R->q[k].head + i - 1].stamp) viol(o, 153);
+      if ((uint64_t)R->q[k].v[R->q[k].head + i].dl < (uint64_t)o->steps_done) viol(o, 154);
+      if ((R->q[k].v[R->q[k].head + i].dl != DL_NEVER) != (o->tab_pat[k] != NULL)) viol(o, 155);
     }
   }
+  for (int64_t i = 0; i < R->dbuf.len; i++)
+    if ((uint64_t)R->dbuf.v[R->dbuf.head + i].dl < (uint64_t)o->steps_done) viol(o, 156);
   return o->violations - before;
 }
 
@@ -475,6 +508,29 @@ static void step_rep(oracle_t *o, int r, uint32_t s)
   const int64_t T = ((int64_t)s + 1) * o->dt_ns;       /* boundary time of this step */
   uint32_t w[4];
 
+  /* 0. abandonment (Sec. 2.3): a job still waiting at the start of the step its patience ends in leaves,
+   *    from the class prefill queues and from the decode buffer; the order of the others is kept */
+  if (o->any_theta) {
+    for (int k = 0; k < K; k++) {
+      fifoq *f = &R->q[k];
+      int64_t w = 0;
+      for (int64_t i = 0; i < f->len; i++) {
+        qent_t e = f->v[f->head + i];
+        if (e.dl <= s) { R->Qp[k]--; R->tally[k][T_AB_P]++; }
+        else f->v[f->head + w++] = e;
+      }
+      f->len = w;
+    }
+    fifojob *d = &R->dbuf;
+    int64_t w = 0;
+    for (int64_t i = 0; i < d->len; i++) {
+      job_t e = d->v[d->head + i];
+      if (e.dl <= s) { R->Qd[e.cls]--; R->tally[e.cls][T_AB_D]++; }
+      else d->v[d->head + w++] = e;
+    }
+    d->len = w;
+  }
+
   /* 1. arrivals: one block per server, word 0 -> count, words 1.. -> classes */
   {
     const uint32_t *thr = o->arr_thr + 3 * (o->cfg.mod_period > 0 ? (int64_t)(s % (uint64_t)o->cfg.mod_period) : 0);
@@ -491,7 +547,13 @@ static void step_rep(oracle_t *o, int r, uint32_t s)
     for (int k = 0; k < K; k++) {
       int64_t room = o->cfg.queue_cap - R->Qp[k];
       int64_t take = acc[k] < room ? acc[k] : room;
-      for (int64_t j = 0; j < take; j++) f32_push(&R->q[k], s);
+      /* the accepted arrivals of a class are exchangeable; the j-th of this step draws its patience from
+       * block (step, stream 2+k, j, replication) */
+      for (int64_t j = 0; j < take; j++) {
+        qent_t e = { s, DL_NEVER };
+        if (o->tab_pat[k]) { draw(o, r, (int)j, s, 2u + (uint32_t)k, w); e.dl = s + o->tab_pat[k][w[0] >> 16]; }
+        fq_push(&R->q[k], e);
+      }
       R->Qp[k] += take;
       R->tally[k][T_A] += (uint64_t)take;
       R->tally[k][T_DROP_P] += (uint64_t)(acc[k] - take);
@@ -547,7 +609,9 @@ static void step_rep(oracle_t *o, int r, uint32_t s)
           R->Ym[i] -= sv->n_cls[i]; R->Ys[i] += sv->n_cls[i];
         }
         if (R->dbuf.len < o->cfg.dbuf_cap) {
-          job_t jb = { k, sv->pf_P, sv->pf_D, sv->pf_stamp };
+          /* patience for the wait in the decode buffer: block (step, stream 10, server, replication) */
+          job_t jb = { k, sv->pf_P, sv->pf_D, sv->pf_stamp, DL_NEVER };
+          if (o->tab_pat[k]) { draw(o, r, g, s, 10u, w); jb.dl = s + o->tab_pat[k][w[0] >> 16]; }
           fj_push(&R->dbuf, jb); R->Qd[k]++;
         } else { R->tally[k][T_DROP_D]++; R->glob[G_OVERFLOW] = 1; }
       }
@@ -572,13 +636,13 @@ static void step_rep(oracle_t *o, int r, uint32_t s)
         double pr = o->cls[i].priority;
         if (best < 0 || pr > bxi) { best = i; bxi = pr; }
       } else {                                         /* FCFS across classes: oldest head, ties lowest class */
-        double st = (double)R->q[i].v[R->q[i].head];
+        double st = (double)R->q[i].v[R->q[i].head].stamp;
         if (best < 0 || st < bxi) { best = i; bxi = st; }
       }
     }
     if (best < 0) break;
     const int k = best;
-    uint32_t stamp = f32_pop(&R->q[k]);
+    uint32_t stamp = fq_pop(&R->q[k]).stamp;
     R->Qp[k]--; R->X[k]++; R->tally[k][T_U_P]++;
     R->tally[k][T_WAIT_STEPS] += (uint64_t)(s - stamp);
     draw(o, r, g, s, 1, w);
@@ -749,7 +813,22 @@ int oracle_get_queue(oracle_t *o, int r, int k, uint64_t *out, int64_t cap, int6
   } else {
     if (k >= o->cfg.K) return -1;
     *len = R->q[k].len;
-    for (int64_t i = 0; i < R->q[k].len && i < cap; i++) out[i] = R->q[k].v[R->q[k].head + i];
+    for (int64_t i = 0; i < R->q[k].len && i < cap; i++) out[i] = R->q[k].v[R->q[k].head + i].stamp;
+  }
+  return 0;
+}
+
+/* the steps at which the same entries abandon if still waiting (0xFFFFFFFF: never), same order */
+int oracle_get_queue_deadlines(oracle_t *o, int r, int k, uint64_t *out, int64_t cap, int64_t *len)
+{
+  rep_t *R = getrep(o, r); if (!R) return -1;
+  if (k < 0) {
+    *len = R->dbuf.len;
+    for (int64_t i = 0; i < R->dbuf.len && i < cap; i++) out[i] = R->dbuf.v[R->dbuf.head + i].dl;
+  } else {
+    if (k >= o->cfg.K) return -1;
+    *len = R->q[k].len;
+    for (int64_t i = 0; i < R->q[k].len && i < cap; i++) out[i] = R->q[k].v[R->q[k].head + i].dl;
   }
   return 0;
 }
@@ -810,12 +889,17 @@ int oracle_digest(oracle_t *o, int r, uint64_t *out)
     h = chain(h, (uint64_t)R->Qp[k]); h = chain(h, (uint64_t)R->X[k]); h = chain(h, (uint64_t)R->Qd[k]);
     h = chain(h, (uint64_t)R->Ym[k]); h = chain(h, (uint64_t)R->Ys[k]);
     d += h;
-    for (int64_t i = 0; i < R->q[k].len; i++)
-      d += chain(chain(chain(2, (uint64_t)k), (uint64_t)i), R->q[k].v[R->q[k].head + i]);
+    for (int64_t i = 0; i < R->q[k].len; i++) {
+      uint64_t h2 = chain(chain(chain(2, (uint64_t)k), (uint64_t)i), R->q[k].v[R->q[k].head + i].stamp);
+      if (o->any_theta) h2 = chain(h2, R->q[k].v[R->q[k].head + i].dl);
+      d += h2;
+    }
   }
   for (int64_t i = 0; i < R->dbuf.len; i++) {
     job_t *j = &R->dbuf.v[R->dbuf.head + i];
-    d += chain(chain(3, (uint64_t)i), jobword(j->cls, j->P, j->D, j->stamp));
+    uint64_t h2 = chain(chain(3, (uint64_t)i), jobword(j->cls, j->P, j->D, j->stamp));
+    if (o->any_theta) h2 = chain(h2, j->dl);
+    d += h2;
   }
   for (int g = 0; g < N; g++) {
     server_t *s = &R->sv[g];
@@ -857,6 +941,7 @@ typedef struct {
   double fair_gap_x, fair_gap_ys, fair_min_served;
   double util_mix, util_solo;             /* busy time per server-time, by iteration kind */
   double iter_rate;                       /* executed iterations per server per unit time */
+  double abandon_rate_p[MAXK], abandon_rate_d[MAXK]; /* abandonments per server per unit time: prefill queue, decode buffer */
 } oracle_stats_t;
 
 static int64_t hedge(int b)
@@ -923,6 +1008,8 @@ int oracle_stats(oracle_t *o, oracle_stats_t *st)
     st->ttft_mean[k] = ratio((double)t[T_TTFT_SUM] * 1e-9, (double)t[T_S_P]);
     st->e2e_mean[k] = ratio((double)t[T_E2E_SUM] * 1e-9, sd);
     st->tbt_mean[k] = ratio((double)t[T_TBT_SUM] * 1e-9, (double)t[T_TOK_EMIT]);
+    st->abandon_rate_p[k] = ratio((double)t[T_AB_P], nt);
+    st->abandon_rate_d[k] = ratio((double)t[T_AB_D], nt);
     st->mean_wait[k] = ratio((double)t[T_WAIT_STEPS] * ((double)o->dt_ns * 1e-9), (double)t[T_U_P]);
     const uint64_t *h0 = hs + ((size_t)0 * MAXK + k) * NBIN, *h1 = hs + ((size_t)1 * MAXK + k) * NBIN,
                    *h2 = hs + ((size_t)2 * MAXK + k) * NBIN;

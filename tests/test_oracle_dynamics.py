@@ -15,7 +15,7 @@ GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 TI = {n: i for i, n in enumerate(["A", "DROP_P", "U_P", "S_P", "U_DM", "U_DS", "S_DM", "S_DS", "M_SM", "M_MS",
                                   "DROP_D", "TOKP_PRE", "TOKP_DEC", "TOKD_DEC", "TOK_EMIT", "TOK_PREF", "SUM_QP",
                                   "SUM_QD", "SUM_X", "SUM_YM", "SUM_YS", "WAIT_STEPS", "TTFT_SUM", "E2E_SUM",
-                                  "TBT_SUM"])}
+                                  "TBT_SUM", "AB_P", "AB_D"])}
 GI = {n: i for i, n in enumerate(["ITERS_MIX", "ITERS_SOLO", "BUSY_MIX", "BUSY_SOLO", "STEPS", "OVERFLOW"])}
 
 
