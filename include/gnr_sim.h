@@ -15,6 +15,7 @@
  *
  * Time advances in fixed steps of length dt. Every server keeps an exact clock (integer ns) for
  * the end of its running iteration; in step s (boundary time T_s = (s+1)*dt) the library
+ *   0. removes from the class queues and from the decode buffer every request whose patience ends in this step,
  *   1. draws per-server Poisson arrivals for the window and appends them to the class queues,
  *   2. completes the iteration of every server whose clock is <= T_s,
  *   3. runs the prefill gate over idle prefill slots of the mixed group, ascending server index,
@@ -23,6 +24,15 @@
  *   6. adds the end-of-step queue lengths and occupancies to their running sums.
  * Replications are independent copies of the system with their own random streams
  * (Philox4x32-10 keyed on the seed, counter = (step, stream, server, replication)).
+ *
+ * Abandonment (Sec. 2.3: a waiting class-i request has an exponential patience with rate theta_i, in the prefill
+ * queue and again in the decode buffer). A request is asked at the start of every step after the one it joined
+ * the queue in, so its patience in steps is geometric: Pr(patience >= m) = exp(-theta*dt*(m-1)), m = 1, 2, ...,
+ * drawn by the same quantile-table lookup as the lengths (hence at most 32768 steps). The j-th accepted
+ * class-k arrival of step s takes word 0 of block (s, stream 2+k, j, replication); a request whose prefill
+ * completes on server g in step s takes word 0 of block (s, stream 10, g, replication) for the decode buffer.
+ * A request that joined in step s with patience m can be admitted (routed) in steps s .. s+m-1 and leaves at
+ * the start of step s+m.
  *
  * All functions return 0 on success or a negative sim_err; none throws, aborts or prints.
  * Pointers are host pointers unless a comment says "device".
@@ -54,12 +64,13 @@ enum sim_gate { SIM_GATE_OCCUPANCY = 0, SIM_GATE_PRIORITY = 1, SIM_GATE_FCFS = 2
  * recognised at prefill completion; TOKP_DEC/TOKD_DEC: prompt/output tokens recognised at decode
  * completion; TOK_EMIT output tokens emitted; TOK_PREF prompt tokens processed. SUM_*: end-of-step
  * values summed over steps. WAIT_STEPS: sum over admitted requests of (admission step - arrival
- * step). *_SUM: latency sums in ns (TTFT over S_P, E2E over S_DM+S_DS, TBT over TOK_EMIT). */
+ * step). *_SUM: latency sums in ns (TTFT over S_P, E2E over S_DM+S_DS, TBT over TOK_EMIT).
+ * AB_P / AB_D: abandonments from the class prefill queue / from the decode buffer (B_p,i and B_d,i). */
 enum sim_tally {
   SIM_T_A = 0, SIM_T_DROP_P, SIM_T_U_P, SIM_T_S_P, SIM_T_U_DM, SIM_T_U_DS, SIM_T_S_DM, SIM_T_S_DS,
   SIM_T_M_SM, SIM_T_M_MS, SIM_T_DROP_D, SIM_T_TOKP_PRE, SIM_T_TOKP_DEC, SIM_T_TOKD_DEC, SIM_T_TOK_EMIT,
   SIM_T_TOK_PREF, SIM_T_SUM_QP, SIM_T_SUM_QD, SIM_T_SUM_X, SIM_T_SUM_YM, SIM_T_SUM_YS, SIM_T_WAIT_STEPS,
-  SIM_T_TTFT_SUM, SIM_T_E2E_SUM, SIM_T_TBT_SUM, SIM_NTALLY
+  SIM_T_TTFT_SUM, SIM_T_E2E_SUM, SIM_T_TBT_SUM, SIM_T_AB_P, SIM_T_AB_D, SIM_NTALLY
 };
 /* Per-replication tallies: executed iterations and busy ns by kind (a "mix" iteration holds a
  * prefill chunk), steps run, and 1 if any ring overflowed. */
@@ -78,7 +89,7 @@ typedef struct {
   double price_in, price_out;    /* c_p, c_d: price per prompt / output token */
   int bundled;                   /* 1: this class counts bundled revenue in rev_mixed, 0: separate */
   double priority;               /* static index of the priority gate (larger first), e.g. D_i/P_i */
-  double theta;                  /* patience rate; abandonment is not simulated: must be 0 */
+  double theta;                  /* patience rate of a waiting request, >= 0; 0 = never abandons */
 } sim_class;
 
 typedef struct {
@@ -114,6 +125,7 @@ typedef struct {
   double mean_wait[SIM_MAXK];
   double fair_gap_x, fair_gap_ys, fair_min_served;   /* fairness SLIs of Sec. 5.2, measured */
   double util_mix, util_solo, iter_rate;
+  double abandon_rate_p[SIM_MAXK], abandon_rate_d[SIM_MAXK]; /* abandonments per server per unit time */
 } sim_stats_t;
 
 /* Integer state of one replication, copied into caller-allocated host arrays (NULL = skip).
@@ -131,6 +143,8 @@ typedef struct {
   int32_t *n_dec;         /* [N] */
   uint64_t *queue[SIM_MAXK]; int64_t queue_len[SIM_MAXK]; /* arrival stamps, head first; capacity queue_cap */
   uint64_t *dbuf; int64_t dbuf_len;                        /* decode buffer requests, head first; capacity dbuf_cap */
+  uint64_t *queue_dl[SIM_MAXK];  /* per queue entry: the step at whose start it abandons if still waiting (2^32-1: never) */
+  uint64_t *dbuf_dl;             /* the same for the decode buffer entries */
 } sim_state_t;
 
 typedef struct sim_t sim_t;  /* opaque; owned by the library */
@@ -140,7 +154,7 @@ int sim_workspace_bytes(const sim_config *cfg, int max_replications, size_t *out
 
 /* Validates and deep-copies the config, builds the sampler tables on the host and uploads them
  * into `dev_workspace` (device pointer, 256-byte aligned, owned by the caller, must outlive the
- * handle). SIM_EINVAL: bad sizes, negative target, M outside [0,N], dt > c0, theta != 0, total
+ * handle). SIM_EINVAL: bad sizes, negative target, M outside [0,N], dt > c0, negative theta, total
  * arrival mean per server-step above 0.05 (the per-step count is truncated at 3).
  * SIM_ENOMEM: workspace too small. The library never allocates device memory itself. */
 int sim_create(const sim_config *cfg, int max_replications, void *dev_workspace, size_t bytes, sim_t **out);
@@ -184,6 +198,8 @@ const char *sim_strerror(int err);
  * one Philox4x32-10 block, the sampler thresholds a config would use
  * (arr_thr[rows][3] for rows 0..rows-1, cls_thr[SIM_MAXK]). */
 int sim_length_table(int law, double p0, double p1, uint16_t *out);
+/* the patience table (65536 entries, in steps) of a class with patience rate theta > 0 at step length dt */
+int sim_patience_table(double theta, double dt, uint16_t *out);
 int sim_philox(uint64_t seed, uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t *out4);
 int sim_thresholds(const sim_config *cfg, int64_t rows, uint32_t *arr_thr, uint32_t *cls_thr);
 /* sizeof of the four ABI structs, in the order class, config, stats, state (for binding checks). */

@@ -15,7 +15,7 @@ from .build import lib_path
 MAXK, MAXB, NBIN = 8, 128, 720
 TALLY = ["A", "DROP_P", "U_P", "S_P", "U_DM", "U_DS", "S_DM", "S_DS", "M_SM", "M_MS", "DROP_D", "TOKP_PRE",
          "TOKP_DEC", "TOKD_DEC", "TOK_EMIT", "TOK_PREF", "SUM_QP", "SUM_QD", "SUM_X", "SUM_YM", "SUM_YS",
-         "WAIT_STEPS", "TTFT_SUM", "E2E_SUM", "TBT_SUM"]
+         "WAIT_STEPS", "TTFT_SUM", "E2E_SUM", "TBT_SUM", "AB_P", "AB_D"]
 GLOBAL = ["ITERS_MIX", "ITERS_SOLO", "BUSY_MIX", "BUSY_SOLO", "STEPS", "OVERFLOW"]
 SIM_EOVERFLOW = -4
 
@@ -52,7 +52,7 @@ class SimStatsC(C.Structure):
                 ("tbt_mean", _D8), ("tbt_p50", _D8), ("tbt_p95", _D8), ("tbt_p99", _D8),
                 ("mean_wait", _D8), ("fair_gap_x", C.c_double), ("fair_gap_ys", C.c_double),
                 ("fair_min_served", C.c_double), ("util_mix", C.c_double), ("util_solo", C.c_double),
-                ("iter_rate", C.c_double)]
+                ("iter_rate", C.c_double), ("abandon_rate_p", _D8), ("abandon_rate_d", _D8)]
 
 
 class SimStateC(C.Structure):
@@ -60,7 +60,8 @@ class SimStateC(C.Structure):
                 ("ptok", C.c_void_p), ("pfjob", C.c_void_p), ("n_cls", C.c_void_p), ("n_join", C.c_void_p),
                 ("fin", C.c_void_p), ("job", C.c_void_p), ("n_dec", C.c_void_p),
                 ("queue", C.c_void_p * MAXK), ("queue_len", C.c_int64 * MAXK),
-                ("dbuf", C.c_void_p), ("dbuf_len", C.c_int64)]
+                ("dbuf", C.c_void_p), ("dbuf_len", C.c_int64),
+                ("queue_dl", C.c_void_p * MAXK), ("dbuf_dl", C.c_void_p)]
 
 
 _lib = None
@@ -87,6 +88,7 @@ def lib():
         L.sim_kernel_time.argtypes = [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.c_int, C.c_void_p]
         L.sim_destroy.argtypes = [C.c_void_p]
         L.sim_length_table.argtypes = [C.c_int, C.c_double, C.c_double, C.c_void_p]
+        L.sim_patience_table.argtypes = [C.c_double, C.c_double, C.c_void_p]
         L.sim_philox.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, C.c_void_p]
         L.sim_thresholds.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
         _lib = L
@@ -146,6 +148,12 @@ def sim_workspace_bytes(cfg, max_replications):
 def sim_length_table(law, p0, p1=0.0):
     out = np.zeros(65536, np.uint16)
     _check(lib().sim_length_table(int(law), float(p0), float(p1), out.ctypes.data), "sim_length_table")
+    return out
+
+
+def sim_patience_table(theta, dt):
+    out = np.zeros(65536, np.uint16)
+    _check(lib().sim_patience_table(float(theta), float(dt), out.ctypes.data), "sim_patience_table")
     return out
 
 
@@ -266,15 +274,21 @@ class Sim:
                  fin=np.zeros((N, B), np.uint32), job=np.zeros((N, B), np.uint64), n_dec=np.zeros(N, np.int32))
         queues = [np.zeros(cfg.queue_cap, np.uint64) for _ in range(K)]
         dbuf = np.zeros(cfg.dbuf_cap, np.uint64)
+        queue_dl = [np.zeros(cfg.queue_cap, np.uint64) for _ in range(K)]
+        dbuf_dl = np.zeros(cfg.dbuf_cap, np.uint64)
         st = SimStateC()
         for k, v in a.items():
             setattr(st, k, v.ctypes.data)
         for k in range(K):
             st.queue[k] = queues[k].ctypes.data
+            st.queue_dl[k] = queue_dl[k].ctypes.data
         st.dbuf = dbuf.ctypes.data
+        st.dbuf_dl = dbuf_dl.ctypes.data
         _check(lib().sim_snapshot(self.h, int(r), C.byref(st), self._stream()), "sim_snapshot")
         a["queues"] = [queues[k][:st.queue_len[k]].copy() for k in range(K)]
         a["dbuf"] = dbuf[:st.dbuf_len].copy()
+        a["queue_dl"] = [queue_dl[k][:st.queue_len[k]].copy() for k in range(K)]
+        a["dbuf_dl"] = dbuf_dl[:st.dbuf_len].copy()
         cs = a.pop("class_state")
         a.update(Qp=cs[0], X=cs[1], Qd=cs[2], Ym=cs[3], Ys=cs[4])
         return a

@@ -40,12 +40,20 @@ constexpr uint32_t kStepsPerLaunch = 2048;
 
 struct Layout {
   size_t arr_thr, len_tab, t_next, iter, remptok, pf_job, n_cls, n_join, fin, job, qring, dring, cstate, tally, hist,
-      digest, reduced, params, total;
+      digest, reduced, params, pat_tab, qdl, ddl, cal, dcal, total;
 };
+
+bool any_patience(const sim_config &c)
+{
+  for (int k = 0; k < c.K; ++k)
+    if (c.cls[k].theta > 0.0) return true;
+  return false;
+}
 
 size_t align_up(size_t v) { return (v + 255) & ~size_t(255); }
 
-Layout make_layout(const sim_config &c, int R, int64_t rows)
+// `cal_entries`: size of one deadline calendar (0 when no class has a patience rate)
+Layout make_layout(const sim_config &c, int R, int64_t rows, size_t cal_entries)
 {
   Layout L{};
   size_t off = 0;
@@ -70,6 +78,13 @@ Layout make_layout(const sim_config &c, int R, int64_t rows)
   L.digest = take(static_cast<size_t>(R) * sizeof(uint64_t));
   L.reduced = take((kTallyWords + static_cast<size_t>(3) * c.K * kNBin) * sizeof(uint64_t));
   L.params = take(sizeof(Params));
+  if (cal_entries) {
+    L.pat_tab = take(static_cast<size_t>(c.K) * kTableSize * sizeof(uint16_t));
+    L.qdl = take(static_cast<size_t>(R) * c.K * c.queue_cap * sizeof(uint32_t));
+    L.ddl = take(static_cast<size_t>(R) * c.dbuf_cap * sizeof(uint32_t));
+    L.cal = take(static_cast<size_t>(R) * c.K * cal_entries * sizeof(uint32_t));
+    L.dcal = take(static_cast<size_t>(R) * c.K * cal_entries * sizeof(uint32_t));
+  }
   L.total = off;
   return L;
 }
@@ -108,7 +123,7 @@ int validate(const sim_config *c, int max_reps, Ticks *t)
   if (t->c0 > (int64_t(1) << 40) || t->cpre > (int64_t(1) << 32) || t->cdec > (int64_t(1) << 32)) return SIM_EINVAL;
   for (int k = 0; k < c->K; ++k) {
     const sim_class &q = c->cls[k];
-    if (q.theta != 0.0 || !(q.lambda >= 0.0) || !(c->x_star[k] >= 0.0) || !std::isfinite(c->qp_star[k])) return SIM_EINVAL;
+    if (!(q.theta >= 0.0) || !std::isfinite(q.theta) || !(q.lambda >= 0.0) || !(c->x_star[k] >= 0.0) || !std::isfinite(c->qp_star[k])) return SIM_EINVAL;
     if (!std::isfinite(q.price_in) || !std::isfinite(q.price_out) || !std::isfinite(q.priority)) return SIM_EINVAL;
   }
   const double lam = total_rate(c->cls, c->K);
@@ -117,6 +132,27 @@ int validate(const sim_config *c, int max_reps, Ticks *t)
   if (hi - lo + 1 > kMaxTbtBins) return SIM_EINVAL;
   // clocks are compared modulo 2^32 ns on the device: the longest iteration must stay far below 2^31 ns
   if (t->c0 + t->cpre * c->C + t->cdec * c->B > 2000000000ll) return SIM_EINVAL;
+  return SIM_OK;
+}
+
+// Patience tables of the classes that have a rate (others zero-filled) and the calendar size they need:
+// the power of two above the longest patience. Returns 0 entries when no class abandons.
+int patience_tables(const sim_config &c, const Ticks &t, std::vector<uint16_t> *tab, size_t *cal_entries)
+{
+  *cal_entries = 0;
+  if (!any_patience(c)) return SIM_OK;
+  tab->assign(static_cast<size_t>(c.K) * kTableSize, 0);
+  uint32_t longest = 1;
+  for (int k = 0; k < c.K; ++k) {
+    if (!(c.cls[k].theta > 0.0)) continue;
+    uint16_t *out = tab->data() + static_cast<size_t>(k) * kTableSize;
+    const int rc = build_patience_table(c.cls[k].theta, static_cast<double>(t.dt) * 1e-9, out);
+    if (rc != SIM_OK) return rc;
+    if (out[kTableSize - 1] > longest) longest = out[kTableSize - 1];
+  }
+  size_t n = 2;
+  while (n <= longest) n <<= 1;
+  *cal_entries = n;
   return SIM_OK;
 }
 
@@ -167,7 +203,11 @@ int sim_workspace_bytes(const sim_config *cfg, int max_replications, size_t *out
   const int rc = validate(cfg, max_replications, &t);
   if (rc != SIM_OK || !out_bytes) return rc != SIM_OK ? rc : SIM_EINVAL;
   const int64_t rows = cfg->mod_period > 0 ? cfg->mod_period : 1;
-  *out_bytes = make_layout(*cfg, max_replications, rows).total;
+  std::vector<uint16_t> pat;
+  size_t cal_entries = 0;
+  const int rp = patience_tables(*cfg, t, &pat, &cal_entries);
+  if (rp != SIM_OK) return rp;
+  *out_bytes = make_layout(*cfg, max_replications, rows, cal_entries).total;
   return SIM_OK;
 }
 
@@ -178,7 +218,11 @@ int sim_create(const sim_config *cfg, int max_replications, void *dev_workspace,
   if (rc != SIM_OK) return rc;
   if (!dev_workspace || !out || (reinterpret_cast<uintptr_t>(dev_workspace) & 255u)) return SIM_EINVAL;
   const int64_t rows = cfg->mod_period > 0 ? cfg->mod_period : 1;
-  const Layout L = make_layout(*cfg, max_replications, rows);
+  std::vector<uint16_t> pat;
+  size_t cal_entries = 0;
+  rc = patience_tables(*cfg, t, &pat, &cal_entries);
+  if (rc != SIM_OK) return rc;
+  const Layout L = make_layout(*cfg, max_replications, rows, cal_entries);
   if (bytes < L.total) return SIM_ENOMEM;
 
   sim_t *h = new (std::nothrow) sim_t();
@@ -250,6 +294,16 @@ int sim_create(const sim_config *cfg, int max_replications, void *dev_workspace,
   p.hist = reinterpret_cast<uint64_t *>(w + L.hist);
   p.digest = reinterpret_cast<uint64_t *>(w + L.digest);
   p.reduced = reinterpret_cast<uint64_t *>(w + L.reduced);
+  if (cal_entries) {
+    for (int k = 0; k < cfg->K; ++k)
+      if (cfg->cls[k].theta > 0.0) p.ab_classes |= 1u << k;
+    p.cal_mask = static_cast<uint32_t>(cal_entries - 1);
+    p.pat_tab = reinterpret_cast<uint16_t *>(w + L.pat_tab);
+    p.qdl = reinterpret_cast<uint32_t *>(w + L.qdl);
+    p.ddl = reinterpret_cast<uint32_t *>(w + L.ddl);
+    p.cal = reinterpret_cast<uint32_t *>(w + L.cal);
+    p.dcal = reinterpret_cast<uint32_t *>(w + L.dcal);
+  }
 
   p.self = reinterpret_cast<const Params *>(w + L.params);
   h->threads = step_threads(cfg->N);
@@ -258,7 +312,9 @@ int sim_create(const sim_config *cfg, int max_replications, void *dev_workspace,
   if (h->lds_bytes > 160 * 1024) { delete h; return SIM_EINVAL; }
   if (hipMemcpy(w + L.arr_thr, arr.data(), arr.size() * sizeof(uint32_t), hipMemcpyHostToDevice) != hipSuccess ||
       hipMemcpy(w + L.len_tab, tab.data(), tab.size() * sizeof(uint16_t), hipMemcpyHostToDevice) != hipSuccess ||
-      hipMemcpy(w + L.params, &p, sizeof(Params), hipMemcpyHostToDevice) != hipSuccess) {
+      hipMemcpy(w + L.params, &p, sizeof(Params), hipMemcpyHostToDevice) != hipSuccess ||
+      (cal_entries &&
+       hipMemcpy(w + L.pat_tab, pat.data(), pat.size() * sizeof(uint16_t), hipMemcpyHostToDevice) != hipSuccess)) {
     delete h;
     return SIM_EHIP;
   }
@@ -380,6 +436,8 @@ int sim_stats(sim_t *h, sim_stats_t *st, void *hip_stream)
     st->ttft_mean[k] = ratio(static_cast<double>(t[SIM_T_TTFT_SUM]) * 1e-9, static_cast<double>(t[SIM_T_S_P]));
     st->e2e_mean[k] = ratio(static_cast<double>(t[SIM_T_E2E_SUM]) * 1e-9, done);
     st->tbt_mean[k] = ratio(static_cast<double>(t[SIM_T_TBT_SUM]) * 1e-9, static_cast<double>(t[SIM_T_TOK_EMIT]));
+    st->abandon_rate_p[k] = ratio(static_cast<double>(t[SIM_T_AB_P]), server_time);
+    st->abandon_rate_d[k] = ratio(static_cast<double>(t[SIM_T_AB_D]), server_time);
     st->mean_wait[k] = ratio(static_cast<double>(t[SIM_T_WAIT_STEPS]) * dts, static_cast<double>(t[SIM_T_U_P]));
     const uint64_t *h0 = hs + (static_cast<size_t>(0) * K + k) * kNBin;
     const uint64_t *h1 = hs + (static_cast<size_t>(1) * K + k) * kNBin;
@@ -499,6 +557,13 @@ int sim_snapshot(sim_t *h, int r, sim_state_t *out, void *hip_stream)
     rc = copy_out(ring.data(), p.qring + (static_cast<size_t>(r) * K + k) * p.queue_cap, ring.size() * sizeof(uint32_t));
     if (rc != SIM_OK) return rc;
     for (int64_t i = 0; i < len; ++i) out->queue[k][i] = ring[(static_cast<uint32_t>(cs[CS_QHEAD + k]) + i) % p.queue_cap];
+    if (!out->queue_dl[k]) continue;
+    if (p.ab_classes) {
+      rc = copy_out(ring.data(), p.qdl + (static_cast<size_t>(r) * K + k) * p.queue_cap, ring.size() * sizeof(uint32_t));
+      if (rc != SIM_OK) return rc;
+    }
+    for (int64_t i = 0; i < len; ++i)
+      out->queue_dl[k][i] = p.ab_classes ? ring[(static_cast<uint32_t>(cs[CS_QHEAD + k]) + i) % p.queue_cap] : kNever;
   }
   out->dbuf_len = cs[CS_DCOUNT];
   if (out->dbuf && cs[CS_DCOUNT] > 0) {
@@ -506,6 +571,14 @@ int sim_snapshot(sim_t *h, int r, sim_state_t *out, void *hip_stream)
     rc = copy_out(ring.data(), p.dring + static_cast<size_t>(r) * p.dbuf_cap, ring.size() * sizeof(uint64_t));
     if (rc != SIM_OK) return rc;
     for (int64_t i = 0; i < cs[CS_DCOUNT]; ++i) out->dbuf[i] = ring[(static_cast<uint32_t>(cs[CS_DHEAD]) + i) % p.dbuf_cap];
+  }
+  if (out->dbuf_dl && cs[CS_DCOUNT] > 0) {
+    std::vector<uint32_t> ring(p.dbuf_cap, kNever);
+    if (p.ab_classes) {
+      rc = copy_out(ring.data(), p.ddl + static_cast<size_t>(r) * p.dbuf_cap, ring.size() * sizeof(uint32_t));
+      if (rc != SIM_OK) return rc;
+    }
+    for (int64_t i = 0; i < cs[CS_DCOUNT]; ++i) out->dbuf_dl[i] = ring[(static_cast<uint32_t>(cs[CS_DHEAD]) + i) % p.dbuf_cap];
   }
   return SIM_OK;
 }
@@ -534,6 +607,12 @@ int sim_length_table(int law, double p0, double p1, uint16_t *out)
 {
   if (!out || law == SIM_TABLE) return SIM_EINVAL;
   return build_length_table(law, p0, p1, nullptr, out);
+}
+
+int sim_patience_table(double theta, double dt, uint16_t *out)
+{
+  if (!out) return SIM_EINVAL;
+  return build_patience_table(theta, dt, out);
 }
 
 int sim_philox(uint64_t seed, uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t *out4)

@@ -27,6 +27,9 @@ constexpr int kMaxTbtBins = 256;  // width of the on-chip time-between-tokens hi
 enum ClassStateWord {
   CS_QP = 0, CS_X = 8, CS_QD = 16, CS_YM = 24, CS_YS = 32, CS_QHEAD = 40, CS_DHEAD = 48, CS_DCOUNT = 49, CS_WORDS = 64
 };
+constexpr uint32_t kNever = 0xFFFFFFFFu;   // deadline of a request that never abandons
+constexpr int kStreamPatienceP = 2;        // random streams: 0 arrivals, 1 lengths, 2+k prefill-queue patience of class k,
+constexpr int kStreamPatienceD = 10;       // 10 decode-buffer patience
 
 // Everything a kernel needs, passed by value.
 struct Params {
@@ -42,9 +45,13 @@ struct Params {
   int64_t mod_period;
   double nx[kMaxK], invx[kMaxK], xstar[kMaxK], nq[kMaxK], prio[kMaxK];   // n x*, 1/x*, x*, n q*, priority index
   uint32_t cls_thr[kMaxK];
+  // abandonment: classes with a patience rate (bit k), mask of the deadline calendars (entries - 1, a power of two
+  // above the longest patience in steps)
+  uint32_t ab_classes, cal_mask;
   // tables (device)
   const uint32_t *arr_thr;    // [rows][3]
   const uint16_t *len_tab;    // [K][2][65536]: in, out
+  const uint16_t *pat_tab;    // [K][65536] patience in steps (abandonment only)
   // per-server state, [R][N]
   int64_t *t_next;
   uint32_t *iter;
@@ -57,6 +64,12 @@ struct Params {
   // rings
   uint32_t *qring;            // [R][K][queue_cap] arrival stamps
   uint64_t *dring;            // [R][dbuf_cap] requests
+  // abandonment only: the step at whose start a waiting request leaves, beside each ring entry; per class and
+  // step (modulo the calendar size), how many waiting requests leave at that step
+  uint32_t *qdl;              // [R][K][queue_cap]
+  uint32_t *ddl;              // [R][dbuf_cap]
+  uint32_t *cal;              // [R][K][cal_mask+1] prefill queues
+  uint32_t *dcal;             // [R][K][cal_mask+1] decode buffer
   // class state, tallies, histograms
   int32_t *cstate;            // [R][CS_WORDS]
   uint64_t *tally;            // [R][kTallyWords]
@@ -68,6 +81,7 @@ struct Params {
 
 // host-side table builders (gnr_tables.cpp)
 int build_length_table(int law, double p0, double p1, const uint16_t *user, uint16_t *out);
+int build_patience_table(double theta, double dt_seconds, uint16_t *out);
 double total_rate(const sim_class *cls, int K);
 void build_arrival_row(double lam, int64_t dt_ns, double amp, int64_t period, int64_t row, uint32_t thr[3]);
 void build_class_thresholds(const sim_class *cls, int K, uint32_t *thr);

@@ -119,6 +119,12 @@ __device__ unsigned long long g_prof[32];
 // ------------------------------------------------------------------ LDS layout ----
 enum Scalar {
   SC_NIDLE = 0, SC_NCOMP,
+  // abandonment only:
+  SC_LEAD = 2,    // [8] 1 if the gate's scan of the class queue found a waiting request in this pass
+  SC_DLEN = 10,   // entries of the decode buffer ring between head and tail, abandoned ones included
+  SC_DSCAN = 11,  // entries of that ring the routing passes of this step have gone past
+  SC_COMPACT = 12,// bit k: class queue ring k (bit 8: the decode buffer ring) must be compacted before the appends
+  SC_QLEN = 32,   // [8] entries of each class queue ring between head and tail, abandoned ones included
   SC_TAKE = 16,   // [8] accepted arrivals this step
   SC_TAIL = 24,   // [8] ring position of the first accepted arrival
   SC_ADMK = 40,   // [8] admissions per class in this gate pass
@@ -164,6 +170,7 @@ struct Lds {
   uint8_t *loads;     // [N] decodes per server
   uint8_t *pend;      // [N] completed iterations not yet tallied (all with the server's current batch)
   uint16_t *rem;      // [M] prompt tokens left of the prefill a mixed-group server has in service (0: slot idle)
+  uint32_t *live_off; // [K][kAdmChunk] abandonment only: ring offset from the head of the m-th waiting request of a class
 };
 
 // Carves the dynamic LDS block; 8-byte granules, 64-bit arrays first.
@@ -205,6 +212,7 @@ __host__ __device__ __forceinline__ Lds lds_carve(const Params &p, unsigned char
   GNR_TAKE(pend, uint8_t, p.N)
   GNR_TAKE(rem, uint16_t, p.M)
   GNR_TAKE(stage, uint16_t, 2 * p.threads)
+  GNR_TAKE(live_off, uint32_t, p.ab_classes ? p.K * kAdmChunk : 0)
 #undef GNR_TAKE
   if (total) *total = off;
   return L;
@@ -341,8 +349,10 @@ __device__ __forceinline__ void tally_iterations(uint64_t *tl, uint64_t *tbth, i
 // gate's one-at-a-time argmin is the merge of the classes' sequences in this order.
 struct GateKey { double a, b; };
 
-__device__ __forceinline__ GateKey gate_key(const Params &p, const uint32_t *qring, const int (&xs)[kMaxK],
-                                            const int (&qp)[kMaxK], const uint32_t (&head)[kMaxK], int k, int m)
+// `live_off` (abandonment only, else null): ring offset of the m-th request of class k that still waits.
+__device__ __forceinline__ GateKey gate_key(const Params &p, const uint32_t *qring, const uint32_t *live_off,
+                                            const int (&xs)[kMaxK], const int (&qp)[kMaxK],
+                                            const uint32_t (&head)[kMaxK], int k, int m)
 {
   GateKey key;
   if (p.gate_mode == SIM_GATE_OCCUPANCY) {
@@ -352,7 +362,7 @@ __device__ __forceinline__ GateKey gate_key(const Params &p, const uint32_t *qri
     key.a = -p.prio[k];
     key.b = 0.0;
   } else {
-    uint32_t pos = head[k] + static_cast<uint32_t>(m);
+    uint32_t pos = head[k] + (live_off ? live_off[k * kAdmChunk + m] : static_cast<uint32_t>(m));
     if (pos >= p.queue_cap) pos -= p.queue_cap;
     key.a = static_cast<double>(qring[static_cast<size_t>(k) * p.queue_cap + pos]);
     key.b = 0.0;
@@ -391,9 +401,17 @@ struct StepArrays {
   uint64_t *dring;
   int32_t *cstate;
   uint64_t *tally, *hist;
+  // abandonment only
+  const uint16_t *pat_tab;
+  uint32_t *qdl, *ddl, *cal, *dcal;
 };
 
-template <int MAXT>
+// AB: the variant with abandonment (some class has a patience rate). Ring entries then carry the step at whose
+// start the request leaves if it still waits. Such entries stay in the rings as dead entries until the head
+// passes them: the counters Q_p, Q_d follow the abandonments eagerly through per-step calendars, the gate and
+// the router skip dead entries when they take requests, and a ring is compacted when it would not hold the
+// step's appends and at the end of every launch (so the state between launches holds waiting requests only).
+template <int MAXT, bool AB>
 __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict__ params, const StepArrays a,
                                                         const uint32_t key0, const uint32_t key1,
                                                         const uint32_t step_begin, const uint32_t n_steps)
@@ -428,6 +446,13 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
   uint64_t *hist = a.hist + static_cast<size_t>(r) * 3 * K * kNBin;
   uint32_t *ev_g = L.ev_g + wave * kEvPerWave;
   uint32_t *ev_q = L.ev_q + wave * kEvPerWave;
+  // abandonment only
+  const uint32_t cal_n = p.cal_mask + 1u;
+  uint32_t *qdl = AB ? a.qdl + static_cast<size_t>(r) * K * p.queue_cap : nullptr;
+  uint32_t *ddl = AB ? a.ddl + static_cast<size_t>(r) * p.dbuf_cap : nullptr;
+  uint32_t *cal = AB ? a.cal + static_cast<size_t>(r) * K * cal_n : nullptr;
+  uint32_t *dcal = AB ? a.dcal + static_cast<size_t>(r) * K * cal_n : nullptr;
+  const uint32_t *lo_tab = AB ? L.live_off : nullptr;
 
   // ---- load the replication's class state and rebuild the on-chip views of the server state
   for (int i = tid; i < CS_WORDS; i += NT) L.cs[i] = a.cstate[static_cast<size_t>(r) * CS_WORDS + i];
@@ -439,6 +464,10 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
   for (int i = tid; i < SC_WORDS; i += NT) L.sc[i] = 0;
   for (int i = tid; i < 2 * kLoadBins; i += NT) L.lh[i] = 0;
   __syncthreads();
+  if constexpr (AB) {   // between launches the rings hold waiting requests only
+    if (tid < K) L.sc[SC_QLEN + tid] = L.cs[CS_QP + tid];
+    if (tid == 0) L.sc[SC_DLEN] = L.cs[CS_DCOUNT];
+  }
   for (int i = 0; i < nper; ++i) {
     const int g = i * NT + tid;
     const bool valid = g < N;
@@ -470,6 +499,60 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
   }
   __syncthreads();
 
+  // ---- abandonment only: ring compaction, one wave per ring. Entries whose deadline is not after `now` are
+  //      dropped, the others keep their order and move towards the head (a lane never writes ahead of what
+  //      the wave has read). `pending`: entries already counted in the ring length but not yet written.
+  auto compact_queue = [&](int k, uint32_t now, uint32_t pending) __attribute__((always_inline)) {
+    uint32_t *ring = qring + static_cast<size_t>(k) * p.queue_cap;
+    uint32_t *dlr = qdl + static_cast<size_t>(k) * p.queue_cap;
+    const uint32_t hd = static_cast<uint32_t>(L.cs[CS_QHEAD + k]);
+    uint32_t n = static_cast<uint32_t>(L.sc[SC_QLEN + k]) - pending;
+    if (n > p.queue_cap) n = p.queue_cap;   // (a ring never holds more; keeps every access inside it regardless)
+    uint32_t w = 0;
+    for (uint32_t off = 0; off < n; off += 64) {   // wave-uniform
+      const uint32_t i = off + lane;
+      uint32_t pos = hd + i;
+      if (pos >= p.queue_cap) pos -= p.queue_cap;
+      const uint32_t st = i < n ? ring[pos] : 0u, dl = i < n ? dlr[pos] : 0u;
+      const bool live = i < n && dl > now;
+      const uint64_t bal = __ballot(live);
+      if (live) {
+        uint32_t wp = hd + w + static_cast<uint32_t>(__popcll(bal & lanes_below()));
+        if (wp >= p.queue_cap) wp -= p.queue_cap;
+        ring[wp] = st; dlr[wp] = dl;
+      }
+      w += static_cast<uint32_t>(__popcll(bal));
+    }
+    if (lane == 0) {
+      uint32_t tail = hd + w;
+      if (tail >= p.queue_cap) tail -= p.queue_cap;
+      L.sc[SC_QLEN + k] = static_cast<int32_t>(w + pending);
+      L.sc[SC_TAIL + k] = static_cast<int32_t>(tail);
+    }
+  };
+  auto compact_buffer = [&](uint32_t now) __attribute__((always_inline)) {
+    const uint32_t hd = static_cast<uint32_t>(L.cs[CS_DHEAD]);
+    uint32_t n = static_cast<uint32_t>(L.sc[SC_DLEN]);
+    if (n > p.dbuf_cap) n = p.dbuf_cap;
+    uint32_t w = 0;
+    for (uint32_t off = 0; off < n; off += 64) {   // wave-uniform
+      const uint32_t i = off + lane;
+      uint32_t pos = hd + i;
+      if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
+      const uint64_t jw = i < n ? dring[pos] : 0ull;
+      const uint32_t dl = i < n ? ddl[pos] : 0u;
+      const bool live = i < n && dl > now;
+      const uint64_t bal = __ballot(live);
+      if (live) {
+        uint32_t wp = hd + w + static_cast<uint32_t>(__popcll(bal & lanes_below()));
+        if (wp >= p.dbuf_cap) wp -= p.dbuf_cap;
+        dring[wp] = jw; ddl[wp] = dl;
+      }
+      w += static_cast<uint32_t>(__popcll(bal));
+    }
+    if (lane == 0) L.sc[SC_DLEN] = static_cast<int32_t>(w);
+  };
+
   int64_t T = 0;
   PROF_DECL
   // A server that completed an iteration, or was given work while idle, is restarted lazily: when its block
@@ -483,6 +566,15 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
     const int64_t Tp = T - p.dt;   // the boundary of the previous step: restarts refer to it
     const uint32_t Tp32 = static_cast<uint32_t>(Tp);
     if (tid < 8) L.acc[tid] = 0;
+    // abandonment only: how many waiting requests of class `tid` leave at the start of this step (asked for
+    // here, used after the completion pass)
+    uint32_t n_leave_p = 0, n_leave_d = 0;
+    if constexpr (AB) {
+      if (!final_pass && tid < K) {
+        n_leave_p = atomicExch(&cal[static_cast<size_t>(tid) * cal_n + (s & p.cal_mask)], 0u);
+        n_leave_d = atomicExch(&dcal[static_cast<size_t>(tid) * cal_n + (s & p.cal_mask)], 0u);
+      }
+    }
     const uint32_t *thr = a.arr_thr + 3 * (p.mod_period > 0 ? static_cast<int64_t>(s % static_cast<uint64_t>(p.mod_period)) : 0);
     const uint32_t thr0 = thr[0], thr1 = thr[1], thr2 = thr[2];
     __syncthreads();
@@ -843,11 +935,28 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
     // ================= arrivals into the class queues; ranks of completions and idle slots =================
     if (tid < K) {
       const int k = tid;
+      if constexpr (AB) {   // abandonments come first: they free room in the queue
+        if (n_leave_p) {
+          L.cs[CS_QP + k] -= static_cast<int32_t>(n_leave_p);
+          L.tl[k * kNTally + SIM_T_AB_P] += n_leave_p;
+        }
+        if (n_leave_d) {
+          L.cs[CS_QD + k] -= static_cast<int32_t>(n_leave_d);
+          L.tl[k * kNTally + SIM_T_AB_D] += n_leave_d;
+          atomicSub(&L.cs[CS_DCOUNT], static_cast<int32_t>(n_leave_d));
+        }
+      }
       const uint32_t a = L.acc[k];
       const uint32_t room = p.queue_cap - static_cast<uint32_t>(L.cs[CS_QP + k]);
       const uint32_t take = a < room ? a : room;
-      uint32_t tail = static_cast<uint32_t>(L.cs[CS_QHEAD + k]) + static_cast<uint32_t>(L.cs[CS_QP + k]);
+      // entries between head and tail: the waiting requests, with abandonment also the dead entries
+      const uint32_t in_ring = static_cast<uint32_t>(AB ? L.sc[SC_QLEN + k] : L.cs[CS_QP + k]);
+      uint32_t tail = static_cast<uint32_t>(L.cs[CS_QHEAD + k]) + in_ring;
       if (tail >= p.queue_cap) tail -= p.queue_cap;
+      if constexpr (AB) {
+        if (in_ring + take > p.queue_cap) atomicOr(&L.sc[SC_COMPACT], 1 << k);
+        L.sc[SC_QLEN + k] = static_cast<int32_t>(in_ring + take);
+      }
       L.sc[SC_TAKE + k] = static_cast<int32_t>(take);
       L.sc[SC_TAIL + k] = static_cast<int32_t>(tail);
       L.cs[CS_QP + k] += static_cast<int32_t>(take);
@@ -864,18 +973,46 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
       if (lane == 0) L.sc[SC_NIDLE] = static_cast<int32_t>(nidle);
     }
     __syncthreads();
+    if constexpr (AB) {
+      // a ring that cannot hold this step's appends behind its dead entries is compacted first
+      if (tid == 0) {
+        const uint32_t ncp = static_cast<uint32_t>(L.sc[SC_NCOMP]);
+        const uint32_t room = p.dbuf_cap - static_cast<uint32_t>(L.cs[CS_DCOUNT]);
+        if (static_cast<uint32_t>(L.sc[SC_DLEN]) + (ncp < room ? ncp : room) > p.dbuf_cap) atomicOr(&L.sc[SC_COMPACT], 256);
+      }
+      __syncthreads();
+      const int flags = L.sc[SC_COMPACT];   // cleared at the end of the step
+      if (flags) {   // the same for every thread
+        for (int k = wave; k < K; k += nwaves)
+          if ((flags >> k) & 1) compact_queue(k, s, static_cast<uint32_t>(L.sc[SC_TAKE + k]));
+        if ((flags & 256) && wave == nwaves - 1) compact_buffer(s);
+        __syncthreads();
+      }
+    }
     for (int k = 0; k < K; ++k) {
       const uint32_t take = static_cast<uint32_t>(L.sc[SC_TAKE + k]), tail = static_cast<uint32_t>(L.sc[SC_TAIL + k]);
       for (uint32_t j = tid; j < take; j += NT) {
         uint32_t pos = tail + j;
         if (pos >= p.queue_cap) pos -= p.queue_cap;
         qring[static_cast<size_t>(k) * p.queue_cap + pos] = s;
+        if constexpr (AB) {
+          // the accepted arrivals of a class are exchangeable: the j-th of this step draws its patience
+          uint32_t dl = kNever;
+          if ((p.ab_classes >> k) & 1u) {
+            uint32_t w[4];
+            philox4x32_10(key0, key1, s, static_cast<uint32_t>(kStreamPatienceP + k), j, static_cast<uint32_t>(r), w);
+            dl = s + a.pat_tab[static_cast<size_t>(k) * kTableSize + (w[0] >> 16)];
+            atomicAdd(&cal[static_cast<size_t>(k) * cal_n + (dl & p.cal_mask)], 1u);
+          }
+          qdl[static_cast<size_t>(k) * p.queue_cap + pos] = dl;
+        }
       }
     }
     // completed prefills join the decode buffer in ascending server order
     {
       const uint32_t ncomp = static_cast<uint32_t>(L.sc[SC_NCOMP]);
       const uint32_t dcount = static_cast<uint32_t>(L.cs[CS_DCOUNT]), dhead = static_cast<uint32_t>(L.cs[CS_DHEAD]);
+      const uint32_t dfill = AB ? static_cast<uint32_t>(L.sc[SC_DLEN]) : dcount;   // ring entries before the tail
       for (uint32_t j0 = wave_base; j0 < ncomp; j0 += NT) {   // wave-uniform trip count
         const uint32_t j = j0 + lane;
         const bool active = j < ncomp;
@@ -887,9 +1024,20 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           k = static_cast<int>(jw >> 29) & 7;
           kept = dcount + j < p.dbuf_cap;
           if (kept) {
-            uint32_t pos = dhead + dcount + j;
+            uint32_t pos = dhead + dfill + j;
             if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
             dring[pos] = jw;
+            if constexpr (AB) {   // patience for the wait in the decode buffer
+              uint32_t dl = kNever;
+              if ((p.ab_classes >> k) & 1u) {
+                uint32_t w[4];
+                philox4x32_10(key0, key1, s, static_cast<uint32_t>(kStreamPatienceD), static_cast<uint32_t>(g),
+                              static_cast<uint32_t>(r), w);
+                dl = s + a.pat_tab[static_cast<size_t>(k) * kTableSize + (w[0] >> 16)];
+                atomicAdd(&dcal[static_cast<size_t>(k) * cal_n + (dl & p.cal_mask)], 1u);
+              }
+              ddl[pos] = dl;
+            }
           }
         }
         wave_count_by_class_i32(active && kept, k, K, &L.cs[CS_QD], 1);
@@ -926,6 +1074,12 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
         jrem = dcount0 + (ncp < room ? ncp : room);
       }
       const uint32_t dhead0 = static_cast<uint32_t>(L.cs[CS_DHEAD]);
+      // abandonment only: ring entries of the decode buffer, this step's completions included
+      uint32_t dlen_all = AB ? static_cast<uint32_t>(L.sc[SC_DLEN]) + static_cast<uint32_t>(jrem - dcount0) : 0u;
+      if (dlen_all > p.dbuf_cap) dlen_all = p.dbuf_cap;   // (never more: the ring was compacted if it had to be)
+      if constexpr (AB) {
+        if (tid == 0) L.sc[SC_DSCAN] = 0;
+      }
       bool gate_on = true, route_on = jrem > 0;
       for (int pass = 0; gate_on || route_on; ++pass) {
         if (gate_on && pass > 0) {
@@ -935,7 +1089,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           }
           __syncthreads();
         }
-        if (p.gate_mode == SIM_GATE_FCFS && pass == 0) __syncthreads();   // stamps written above are read below
+        if ((AB || p.gate_mode == SIM_GATE_FCFS) && pass == 0) __syncthreads();   // ring entries written above are read below
 
         // ---------------- segment A ----------------
         int nadm = 0, nidle = 0;
@@ -955,6 +1109,35 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
             ncand += cnt[k];
           }
           nadm = ncand < limit ? ncand : limit;
+          if constexpr (AB) {
+            // where the candidates sit in their rings: a wave per class walks from the head past the dead entries
+            for (int k = wave; k < K; k += nwaves) {   // wave-uniform
+              uint32_t need = 0;
+#pragma unroll
+              for (int kk = 0; kk < kMaxK; ++kk)
+                if (kk == k) need = static_cast<uint32_t>(cnt[kk]);
+              uint32_t qlen = static_cast<uint32_t>(L.sc[SC_QLEN + k]);
+              if (qlen > p.queue_cap) qlen = p.queue_cap;
+              const uint32_t hd = static_cast<uint32_t>(L.cs[CS_QHEAD + k]);
+              const uint32_t *dlr = qdl + static_cast<size_t>(k) * p.queue_cap;
+              uint32_t found = 0;
+              for (uint32_t off = 0; off < qlen && found < need; off += 64) {   // wave-uniform
+                const uint32_t i = off + lane;
+                uint32_t pos = hd + i;
+                if (pos >= p.queue_cap) pos -= p.queue_cap;
+                const bool live = i < qlen && dlr[pos] > s;
+                const uint64_t bal = __ballot(live);
+                const uint32_t rk = found + static_cast<uint32_t>(__popcll(bal & lanes_below()));
+                if (live && rk < need) L.live_off[k * kAdmChunk + rk] = i;
+                found += static_cast<uint32_t>(__popcll(bal));
+              }
+              // (the ring holds as many live entries as the class counter says; if it ever did not, the
+              // candidates beyond them would point at the head entry)
+              for (uint32_t rk = found + lane; rk < need; rk += 64) L.live_off[k * kAdmChunk + rk] = 0;
+              if (lane == 0) L.sc[SC_LEAD + k] = (need > 0 && found > 0) ? 1 : 0;
+            }
+            __syncthreads();
+          }
           // The admissions take the first nadm idle prefill slots, whatever their order: the slot bitmaps are
           // updated here a word at a time (no atomics).
           // A wave takes a word, a lane a slot; the slot of every admission rank goes into a table.
@@ -984,7 +1167,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
             GateKey key = {0.0, 0.0};
 #pragma unroll
             for (int kk = 0; kk < kMaxK; ++kk)
-              if (k == kk) key = gate_key(p, qring, xs, qp, head, kk, m);
+              if (k == kk) key = gate_key(p, qring, lo_tab, xs, qp, head, kk, m);
             int rank = m;
 #pragma unroll
             for (int k2 = 0; k2 < kMaxK; ++k2) {
@@ -999,15 +1182,15 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
                 const int g0 = est > 0.0 ? (est < static_cast<double>(hi) ? static_cast<int>(est) : hi) : 0;
                 const int l2 = g0 > 1 ? g0 - 1 : 0, h2 = g0 + 2 < hi ? g0 + 2 : hi;
                 if (l2 > 0) {
-                  if (gate_before(gate_key(p, qring, xs, qp, head, k2, l2 - 1), k2, key, k)) lo = l2; else hi = l2 - 1;
+                  if (gate_before(gate_key(p, qring, lo_tab, xs, qp, head, k2, l2 - 1), k2, key, k)) lo = l2; else hi = l2 - 1;
                 }
                 if (h2 < hi) {
-                  if (gate_before(gate_key(p, qring, xs, qp, head, k2, h2), k2, key, k)) lo = h2 + 1; else hi = h2;
+                  if (gate_before(gate_key(p, qring, lo_tab, xs, qp, head, k2, h2), k2, key, k)) lo = h2 + 1; else hi = h2;
                 }
               }
               while (lo < hi) {
                 const int mid = (lo + hi) >> 1;
-                if (gate_before(gate_key(p, qring, xs, qp, head, k2, mid), k2, key, k)) lo = mid + 1; else hi = mid;
+                if (gate_before(gate_key(p, qring, lo_tab, xs, qp, head, k2, mid), k2, key, k)) lo = mid + 1; else hi = mid;
               }
               rank += lo;
             }
@@ -1026,14 +1209,20 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
         // servers of G with at most lminG + (t - firstG) decodes.
         int nl = 0, total = 0;
         int lminG[2] = {0, 0}, nG[2] = {0, 0}, csumG[2] = {0, 0}, tlastG[2] = {0, 0};
+        // Placements on a mixed-group server must see every admission of the step (it decides whether the job
+        // counts as mixed or solo decode): while the gate may need another pass, only the solo group is routed.
+        const bool gate_unfinished = gate_on && nadm == kAdmChunk && nidle > kAdmChunk;
+        bool route_wait = false;   // nothing to route in this pass, but the mixed group is still to come
         if (route_on) {
           // (every wave computes the same values and stores them: no broadcast, no barrier)
-          int rem_jobs = jrem;
+          // (with abandonment a pass places no more jobs than are staged in LDS)
+          const int jpass = AB && jrem > kJobsLds ? kJobsLds : jrem;
+          int rem_jobs = jpass;
 #pragma unroll
           for (int gi = 0; gi < 2; ++gi) {
             const int glo = gi == 0 ? M : 0, ghi = gi == 0 ? N : M;
             const int capg = gi == 0 ? B : B - 1;
-            if (glo >= ghi || nl >= kRouteLevels || rem_jobs <= 0) continue;   // wave-uniform
+            if (glo >= ghi || nl >= kRouteLevels || rem_jobs <= 0 || (gi == 1 && gate_unfinished)) continue;   // wave-uniform
             int lm = -1;
             for (int base = 0; base < capg && lm < 0; base += 64) {
               const int l = base + lane;
@@ -1045,7 +1234,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
             for (int u = 0; nl < kRouteLevels && rem_jobs > 0 && lm + u < capg; ++u) {
               csumG[gi] += static_cast<int>(L.lh[gi * kLoadBins + lm + u]);
               const int tk = csumG[gi] < rem_jobs ? csumG[gi] : rem_jobs;
-              if (lane == 0) { L.sc[SC_TAKE_T + nl] = tk; L.sc[SC_W_T + nl] = jrem - rem_jobs; }
+              if (lane == 0) { L.sc[SC_TAKE_T + nl] = tk; L.sc[SC_W_T + nl] = jpass - rem_jobs; }
               rem_jobs -= tk;
               tlastG[gi] = tk;
               ++nG[gi];
@@ -1053,9 +1242,10 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
             }
           }
           PROF(24)
-          total = jrem - rem_jobs;
+          total = jpass - rem_jobs;
           if (nl == 0) {
-            route_on = false;   // every slot is taken: the jobs stay in the buffer
+            if (gate_unfinished) route_wait = true;
+            else route_on = false;   // every slot is taken: the jobs stay in the buffer
           } else {
             PROF(25)
             // four blocks per round: their decode counts are read together, then compared level by level
@@ -1108,9 +1298,13 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
               const int g = L.adm_slot[j];
               const uint32_t e = L.adm[j];
               k = static_cast<int>(e & 7u);
-              uint32_t pos = static_cast<uint32_t>(L.cs[CS_QHEAD + k]) + (e >> 3);
+              uint32_t pos = static_cast<uint32_t>(L.cs[CS_QHEAD + k]) + (AB ? L.live_off[k * kAdmChunk + (e >> 3)] : (e >> 3));
               if (pos >= p.queue_cap) pos -= p.queue_cap;
               const uint32_t stamp = qring[static_cast<size_t>(k) * p.queue_cap + pos];
+              if constexpr (AB) {   // the request no longer waits: it leaves the calendar of its deadline
+                const uint32_t dl = qdl[static_cast<size_t>(k) * p.queue_cap + pos];
+                if (dl != kNever) atomicSub(&cal[static_cast<size_t>(k) * cal_n + (dl & p.cal_mask)], 1u);
+              }
               if (L.loads[g]) nc = n_cls[g];
               wait = static_cast<uint64_t>(s - stamp);
               uint32_t w[4];
@@ -1146,14 +1340,42 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
             }
           }
         }
-        if (route_on) {
+        if (route_on && !route_wait) {
           // the requests this pass places are staged in LDS
           const int nstage = total < kJobsLds ? total : kJobsLds;
+          if constexpr (AB) {
+            // one wave walks the ring from where the last pass stopped and stages the next `total` waiting jobs
+            if (wave == 0) {
+              uint32_t off = static_cast<uint32_t>(L.sc[SC_DSCAN]), found = 0, stop = off;
+              const uint32_t need = static_cast<uint32_t>(total);
+              for (; off < dlen_all && found < need; off += 64) {   // wave-uniform
+                const uint32_t i = off + lane;
+                uint32_t pos = dhead0 + i;
+                if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
+                const uint32_t dl = i < dlen_all ? ddl[pos] : 0u;
+                const bool live = i < dlen_all && dl > s;
+                const uint64_t bal = __ballot(live);
+                const uint32_t rk = found + static_cast<uint32_t>(__popcll(bal & lanes_below()));
+                const bool mine = live && rk < need;
+                if (mine) {
+                  const uint64_t jw = dring[pos];
+                  L.jobs[rk] = jw;
+                  if (dl != kNever)
+                    atomicSub(&dcal[static_cast<size_t>((jw >> 29) & 7u) * cal_n + (dl & p.cal_mask)], 1u);
+                }
+                const uint64_t last = __ballot(mine && rk + 1 == need);
+                if (last) stop = off + static_cast<uint32_t>(__ffsll(static_cast<long long>(last)));   // one past the last staged entry
+                found += static_cast<uint32_t>(__popcll(bal));
+              }
+              if (lane == 0) L.sc[SC_DSCAN] = static_cast<int32_t>(found >= need ? stop : dlen_all);   // (found < need: see the gate's scan)
+            }
+          } else {
           for (int j = tid; j < nstage; j += NT) {
             uint32_t pos = dhead0 + static_cast<uint32_t>(next + j);
             if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
             if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
             L.jobs[j] = dring[pos];
+          }
           }
           // counts -> exclusive prefix over the words; the last waves take this
           for (int t = nwaves - 1 - wave; t < nl; t += nwaves) {
@@ -1175,8 +1397,22 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
         // ---------------- segment C ----------------
         if (gate_on && tid < K) {   // class counters follow the admissions of this pass
           const int k = tid, adm_k = L.sc[SC_ADMK + k];
+          // ring entries the head moves past: the admitted requests; with abandonment also the dead entries
+          // before the last of them (before the first waiting request when none was admitted)
+          uint32_t past = static_cast<uint32_t>(adm_k);
+          if constexpr (AB) {
+            past = adm_k ? L.live_off[k * kAdmChunk + adm_k - 1] + 1u : (L.sc[SC_LEAD + k] ? L.live_off[k * kAdmChunk] : 0u);
+            if (past) {
+              L.sc[SC_QLEN + k] -= static_cast<int32_t>(past);
+              if (!adm_k) {
+                uint32_t h = static_cast<uint32_t>(L.cs[CS_QHEAD + k]) + past;
+                if (h >= p.queue_cap) h -= p.queue_cap;
+                L.cs[CS_QHEAD + k] = static_cast<int32_t>(h);
+              }
+            }
+          }
           if (adm_k) {
-            uint32_t h = static_cast<uint32_t>(L.cs[CS_QHEAD + k]) + static_cast<uint32_t>(adm_k);
+            uint32_t h = static_cast<uint32_t>(L.cs[CS_QHEAD + k]) + past;
             if (h >= p.queue_cap) h -= p.queue_cap;
             L.cs[CS_QHEAD + k] = static_cast<int32_t>(h);
             L.cs[CS_QP + k] -= adm_k;
@@ -1185,7 +1421,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
             L.sc[SC_ADMK + k] = 0;
           }
         }
-        if (route_on) {
+        if (route_on && !route_wait) {
           int take_r[kRouteLevels], w_r[kRouteLevels];
 #pragma unroll
           for (int t = 0; t < kRouteLevels; ++t) {
@@ -1282,11 +1518,23 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
         __syncthreads();
         PROF(17)
       }
+      if constexpr (AB) {
+        if (tid == 0) {   // the head moves past everything the routing passes walked over
+          const uint32_t past = static_cast<uint32_t>(L.sc[SC_DSCAN]);
+          uint32_t h = dhead0 + past;
+          if (h >= p.dbuf_cap) h -= p.dbuf_cap;
+          L.cs[CS_DHEAD] = static_cast<int32_t>(h);
+          L.cs[CS_DCOUNT] -= next;
+          L.sc[SC_DLEN] = static_cast<int32_t>(dlen_all - past);
+          L.sc[SC_COMPACT] = 0;
+        }
+      } else {
       if (tid == 0 && next > 0) {
         uint32_t h = dhead0 + static_cast<uint32_t>(next);
         if (h >= p.dbuf_cap) h -= p.dbuf_cap;
         L.cs[CS_DHEAD] = static_cast<int32_t>(h);
         L.cs[CS_DCOUNT] -= next;
+      }
       }
     }
 
@@ -1303,6 +1551,12 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
   }
   PROF_FLUSH
   __syncthreads();
+  if constexpr (AB) {   // the rings leave the launch without dead entries
+    const uint32_t s_last = step_begin + n_steps - 1u;
+    for (int k = wave; k < K; k += nwaves) compact_queue(k, s_last, 0u);
+    if (wave == nwaves - 1) compact_buffer(s_last);
+    __syncthreads();
+  }
 
   // ---- the emitted-token tally is the total of the time-between-tokens counts of this launch
   if (tid < K) {
@@ -1361,6 +1615,8 @@ __global__ void gnr_reset_kernel(const Params p, const int reps)
   for (size_t i = t0; i < static_cast<size_t>(reps) * CS_WORDS; i += stride) p.cstate[i] = 0;
   for (size_t i = t0; i < static_cast<size_t>(reps) * kTallyWords; i += stride) p.tally[i] = 0;
   for (size_t i = t0; i < static_cast<size_t>(reps) * 3 * p.K * kNBin; i += stride) p.hist[i] = 0;
+  if (p.ab_classes)
+    for (size_t i = t0; i < static_cast<size_t>(reps) * p.K * (p.cal_mask + 1u); i += stride) { p.cal[i] = 0; p.dcal[i] = 0; }
 }
 
 // ------------------------------------------------------------------ reduce ----
@@ -1415,19 +1671,25 @@ __global__ void gnr_digest_kernel(const Params p)
   for (int k = 0; k < K; ++k) {
     const uint32_t head = static_cast<uint32_t>(cs[CS_QHEAD + k]), len = static_cast<uint32_t>(cs[CS_QP + k]);
     const uint32_t *ring = p.qring + (static_cast<size_t>(r) * K + k) * p.queue_cap;
+    const uint32_t *dlr = p.ab_classes ? p.qdl + (static_cast<size_t>(r) * K + k) * p.queue_cap : nullptr;
     for (uint32_t i = tid; i < len; i += NT) {
       uint32_t pos = head + i;
       if (pos >= p.queue_cap) pos -= p.queue_cap;
-      d += chain(chain(chain(2, static_cast<uint64_t>(k)), i), ring[pos]);
+      uint64_t h = chain(chain(chain(2, static_cast<uint64_t>(k)), i), ring[pos]);
+      if (dlr) h = chain(h, dlr[pos]);   // with abandonment the deadline is part of the state
+      d += h;
     }
   }
   {
     const uint32_t head = static_cast<uint32_t>(cs[CS_DHEAD]), len = static_cast<uint32_t>(cs[CS_DCOUNT]);
     const uint64_t *ring = p.dring + static_cast<size_t>(r) * p.dbuf_cap;
+    const uint32_t *dlr = p.ab_classes ? p.ddl + static_cast<size_t>(r) * p.dbuf_cap : nullptr;
     for (uint32_t i = tid; i < len; i += NT) {
       uint32_t pos = head + i;
       if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
-      d += chain(chain(3, i), ring[pos]);
+      uint64_t h = chain(chain(3, i), ring[pos]);
+      if (dlr) h = chain(h, dlr[pos]);
+      d += h;
     }
   }
   for (int g = tid; g < N; g += NT) {
@@ -1465,14 +1727,17 @@ int launch_reset(const Params &p, int reps, void *stream)
 int launch_steps(const Params &p, int reps, int threads, size_t lds_bytes, uint32_t step_begin, uint32_t n_steps,
                  void *stream)
 {
-  auto kernel = threads > 768 ? gnr_step_kernel<1024> : threads > 512 ? gnr_step_kernel<768> : gnr_step_kernel<512>;
+  auto kernel = p.ab_classes
+                    ? (threads > 768 ? gnr_step_kernel<1024, true> : threads > 512 ? gnr_step_kernel<768, true> : gnr_step_kernel<512, true>)
+                    : (threads > 768 ? gnr_step_kernel<1024, false> : threads > 512 ? gnr_step_kernel<768, false> : gnr_step_kernel<512, false>);
   if (lds_bytes > 64 * 1024) {   // more than the default dynamic LDS limit has to be asked for
     const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes));
     if (e != hipSuccess) return SIM_EHIP;
   }
   const StepArrays a = {p.arr_thr, p.len_tab, p.t_next, p.iter, p.remptok, p.pf_job, p.n_cls, p.n_join,
-                        p.fin,     p.job,     p.qring,  p.dring, p.cstate, p.tally,  p.hist};
+                        p.fin,     p.job,     p.qring,  p.dring, p.cstate, p.tally,  p.hist,
+                        p.pat_tab, p.qdl,     p.ddl,    p.cal,   p.dcal};
   hipLaunchKernelGGL(kernel, dim3(reps), dim3(threads), lds_bytes, static_cast<hipStream_t>(stream), p.self, a, p.key0,
                      p.key1, step_begin, n_steps);
   return hip_ok(hipGetLastError());

@@ -6,6 +6,8 @@
 //  * length table: entry j = min{k in [1,32768] : F(k) >= (j+0.5)/65536}, with
 //      geometric  F(k) = -expm1(k*log1p(-1/mean))      (Pr(X>=k) = (1-p)^(k-1), paper EC, geometric check)
 //      lognormal  F(k) = erfc(-z/sqrt2)/2, z = (log(k+0.5)-log(median))/sigma  (rounded to nearest, clamped)
+//  * patience table (abandonment): the geometric length table with mean 1/(1 - e^(-theta*dt)), the mean computed
+//      as 1.0 / -expm1(-theta*dt): Pr(patience >= m steps) = e^(-theta*dt*(m-1))
 //  * arrival thresholds for a per-server, per-step mean m = Lambda*dt*(1+amp*sin(2*pi*row/period)):
 //      t0 = q(e^-m), t1 = q(e^-m + m e^-m), t2 = q((e^-m + m e^-m) + m^2 e^-m/2), q(p) = floor(p*2^32)
 //      clamped to [0, 2^32-1]; the count is the number of thresholds the random word reaches.
@@ -82,6 +84,12 @@ int build_length_table(int law, double p0, double p1, const uint16_t *user, uint
     default:
       return SIM_EINVAL;
   }
+}
+
+int build_patience_table(double theta, double dt_seconds, uint16_t *out)
+{
+  if (!(theta > 0.0) || !(dt_seconds > 0.0) || !std::isfinite(theta)) return SIM_EINVAL;
+  return build_length_table(SIM_GEOMETRIC, 1.0 / -std::expm1(-theta * dt_seconds), 0.0, nullptr, out);
 }
 
 double total_rate(const sim_class *cls, int K)

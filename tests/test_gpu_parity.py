@@ -137,6 +137,19 @@ def test_more_admissions_and_placements_than_one_pass_stages(B, oracle_mod):
     assert t[:, ti["U_P"]].sum() / 40 > 300 and (t[:, ti["U_DM"]].sum() + t[:, ti["U_DS"]].sum()) / 40 > 280
 
 
+def test_placements_on_mixed_servers_wait_for_the_last_gate_pass(B, oracle_mod):
+    """More idle prefill slots than one gate pass serves (256) while the solo group is full, so that jobs go to
+    mixed-group servers in the same steps: such a placement counts as mixed or solo decode by what the whole
+    gate of the step admitted, not by what its first pass did."""
+    cls = [_limits_class(lam=2.5, out_p0=300.0), _limits_class(lam=2.0, in_p0=40.0, out_p0=500.0)]
+    cfg = _limits_cfg("late-passes", cls, N=8192, M=300, B=2, steps=300, replications=1, dbuf_cap=2048, queue_cap=8192)
+    sim, orc = run_both(B, oracle_mod, cfg, 300, checkpoints=3)
+    t, _ = orc.tallies(0)
+    from paper_2602_02987_amd.binding import TALLY
+    ti = {n: i for i, n in enumerate(TALLY)}
+    assert t[:, ti["U_DM"]].sum() > 100 and t[:, ti["U_DS"]].sum() > 10000
+
+
 def test_jobs_spread_over_many_load_levels(B, oracle_mod):
     """Three solo servers with unequal loads take several jobs per step: more load levels than one routing
     pass fills (4), then the mixed group once the solo group is full."""

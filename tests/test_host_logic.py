@@ -24,7 +24,8 @@ def test_library_exports_every_declared_symbol(B):
     header = open(os.path.join(ROOT, "include", "gnr_sim.h")).read()
     names = set(re.findall(r"^(?:int|const char \*)\s*\*?(sim_[a-z_]+)\(", header, flags=re.M))
     assert {"sim_workspace_bytes", "sim_create", "sim_run", "sim_stats", "sim_snapshot", "sim_destroy",
-            "sim_strerror", "sim_tallies", "sim_hist", "sim_digest", "sim_kernel_time", "sim_set_targets"} <= names
+            "sim_strerror", "sim_tallies", "sim_hist", "sim_digest", "sim_kernel_time", "sim_set_targets",
+            "sim_patience_table"} <= names
     L = B.lib()
     for n in names:
         assert hasattr(L, n), n
@@ -39,6 +40,8 @@ def test_tables_match_the_oracle(B, oracle_mod):
     for law, p0, p1 in [(0, 512.0, 0.0), (0, 64.0, 0.0), (0, 1.0, 0.0), (1, 256.0, 0.8), (1, 4096.0, 1.0),
                         (1, 8192.0, 1.0), (2, 600.0, 0.0)]:
         assert np.array_equal(B.sim_length_table(law, p0, p1), oracle_mod.length_table(law, p0, p1)), (law, p0, p1)
+    for theta, dt in [(0.1, 0.010), (0.1, 10000000 * 1e-9), (5.0, 0.010), (40.0, 0.010), (2.0, 0.004), (1e-3, 0.010)]:
+        assert np.array_equal(B.sim_patience_table(theta, dt), oracle_mod.patience_table(theta, dt)), (theta, dt)
     rng = np.random.default_rng(11)
     for _ in range(50):
         seed = int(rng.integers(0, 2**63)); c = [int(v) for v in rng.integers(0, 2**32, 4)]
@@ -61,13 +64,24 @@ def test_invalid_configurations_are_rejected(B):
            replace(good, queue_cap=0), replace(good, dbuf_cap=0), replace(good, gate_mode=7), replace(good, route_mode=1),
            replace(good, x_star=[-0.1, 0.1]), replace(good, mod_amp=2.0)]
     heavy = W.config(1); heavy.classes[0].lam = 6.0
-    theta = W.config(1); theta.classes[1].theta = 0.1
+    theta = W.config(1); theta.classes[1].theta = -0.1
     for cfg in bad + [heavy, theta]:
         with pytest.raises(B.SimError) as e:
             B.sim_workspace_bytes(cfg, 16)
         assert e.value.code == -1
     with pytest.raises(B.SimError):
         B.sim_workspace_bytes(good, 0)
+
+
+def test_patience_adds_deadline_rings_and_calendars_to_the_workspace(B):
+    cfg = W.config(2)
+    plain = B.sim_workspace_bytes(cfg, 4)
+    cfg.classes[1].theta = 0.1          # longest patience 11783 steps -> calendars of 16384 entries
+    longest = int(B.sim_patience_table(0.1, cfg.c0)[-1])
+    assert 8192 < longest < 16384
+    extra = B.sim_workspace_bytes(cfg, 4) - plain
+    want = 4 * (cfg.K * cfg.queue_cap * 4 + cfg.dbuf_cap * 4 + 2 * cfg.K * 16384 * 4) + cfg.K * 65536 * 2
+    assert want <= extra <= want + 8 * 256
 
 
 def test_workspace_size_scales_with_replications(B):
