@@ -64,11 +64,13 @@ def measured_traffic():
 
 
 def _oracle_worker(args):
-    n, N, rep, steps = args
+    n, N, rep, steps, theta = args
     sys.path.insert(0, ROOT)
     from oracle import binding as ob
     from paper_2602_02987_amd import workloads as W
     cfg = W.config(n, N=N)
+    for c in cfg.classes:
+        c.theta = theta or c.theta
     o = ob.Oracle(cfg, max_reps=cfg.replications)
     o.select([rep])
     t = time.perf_counter()
@@ -76,7 +78,7 @@ def _oracle_worker(args):
     return time.perf_counter() - t
 
 
-def cpu_baseline(n, N, steps):
+def cpu_baseline(n, N, steps, theta=0.0):
     """The oracle as it stands, one replication per host process, on a bounded sample."""
     import multiprocessing as mp
     from oracle import binding as ob
@@ -84,7 +86,7 @@ def cpu_baseline(n, N, steps):
     cores = min(16, os.cpu_count() or 1)
     t = time.perf_counter()
     with mp.get_context("spawn").Pool(cores) as pool:
-        pool.map(_oracle_worker, [(n, N, r, steps) for r in range(cores)])
+        pool.map(_oracle_worker, [(n, N, r, steps, theta) for r in range(cores)])
     wall = time.perf_counter() - t
     return dict(value=cores * N * steps / wall, unit="server-steps/s", cores=cores, kind="oracle",
                 sample=f"replications 0..{cores - 1} of the workload, first {steps} steps from the empty system, "
@@ -101,6 +103,8 @@ def main():
     ap.add_argument("--config", type=int, default=5)
     ap.add_argument("--servers", type=int, default=0, help="override N (0 = the configuration's own)")
     ap.add_argument("--replications", type=int, default=0)
+    ap.add_argument("--theta", type=float, default=0.0,
+                    help="patience rate given to every class (abandonment; 0 = the configuration's own, none)")
     ap.add_argument("--oracle-steps", type=int, default=1500, help="0 skips the CPU baseline")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run one device-to-device copy of this size before the timed region "
@@ -116,7 +120,7 @@ def main():
     base = None
     if args.oracle_steps > 0:
         n_servers = args.servers if args.servers else W.config(args.config).N
-        base = cpu_baseline(args.config, n_servers, args.oracle_steps)
+        base = cpu_baseline(args.config, n_servers, args.oracle_steps, args.theta)
 
     import torch
     from paper_2602_02987_amd import binding
@@ -126,6 +130,9 @@ def main():
     if args.replications:
         over["replications"] = args.replications
     cfg = W.config(args.config, **over)
+    if args.theta:
+        for c in cfg.classes:
+            c.theta = args.theta
     slots_per_step = cfg.N * cfg.replications * args.sim_steps
 
     sim = binding.Sim(cfg)
@@ -169,7 +176,8 @@ def main():
         "ms_per_step": wall * 1e3 / args.steps,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int64", "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: K={cfg.K} N={cfg.N} R={cfg.replications} B={cfg.B} C={cfg.C} M={cfg.M}, "
+        "config": {"workload": f"{cfg.name}: K={cfg.K} N={cfg.N} R={cfg.replications} B={cfg.B} C={cfg.C} M={cfg.M}"
+                               + (f" theta={args.theta}" if args.theta else "") + ", "
                                f"{args.sim_steps} simulation steps per bench step after {args.preload + args.warmup * args.sim_steps} untimed steps",
                    "server_step_slots_per_bench_step": slots_per_step,
                    "executed_iterations_per_s": iters / wall,
