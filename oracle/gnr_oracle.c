@@ -52,6 +52,7 @@
 
 enum { LAW_GEOMETRIC = 0, LAW_LOGNORMAL = 1, LAW_CONST = 2, LAW_TABLE = 3 };
 enum { GATE_OCCUPANCY = 0, GATE_PRIORITY = 1, GATE_FCFS = 2 };
+enum { ROUTE_SOLO_FIRST = 0, ROUTE_RANDOM_SPLIT = 1 };
 
 /* per-class tally indices */
 enum {
@@ -84,6 +85,7 @@ typedef struct {
   double mod_amp;
   int64_t mod_period;
   int64_t queue_cap, dbuf_cap;
+  const double *p_solo;       /* ROUTE_RANDOM_SPLIT: probability p_s,i that a class-i decode is sent to the solo group */
 } oracle_config;
 
 typedef struct { int used; uint32_t fin; int cls, P, D; uint32_t stamp; } slot_t;
@@ -112,7 +114,8 @@ typedef struct {
   int inited;
   int64_t Qp[MAXK], X[MAXK], Qd[MAXK], Ym[MAXK], Ys[MAXK];
   fifoq q[MAXK];
-  fifojob dbuf;
+  fifojob dbuf;              /* decode buffer; under ROUTE_RANDOM_SPLIT the solo component */
+  fifojob dbuf_m;            /* ROUTE_RANDOM_SPLIT: the mixed component */
   server_t *sv;
   uint64_t tally[MAXK][NTALLY];
   uint64_t glob[NGLOBAL];
@@ -122,7 +125,8 @@ typedef struct {
 typedef struct oracle_t {
   oracle_config cfg;
   oracle_class cls[MAXK];
-  double x_star[MAXK], qp_star[MAXK];
+  double x_star[MAXK], qp_star[MAXK], p_solo[MAXK];
+  uint32_t solo_thr[MAXK];   /* a decode goes to the solo group when its random word is below this */
   int64_t c0_ns, cpre_ns, cdec_ns, dt_ns;
   double nx[MAXK], invx[MAXK], nq[MAXK];
   uint32_t *arr_thr;      /* [rows][3] */
@@ -314,7 +318,15 @@ int oracle_create(const oracle_config *cfg, int max_reps, oracle_t **out)
     if (!(cfg->cls[k].theta >= 0.0) || !isfinite(cfg->cls[k].theta) || !(cfg->cls[k].lambda >= 0.0) ||
         cfg->x_star[k] < 0.0) { free(o); return -1; }
   }
-  o->cfg.cls = o->cls; o->cfg.x_star = o->x_star; o->cfg.qp_star = o->qp_star;
+  if (cfg->route_mode != ROUTE_SOLO_FIRST && cfg->route_mode != ROUTE_RANDOM_SPLIT) { free(o); return -1; }
+  if (cfg->route_mode == ROUTE_RANDOM_SPLIT) {
+    if (!cfg->p_solo) { free(o); return -1; }
+    for (int k = 0; k < cfg->K; k++) {
+      if (!(cfg->p_solo[k] >= 0.0) || !(cfg->p_solo[k] <= 1.0)) { free(o); return -1; }
+      o->p_solo[k] = cfg->p_solo[k];
+    }
+  }
+  o->cfg.cls = o->cls; o->cfg.x_star = o->x_star; o->cfg.qp_star = o->qp_star; o->cfg.p_solo = o->p_solo;
   o->c0_ns = llround(cfg->c0 * 1e9);
   o->cpre_ns = llround(cfg->c_pre * 1e9);
   o->cdec_ns = llround(cfg->c_dec * 1e9);
@@ -327,6 +339,7 @@ int oracle_create(const oracle_config *cfg, int max_reps, oracle_t **out)
     o->invx[k] = o->x_star[k] > 0.0 ? 1.0 / o->x_star[k] : 0.0;
     o->nq[k] = (double)cfg->N * o->qp_star[k];
   }
+  for (int k = 0; k < cfg->K; k++) o->solo_thr[k] = thr32(o->p_solo[k]);
   o->rows = cfg->mod_period > 0 ? cfg->mod_period : 1;
   o->arr_thr = malloc((size_t)o->rows * 3 * sizeof(uint32_t));
   for (int64_t j = 0; j < o->rows; j++) arrival_row(o, j, o->arr_thr + 3 * j);
@@ -366,7 +379,7 @@ int oracle_create(const oracle_config *cfg, int max_reps, oracle_t **out)
 static void rep_free(rep_t *R)
 {
   for (int k = 0; k < MAXK; k++) free(R->q[k].v);
-  free(R->dbuf.v); free(R->sv); free(R->hist);
+  free(R->dbuf.v); free(R->dbuf_m.v); free(R->sv); free(R->hist);
   memset(R, 0, sizeof *R);
 }
 
@@ -451,11 +464,13 @@ static int64_t check_rep(oracle_t *o, int r)
     if (busy && s->t_next <= (int64_t)o->steps_done * o->dt_ns) viol(o, 112);
   }
   for (int64_t i = 0; i < R->dbuf.len; i++) Qd[R->dbuf.v[R->dbuf.head + i].cls]++;
+  for (int64_t i = 0; i < R->dbuf_m.len; i++) Qd[R->dbuf_m.v[R->dbuf_m.head + i].cls]++;
+  if (o->cfg.route_mode == ROUTE_SOLO_FIRST && R->dbuf_m.len) viol(o, 124);
   /* capacity constraints */
   if (Xtot > N) viol(o, 120);
   if (Ymtot > (int64_t)(B - 1) * Xtot) viol(o, 121);
   if (Ystot > (int64_t)B * (N - Xtot)) viol(o, 122);
-  if (R->dbuf.len > o->cfg.dbuf_cap) viol(o, 123);
+  if (R->dbuf.len > o->cfg.dbuf_cap || R->dbuf_m.len > o->cfg.dbuf_cap) viol(o, 123);
   for (int k = 0; k < K; k++) {
     uint64_t *t = R->tally[k];
     if (X[k] != R->X[k]) viol(o, 130);
@@ -484,6 +499,8 @@ static int64_t check_rep(oracle_t *o, int r)
   }
   for (int64_t i = 0; i < R->dbuf.len; i++)
     if ((uint64_t)R->dbuf.v[R->dbuf.head + i].dl < (uint64_t)o->steps_done) viol(o, 156);
+  for (int64_t i = 0; i < R->dbuf_m.len; i++)
+    if ((uint64_t)R->dbuf_m.v[R->dbuf_m.head + i].dl < (uint64_t)o->steps_done) viol(o, 156);
   return o->violations - before;
 }
 
@@ -521,14 +538,16 @@ static void step_rep(oracle_t *o, int r, uint32_t s)
       }
       f->len = w;
     }
-    fifojob *d = &R->dbuf;
-    int64_t w = 0;
-    for (int64_t i = 0; i < d->len; i++) {
-      job_t e = d->v[d->head + i];
-      if (e.dl <= s) { R->Qd[e.cls]--; R->tally[e.cls][T_AB_D]++; }
-      else d->v[d->head + w++] = e;
+    for (int b = 0; b < 2; b++) {
+      fifojob *d = b ? &R->dbuf_m : &R->dbuf;
+      int64_t w = 0;
+      for (int64_t i = 0; i < d->len; i++) {
+        job_t e = d->v[d->head + i];
+        if (e.dl <= s) { R->Qd[e.cls]--; R->tally[e.cls][T_AB_D]++; }
+        else d->v[d->head + w++] = e;
+      }
+      d->len = w;
     }
-    d->len = w;
   }
 
   /* 1. arrivals: one block per server, word 0 -> count, words 1.. -> classes */
@@ -608,11 +627,18 @@ static void step_rep(oracle_t *o, int r, uint32_t s)
           R->tally[i][T_M_MS] += (uint64_t)sv->n_cls[i];
           R->Ym[i] -= sv->n_cls[i]; R->Ys[i] += sv->n_cls[i];
         }
-        if (R->dbuf.len < o->cfg.dbuf_cap) {
-          /* patience for the wait in the decode buffer: block (step, stream 10, server, replication) */
+        /* block (step, stream 10, server, replication): word 0 -> patience for the wait in the decode
+         * buffer; word 1 -> under the randomized router (Sec. 5.2), the group the decode is sent to:
+         * solo with probability p_s,i, else mixed, each with its own FIFO buffer */
+        fifojob *buf = &R->dbuf;
+        if (o->cfg.route_mode == ROUTE_RANDOM_SPLIT) {
+          draw(o, r, g, s, 10u, w);
+          if (!(w[1] < o->solo_thr[k])) buf = &R->dbuf_m;
+        }
+        if (buf->len < o->cfg.dbuf_cap) {
           job_t jb = { k, sv->pf_P, sv->pf_D, sv->pf_stamp, DL_NEVER };
           if (o->tab_pat[k]) { draw(o, r, g, s, 10u, w); jb.dl = s + o->tab_pat[k][w[0] >> 16]; }
-          fj_push(&R->dbuf, jb); R->Qd[k]++;
+          fj_push(buf, jb); R->Qd[k]++;
         } else { R->tally[k][T_DROP_D]++; R->glob[G_OVERFLOW] = 1; }
       }
     }
@@ -658,13 +684,21 @@ static void step_rep(oracle_t *o, int r, uint32_t s)
 
   /* 4. decode routing: buffer in FIFO order; solo group first, then mixed group;
    *    least-loaded feasible server, ties to the lowest index */
-  while (R->dbuf.len > 0) {
+  /*    Under the randomized router each component of the buffer feeds its own group only: first the
+   *    solo component to the solo group, then the mixed component to the mixed group (the two do not
+   *    interact); within the group the same least-loaded rule. */
+  for (int pass = 0; pass < 2; pass++) {
+  const int split = o->cfg.route_mode == ROUTE_RANDOM_SPLIT;
+  fifojob *buf = (split && pass == 1) ? &R->dbuf_m : &R->dbuf;
+  if (!split && pass == 1) break;
+  while (buf->len > 0) {
     int dst = -1, bl = 0;
-    for (int g = M; g < N; g++) { int l = R->sv[g].n_dec; if (l < B && (dst < 0 || l < bl)) { dst = g; bl = l; } }
-    if (dst < 0)
+    if (!split || pass == 0)
+      for (int g = M; g < N; g++) { int l = R->sv[g].n_dec; if (l < B && (dst < 0 || l < bl)) { dst = g; bl = l; } }
+    if (dst < 0 && (!split || pass == 1))
       for (int g = 0; g < M; g++) { int l = R->sv[g].n_dec; if (l < B - 1 && (dst < 0 || l < bl)) { dst = g; bl = l; } }
     if (dst < 0) break;
-    job_t jb = fj_pop(&R->dbuf);
+    job_t jb = fj_pop(buf);
     server_t *sv = &R->sv[dst];
     R->Qd[jb.cls]--;
     int j = 0; while (sv->slot[j].used) j++;
@@ -676,6 +710,7 @@ static void step_rep(oracle_t *o, int r, uint32_t s)
     if (mid) sv->n_join[jb.cls]++;
     if (sv->pf_rem > 0) { R->tally[jb.cls][T_U_DM]++; R->Ym[jb.cls]++; }
     else { R->tally[jb.cls][T_U_DS]++; R->Ys[jb.cls]++; }
+  }
   }
 
   /* 5. (re)start: servers at an iteration boundary, and idle servers that got work */
@@ -804,10 +839,11 @@ int oracle_get_slots(oracle_t *o, int r, uint32_t *fin, uint64_t *job, int32_t *
 int oracle_get_queue(oracle_t *o, int r, int k, uint64_t *out, int64_t cap, int64_t *len)
 {
   rep_t *R = getrep(o, r); if (!R) return -1;
-  if (k < 0) {
-    *len = R->dbuf.len;
-    for (int64_t i = 0; i < R->dbuf.len && i < cap; i++) {
-      job_t *j = &R->dbuf.v[R->dbuf.head + i];
+  if (k < 0) {   /* -1: decode buffer (solo component), -2: mixed component */
+    fifojob *b = k == -2 ? &R->dbuf_m : &R->dbuf;
+    *len = b->len;
+    for (int64_t i = 0; i < b->len && i < cap; i++) {
+      job_t *j = &b->v[b->head + i];
       out[i] = jobword(j->cls, j->P, j->D, j->stamp);
     }
   } else {
@@ -823,8 +859,9 @@ int oracle_get_queue_deadlines(oracle_t *o, int r, int k, uint64_t *out, int64_t
 {
   rep_t *R = getrep(o, r); if (!R) return -1;
   if (k < 0) {
-    *len = R->dbuf.len;
-    for (int64_t i = 0; i < R->dbuf.len && i < cap; i++) out[i] = R->dbuf.v[R->dbuf.head + i].dl;
+    fifojob *b = k == -2 ? &R->dbuf_m : &R->dbuf;
+    *len = b->len;
+    for (int64_t i = 0; i < b->len && i < cap; i++) out[i] = b->v[b->head + i].dl;
   } else {
     if (k >= o->cfg.K) return -1;
     *len = R->q[k].len;
@@ -898,6 +935,12 @@ int oracle_digest(oracle_t *o, int r, uint64_t *out)
   for (int64_t i = 0; i < R->dbuf.len; i++) {
     job_t *j = &R->dbuf.v[R->dbuf.head + i];
     uint64_t h2 = chain(chain(3, (uint64_t)i), jobword(j->cls, j->P, j->D, j->stamp));
+    if (o->any_theta) h2 = chain(h2, j->dl);
+    d += h2;
+  }
+  for (int64_t i = 0; i < R->dbuf_m.len; i++) {
+    job_t *j = &R->dbuf_m.v[R->dbuf_m.head + i];
+    uint64_t h2 = chain(chain(6, (uint64_t)i), jobword(j->cls, j->P, j->D, j->stamp));
     if (o->any_theta) h2 = chain(h2, j->dl);
     d += h2;
   }

@@ -33,7 +33,8 @@ class SimConfigC(C.Structure):
                 ("c0", C.c_double), ("c_pre", C.c_double), ("c_dec", C.c_double), ("dt", C.c_double),
                 ("cls", C.c_void_p), ("M", C.c_int), ("x_star", C.c_void_p), ("qp_star", C.c_void_p),
                 ("gate_mode", C.c_int), ("route_mode", C.c_int), ("mod_amp", C.c_double),
-                ("mod_period", C.c_int64), ("queue_cap", C.c_int64), ("dbuf_cap", C.c_int64)]
+                ("mod_period", C.c_int64), ("queue_cap", C.c_int64), ("dbuf_cap", C.c_int64),
+                ("p_solo", C.c_void_p)]
 
 
 _D8 = C.c_double * MAXK
@@ -130,11 +131,13 @@ def marshal_config(cfg):
         cls[i].theta = c.theta
     xs = (C.c_double * K)(*cfg.x_star)
     qs = (C.c_double * K)(*cfg.qp_star)
+    ps = (C.c_double * K)(*(list(getattr(cfg, "p_solo", [])) or [1.0] * K))
     cc = SimConfigC(K=K, N=cfg.N, B=cfg.B, C=cfg.C, c0=cfg.c0, c_pre=cfg.c_pre, c_dec=cfg.c_dec, dt=cfg.dt,
                     cls=C.addressof(cls), M=cfg.M, x_star=C.addressof(xs), qp_star=C.addressof(qs),
                     gate_mode=cfg.gate_mode, route_mode=cfg.route_mode, mod_amp=cfg.mod_amp,
-                    mod_period=cfg.mod_period, queue_cap=cfg.queue_cap, dbuf_cap=cfg.dbuf_cap)
-    keep += [cls, xs, qs]
+                    mod_period=cfg.mod_period, queue_cap=cfg.queue_cap, dbuf_cap=cfg.dbuf_cap,
+                    p_solo=C.addressof(ps))
+    keep += [cls, xs, qs, ps]
     return cc, keep
 
 

@@ -139,6 +139,14 @@ def solve_lp(cfg, lam, objective="bundled", tbt_mixed_share=None, served_floor=N
                 tau_mix=r["tau_mix"], tau_solo=r["tau_solo"], EP=r["EP"], ED=r["ED"])
 
 
+def solo_probabilities(plan: Plan) -> np.ndarray:
+    """p_s,i = mu_s,i y_s,i* / (mu_m,i y_m,i* + mu_s,i y_s,i*), 1 where the denominator vanishes: the share of
+    class-i decode service the plan gives to solo servers (paper Sec. 5.2, randomized decode router)."""
+    a = plan.mu_s * plan.ys
+    b = plan.mu_m * plan.ym
+    return np.where(a + b > 0.0, a / np.where(a + b > 0.0, a + b, 1.0), 1.0)
+
+
 def capacity_scale(cfg, mix, tbt_mixed_share=None, **kw) -> float:
     """Largest s such that arrivals s*mix are served in full by the fluid LP (all classes at 100 %),
     under the optional per-class bound on the share of decode tokens emitted in mixed iterations."""

@@ -22,6 +22,7 @@ from . import plan as _plan
 
 LAW_GEOMETRIC, LAW_LOGNORMAL, LAW_CONST, LAW_TABLE = 0, 1, 2, 3
 GATE_OCCUPANCY, GATE_PRIORITY, GATE_FCFS = 0, 1, 2
+ROUTE_SOLO_FIRST, ROUTE_RANDOM_SPLIT = 0, 1
 
 
 @dataclass
@@ -67,6 +68,7 @@ class SimConfig:
     steps: int = 1000
     seed: int = 1
     notes: dict = field(default_factory=dict)
+    p_solo: List[float] = field(default_factory=list)   # ROUTE_RANDOM_SPLIT: Pr(a class-i decode goes to the solo group)
 
 
 def with_plan(cfg: SimConfig, lam_plan=None, objective="bundled", **kw) -> SimConfig:
@@ -87,6 +89,13 @@ def _two_class(lam=(0.6, 0.3), prices=(1.0, 1.0)):
                      price_in=prices[0], price_out=prices[1], priority=64.0 / 512.0),
             SimClass(lam=lam[1], in_law=LAW_GEOMETRIC, in_p0=128.0, out_law=LAW_GEOMETRIC, out_p0=256.0,
                      price_in=prices[0], price_out=prices[1], priority=256.0 / 128.0)]
+
+
+def with_random_split(cfg: SimConfig, lam_plan=None, **kw) -> SimConfig:
+    """The SLI-aware randomized decode router (paper Sec. 5.2) with solo probabilities from the plan."""
+    lam = [c.lam for c in cfg.classes] if lam_plan is None else lam_plan
+    p = _plan.solve_lp(cfg, lam, **kw)
+    return replace(cfg, route_mode=ROUTE_RANDOM_SPLIT, p_solo=[float(v) for v in _plan.solo_probabilities(p)])
 
 
 def _scaled_to_load(cfg: SimConfig, mix, rho: float, **kw) -> SimConfig:
