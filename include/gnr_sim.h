@@ -55,6 +55,14 @@ extern "C" {
 enum sim_err { SIM_OK = 0, SIM_EINVAL = -1, SIM_ENOMEM = -2, SIM_EHIP = -3, SIM_EOVERFLOW = -4 };
 enum sim_law { SIM_GEOMETRIC = 0, SIM_LOGNORMAL = 1, SIM_CONST = 2, SIM_TABLE = 3 };
 enum sim_gate { SIM_GATE_OCCUPANCY = 0, SIM_GATE_PRIORITY = 1, SIM_GATE_FCFS = 2 };
+/* Decode routers. SOLO_FIRST: the router of Sec. 4 (one buffer; solo group first, then the mixed group).
+ * RANDOM_SPLIT: the SLI-aware randomized router of Sec. 5.2 (zero-buffer case): when the prefill of a class-i
+ * request completes it is sent to the solo group with probability p_s,i, else to the mixed group; each group
+ * has its own FIFO buffer (capacity dbuf_cap each) that feeds that group only; within the group the placement
+ * rule is the same as for SOLO_FIRST (least-loaded feasible server, lowest index). The draw is word 1 of block
+ * (step, stream 10, server of the prefill, replication): solo iff word < floor(p_s,i * 2^32) (clamped to
+ * 2^32 - 1, so p_s,i = 1 sends one request in 2^32 to the mixed group). */
+enum sim_route { SIM_ROUTE_SOLO_FIRST = 0, SIM_ROUTE_RANDOM_SPLIT = 1 };
 
 /* Per-class cumulative tallies (uint64), in this order. Counting processes as in Sec. 2.3:
  * A arrivals, U_P admissions to prefill, S_P prefill completions, U_DM/U_DS admissions to a
@@ -101,10 +109,11 @@ typedef struct {
   const double *x_star;          /* K prefill-occupancy targets per server; 0 = never admit (occupancy gate) */
   const double *qp_star;         /* K prefill-queue targets per server (gate tie-break) */
   int gate_mode;                 /* enum sim_gate */
-  int route_mode;                /* 0: solo-first, least-loaded, lowest index */
+  int route_mode;                /* enum sim_route; RANDOM_SPLIT needs every theta = 0 in this version */
   double mod_amp;                /* arrival modulation lambda(s) = lambda*(1 + amp*sin(2*pi*(s mod period)/period)) */
   int64_t mod_period;            /* in steps; 0 = homogeneous */
   int64_t queue_cap, dbuf_cap;   /* ring capacities: per class prefill queue, decode buffer */
+  const double *p_solo;          /* RANDOM_SPLIT: K probabilities p_s,i in [0,1], copied; else unused, may be NULL */
 } sim_config;
 
 /* Totals over replications plus derived fp64 figures (rates per server per unit time). */
@@ -145,6 +154,7 @@ typedef struct {
   uint64_t *dbuf; int64_t dbuf_len;                        /* decode buffer requests, head first; capacity dbuf_cap */
   uint64_t *queue_dl[SIM_MAXK];  /* per queue entry: the step at whose start it abandons if still waiting (2^32-1: never) */
   uint64_t *dbuf_dl;             /* the same for the decode buffer entries */
+  uint64_t *dbuf_m; int64_t dbuf_m_len; /* RANDOM_SPLIT: the mixed group's buffer (`dbuf` is then the solo group's) */
 } sim_state_t;
 
 typedef struct sim_t sim_t;  /* opaque; owned by the library */
@@ -154,7 +164,8 @@ int sim_workspace_bytes(const sim_config *cfg, int max_replications, size_t *out
 
 /* Validates and deep-copies the config, builds the sampler tables on the host and uploads them
  * into `dev_workspace` (device pointer, 256-byte aligned, owned by the caller, must outlive the
- * handle). SIM_EINVAL: bad sizes, negative target, M outside [0,N], dt > c0, negative theta, total
+ * handle). SIM_EINVAL: bad sizes, negative target, M outside [0,N], dt > c0, negative theta, p_solo outside
+ * [0,1] or missing or combined with a positive theta under RANDOM_SPLIT, total
  * arrival mean per server-step above 0.05 (the per-step count is truncated at 3).
  * SIM_ENOMEM: workspace too small. The library never allocates device memory itself. */
 int sim_create(const sim_config *cfg, int max_replications, void *dev_workspace, size_t bytes, sim_t **out);

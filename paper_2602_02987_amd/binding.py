@@ -62,7 +62,8 @@ class SimStateC(C.Structure):
                 ("fin", C.c_void_p), ("job", C.c_void_p), ("n_dec", C.c_void_p),
                 ("queue", C.c_void_p * MAXK), ("queue_len", C.c_int64 * MAXK),
                 ("dbuf", C.c_void_p), ("dbuf_len", C.c_int64),
-                ("queue_dl", C.c_void_p * MAXK), ("dbuf_dl", C.c_void_p)]
+                ("queue_dl", C.c_void_p * MAXK), ("dbuf_dl", C.c_void_p),
+                ("dbuf_m", C.c_void_p), ("dbuf_m_len", C.c_int64)]
 
 
 _lib = None
@@ -279,6 +280,7 @@ class Sim:
         dbuf = np.zeros(cfg.dbuf_cap, np.uint64)
         queue_dl = [np.zeros(cfg.queue_cap, np.uint64) for _ in range(K)]
         dbuf_dl = np.zeros(cfg.dbuf_cap, np.uint64)
+        dbuf_m = np.zeros(cfg.dbuf_cap, np.uint64)
         st = SimStateC()
         for k, v in a.items():
             setattr(st, k, v.ctypes.data)
@@ -287,11 +289,13 @@ class Sim:
             st.queue_dl[k] = queue_dl[k].ctypes.data
         st.dbuf = dbuf.ctypes.data
         st.dbuf_dl = dbuf_dl.ctypes.data
+        st.dbuf_m = dbuf_m.ctypes.data
         _check(lib().sim_snapshot(self.h, int(r), C.byref(st), self._stream()), "sim_snapshot")
         a["queues"] = [queues[k][:st.queue_len[k]].copy() for k in range(K)]
         a["dbuf"] = dbuf[:st.dbuf_len].copy()
         a["queue_dl"] = [queue_dl[k][:st.queue_len[k]].copy() for k in range(K)]
         a["dbuf_dl"] = dbuf_dl[:st.dbuf_len].copy()
+        a["dbuf_m"] = dbuf_m[:st.dbuf_m_len].copy()
         cs = a.pop("class_state")
         a.update(Qp=cs[0], X=cs[1], Qd=cs[2], Ym=cs[3], Ys=cs[4])
         return a

@@ -13,7 +13,7 @@ using namespace gnr;
 struct sim_t {
   sim_config cfg;
   sim_class cls[kMaxK];
-  double x_star[kMaxK], qp_star[kMaxK];
+  double x_star[kMaxK], qp_star[kMaxK], p_solo[kMaxK];
   Params p;
   int max_reps;
   int reps;
@@ -40,7 +40,7 @@ constexpr uint32_t kStepsPerLaunch = 2048;
 
 struct Layout {
   size_t arr_thr, len_tab, t_next, iter, remptok, pf_job, n_cls, n_join, fin, job, qring, dring, cstate, tally, hist,
-      digest, reduced, params, pat_tab, qdl, ddl, cal, dcal, total;
+      digest, reduced, params, pat_tab, qdl, ddl, cal, dcal, dring_m, total;
 };
 
 bool any_patience(const sim_config &c)
@@ -85,6 +85,7 @@ Layout make_layout(const sim_config &c, int R, int64_t rows, size_t cal_entries)
     L.cal = take(static_cast<size_t>(R) * c.K * cal_entries * sizeof(uint32_t));
     L.dcal = take(static_cast<size_t>(R) * c.K * cal_entries * sizeof(uint32_t));
   }
+  if (c.route_mode == SIM_ROUTE_RANDOM_SPLIT) L.dring_m = take(static_cast<size_t>(R) * c.dbuf_cap * sizeof(uint64_t));
   L.total = off;
   return L;
 }
@@ -112,7 +113,13 @@ int validate(const sim_config *c, int max_reps, Ticks *t)
   if (c->C < 1 || c->C > kMaxChunk || c->M < 0 || c->M > c->N) return SIM_EINVAL;
   if (c->queue_cap < 1 || c->queue_cap > (int64_t(1) << 30) || c->dbuf_cap < 1 || c->dbuf_cap > (int64_t(1) << 30))
     return SIM_EINVAL;
-  if (c->gate_mode < SIM_GATE_OCCUPANCY || c->gate_mode > SIM_GATE_FCFS || c->route_mode != 0) return SIM_EINVAL;
+  if (c->gate_mode < SIM_GATE_OCCUPANCY || c->gate_mode > SIM_GATE_FCFS) return SIM_EINVAL;
+  if (c->route_mode != SIM_ROUTE_SOLO_FIRST && c->route_mode != SIM_ROUTE_RANDOM_SPLIT) return SIM_EINVAL;
+  if (c->route_mode == SIM_ROUTE_RANDOM_SPLIT) {
+    if (!c->p_solo) return SIM_EINVAL;
+    for (int k = 0; k < c->K; ++k)
+      if (!(c->p_solo[k] >= 0.0) || !(c->p_solo[k] <= 1.0) || c->cls[k].theta > 0.0) return SIM_EINVAL;
+  }
   if (c->mod_period < 0 || !(std::fabs(c->mod_amp) <= 1.0)) return SIM_EINVAL;
   if (!(c->c0 > 0.0) || !(c->c_pre >= 0.0) || !(c->c_dec >= 0.0) || !(c->dt >= 0.0)) return SIM_EINVAL;
   t->c0 = std::llround(c->c0 * 1e9);
@@ -233,7 +240,8 @@ int sim_create(const sim_config *cfg, int max_replications, void *dev_workspace,
     h->x_star[k] = cfg->x_star[k];
     h->qp_star[k] = cfg->qp_star[k];
   }
-  h->cfg.cls = h->cls; h->cfg.x_star = h->x_star; h->cfg.qp_star = h->qp_star;
+  for (int k = 0; k < cfg->K; ++k) h->p_solo[k] = cfg->route_mode == SIM_ROUTE_RANDOM_SPLIT ? cfg->p_solo[k] : 1.0;
+  h->cfg.cls = h->cls; h->cfg.x_star = h->x_star; h->cfg.qp_star = h->qp_star; h->cfg.p_solo = h->p_solo;
   h->max_reps = max_replications;
   h->reps = 0; h->seed = 0; h->steps_done = 0; h->started = false;
   h->rows = rows;
@@ -261,6 +269,8 @@ int sim_create(const sim_config *cfg, int max_replications, void *dev_workspace,
   p.K = cfg->K; p.N = cfg->N; p.B = cfg->B; p.C = cfg->C; p.M = cfg->M; p.R = max_replications;
   p.BS = (cfg->B + 3) & ~3;
   p.gate_mode = cfg->gate_mode;
+  p.route_mode = cfg->route_mode;
+  for (int k = 0; k < cfg->K; ++k) p.solo_thr[k] = probability_threshold(h->p_solo[k]);
   p.tbt_lo = host_hbin(t.c0);
   p.tbt_w = host_hbin(t.c0 + t.cpre * cfg->C + t.cdec * cfg->B) - p.tbt_lo + 1;
   p.nwords = (cfg->N + 63) / 64;
@@ -294,6 +304,7 @@ int sim_create(const sim_config *cfg, int max_replications, void *dev_workspace,
   p.hist = reinterpret_cast<uint64_t *>(w + L.hist);
   p.digest = reinterpret_cast<uint64_t *>(w + L.digest);
   p.reduced = reinterpret_cast<uint64_t *>(w + L.reduced);
+  if (cfg->route_mode == SIM_ROUTE_RANDOM_SPLIT) p.dring_m = reinterpret_cast<uint64_t *>(w + L.dring_m);
   if (cal_entries) {
     for (int k = 0; k < cfg->K; ++k)
       if (cfg->cls[k].theta > 0.0) p.ab_classes |= 1u << k;
@@ -571,6 +582,13 @@ int sim_snapshot(sim_t *h, int r, sim_state_t *out, void *hip_stream)
     rc = copy_out(ring.data(), p.dring + static_cast<size_t>(r) * p.dbuf_cap, ring.size() * sizeof(uint64_t));
     if (rc != SIM_OK) return rc;
     for (int64_t i = 0; i < cs[CS_DCOUNT]; ++i) out->dbuf[i] = ring[(static_cast<uint32_t>(cs[CS_DHEAD]) + i) % p.dbuf_cap];
+  }
+  out->dbuf_m_len = p.route_mode == SIM_ROUTE_RANDOM_SPLIT ? cs[CS_DCOUNT_M] : 0;
+  if (out->dbuf_m && out->dbuf_m_len > 0) {
+    std::vector<uint64_t> ring(p.dbuf_cap);
+    rc = copy_out(ring.data(), p.dring_m + static_cast<size_t>(r) * p.dbuf_cap, ring.size() * sizeof(uint64_t));
+    if (rc != SIM_OK) return rc;
+    for (int64_t i = 0; i < out->dbuf_m_len; ++i) out->dbuf_m[i] = ring[(static_cast<uint32_t>(cs[CS_DHEAD_M]) + i) % p.dbuf_cap];
   }
   if (out->dbuf_dl && cs[CS_DCOUNT] > 0) {
     std::vector<uint32_t> ring(p.dbuf_cap, kNever);

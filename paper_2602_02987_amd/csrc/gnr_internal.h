@@ -25,7 +25,9 @@ constexpr int kMaxTbtBins = 256;  // width of the on-chip time-between-tokens hi
 
 // Per-replication class-level state, int32 words (persisted between launches).
 enum ClassStateWord {
-  CS_QP = 0, CS_X = 8, CS_QD = 16, CS_YM = 24, CS_YS = 32, CS_QHEAD = 40, CS_DHEAD = 48, CS_DCOUNT = 49, CS_WORDS = 64
+  CS_QP = 0, CS_X = 8, CS_QD = 16, CS_YM = 24, CS_YS = 32, CS_QHEAD = 40, CS_DHEAD = 48, CS_DCOUNT = 49,
+  CS_DHEAD_M = 50, CS_DCOUNT_M = 51,   // the mixed group's buffer under the randomized router
+  CS_WORDS = 64
 };
 constexpr uint32_t kNever = 0xFFFFFFFFu;   // deadline of a request that never abandons
 constexpr int kStreamPatienceP = 2;        // random streams: 0 arrivals, 1 lengths, 2+k prefill-queue patience of class k,
@@ -48,6 +50,9 @@ struct Params {
   // abandonment: classes with a patience rate (bit k), mask of the deadline calendars (entries - 1, a power of two
   // above the longest patience in steps)
   uint32_t ab_classes, cal_mask;
+  // randomized router: a decode of class k goes to the solo group when its random word is below solo_thr[k]
+  int route_mode;
+  uint32_t solo_thr[kMaxK];
   // tables (device)
   const uint32_t *arr_thr;    // [rows][3]
   const uint16_t *len_tab;    // [K][2][65536]: in, out
@@ -64,6 +69,7 @@ struct Params {
   // rings
   uint32_t *qring;            // [R][K][queue_cap] arrival stamps
   uint64_t *dring;            // [R][dbuf_cap] requests
+  uint64_t *dring_m;          // [R][dbuf_cap] randomized router only: the mixed group's buffer
   // abandonment only: the step at whose start a waiting request leaves, beside each ring entry; per class and
   // step (modulo the calendar size), how many waiting requests leave at that step
   uint32_t *qdl;              // [R][K][queue_cap]
@@ -85,6 +91,7 @@ int build_patience_table(double theta, double dt_seconds, uint16_t *out);
 double total_rate(const sim_class *cls, int K);
 void build_arrival_row(double lam, int64_t dt_ns, double amp, int64_t period, int64_t row, uint32_t thr[3]);
 void build_class_thresholds(const sim_class *cls, int K, uint32_t *thr);
+uint32_t probability_threshold(double p);   // floor(p * 2^32) clamped to [0, 2^32 - 1]
 
 // kernel launchers (gnr_kernels.hip); stream is a hipStream_t
 int launch_reset(const Params &p, int reps, void *stream);

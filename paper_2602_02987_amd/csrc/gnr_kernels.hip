@@ -124,6 +124,9 @@ enum Scalar {
   SC_DLEN = 10,   // entries of the decode buffer ring between head and tail, abandoned ones included
   SC_DSCAN = 11,  // entries of that ring the routing passes of this step have gone past
   SC_COMPACT = 12,// bit k: class queue ring k (bit 8: the decode buffer ring) must be compacted before the appends
+  // randomized router only:
+  SC_NCS = 13,    // completed prefills of this step that joined the solo group's buffer
+  SC_NCM = 14,    // ... the mixed group's buffer
   SC_QLEN = 32,   // [8] entries of each class queue ring between head and tail, abandoned ones included
   SC_TAKE = 16,   // [8] accepted arrivals this step
   SC_TAIL = 24,   // [8] ring position of the first accepted arrival
@@ -404,6 +407,8 @@ struct StepArrays {
   // abandonment only
   const uint16_t *pat_tab;
   uint32_t *qdl, *ddl, *cal, *dcal;
+  // randomized router only
+  uint64_t *dring_m;
 };
 
 // AB: the variant with abandonment (some class has a patience rate). Ring entries then carry the step at whose
@@ -411,7 +416,10 @@ struct StepArrays {
 // passes them: the counters Q_p, Q_d follow the abandonments eagerly through per-step calendars, the gate and
 // the router skip dead entries when they take requests, and a ring is compacted when it would not hold the
 // step's appends and at the end of every launch (so the state between launches holds waiting requests only).
-template <int MAXT, bool AB>
+// RR: the variant with the randomized decode router: every completed prefill is sent to the solo or to the
+// mixed group by a random word, each group has its own buffer ring and is fed from that ring only. A routing
+// pass then takes jobs from both rings: the staged list holds the solo ring's jobs first.
+template <int MAXT, bool AB, bool RR>
 __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict__ params, const StepArrays a,
                                                         const uint32_t key0, const uint32_t key1,
                                                         const uint32_t step_begin, const uint32_t n_steps)
@@ -453,6 +461,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
   uint32_t *cal = AB ? a.cal + static_cast<size_t>(r) * K * cal_n : nullptr;
   uint32_t *dcal = AB ? a.dcal + static_cast<size_t>(r) * K * cal_n : nullptr;
   const uint32_t *lo_tab = AB ? L.live_off : nullptr;
+  uint64_t *dring_m = RR ? a.dring_m + static_cast<size_t>(r) * p.dbuf_cap : nullptr;
 
   // ---- load the replication's class state and rebuild the on-chip views of the server state
   for (int i = tid; i < CS_WORDS; i += NT) L.cs[i] = a.cstate[static_cast<size_t>(r) * CS_WORDS + i];
@@ -1009,7 +1018,54 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
       }
     }
     // completed prefills join the decode buffer in ascending server order
-    {
+    if constexpr (RR) {
+      // randomized router: word 1 of the completion's block picks the group; one wave takes the completions in
+      // order, so the rank of each within its group's ring follows from running counts
+      if (wave == 0) {
+        const uint32_t ncomp = static_cast<uint32_t>(L.sc[SC_NCOMP]);
+        const uint32_t dc0 = static_cast<uint32_t>(L.cs[CS_DCOUNT]), dc1 = static_cast<uint32_t>(L.cs[CS_DCOUNT_M]);
+        const uint32_t dh0 = static_cast<uint32_t>(L.cs[CS_DHEAD]), dh1 = static_cast<uint32_t>(L.cs[CS_DHEAD_M]);
+        uint32_t seen0 = 0, seen1 = 0;   // completions sent to either group so far
+        for (uint32_t j0 = 0; j0 < ncomp; j0 += 64) {   // wave-uniform
+          const uint32_t j = j0 + lane;
+          const bool active = j < ncomp;
+          int k = 0;
+          bool solo = false;
+          uint64_t jw = 0;
+          if (active) {
+            const int g = select_bit(L.bm_comp, L.pre_c, nwords_m, j);
+            jw = pf_job[g];
+            k = static_cast<int>(jw >> 29) & 7;
+            uint32_t w[4];
+            philox4x32_10(key0, key1, s, static_cast<uint32_t>(kStreamPatienceD), static_cast<uint32_t>(g),
+                          static_cast<uint32_t>(r), w);
+            solo = w[1] < p.solo_thr[k];
+          }
+          const uint64_t bal0 = __ballot(active && solo), bal1 = __ballot(active && !solo);
+          const uint32_t idx = solo ? seen0 + static_cast<uint32_t>(__popcll(bal0 & lanes_below()))
+                                    : seen1 + static_cast<uint32_t>(__popcll(bal1 & lanes_below()));
+          const bool kept = active && (solo ? dc0 : dc1) + idx < p.dbuf_cap;
+          if (kept) {
+            uint32_t pos = (solo ? dh0 + dc0 : dh1 + dc1) + idx;
+            if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
+            (solo ? dring : dring_m)[pos] = jw;
+          }
+          wave_count_by_class_i32(kept, k, K, &L.cs[CS_QD], 1);
+          if (__ballot(active && !kept)) {
+            wave_count_by_class(active && !kept, k, K, &L.tl[SIM_T_DROP_D], kNTally);
+            if (lane == 0) L.tl[kMaxK * kNTally + SIM_G_OVERFLOW] = 1;
+          }
+          seen0 += static_cast<uint32_t>(__popcll(bal0));
+          seen1 += static_cast<uint32_t>(__popcll(bal1));
+        }
+        if (lane == 0) {   // what each ring accepted (a prefix of what it was sent)
+          const uint32_t room0 = p.dbuf_cap - dc0, room1 = p.dbuf_cap - dc1;
+          L.sc[SC_NCS] = static_cast<int32_t>(seen0 < room0 ? seen0 : room0);
+          L.sc[SC_NCM] = static_cast<int32_t>(seen1 < room1 ? seen1 : room1);
+        }
+      }
+      __syncthreads();
+    } else {
       const uint32_t ncomp = static_cast<uint32_t>(L.sc[SC_NCOMP]);
       const uint32_t dcount = static_cast<uint32_t>(L.cs[CS_DCOUNT]), dhead = static_cast<uint32_t>(L.cs[CS_DHEAD]);
       const uint32_t dfill = AB ? static_cast<uint32_t>(L.sc[SC_DLEN]) : dcount;   // ring entries before the tail
@@ -1074,6 +1130,14 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
         jrem = dcount0 + (ncp < room ? ncp : room);
       }
       const uint32_t dhead0 = static_cast<uint32_t>(L.cs[CS_DHEAD]);
+      // randomized router only: jobs left, jobs placed and ring head of the solo [0] and the mixed [1] group's buffer
+      int jremL[2] = {0, 0}, nextL[2] = {0, 0}, takenL[2] = {0, 0};
+      const uint32_t dheadL[2] = {dhead0, RR ? static_cast<uint32_t>(L.cs[CS_DHEAD_M]) : 0u};
+      if constexpr (RR) {
+        jremL[0] = dcount0 + L.sc[SC_NCS];
+        jremL[1] = L.cs[CS_DCOUNT_M] + L.sc[SC_NCM];
+        jrem = jremL[0] + jremL[1];
+      }
       // abandonment only: ring entries of the decode buffer, this step's completions included
       uint32_t dlen_all = AB ? static_cast<uint32_t>(L.sc[SC_DLEN]) + static_cast<uint32_t>(jrem - dcount0) : 0u;
       if (dlen_all > p.dbuf_cap) dlen_all = p.dbuf_cap;   // (never more: the ring was compacted if it had to be)
@@ -1218,6 +1282,40 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           // (with abandonment a pass places no more jobs than are staged in LDS)
           const int jpass = AB && jrem > kJobsLds ? kJobsLds : jrem;
           int rem_jobs = jpass;
+          if constexpr (RR) {
+            // each group takes jobs from its own ring; the pass's list holds the solo ring's jobs first and is
+            // never longer than what is staged in LDS
+            int listed = 0;
+            takenL[0] = takenL[1] = 0;
+#pragma unroll
+            for (int gi = 0; gi < 2; ++gi) {
+              const int glo = gi == 0 ? M : 0, ghi = gi == 0 ? N : M;
+              const int capg = gi == 0 ? B : B - 1;
+              int rem_g = jremL[gi] < kJobsLds - listed ? jremL[gi] : kJobsLds - listed;
+              const int start_g = rem_g;
+              if (glo >= ghi || nl >= kRouteLevels || rem_g <= 0 || (gi == 1 && gate_unfinished)) continue;   // wave-uniform
+              int lm = -1;
+              for (int base = 0; base < capg && lm < 0; base += 64) {
+                const int l = base + lane;
+                const uint64_t nz = __ballot(l < capg && L.lh[gi * kLoadBins + l] != 0);
+                if (nz) lm = base + __ffsll(static_cast<long long>(nz)) - 1;
+              }
+              if (lm < 0) continue;   // no free slot in this group
+              lminG[gi] = lm;
+              for (int u = 0; nl < kRouteLevels && rem_g > 0 && lm + u < capg; ++u) {
+                csumG[gi] += static_cast<int>(L.lh[gi * kLoadBins + lm + u]);
+                const int tk = csumG[gi] < rem_g ? csumG[gi] : rem_g;
+                if (lane == 0) { L.sc[SC_TAKE_T + nl] = tk; L.sc[SC_W_T + nl] = listed + (start_g - rem_g); }
+                rem_g -= tk;
+                tlastG[gi] = tk;
+                ++nG[gi];
+                ++nl;
+              }
+              takenL[gi] = start_g - rem_g;
+              listed += takenL[gi];
+            }
+            rem_jobs = jpass - listed;
+          } else {
 #pragma unroll
           for (int gi = 0; gi < 2; ++gi) {
             const int glo = gi == 0 ? M : 0, ghi = gi == 0 ? N : M;
@@ -1240,6 +1338,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
               ++nG[gi];
               ++nl;
             }
+          }
           }
           PROF(24)
           total = jpass - rem_jobs;
@@ -1287,7 +1386,10 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
         // ---------------- segment B ----------------
         bool gate_more = false;
         if (gate_on) {
-          if (pass == 0 && tid == 0) L.cs[CS_DCOUNT] = jrem;   // the completions of this step are in the buffer
+          if (pass == 0 && tid == 0) {   // the completions of this step are in the buffer
+            if constexpr (RR) { L.cs[CS_DCOUNT] = jremL[0]; L.cs[CS_DCOUNT_M] = jremL[1]; }
+            else L.cs[CS_DCOUNT] = jrem;
+          }
           // admission j goes to the idle prefill slot of rank j; one thread per admission
           for (int j0 = wave_base; j0 < nadm; j0 += NT) {   // wave-uniform trip count
             const int j = j0 + lane;
@@ -1368,6 +1470,14 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
                 found += static_cast<uint32_t>(__popcll(bal));
               }
               if (lane == 0) L.sc[SC_DSCAN] = static_cast<int32_t>(found >= need ? stop : dlen_all);   // (found < need: see the gate's scan)
+            }
+          } else if constexpr (RR) {
+            for (int j = tid; j < nstage; j += NT) {
+              const int li = j < takenL[0] ? 0 : 1;
+              uint32_t pos = dheadL[li] + static_cast<uint32_t>(nextL[li] + (li ? j - takenL[0] : j));
+              if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
+              if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
+              L.jobs[j] = (li ? dring_m : dring)[pos];
             }
           } else {
           for (int j = tid; j < nstage; j += NT) {
@@ -1511,6 +1621,10 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           }
           jrem -= total;
           next += total;
+          if constexpr (RR) {
+            jremL[0] -= takenL[0]; nextL[0] += takenL[0];
+            jremL[1] -= takenL[1]; nextL[1] += takenL[1];
+          }
           route_on = jrem > 0;
         }
         gate_on = gate_more;
@@ -1527,6 +1641,17 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           L.cs[CS_DCOUNT] -= next;
           L.sc[SC_DLEN] = static_cast<int32_t>(dlen_all - past);
           L.sc[SC_COMPACT] = 0;
+        }
+      } else if constexpr (RR) {
+        if (tid == 0 && next > 0) {
+          uint32_t h = dheadL[0] + static_cast<uint32_t>(nextL[0]);
+          if (h >= p.dbuf_cap) h -= p.dbuf_cap;
+          L.cs[CS_DHEAD] = static_cast<int32_t>(h);
+          L.cs[CS_DCOUNT] -= nextL[0];
+          h = dheadL[1] + static_cast<uint32_t>(nextL[1]);
+          if (h >= p.dbuf_cap) h -= p.dbuf_cap;
+          L.cs[CS_DHEAD_M] = static_cast<int32_t>(h);
+          L.cs[CS_DCOUNT_M] -= nextL[1];
         }
       } else {
       if (tid == 0 && next > 0) {
@@ -1692,6 +1817,15 @@ __global__ void gnr_digest_kernel(const Params p)
       d += h;
     }
   }
+  if (p.route_mode == SIM_ROUTE_RANDOM_SPLIT) {   // the mixed group's buffer
+    const uint32_t head = static_cast<uint32_t>(cs[CS_DHEAD_M]), len = static_cast<uint32_t>(cs[CS_DCOUNT_M]);
+    const uint64_t *ring = p.dring_m + static_cast<size_t>(r) * p.dbuf_cap;
+    for (uint32_t i = tid; i < len; i += NT) {
+      uint32_t pos = head + i;
+      if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
+      d += chain(chain(6, i), ring[pos]);
+    }
+  }
   for (int g = tid; g < N; g += NT) {
     const size_t sg = static_cast<size_t>(r) * N + g;
     const uint32_t pk = p.remptok[sg];
@@ -1727,9 +1861,13 @@ int launch_reset(const Params &p, int reps, void *stream)
 int launch_steps(const Params &p, int reps, int threads, size_t lds_bytes, uint32_t step_begin, uint32_t n_steps,
                  void *stream)
 {
-  auto kernel = p.ab_classes
-                    ? (threads > 768 ? gnr_step_kernel<1024, true> : threads > 512 ? gnr_step_kernel<768, true> : gnr_step_kernel<512, true>)
-                    : (threads > 768 ? gnr_step_kernel<1024, false> : threads > 512 ? gnr_step_kernel<768, false> : gnr_step_kernel<512, false>);
+  if (p.ab_classes && p.route_mode == SIM_ROUTE_RANDOM_SPLIT) return SIM_EINVAL;   // not built together
+  auto kernel =
+      p.ab_classes
+          ? (threads > 768 ? gnr_step_kernel<1024, true, false> : threads > 512 ? gnr_step_kernel<768, true, false> : gnr_step_kernel<512, true, false>)
+      : p.route_mode == SIM_ROUTE_RANDOM_SPLIT
+          ? (threads > 768 ? gnr_step_kernel<1024, false, true> : threads > 512 ? gnr_step_kernel<768, false, true> : gnr_step_kernel<512, false, true>)
+          : (threads > 768 ? gnr_step_kernel<1024, false, false> : threads > 512 ? gnr_step_kernel<768, false, false> : gnr_step_kernel<512, false, false>);
   if (lds_bytes > 64 * 1024) {   // more than the default dynamic LDS limit has to be asked for
     const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes));
@@ -1737,7 +1875,7 @@ int launch_steps(const Params &p, int reps, int threads, size_t lds_bytes, uint3
   }
   const StepArrays a = {p.arr_thr, p.len_tab, p.t_next, p.iter, p.remptok, p.pf_job, p.n_cls, p.n_join,
                         p.fin,     p.job,     p.qring,  p.dring, p.cstate, p.tally,  p.hist,
-                        p.pat_tab, p.qdl,     p.ddl,    p.cal,   p.dcal};
+                        p.pat_tab, p.qdl,     p.ddl,    p.cal,   p.dcal,   p.dring_m};
   hipLaunchKernelGGL(kernel, dim3(reps), dim3(threads), lds_bytes, static_cast<hipStream_t>(stream), p.self, a, p.key0,
                      p.key1, step_begin, n_steps);
   return hip_ok(hipGetLastError());

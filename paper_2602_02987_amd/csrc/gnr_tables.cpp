@@ -86,6 +86,8 @@ int build_length_table(int law, double p0, double p1, const uint16_t *user, uint
   }
 }
 
+uint32_t probability_threshold(double p) { return quantise32(p); }
+
 int build_patience_table(double theta, double dt_seconds, uint16_t *out)
 {
   if (!(theta > 0.0) || !(dt_seconds > 0.0) || !std::isfinite(theta)) return SIM_EINVAL;

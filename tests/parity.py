@@ -30,6 +30,7 @@ def assert_replication_equal(sim, orc, r, ro=None, what=""):
         assert np.array_equal(s["queue_dl"][k], orc.queue_deadlines(ro, k)), (tag, "queue deadlines", k)
     assert np.array_equal(s["dbuf"], orc.queue(ro, -1)), (tag, "decode buffer")
     assert np.array_equal(s["dbuf_dl"], orc.queue_deadlines(ro, -1)), (tag, "decode buffer deadlines")
+    assert np.array_equal(s["dbuf_m"], orc.queue(ro, -2)), (tag, "decode buffer of the mixed group")
     st, sg = sim.tallies(r)
     ot, og = orc.tallies(ro)
     assert np.array_equal(st, ot), (tag, "tallies", np.nonzero(st != ot), st[st != ot], ot[st != ot])
