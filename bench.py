@@ -64,11 +64,13 @@ def measured_traffic():
 
 
 def _oracle_worker(args):
-    n, N, rep, steps, theta = args
+    n, N, rep, steps, theta, split = args
     sys.path.insert(0, ROOT)
     from oracle import binding as ob
     from paper_2602_02987_amd import workloads as W
     cfg = W.config(n, N=N)
+    if split:
+        cfg = W.with_random_split(cfg, lam_plan=[c.lam / 0.95 for c in cfg.classes])
     for c in cfg.classes:
         c.theta = theta or c.theta
     o = ob.Oracle(cfg, max_reps=cfg.replications)
@@ -78,7 +80,7 @@ def _oracle_worker(args):
     return time.perf_counter() - t
 
 
-def cpu_baseline(n, N, steps, theta=0.0):
+def cpu_baseline(n, N, steps, theta=0.0, split=False):
     """The oracle as it stands, one replication per host process, on a bounded sample."""
     import multiprocessing as mp
     from oracle import binding as ob
@@ -86,7 +88,7 @@ def cpu_baseline(n, N, steps, theta=0.0):
     cores = min(16, os.cpu_count() or 1)
     t = time.perf_counter()
     with mp.get_context("spawn").Pool(cores) as pool:
-        pool.map(_oracle_worker, [(n, N, r, steps, theta) for r in range(cores)])
+        pool.map(_oracle_worker, [(n, N, r, steps, theta, split) for r in range(cores)])
     wall = time.perf_counter() - t
     return dict(value=cores * N * steps / wall, unit="server-steps/s", cores=cores, kind="oracle",
                 sample=f"replications 0..{cores - 1} of the workload, first {steps} steps from the empty system, "
@@ -105,6 +107,8 @@ def main():
     ap.add_argument("--replications", type=int, default=0)
     ap.add_argument("--theta", type=float, default=0.0,
                     help="patience rate given to every class (abandonment; 0 = the configuration's own, none)")
+    ap.add_argument("--random-split", action="store_true",
+                    help="route decodes with the randomized router, solo probabilities from the configuration's plan")
     ap.add_argument("--oracle-steps", type=int, default=1500, help="0 skips the CPU baseline")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run one device-to-device copy of this size before the timed region "
@@ -120,7 +124,7 @@ def main():
     base = None
     if args.oracle_steps > 0:
         n_servers = args.servers if args.servers else W.config(args.config).N
-        base = cpu_baseline(args.config, n_servers, args.oracle_steps, args.theta)
+        base = cpu_baseline(args.config, n_servers, args.oracle_steps, args.theta, args.random_split)
 
     import torch
     from paper_2602_02987_amd import binding
@@ -130,6 +134,8 @@ def main():
     if args.replications:
         over["replications"] = args.replications
     cfg = W.config(args.config, **over)
+    if args.random_split:
+        cfg = W.with_random_split(cfg, lam_plan=[c.lam / 0.95 for c in cfg.classes])
     if args.theta:
         for c in cfg.classes:
             c.theta = args.theta
@@ -177,7 +183,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int64", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: K={cfg.K} N={cfg.N} R={cfg.replications} B={cfg.B} C={cfg.C} M={cfg.M}"
-                               + (f" theta={args.theta}" if args.theta else "") + ", "
+                               + (f" theta={args.theta}" if args.theta else "")
+                               + (" randomized router" if args.random_split else "") + ", "
                                f"{args.sim_steps} simulation steps per bench step after {args.preload + args.warmup * args.sim_steps} untimed steps",
                    "server_step_slots_per_bench_step": slots_per_step,
                    "executed_iterations_per_s": iters / wall,
