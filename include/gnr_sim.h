@@ -181,10 +181,18 @@ int sim_run(sim_t *h, int64_t steps, int replications, uint64_t seed, void *hip_
  * adaptive algorithm (trace-driven online policy evaluation: the controller re-estimates the class arrival
  * rates from a rolling window, Eq. main-online-arrival-estimate, re-solves the fluid LP at every replanning
  * epoch, and the gate then ranks by the deviation from the current targets). Only the targets move: the
- * mixed/solo split M keeps the value given to sim_create (moving M*(t_k), Eq. main-online-mixed-target, is not
- * built). x_star, qp_star: host arrays of K doubles. SIM_EINVAL: a negative or non-finite target.
+ * mixed/solo split M is moved by sim_set_split. x_star, qp_star: host arrays of K doubles. SIM_EINVAL: a negative or non-finite target.
  * The new values are copied to the device asynchronously on `hip_stream`, ordered after earlier runs. */
 int sim_set_targets(sim_t *h, const double *x_star, const double *qp_star, void *hip_stream);
+
+/* Moves the mixed/solo split between two sim_run calls: servers 0..M-1 are the mixed group from the next step
+ * on (the online adaptive algorithm's M*(t_k) = ceil(n * sum_i x*_i(t_k)), Eq. main-online-mixed-target).
+ * Existing service is not pre-empted: a prefill in service on a server that turns solo runs to its end (that
+ * server admits no further prefill), decodes on a server that turns mixed stay (it takes new ones only while
+ * it holds fewer than B-1); the new split governs later admissions and placements. SIM_EINVAL: M outside
+ * [0, N], or the on-chip state of the enlarged mixed group no longer fits a compute unit's LDS. The new value
+ * is copied to the device asynchronously on `hip_stream`, ordered after earlier runs. */
+int sim_set_split(sim_t *h, int M, void *hip_stream);
 
 /* Sums the tallies over replications on the device, copies them out and derives the fp64 figures.
  * Synchronises the stream. Returns SIM_EOVERFLOW (with `out` filled) if any ring overflowed. */

@@ -193,6 +193,11 @@ class Oracle:
         if self.L.oracle_set_targets(self.h, x.ctypes.data, q.ctypes.data):
             raise RuntimeError("oracle_set_targets failed")
 
+    def set_split(self, M):
+        """Servers 0..M-1 are the mixed group from here on; work in service stays where it is."""
+        if self.L.oracle_set_split(self.h, int(M)):
+            raise RuntimeError("oracle_set_split failed")
+
     def violations(self):
         return int(self.L.oracle_violations(self.h)), int(self.L.oracle_first_violation(self.h))
 

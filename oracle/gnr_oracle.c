@@ -135,6 +135,7 @@ typedef struct oracle_t {
   uint16_t *tab_in[MAXK], *tab_out[MAXK];
   uint16_t *tab_pat[MAXK]; /* patience in steps, NULL for a class that never abandons */
   int any_theta;
+  int split_moved;        /* oracle_set_split changed M during the run: servers may hold work their new group would not take */
   int max_reps, reps;
   uint64_t seed;
   int64_t steps_done;
@@ -450,7 +451,12 @@ static int64_t check_rep(oracle_t *o, int r)
       if (cnt[k] != s->n_cls[k]) viol(o, 104);
       if (joiners[k] != s->n_join[k]) viol(o, 105);
     }
-    if (g < M) { if (used > B - 1) viol(o, 106); } else { if (used > B) viol(o, 107); if (s->pf_rem) viol(o, 108); }
+    /* per-server capacity (Sec. 2.3). After the split has moved, work that was there before stays (no
+     * pre-emption): a server that turned mixed may still hold B decodes, one that turned solo its prefill. */
+    if (used > B) viol(o, 107);
+    if (!o->split_moved) {
+      if (g < M) { if (used > B - 1) viol(o, 106); } else { if (s->pf_rem) viol(o, 108); }
+    }
     if (s->pf_rem) {
       if (s->pf_rem > s->pf_P || s->pf_rem < 0) viol(o, 109);
       X[s->pf_cls]++; Xtot++;
@@ -468,8 +474,13 @@ static int64_t check_rep(oracle_t *o, int r)
   if (o->cfg.route_mode == ROUTE_SOLO_FIRST && R->dbuf_m.len) viol(o, 124);
   /* capacity constraints */
   if (Xtot > N) viol(o, 120);
-  if (Ymtot > (int64_t)(B - 1) * Xtot) viol(o, 121);
-  if (Ystot > (int64_t)B * (N - Xtot)) viol(o, 122);
+  if (!o->split_moved) {
+    if (Ymtot > (int64_t)(B - 1) * Xtot) viol(o, 121);
+    if (Ystot > (int64_t)B * (N - Xtot)) viol(o, 122);
+  } else {
+    if (Ymtot > (int64_t)B * Xtot) viol(o, 121);
+    if (Ystot > (int64_t)B * (N - Xtot)) viol(o, 122);
+  }
   if (R->dbuf.len > o->cfg.dbuf_cap || R->dbuf_m.len > o->cfg.dbuf_cap) viol(o, 123);
   for (int k = 0; k < K; k++) {
     uint64_t *t = R->tally[k];
@@ -755,13 +766,25 @@ int oracle_set_targets(oracle_t *o, const double *x_star, const double *qp_star)
   return 0;
 }
 
+/* Moves the mixed/solo split between runs: servers 0..M-1 are the mixed group from here on (the online
+ * adaptive algorithm's M*(t_k), Eq. main-online-mixed-target). Existing service is not pre-empted: a prefill
+ * in service on a server that turns solo runs to its end (no further admission there), decodes on a server
+ * that turns mixed stay (it takes new ones only below B-1); the new split governs later admissions and
+ * placements. */
+int oracle_set_split(oracle_t *o, int M)
+{
+  if (!o || M < 0 || M > o->cfg.N) return -1;
+  if (M != o->cfg.M) { o->cfg.M = M; o->split_moved = 1; }
+  return 0;
+}
+
 /* run `steps` more steps; a different (replications, seed) pair restarts from the empty system */
 int oracle_run(oracle_t *o, int64_t steps, int replications, uint64_t seed)
 {
   if (!o || steps < 0 || replications < 1 || replications > o->max_reps) return -1;
   if (replications != o->reps || seed != o->seed || o->steps_done == 0) {
     for (int r = 0; r < o->max_reps; r++) rep_free(&o->rep[r]);
-    o->reps = replications; o->seed = seed; o->steps_done = 0;
+    o->reps = replications; o->seed = seed; o->steps_done = 0; o->split_moved = 0;
   }
   if (o->steps_done + steps >= ((int64_t)1 << 29)) return -1;
   int n = o->nsel ? o->nsel : replications;

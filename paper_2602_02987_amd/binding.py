@@ -87,6 +87,7 @@ def lib():
         L.sim_hist.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
         L.sim_digest.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_uint64), C.c_void_p]
         L.sim_set_targets.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.sim_set_split.argtypes = [C.c_void_p, C.c_int, C.c_void_p]
         L.sim_kernel_time.argtypes = [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.c_int, C.c_void_p]
         L.sim_destroy.argtypes = [C.c_void_p]
         L.sim_length_table.argtypes = [C.c_int, C.c_double, C.c_double, C.c_void_p]
@@ -237,6 +238,11 @@ class Sim:
             raise ValueError("set_targets wants K values each")
         with self.torch.cuda.device(self.device):
             _check(lib().sim_set_targets(self.h, x.ctypes.data, q.ctypes.data, self._stream()), "sim_set_targets")
+
+    def set_split(self, M):
+        """Servers 0..M-1 are the mixed group for the steps still to run; work in service stays where it is."""
+        with self.torch.cuda.device(self.device):
+            _check(lib().sim_set_split(self.h, int(M), self._stream()), "sim_set_split")
 
     def stats(self):
         st = SimStatsC()

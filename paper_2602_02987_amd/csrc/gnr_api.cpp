@@ -267,6 +267,7 @@ int sim_create(const sim_config *cfg, int max_replications, void *dev_workspace,
   Params &p = h->p;
   std::memset(&p, 0, sizeof p);
   p.K = cfg->K; p.N = cfg->N; p.B = cfg->B; p.C = cfg->C; p.M = cfg->M; p.R = max_replications;
+  p.Mp = cfg->M;
   p.BS = (cfg->B + 3) & ~3;
   p.gate_mode = cfg->gate_mode;
   p.route_mode = cfg->route_mode;
@@ -378,6 +379,23 @@ int sim_set_targets(sim_t *h, const double *x_star, const double *qp_star, void 
   }
   // the step kernel reads its parameters from the device copy; stream order puts the update after earlier runs
   // (the source is pageable host memory: the call returns once the bytes have been staged)
+  if (hipMemcpyAsync(const_cast<Params *>(h->p.self), &h->p, sizeof(Params), hipMemcpyHostToDevice,
+                     static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+    return SIM_EHIP;
+  return SIM_OK;
+}
+
+int sim_set_split(sim_t *h, int M, void *hip_stream)
+{
+  if (!h || M < 0 || M > h->p.N) return SIM_EINVAL;
+  Params q = h->p;
+  q.M = M;
+  if (M > q.Mp) q.Mp = M;   // never lowered: a server that turns solo may still hold a prefill
+  const size_t lds = step_lds_bytes(q);
+  if (lds > 160 * 1024) return SIM_EINVAL;
+  h->p = q;
+  h->cfg.M = M;
+  h->lds_bytes = lds;
   if (hipMemcpyAsync(const_cast<Params *>(h->p.self), &h->p, sizeof(Params), hipMemcpyHostToDevice,
                      static_cast<hipStream_t>(hip_stream)) != hipSuccess)
     return SIM_EHIP;

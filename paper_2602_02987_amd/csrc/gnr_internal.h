@@ -36,6 +36,7 @@ constexpr int kStreamPatienceD = 10;       // 10 decode-buffer patience
 // Everything a kernel needs, passed by value.
 struct Params {
   int K, N, B, C, M, R;
+  int Mp;                     // servers below this may hold a prefill: the largest M the handle has had
   int BS;                     // slot-row stride in words: B rounded up to a multiple of 4
   int gate_mode;
   int tbt_lo, tbt_w;          // first bin and width of the TBT histogram window kept in LDS

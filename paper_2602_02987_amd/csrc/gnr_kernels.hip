@@ -150,7 +150,7 @@ struct Lds {
   uint64_t *prof;     // [32] cycle buckets of the optional phase profile
 #endif
   uint64_t *tbth;     // [K][tbt_w]
-  uint64_t *bm_idle;  // [nwords] mixed-group servers whose prefill slot is idle
+  uint64_t *bm_idle;  // [nwords] servers below Mp with no prefill in service (the gate looks at those below M)
   uint64_t *bm_comp;  // [nwords] servers whose prefill completed this step
   uint64_t *bm_busy;  // [nwords] servers running an iteration
   uint64_t *bm_join;  // [nwords] servers holding decodes that are not part of their untallied iterations
@@ -172,7 +172,7 @@ struct Lds {
   uint32_t *iter;     // [N] completed iterations
   uint8_t *loads;     // [N] decodes per server
   uint8_t *pend;      // [N] completed iterations not yet tallied (all with the server's current batch)
-  uint16_t *rem;      // [M] prompt tokens left of the prefill a mixed-group server has in service (0: slot idle)
+  uint16_t *rem;      // [Mp] prompt tokens left of the prefill a server has in service (0: none)
   uint32_t *live_off; // [K][kAdmChunk] abandonment only: ring offset from the head of the m-th waiting request of a class
 };
 
@@ -213,7 +213,7 @@ __host__ __device__ __forceinline__ Lds lds_carve(const Params &p, unsigned char
   GNR_TAKE(iter, uint32_t, p.N)
   GNR_TAKE(loads, uint8_t, p.N)
   GNR_TAKE(pend, uint8_t, p.N)
-  GNR_TAKE(rem, uint16_t, p.M)
+  GNR_TAKE(rem, uint16_t, p.Mp)
   GNR_TAKE(stage, uint16_t, 2 * p.threads)
   GNR_TAKE(live_off, uint32_t, p.ab_classes ? p.K * kAdmChunk : 0)
 #undef GNR_TAKE
@@ -241,14 +241,22 @@ int step_threads(int N)
   return t;
 }
 
-// Exclusive prefix popcounts of a bitmap, computed by one whole wave; returns the total in every lane.
-__device__ __forceinline__ uint32_t rank_bitmap(const uint64_t *bm, uint32_t *pre, int nwords)
+// Bits of bitmap word w that belong to servers below `nbits`.
+__device__ __forceinline__ uint64_t bits_below(int w, int nbits)
+{
+  const int left = nbits - (w << 6);
+  return left >= 64 ? ~0ull : (left <= 0 ? 0ull : (1ull << left) - 1ull);
+}
+
+// Exclusive prefix popcounts of the first `nbits` bits of a bitmap, computed by one whole wave; returns the
+// total in every lane.
+__device__ __forceinline__ uint32_t rank_bitmap(const uint64_t *bm, uint32_t *pre, int nwords, int nbits)
 {
   const int lane = threadIdx.x & 63;
   uint32_t running = 0;
   for (int base = 0; base < nwords; base += 64) {
     const int w = base + lane;
-    const uint32_t v = w < nwords ? static_cast<uint32_t>(__popcll(bm[w])) : 0u;
+    const uint32_t v = w < nwords ? static_cast<uint32_t>(__popcll(bm[w] & bits_below(w, nbits))) : 0u;
     const uint32_t inc = wave_incl_scan(v);
     if (w < nwords) pre[w] = running + inc - v;
     running += static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(inc), 63));
@@ -439,7 +447,10 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
   const int K = p.K, N = p.N, B = p.B, M = p.M, BS = p.BS;
   const int nper = (N + NT - 1) / NT;
   const int nwords = p.nwords;
-  const int nwords_m = (M + 63) >> 6;   // bitmap words that hold mixed-group servers
+  // Servers 0..M-1 are the mixed group for the gate and the router. Servers below Mp >= M may hold a prefill:
+  // Mp is the largest M the run has had (a prefill in service stays when its server turns solo).
+  const int Mp = p.Mp;
+  const int nwords_m = (Mp + 63) >> 6;   // bitmap words that hold servers with prefill state
 
   int64_t *t_next = a.t_next + static_cast<size_t>(r) * N;
   uint32_t *iter_g = a.iter + static_cast<size_t>(r) * N;
@@ -493,7 +504,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
       joined = n_join[g] != 0;
     }
     bool idle_slot = false, chunk = false;
-    if (valid && g < M) {   // the prefill word stays in LDS during the launch: tokens left, and whether a chunk runs
+    if (valid && g < Mp) {   // the prefill word stays in LDS during the launch: tokens left, and whether a chunk runs
       const uint32_t pk = remptok[g];
       L.rem[g] = static_cast<uint16_t>(pk_rem(pk));
       idle_slot = pk_rem(pk) == 0;
@@ -625,10 +636,10 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           const uint64_t bit = 1ull << (g & 63);
           const bool joined = L.bm_join[g >> 6] & bit;
           const uint64_t nj = joined ? n_join[g] : 0ull;
-          const bool has_chunk = g < M && (L.bm_chunk[g >> 6] & bit);
+          const bool has_chunk = g < Mp && (L.bm_chunk[g >> 6] & bit);
           const uint32_t it = L.iter[g];
           int nd = L.loads[g];
-          int rem = g < M ? static_cast<int>(L.rem[g]) : 0;
+          int rem = g < Mp ? static_cast<int>(L.rem[g]) : 0;
           const int ptok = has_chunk ? (rem < p.C ? rem : p.C) : 0;   // the chunk frozen at the start of the iteration
           const int64_t tn = T + static_cast<int64_t>(static_cast<int32_t>(L.t32[g] - T32));   // exact completion time
           comp = nc - nj;   // bytewise: no class joins more decodes than it holds
@@ -758,7 +769,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
         const uint32_t iter_v = valid ? L.iter[g] : 0u;
         const int nd = valid ? static_cast<int>(L.loads[g]) : 0;
         int pend = valid ? static_cast<int>(L.pend[g]) : 0;
-        const int rem_v = g < M ? static_cast<int>(L.rem[g]) : 0;
+        const int rem_v = g < Mp ? static_cast<int>(L.rem[g]) : 0;
         bool busy = busy_word & lbit;
         // ---- (re)start of the servers that completed an iteration or were given work in the previous step.
         //      Untallied iterations are tallied before the batch changes, and all of them when the launch ends.
@@ -810,7 +821,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           const uint64_t nb = __ballot(busy), nchunk = __ballot(chunk_now);
           if (lane == 0) {
             if (nb != busy_word) L.bm_busy[wi] = nb;
-            if (gw < M) L.bm_chunk[wi] = (chunk_word & ~todo) | nchunk;
+            if (gw < Mp) L.bm_chunk[wi] = (chunk_word & ~todo) | nchunk;
           }
         }
         o_due = false; o_it = 0; o_nd = 0; o_pend = 0; o_q = 0;
@@ -829,7 +840,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           o_nd = nd;
           o_pend = pend;
         }
-        const bool prefill_here = g < M && !(idle_word & lbit);
+        const bool prefill_here = g < Mp && !(idle_word & lbit);
         o_must = o_due && ((join_word & lbit) || prefill_here || o_pend >= kMaxPend);
         o_scan = o_due && o_nd > 0;
         o_big = o_scan && o_nd > 64;   // the row's second half holds decodes too
@@ -974,11 +985,11 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
       if (a > take) L.tl[kMaxK * kNTally + SIM_G_OVERFLOW] = 1;
     }
     if (tid < 64) {
-      const uint32_t ncomp = rank_bitmap(L.bm_comp, L.pre_c, nwords_m);
+      const uint32_t ncomp = rank_bitmap(L.bm_comp, L.pre_c, nwords_m, Mp);
       if (tid == 0) L.sc[SC_NCOMP] = static_cast<int32_t>(ncomp);
     }
     if (NT == 64 ? tid < 64 : (tid >= 64 && tid < 128)) {
-      const uint32_t nidle = rank_bitmap(L.bm_idle, L.pre, nwords_m);
+      const uint32_t nidle = rank_bitmap(L.bm_idle, L.pre, nwords_m, M);   // idle prefill slots of the mixed group
       if (lane == 0) L.sc[SC_NIDLE] = static_cast<int32_t>(nidle);
     }
     __syncthreads();
@@ -1148,7 +1159,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
       for (int pass = 0; gate_on || route_on; ++pass) {
         if (gate_on && pass > 0) {
           if (tid < 64) {
-            const uint32_t nidle = rank_bitmap(L.bm_idle, L.pre, nwords_m);
+            const uint32_t nidle = rank_bitmap(L.bm_idle, L.pre, nwords_m, M);
             if (tid == 0) L.sc[SC_NIDLE] = static_cast<int32_t>(nidle);
           }
           __syncthreads();
@@ -1206,7 +1217,8 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           // updated here a word at a time (no atomics).
           // A wave takes a word, a lane a slot; the slot of every admission rank goes into a table.
           for (int w = wave; w < nwords_m; w += nwaves) {   // wave-uniform
-            const uint64_t idle = L.bm_idle[w], busy_w = L.bm_busy[w], touch_w = L.bm_touch[w];
+            const uint64_t idle_all = L.bm_idle[w], busy_w = L.bm_busy[w], touch_w = L.bm_touch[w];
+            const uint64_t idle = idle_all & bits_below(w, M);   // the gate admits to the mixed group only
             const int before = static_cast<int>(L.pre[w]);   // idle slots in the words before this one
             uint64_t adm = 0;
             if (before < nadm)
@@ -1215,7 +1227,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
               if ((adm >> lane) & 1ull)
                 L.adm_slot[before + __popcll(adm & lanes_below())] = static_cast<uint16_t>((w << 6) + lane);
               if (lane == 0) {
-                L.bm_idle[w] = idle & ~adm;
+                L.bm_idle[w] = idle_all & ~adm;
                 L.bm_touch[w] = touch_w | (adm & ~busy_w);   // an idle server is given work
               }
             }
@@ -1558,7 +1570,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
             if (__ballot(tmin < tend) == 0) continue;   // wave-uniform
             const bool busy0 = busy_word & bit, at_boundary = due_word & bit;
             const bool mid = busy0 && !at_boundary;   // a job placed now joins at the next restart
-            const bool has_prefill = g < M && !(idle_word & bit);
+            const bool has_prefill = g < Mp && !(idle_word & bit);
             // the new decode is not part of the iterations still to be tallied for this server
             const bool joins = mid || (at_boundary && pend_own != 0);
             bool got = false, got_last = false;
@@ -1699,7 +1711,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
     const bool busy = (L.bm_busy[g >> 6] >> (g & 63)) & 1ull;
     t_next[g] = busy ? T + static_cast<int64_t>(static_cast<int32_t>(L.t32[g] - static_cast<uint32_t>(T))) : kIdle;
     iter_g[g] = L.iter[g];
-    if (g < M) {   // prompt tokens already processed of the prefill in service
+    if (g < Mp) {   // prompt tokens already processed of the prefill in service
       const uint32_t rem = L.rem[g];
       uint32_t pk = 0;
       if (rem) {

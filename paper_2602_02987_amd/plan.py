@@ -185,11 +185,14 @@ def estimate_rates(arrivals_now, arrivals_before, n_servers, t_now, window, rho=
     return np.maximum(float(rho) * n_i / (float(n_servers) * w_eff), float(lam_min))
 
 
-def replan(cfg, lam_hat, **kw) -> Plan:
-    """Re-solves the fluid LP for new rate estimates with the mixed/solo split held at cfg.M servers
-    (sum_i x_i <= M/N); the plan's x are the gate's new occupancy targets (paper, online adaptive algorithm:
-    the LP is re-solved with the estimates in place of lambda_i)."""
-    return solve_lp(cfg, lam_hat, max_mixed_fraction=cfg.M / cfg.N, **kw)
+def replan(cfg, lam_hat, hold_split=True, **kw) -> Plan:
+    """Re-solves the fluid LP for new rate estimates (paper, online adaptive algorithm: the LP is re-solved with
+    the estimates in place of lambda_i). The plan's x are the gate's new occupancy targets. With `hold_split`
+    the mixed/solo split stays at cfg.M servers (sum_i x_i <= M/N); without it the plan's M is the new split
+    M*(t_k) = ceil(n sum_i x_i*(t_k)) (Eq. main-online-mixed-target)."""
+    if hold_split:
+        return solve_lp(cfg, lam_hat, max_mixed_fraction=cfg.M / cfg.N, **kw)
+    return solve_lp(cfg, lam_hat, **kw)
 
 
 def erlang_c(c: int, a: float) -> float:

@@ -25,7 +25,7 @@ def test_library_exports_every_declared_symbol(B):
     names = set(re.findall(r"^(?:int|const char \*)\s*\*?(sim_[a-z_]+)\(", header, flags=re.M))
     assert {"sim_workspace_bytes", "sim_create", "sim_run", "sim_stats", "sim_snapshot", "sim_destroy",
             "sim_strerror", "sim_tallies", "sim_hist", "sim_digest", "sim_kernel_time", "sim_set_targets",
-            "sim_patience_table"} <= names
+            "sim_patience_table", "sim_set_split"} <= names
     L = B.lib()
     for n in names:
         assert hasattr(L, n), n
