@@ -196,3 +196,33 @@ def test_targets_moved_between_runs(B, oracle_mod):
             assert_replication_equal(sim, orc, r, what=f"{cfg.name} after the old targets again")
     with pytest.raises(B.SimError):
         sim.set_targets([-1.0] * cfg.K, [0.0] * cfg.K)
+
+
+def test_largest_class_count_and_batch_together(B, oracle_mod):
+    """K = 8 and B = 128 at once (widest class tables, widest time-between-tokens window, full slot rows)."""
+    rng = np.random.default_rng(3)
+    cls = [_limits_class(lam=0.55, in_p0=float(rng.integers(60, 900)), out_p0=float(rng.integers(200, 2500)))
+           for _ in range(8)]
+    cfg = _limits_cfg("k8-b128", cls, N=600, M=120, B=128, steps=2500, replications=2)
+    sim, orc = run_both(B, oracle_mod, cfg, 2500, checkpoints=2)
+    assert_stats_equal(sim.stats(), orc.stats())
+    assert orc.slots(0)["n_dec"].max() > 64
+
+
+def test_degenerate_runs(B, oracle_mod):
+    """No arrivals at all; zero steps; one replication out of several allocated; one server."""
+    cfg = W.config(1, replications=3)
+    for c in cfg.classes:
+        c.lam = 0.0
+    sim, orc = run_both(B, oracle_mod, cfg, 500)
+    assert sim.stats()["tally"].sum() == 0
+    cfg = W.config(1, replications=4)
+    sim = B.Sim(cfg, max_replications=4); orc = oracle_mod.Oracle(cfg, max_reps=4)
+    sim.run(0, 1); orc.run(0, 1)              # nothing simulated yet: the empty system
+    assert_replication_equal(sim, orc, 0, what="zero steps")
+    sim.run(700, 1); orc.run(700, 1)          # one replication of the four the workspace holds
+    assert_replication_equal(sim, orc, 0, what="one of four")
+    with pytest.raises(B.SimError):
+        sim.run(10, 5)                        # more than the workspace was sized for
+    cfg = _heavy(N=1, M=0, B=1)
+    run_both(B, oracle_mod, cfg, 800)
