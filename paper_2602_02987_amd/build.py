@@ -14,7 +14,10 @@ FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared", "-ffp
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function",
          # the kernels combine the lanes of a wave themselves before they touch a shared counter; the
          # compiler's own rewrite of atomics into wave-wide scans only adds code around them
-         "-mllvm", "-amdgpu-atomic-optimizer-strategy=None"]
+         "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
+         # loops are unrolled where the source asks for it (#pragma unroll); unrolling the others by heuristic only
+         # lengthened the step kernel and measured slightly slower
+         "-fno-unroll-loops"]
 
 
 def build(verbose: bool = False) -> str:
