@@ -90,3 +90,22 @@ def test_workspace_size_scales_with_replications(B):
     a, b = B.sim_workspace_bytes(cfg, 8), B.sim_workspace_bytes(cfg, 16)
     per_rep = cfg.N * (8 + 4 + 4 + 8 + 8 + 8 + cfg.B * 12) + cfg.K * cfg.queue_cap * 4 + cfg.dbuf_cap * 8
     assert b > a and (b - a) >= 8 * per_rep
+
+
+def test_plan_of_config_1_matches_its_closed_forms():
+    """Underloaded two-class instance: the fluid LP serves everything, so R* = sum_i lambda_i w_i = 460.8 token-prices
+    per server and second, x*_i = lambda_i * (prefill service time), M = ceil(n sum x*); tau_mix = 29 ms,
+    tau_solo = 16.4 ms, and the solo pool is the faster one per slot (gamma * tau >= (B-1)/B)."""
+    from paper_2602_02987_amd import plan as P
+    cfg = W.config(1)
+    pl = P.solve_lp(cfg, [c.lam for c in cfg.classes])
+    r = P.rates(cfg)
+    assert pl.tau_mix == pytest.approx(0.029, rel=1e-12) and pl.tau_solo == pytest.approx(0.0164, rel=1e-12)
+    assert pl.tau_mix / pl.tau_solo >= (cfg.B - 1) / cfg.B
+    assert pl.value == pytest.approx(0.6 * (512 + 64) + 0.3 * (128 + 256), rel=1e-9)
+    service = r["ECH"] * (cfg.c0 + cfg.c_dec * (cfg.B - 1)) + cfg.c_pre * r["EP"]
+    assert np.allclose(pl.x, np.array([0.6, 0.3]) * service, rtol=1e-9)
+    assert r["EP"] == pytest.approx([512.0, 128.0], rel=2e-5) and r["ED"] == pytest.approx([64.0, 256.0], rel=2e-5)
+    # E ceil(P/C) of a geometric P: 1 / (1 - (1-p)^C)
+    assert r["ECH"] == pytest.approx([1.0 / (1.0 - (1.0 - 1.0 / m) ** 256) for m in (512.0, 128.0)], rel=1e-4)
+    assert cfg.M == pl.M == 1 and W.config(2).M == int(np.ceil(256 * pl.x.sum()))

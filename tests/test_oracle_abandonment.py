@@ -199,3 +199,32 @@ def test_theta_zero_changes_nothing(oracle_mod):
     t, _ = a.tallies(0)
     assert t[:, TI["AB_P"]].sum() == 0 and t[:, TI["AB_D"]].sum() == 0
     assert np.all(a.queue_deadlines(0, 0) == 0xFFFFFFFF)
+
+
+def test_overloaded_network_with_abandonment_sits_at_the_fluid_point(oracle_mod):
+    """With theta > 0 the fluid LP keeps its optimum (the unserved flow lambda_i - mu_p,i x_i* abandons instead of
+    queueing for ever): on the binding-capacity instance the revenue rate approaches R*, and the prefill backlog
+    settles where abandonment balances the unserved flow, q_p,i = (lambda_i - mu_p,i x_i*) / theta (per step:
+    Q_p,i * (1 - e^(-theta*dt)) = unserved arrivals per step)."""
+    from paper_2602_02987_amd import plan as P
+    from test_oracle_dynamics import _lp_instance, _window_revenue
+    theta = 0.1   # the rate of the paper's own convergence instance
+    cfg = _lp_instance(512, 1, 60000, (1024, 3072), (400, 160))
+    for c in cfg.classes:
+        c.theta = theta
+    pl = P.solve_lp(cfg, [c.lam for c in cfg.classes])
+    o = oracle_mod.Oracle(cfg)
+    o.run(20000); s0 = o.stats()
+    o.run(40000); s1 = o.stats()
+    t = s1["tally"].astype(np.float64) - s0["tally"].astype(np.float64)
+    nt = cfg.N * 40000 * cfg.c0
+    rev = sum(c.price_in * t[k, TI["TOKP_DEC"]] + c.price_out * t[k, TI["TOKD_DEC"]] for k, c in enumerate(cfg.classes)) / nt
+    assert rev == pytest.approx(pl.value, rel=0.03) and rev < pl.value   # (some decode-buffer waiters leave too)
+    lam = np.array([c.lam for c in cfg.classes])
+    unserved = lam - pl.served                                  # per server and second
+    assert np.any(unserved > 0.05)
+    qp = t[:cfg.K, TI["SUM_QP"]] / (cfg.N * 40000)              # per server
+    want = unserved * cfg.c0 / (1.0 - np.exp(-theta * cfg.c0))
+    assert np.allclose(qp, want, rtol=0.08, atol=0.15)
+    ab = t[:cfg.K, TI["AB_P"]] / nt
+    assert np.allclose(ab, unserved, rtol=0.08, atol=0.02)
