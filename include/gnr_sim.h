@@ -109,7 +109,7 @@ typedef struct {
   const double *x_star;          /* K prefill-occupancy targets per server; 0 = never admit (occupancy gate) */
   const double *qp_star;         /* K prefill-queue targets per server (gate tie-break) */
   int gate_mode;                 /* enum sim_gate */
-  int route_mode;                /* enum sim_route; RANDOM_SPLIT needs every theta = 0 in this version */
+  int route_mode;                /* enum sim_route */
   double mod_amp;                /* arrival modulation lambda(s) = lambda*(1 + amp*sin(2*pi*(s mod period)/period)) */
   int64_t mod_period;            /* in steps; 0 = homogeneous */
   int64_t queue_cap, dbuf_cap;   /* ring capacities: per class prefill queue, decode buffer */
@@ -165,7 +165,7 @@ int sim_workspace_bytes(const sim_config *cfg, int max_replications, size_t *out
 /* Validates and deep-copies the config, builds the sampler tables on the host and uploads them
  * into `dev_workspace` (device pointer, 256-byte aligned, owned by the caller, must outlive the
  * handle). SIM_EINVAL: bad sizes, negative target, M outside [0,N], dt > c0, negative theta, p_solo outside
- * [0,1] or missing or combined with a positive theta under RANDOM_SPLIT, total
+ * [0,1] or missing under RANDOM_SPLIT, total
  * arrival mean per server-step above 0.05 (the per-step count is truncated at 3).
  * SIM_ENOMEM: workspace too small. The library never allocates device memory itself. */
 int sim_create(const sim_config *cfg, int max_replications, void *dev_workspace, size_t bytes, sim_t **out);

@@ -40,7 +40,7 @@ constexpr uint32_t kStepsPerLaunch = 2048;
 
 struct Layout {
   size_t arr_thr, len_tab, t_next, iter, remptok, pf_job, n_cls, n_join, fin, job, qring, dring, cstate, tally, hist,
-      digest, reduced, params, pat_tab, qdl, ddl, cal, dcal, dring_m, total;
+      digest, reduced, params, pat_tab, qdl, ddl, cal, dcal, dring_m, ddl_m, dcal_m, total;
 };
 
 bool any_patience(const sim_config &c)
@@ -85,7 +85,13 @@ Layout make_layout(const sim_config &c, int R, int64_t rows, size_t cal_entries)
     L.cal = take(static_cast<size_t>(R) * c.K * cal_entries * sizeof(uint32_t));
     L.dcal = take(static_cast<size_t>(R) * c.K * cal_entries * sizeof(uint32_t));
   }
-  if (c.route_mode == SIM_ROUTE_RANDOM_SPLIT) L.dring_m = take(static_cast<size_t>(R) * c.dbuf_cap * sizeof(uint64_t));
+  if (c.route_mode == SIM_ROUTE_RANDOM_SPLIT) {
+    L.dring_m = take(static_cast<size_t>(R) * c.dbuf_cap * sizeof(uint64_t));
+    if (cal_entries) {
+      L.ddl_m = take(static_cast<size_t>(R) * c.dbuf_cap * sizeof(uint32_t));
+      L.dcal_m = take(static_cast<size_t>(R) * c.K * cal_entries * sizeof(uint32_t));
+    }
+  }
   L.total = off;
   return L;
 }
@@ -118,7 +124,7 @@ int validate(const sim_config *c, int max_reps, Ticks *t)
   if (c->route_mode == SIM_ROUTE_RANDOM_SPLIT) {
     if (!c->p_solo) return SIM_EINVAL;
     for (int k = 0; k < c->K; ++k)
-      if (!(c->p_solo[k] >= 0.0) || !(c->p_solo[k] <= 1.0) || c->cls[k].theta > 0.0) return SIM_EINVAL;
+      if (!(c->p_solo[k] >= 0.0) || !(c->p_solo[k] <= 1.0)) return SIM_EINVAL;
   }
   if (c->mod_period < 0 || !(std::fabs(c->mod_amp) <= 1.0)) return SIM_EINVAL;
   if (!(c->c0 > 0.0) || !(c->c_pre >= 0.0) || !(c->c_dec >= 0.0) || !(c->dt >= 0.0)) return SIM_EINVAL;
@@ -315,6 +321,10 @@ int sim_create(const sim_config *cfg, int max_replications, void *dev_workspace,
     p.ddl = reinterpret_cast<uint32_t *>(w + L.ddl);
     p.cal = reinterpret_cast<uint32_t *>(w + L.cal);
     p.dcal = reinterpret_cast<uint32_t *>(w + L.dcal);
+    if (cfg->route_mode == SIM_ROUTE_RANDOM_SPLIT) {
+      p.ddl_m = reinterpret_cast<uint32_t *>(w + L.ddl_m);
+      p.dcal_m = reinterpret_cast<uint32_t *>(w + L.dcal_m);
+    }
   }
 
   p.self = reinterpret_cast<const Params *>(w + L.params);

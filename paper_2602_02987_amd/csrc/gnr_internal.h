@@ -77,6 +77,7 @@ struct Params {
   uint32_t *ddl;              // [R][dbuf_cap]
   uint32_t *cal;              // [R][K][cal_mask+1] prefill queues
   uint32_t *dcal;             // [R][K][cal_mask+1] decode buffer
+  uint32_t *ddl_m, *dcal_m;   // the same for the mixed group's buffer of the randomized router
   // class state, tallies, histograms
   int32_t *cstate;            // [R][CS_WORDS]
   uint64_t *tally;            // [R][kTallyWords]

@@ -127,6 +127,8 @@ enum Scalar {
   // randomized router only:
   SC_NCS = 13,    // completed prefills of this step that joined the solo group's buffer
   SC_NCM = 14,    // ... the mixed group's buffer
+  SC_DLEN_M = 15, // randomized router with abandonment: SC_DLEN / SC_DSCAN of the mixed group's buffer ring
+  SC_DSCAN_M = 52,
   SC_QLEN = 32,   // [8] entries of each class queue ring between head and tail, abandoned ones included
   SC_TAKE = 16,   // [8] accepted arrivals this step
   SC_TAIL = 24,   // [8] ring position of the first accepted arrival
@@ -417,6 +419,7 @@ struct StepArrays {
   uint32_t *qdl, *ddl, *cal, *dcal;
   // randomized router only
   uint64_t *dring_m;
+  uint32_t *ddl_m, *dcal_m;   // ... with abandonment
 };
 
 // AB: the variant with abandonment (some class has a patience rate). Ring entries then carry the step at whose
@@ -473,6 +476,8 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
   uint32_t *dcal = AB ? a.dcal + static_cast<size_t>(r) * K * cal_n : nullptr;
   const uint32_t *lo_tab = AB ? L.live_off : nullptr;
   uint64_t *dring_m = RR ? a.dring_m + static_cast<size_t>(r) * p.dbuf_cap : nullptr;
+  uint32_t *ddl_m = AB && RR ? a.ddl_m + static_cast<size_t>(r) * p.dbuf_cap : nullptr;
+  uint32_t *dcal_m = AB && RR ? a.dcal_m + static_cast<size_t>(r) * K * cal_n : nullptr;
 
   // ---- load the replication's class state and rebuild the on-chip views of the server state
   for (int i = tid; i < CS_WORDS; i += NT) L.cs[i] = a.cstate[static_cast<size_t>(r) * CS_WORDS + i];
@@ -486,7 +491,10 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
   __syncthreads();
   if constexpr (AB) {   // between launches the rings hold waiting requests only
     if (tid < K) L.sc[SC_QLEN + tid] = L.cs[CS_QP + tid];
-    if (tid == 0) L.sc[SC_DLEN] = L.cs[CS_DCOUNT];
+    if (tid == 0) {
+      L.sc[SC_DLEN] = L.cs[CS_DCOUNT];
+      if constexpr (RR) L.sc[SC_DLEN_M] = L.cs[CS_DCOUNT_M];
+    }
   }
   for (int i = 0; i < nper; ++i) {
     const int g = i * NT + tid;
@@ -550,9 +558,12 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
       L.sc[SC_TAIL + k] = static_cast<int32_t>(tail);
     }
   };
-  auto compact_buffer = [&](uint32_t now) __attribute__((always_inline)) {
-    const uint32_t hd = static_cast<uint32_t>(L.cs[CS_DHEAD]);
-    uint32_t n = static_cast<uint32_t>(L.sc[SC_DLEN]);
+  // (`mixed`: the mixed group's buffer ring of the randomized router)
+  auto compact_buffer = [&](uint32_t now, bool mixed) __attribute__((always_inline)) {
+    uint64_t *dring = mixed ? dring_m : a.dring + static_cast<size_t>(r) * p.dbuf_cap;
+    uint32_t *ddl = mixed ? ddl_m : a.ddl + static_cast<size_t>(r) * p.dbuf_cap;
+    const uint32_t hd = static_cast<uint32_t>(L.cs[mixed ? CS_DHEAD_M : CS_DHEAD]);
+    uint32_t n = static_cast<uint32_t>(L.sc[mixed ? SC_DLEN_M : SC_DLEN]);
     if (n > p.dbuf_cap) n = p.dbuf_cap;
     uint32_t w = 0;
     for (uint32_t off = 0; off < n; off += 64) {   // wave-uniform
@@ -570,7 +581,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
       }
       w += static_cast<uint32_t>(__popcll(bal));
     }
-    if (lane == 0) L.sc[SC_DLEN] = static_cast<int32_t>(w);
+    if (lane == 0) L.sc[mixed ? SC_DLEN_M : SC_DLEN] = static_cast<int32_t>(w);
   };
 
   int64_t T = 0;
@@ -588,11 +599,12 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
     if (tid < 8) L.acc[tid] = 0;
     // abandonment only: how many waiting requests of class `tid` leave at the start of this step (asked for
     // here, used after the completion pass)
-    uint32_t n_leave_p = 0, n_leave_d = 0;
+    uint32_t n_leave_p = 0, n_leave_d = 0, n_leave_dm = 0;
     if constexpr (AB) {
       if (!final_pass && tid < K) {
         n_leave_p = atomicExch(&cal[static_cast<size_t>(tid) * cal_n + (s & p.cal_mask)], 0u);
         n_leave_d = atomicExch(&dcal[static_cast<size_t>(tid) * cal_n + (s & p.cal_mask)], 0u);
+        if constexpr (RR) n_leave_dm = atomicExch(&dcal_m[static_cast<size_t>(tid) * cal_n + (s & p.cal_mask)], 0u);
       }
     }
     const uint32_t *thr = a.arr_thr + 3 * (p.mod_period > 0 ? static_cast<int64_t>(s % static_cast<uint64_t>(p.mod_period)) : 0);
@@ -965,6 +977,13 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           L.tl[k * kNTally + SIM_T_AB_D] += n_leave_d;
           atomicSub(&L.cs[CS_DCOUNT], static_cast<int32_t>(n_leave_d));
         }
+        if constexpr (RR) {
+          if (n_leave_dm) {
+            L.cs[CS_QD + k] -= static_cast<int32_t>(n_leave_dm);
+            L.tl[k * kNTally + SIM_T_AB_D] += n_leave_dm;
+            atomicSub(&L.cs[CS_DCOUNT_M], static_cast<int32_t>(n_leave_dm));
+          }
+        }
       }
       const uint32_t a = L.acc[k];
       const uint32_t room = p.queue_cap - static_cast<uint32_t>(L.cs[CS_QP + k]);
@@ -999,13 +1018,20 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
         const uint32_t ncp = static_cast<uint32_t>(L.sc[SC_NCOMP]);
         const uint32_t room = p.dbuf_cap - static_cast<uint32_t>(L.cs[CS_DCOUNT]);
         if (static_cast<uint32_t>(L.sc[SC_DLEN]) + (ncp < room ? ncp : room) > p.dbuf_cap) atomicOr(&L.sc[SC_COMPACT], 256);
+        if constexpr (RR) {   // how the completions split between the two rings is not known yet: either may get all
+          const uint32_t room_m = p.dbuf_cap - static_cast<uint32_t>(L.cs[CS_DCOUNT_M]);
+          if (static_cast<uint32_t>(L.sc[SC_DLEN_M]) + (ncp < room_m ? ncp : room_m) > p.dbuf_cap) atomicOr(&L.sc[SC_COMPACT], 512);
+        }
       }
       __syncthreads();
       const int flags = L.sc[SC_COMPACT];   // cleared at the end of the step
       if (flags) {   // the same for every thread
         for (int k = wave; k < K; k += nwaves)
           if ((flags >> k) & 1) compact_queue(k, s, static_cast<uint32_t>(L.sc[SC_TAKE + k]));
-        if ((flags & 256) && wave == nwaves - 1) compact_buffer(s);
+        if ((flags & 256) && wave == nwaves - 1) compact_buffer(s, false);
+        if constexpr (RR) {
+          if ((flags & 512) && wave == (nwaves > 1 ? nwaves - 2 : 0)) compact_buffer(s, true);
+        }
         __syncthreads();
       }
     }
@@ -1036,6 +1062,8 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
         const uint32_t ncomp = static_cast<uint32_t>(L.sc[SC_NCOMP]);
         const uint32_t dc0 = static_cast<uint32_t>(L.cs[CS_DCOUNT]), dc1 = static_cast<uint32_t>(L.cs[CS_DCOUNT_M]);
         const uint32_t dh0 = static_cast<uint32_t>(L.cs[CS_DHEAD]), dh1 = static_cast<uint32_t>(L.cs[CS_DHEAD_M]);
+        // ring entries before the tail (with abandonment the dead entries count)
+        const uint32_t fill0 = AB ? static_cast<uint32_t>(L.sc[SC_DLEN]) : dc0, fill1 = AB ? static_cast<uint32_t>(L.sc[SC_DLEN_M]) : dc1;
         uint32_t seen0 = 0, seen1 = 0;   // completions sent to either group so far
         for (uint32_t j0 = 0; j0 < ncomp; j0 += 64) {   // wave-uniform
           const uint32_t j = j0 + lane;
@@ -1043,6 +1071,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           int k = 0;
           bool solo = false;
           uint64_t jw = 0;
+          uint32_t dl = kNever;
           if (active) {
             const int g = select_bit(L.bm_comp, L.pre_c, nwords_m, j);
             jw = pf_job[g];
@@ -1051,15 +1080,22 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
             philox4x32_10(key0, key1, s, static_cast<uint32_t>(kStreamPatienceD), static_cast<uint32_t>(g),
                           static_cast<uint32_t>(r), w);
             solo = w[1] < p.solo_thr[k];
+            if constexpr (AB) {
+              if ((p.ab_classes >> k) & 1u) dl = s + a.pat_tab[static_cast<size_t>(k) * kTableSize + (w[0] >> 16)];
+            }
           }
           const uint64_t bal0 = __ballot(active && solo), bal1 = __ballot(active && !solo);
           const uint32_t idx = solo ? seen0 + static_cast<uint32_t>(__popcll(bal0 & lanes_below()))
                                     : seen1 + static_cast<uint32_t>(__popcll(bal1 & lanes_below()));
           const bool kept = active && (solo ? dc0 : dc1) + idx < p.dbuf_cap;
           if (kept) {
-            uint32_t pos = (solo ? dh0 + dc0 : dh1 + dc1) + idx;
+            uint32_t pos = (solo ? dh0 + fill0 : dh1 + fill1) + idx;
             if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
             (solo ? dring : dring_m)[pos] = jw;
+            if constexpr (AB) {
+              (solo ? ddl : ddl_m)[pos] = dl;
+              if (dl != kNever) atomicAdd(&(solo ? dcal : dcal_m)[static_cast<size_t>(k) * cal_n + (dl & p.cal_mask)], 1u);
+            }
           }
           wave_count_by_class_i32(kept, k, K, &L.cs[CS_QD], 1);
           if (__ballot(active && !kept)) {
@@ -1150,10 +1186,15 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
         jrem = jremL[0] + jremL[1];
       }
       // abandonment only: ring entries of the decode buffer, this step's completions included
-      uint32_t dlen_all = AB ? static_cast<uint32_t>(L.sc[SC_DLEN]) + static_cast<uint32_t>(jrem - dcount0) : 0u;
+      uint32_t dlen_all = AB ? static_cast<uint32_t>(L.sc[SC_DLEN]) + static_cast<uint32_t>(RR ? L.sc[SC_NCS] : jrem - dcount0) : 0u;
       if (dlen_all > p.dbuf_cap) dlen_all = p.dbuf_cap;   // (never more: the ring was compacted if it had to be)
+      uint32_t dlen_all_m = AB && RR ? static_cast<uint32_t>(L.sc[SC_DLEN_M]) + static_cast<uint32_t>(L.sc[SC_NCM]) : 0u;
+      if (dlen_all_m > p.dbuf_cap) dlen_all_m = p.dbuf_cap;
       if constexpr (AB) {
-        if (tid == 0) L.sc[SC_DSCAN] = 0;
+        if (tid == 0) {
+          L.sc[SC_DSCAN] = 0;
+          if constexpr (RR) L.sc[SC_DSCAN_M] = 0;
+        }
       }
       bool gate_on = true, route_on = jrem > 0;
       for (int pass = 0; gate_on || route_on; ++pass) {
@@ -1458,30 +1499,40 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           // the requests this pass places are staged in LDS
           const int nstage = total < kJobsLds ? total : kJobsLds;
           if constexpr (AB) {
-            // one wave walks the ring from where the last pass stopped and stages the next `total` waiting jobs
-            if (wave == 0) {
-              uint32_t off = static_cast<uint32_t>(L.sc[SC_DSCAN]), found = 0, stop = off;
-              const uint32_t need = static_cast<uint32_t>(total);
-              for (; off < dlen_all && found < need; off += 64) {   // wave-uniform
+            // one wave walks a ring from where the last pass stopped and stages the next `need` waiting jobs
+            auto stage_ring = [&](const uint64_t *ring, const uint32_t *dlr, uint32_t *calr, uint32_t hd, uint32_t len,
+                                  int scan_word, uint32_t need, int first_job) __attribute__((always_inline)) {
+              uint32_t off = static_cast<uint32_t>(L.sc[scan_word]), found = 0, stop = off;
+              for (; off < len && found < need; off += 64) {   // wave-uniform
                 const uint32_t i = off + lane;
-                uint32_t pos = dhead0 + i;
+                uint32_t pos = hd + i;
                 if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
-                const uint32_t dl = i < dlen_all ? ddl[pos] : 0u;
-                const bool live = i < dlen_all && dl > s;
+                const uint32_t dl = i < len ? dlr[pos] : 0u;
+                const bool live = i < len && dl > s;
                 const uint64_t bal = __ballot(live);
                 const uint32_t rk = found + static_cast<uint32_t>(__popcll(bal & lanes_below()));
                 const bool mine = live && rk < need;
                 if (mine) {
-                  const uint64_t jw = dring[pos];
-                  L.jobs[rk] = jw;
+                  const uint64_t jw = ring[pos];
+                  L.jobs[first_job + rk] = jw;
                   if (dl != kNever)
-                    atomicSub(&dcal[static_cast<size_t>((jw >> 29) & 7u) * cal_n + (dl & p.cal_mask)], 1u);
+                    atomicSub(&calr[static_cast<size_t>((jw >> 29) & 7u) * cal_n + (dl & p.cal_mask)], 1u);
                 }
                 const uint64_t last = __ballot(mine && rk + 1 == need);
                 if (last) stop = off + static_cast<uint32_t>(__ffsll(static_cast<long long>(last)));   // one past the last staged entry
                 found += static_cast<uint32_t>(__popcll(bal));
               }
-              if (lane == 0) L.sc[SC_DSCAN] = static_cast<int32_t>(found >= need ? stop : dlen_all);   // (found < need: see the gate's scan)
+              if (lane == 0) L.sc[scan_word] = static_cast<int32_t>(found >= need ? stop : len);   // (found < need: see the gate's scan)
+            };
+            if (wave == 0) {
+              if constexpr (RR) {
+                if (takenL[0] > 0)
+                  stage_ring(dring, ddl, dcal, dheadL[0], dlen_all, SC_DSCAN, static_cast<uint32_t>(takenL[0]), 0);
+                if (takenL[1] > 0)
+                  stage_ring(dring_m, ddl_m, dcal_m, dheadL[1], dlen_all_m, SC_DSCAN_M, static_cast<uint32_t>(takenL[1]), takenL[0]);
+              } else {
+                stage_ring(dring, ddl, dcal, dhead0, dlen_all, SC_DSCAN, static_cast<uint32_t>(total), 0);
+              }
             }
           } else if constexpr (RR) {
             for (int j = tid; j < nstage; j += NT) {
@@ -1650,8 +1701,16 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           uint32_t h = dhead0 + past;
           if (h >= p.dbuf_cap) h -= p.dbuf_cap;
           L.cs[CS_DHEAD] = static_cast<int32_t>(h);
-          L.cs[CS_DCOUNT] -= next;
+          L.cs[CS_DCOUNT] -= RR ? nextL[0] : next;
           L.sc[SC_DLEN] = static_cast<int32_t>(dlen_all - past);
+          if constexpr (RR) {
+            const uint32_t past_m = static_cast<uint32_t>(L.sc[SC_DSCAN_M]);
+            h = dheadL[1] + past_m;
+            if (h >= p.dbuf_cap) h -= p.dbuf_cap;
+            L.cs[CS_DHEAD_M] = static_cast<int32_t>(h);
+            L.cs[CS_DCOUNT_M] -= nextL[1];
+            L.sc[SC_DLEN_M] = static_cast<int32_t>(dlen_all_m - past_m);
+          }
           L.sc[SC_COMPACT] = 0;
         }
       } else if constexpr (RR) {
@@ -1691,7 +1750,10 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
   if constexpr (AB) {   // the rings leave the launch without dead entries
     const uint32_t s_last = step_begin + n_steps - 1u;
     for (int k = wave; k < K; k += nwaves) compact_queue(k, s_last, 0u);
-    if (wave == nwaves - 1) compact_buffer(s_last);
+    if (wave == nwaves - 1) compact_buffer(s_last, false);
+    if constexpr (RR) {
+      if (wave == (nwaves > 1 ? nwaves - 2 : 0)) compact_buffer(s_last, true);
+    }
     __syncthreads();
   }
 
@@ -1753,7 +1815,10 @@ __global__ void gnr_reset_kernel(const Params p, const int reps)
   for (size_t i = t0; i < static_cast<size_t>(reps) * kTallyWords; i += stride) p.tally[i] = 0;
   for (size_t i = t0; i < static_cast<size_t>(reps) * 3 * p.K * kNBin; i += stride) p.hist[i] = 0;
   if (p.ab_classes)
-    for (size_t i = t0; i < static_cast<size_t>(reps) * p.K * (p.cal_mask + 1u); i += stride) { p.cal[i] = 0; p.dcal[i] = 0; }
+    for (size_t i = t0; i < static_cast<size_t>(reps) * p.K * (p.cal_mask + 1u); i += stride) {
+      p.cal[i] = 0; p.dcal[i] = 0;
+      if (p.dcal_m) p.dcal_m[i] = 0;
+    }
 }
 
 // ------------------------------------------------------------------ reduce ----
@@ -1832,10 +1897,13 @@ __global__ void gnr_digest_kernel(const Params p)
   if (p.route_mode == SIM_ROUTE_RANDOM_SPLIT) {   // the mixed group's buffer
     const uint32_t head = static_cast<uint32_t>(cs[CS_DHEAD_M]), len = static_cast<uint32_t>(cs[CS_DCOUNT_M]);
     const uint64_t *ring = p.dring_m + static_cast<size_t>(r) * p.dbuf_cap;
+    const uint32_t *dlr = p.ab_classes ? p.ddl_m + static_cast<size_t>(r) * p.dbuf_cap : nullptr;
     for (uint32_t i = tid; i < len; i += NT) {
       uint32_t pos = head + i;
       if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
-      d += chain(chain(6, i), ring[pos]);
+      uint64_t h = chain(chain(6, i), ring[pos]);
+      if (dlr) h = chain(h, dlr[pos]);
+      d += h;
     }
   }
   for (int g = tid; g < N; g += NT) {
@@ -1873,9 +1941,10 @@ int launch_reset(const Params &p, int reps, void *stream)
 int launch_steps(const Params &p, int reps, int threads, size_t lds_bytes, uint32_t step_begin, uint32_t n_steps,
                  void *stream)
 {
-  if (p.ab_classes && p.route_mode == SIM_ROUTE_RANDOM_SPLIT) return SIM_EINVAL;   // not built together
   auto kernel =
-      p.ab_classes
+      p.ab_classes && p.route_mode == SIM_ROUTE_RANDOM_SPLIT
+          ? (threads > 768 ? gnr_step_kernel<1024, true, true> : threads > 512 ? gnr_step_kernel<768, true, true> : gnr_step_kernel<512, true, true>)
+      : p.ab_classes
           ? (threads > 768 ? gnr_step_kernel<1024, true, false> : threads > 512 ? gnr_step_kernel<768, true, false> : gnr_step_kernel<512, true, false>)
       : p.route_mode == SIM_ROUTE_RANDOM_SPLIT
           ? (threads > 768 ? gnr_step_kernel<1024, false, true> : threads > 512 ? gnr_step_kernel<768, false, true> : gnr_step_kernel<512, false, true>)
@@ -1887,7 +1956,7 @@ int launch_steps(const Params &p, int reps, int threads, size_t lds_bytes, uint3
   }
   const StepArrays a = {p.arr_thr, p.len_tab, p.t_next, p.iter, p.remptok, p.pf_job, p.n_cls, p.n_join,
                         p.fin,     p.job,     p.qring,  p.dring, p.cstate, p.tally,  p.hist,
-                        p.pat_tab, p.qdl,     p.ddl,    p.cal,   p.dcal,   p.dring_m};
+                        p.pat_tab, p.qdl,     p.ddl,    p.cal,   p.dcal,   p.dring_m, p.ddl_m, p.dcal_m};
   hipLaunchKernelGGL(kernel, dim3(reps), dim3(threads), lds_bytes, static_cast<hipStream_t>(stream), p.self, a, p.key0,
                      p.key1, step_begin, n_steps);
   return hip_ok(hipGetLastError());

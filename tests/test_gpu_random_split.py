@@ -72,10 +72,35 @@ def test_config5_width_with_the_randomized_router_on_a_sampled_replication(B, or
     run_both(B, oracle_mod, cfg, 2500, oracle_reps=[1], checkpoints=2)
 
 
-def test_unsupported_combinations_are_rejected(B):
-    cfg = _split(_heavy(), (0.5, 0.5, 0.5))
-    cfg.classes = [replace(c, theta=1.0) for c in cfg.classes]
-    with pytest.raises(B.SimError):
-        B.Sim(cfg)
+def test_bad_split_probabilities_are_rejected(B):
     with pytest.raises(B.SimError):
         B.Sim(_split(_heavy(), (0.5, 1.5, 0.5)))
+
+
+@pytest.mark.parametrize("gate", [W.GATE_OCCUPANCY, W.GATE_FCFS])
+def test_randomized_router_with_abandonment(B, oracle_mod, gate):
+    """Both group buffers hold dead entries, are compacted and overflow; requests leave from either."""
+    for over, ps in ((dict(), (0.8, 0.3, 0.55)), (dict(M=1), (1.0, 0.0, 0.5)), (dict(B=1, M=6), (0.5, 0.5, 0.5)),
+                     (dict(dbuf_cap=4096, queue_cap=4096), (0.2, 0.9, 0.6)), (dict(N=1, M=1, B=1), (0.4, 0.4, 0.4))):
+        cfg = _split(_heavy(gate, **over), ps)
+        cfg.classes = [replace(c, theta=th) for c, th in zip(cfg.classes, (4.0, 0.0, 25.0))]
+        sim, orc = run_both(B, oracle_mod, cfg, 2500, checkpoints=5)
+        ss, os_ = sim.stats(), orc.stats()
+        assert_stats_equal(ss, os_)
+        assert ss["overflow"] == bool(os_["glob"][5])
+        if not over:
+            assert os_["tally"][:, TI["AB_D"]].sum() > 0 and os_["tally"][:, TI["AB_P"]].sum() > 0
+
+
+def test_randomized_router_with_abandonment_on_wide_workgroups(B, oracle_mod):
+    for N, M, Bcap, steps, ps in ((700, 30, 8, 900, (0.6, 0.4)), (8192, 300, 2, 300, (0.9, 0.8)), (8192, 5000, 8, 60, (0.5, 0.5))):
+        cls = [_limits_class(lam=2.4, theta=3.0, out_p0=300.0), _limits_class(lam=2.0, in_p0=40.0, out_p0=500.0, theta=9.0)]
+        cfg = _split(_limits_cfg(f"ab-rr-{N}-{M}-{Bcap}", cls, N=N, M=M, B=Bcap, steps=steps, replications=1,
+                                 dbuf_cap=2048, queue_cap=8192), ps)
+        sim, orc = run_both(B, oracle_mod, cfg, steps, checkpoints=2)
+        t, g = orc.tallies(0)
+        assert sim.stats()["overflow"] == bool(g[5])
+        if M < 1000:
+            assert t[:, TI["AB_P"]].sum() > 500
+        if Bcap == 2:
+            assert t[:, TI["AB_D"]].sum() > 1000

@@ -54,6 +54,9 @@ def test_moves_with_abandonment_and_with_the_randomized_router(B, oracle_mod):
     _run_moves(B, oracle_mod, cfg, [(None, 400), (10, 400), (2, 400), (7, 400)])
     cfg = replace(_heavy(queue_cap=4096, dbuf_cap=4096), route_mode=W.ROUTE_RANDOM_SPLIT, p_solo=[0.8, 0.3, 0.55])
     _run_moves(B, oracle_mod, cfg, [(None, 400), (10, 400), (2, 400), (7, 400)])
+    cfg = replace(_heavy(), route_mode=W.ROUTE_RANDOM_SPLIT, p_solo=[0.8, 0.3, 0.55])   # both at once, small rings
+    cfg.classes = [replace(c, theta=th) for c, th in zip(cfg.classes, (4.0, 0.0, 25.0))]
+    _run_moves(B, oracle_mod, cfg, [(None, 400), (10, 400), (2, 400), (7, 400)])
 
 
 def test_config5_width_with_a_moving_split(B, oracle_mod):
