@@ -52,7 +52,7 @@
 
 enum { LAW_GEOMETRIC = 0, LAW_LOGNORMAL = 1, LAW_CONST = 2, LAW_TABLE = 3 };
 enum { GATE_OCCUPANCY = 0, GATE_PRIORITY = 1, GATE_FCFS = 2 };
-enum { ROUTE_SOLO_FIRST = 0, ROUTE_RANDOM_SPLIT = 1 };
+enum { ROUTE_SOLO_FIRST = 0, ROUTE_RANDOM_SPLIT = 1, ROUTE_IMMEDIATE = 2 };
 
 /* per-class tally indices */
 enum {
@@ -319,7 +319,7 @@ int oracle_create(const oracle_config *cfg, int max_reps, oracle_t **out)
     if (!(cfg->cls[k].theta >= 0.0) || !isfinite(cfg->cls[k].theta) || !(cfg->cls[k].lambda >= 0.0) ||
         cfg->x_star[k] < 0.0) { free(o); return -1; }
   }
-  if (cfg->route_mode != ROUTE_SOLO_FIRST && cfg->route_mode != ROUTE_RANDOM_SPLIT) { free(o); return -1; }
+  if (cfg->route_mode < ROUTE_SOLO_FIRST || cfg->route_mode > ROUTE_IMMEDIATE) { free(o); return -1; }
   if (cfg->route_mode == ROUTE_RANDOM_SPLIT) {
     if (!cfg->p_solo) { free(o); return -1; }
     for (int k = 0; k < cfg->K; k++) {
@@ -454,7 +454,10 @@ static int64_t check_rep(oracle_t *o, int r)
     /* per-server capacity (Sec. 2.3). After the split has moved, work that was there before stays (no
      * pre-emption): a server that turned mixed may still hold B decodes, one that turned solo its prefill. */
     if (used > B) viol(o, 107);
-    if (!o->split_moved) {
+    if (o->cfg.route_mode == ROUTE_IMMEDIATE) {
+      if (used + (s->pf_rem ? 1 : 0) > B) viol(o, 106);   /* a request keeps its slot from prefill to its last token */
+      if (g >= M && !o->split_moved && (used || s->pf_rem)) viol(o, 108);
+    } else if (!o->split_moved) {
       if (g < M) { if (used > B - 1) viol(o, 106); } else { if (s->pf_rem) viol(o, 108); }
     }
     if (s->pf_rem) {
@@ -474,7 +477,10 @@ static int64_t check_rep(oracle_t *o, int r)
   if (o->cfg.route_mode == ROUTE_SOLO_FIRST && R->dbuf_m.len) viol(o, 124);
   /* capacity constraints */
   if (Xtot > N) viol(o, 120);
-  if (!o->split_moved) {
+  if (o->cfg.route_mode == ROUTE_IMMEDIATE) {
+    if (Ymtot > (int64_t)(B - 1) * Xtot) viol(o, 121);
+    if (R->dbuf.len || R->dbuf_m.len) viol(o, 125);      /* nobody ever waits for a decode slot */
+  } else if (!o->split_moved) {
     if (Ymtot > (int64_t)(B - 1) * Xtot) viol(o, 121);
     if (Ystot > (int64_t)B * (N - Xtot)) viol(o, 122);
   } else {
@@ -641,6 +647,20 @@ static void step_rep(oracle_t *o, int r, uint32_t s)
         /* block (step, stream 10, server, replication): word 0 -> patience for the wait in the decode
          * buffer; word 1 -> under the randomized router (Sec. 5.2), the group the decode is sent to:
          * solo with probability p_s,i, else mixed, each with its own FIFO buffer */
+        if (o->cfg.route_mode == ROUTE_IMMEDIATE) {
+          /* Immediate same-slot decode (the "I" rule of the paper's ablation study): the request goes on
+           * decoding on the server that prefilled it, in the slot it already holds; the gate has seen to
+           * it that the slot exists. It joins the batch at the restart that follows this completion. */
+          int j = 0; while (j < B && sv->slot[j].used) j++;
+          if (j < B) {
+            slot_t *e = &sv->slot[j];
+            e->used = 1; e->cls = k; e->P = sv->pf_P; e->D = sv->pf_D; e->stamp = sv->pf_stamp;
+            e->fin = sv->iter + (uint32_t)sv->pf_D;
+            sv->n_dec++; sv->n_cls[k]++;
+            R->tally[k][T_U_DS]++; R->Ys[k]++;
+          } else { R->tally[k][T_DROP_D]++; R->glob[G_OVERFLOW] = 1; }
+          goto prefill_done;
+        }
         fifojob *buf = &R->dbuf;
         if (o->cfg.route_mode == ROUTE_RANDOM_SPLIT) {
           draw(o, r, g, s, 10u, w);
@@ -651,6 +671,7 @@ static void step_rep(oracle_t *o, int r, uint32_t s)
           if (o->tab_pat[k]) { draw(o, r, g, s, 10u, w); jb.dl = s + o->tab_pat[k][w[0] >> 16]; }
           fj_push(buf, jb); R->Qd[k]++;
         } else { R->tally[k][T_DROP_D]++; R->glob[G_OVERFLOW] = 1; }
+        prefill_done: ;
       }
     }
     for (int k = 0; k < K; k++) sv->n_join[k] = 0;
@@ -661,6 +682,7 @@ static void step_rep(oracle_t *o, int r, uint32_t s)
   for (int g = 0; g < M; g++) {
     server_t *sv = &R->sv[g];
     if (sv->pf_rem) continue;
+    if (o->cfg.route_mode == ROUTE_IMMEDIATE && sv->n_dec >= B) continue;   /* no slot for one more request */
     int best = -1; double bxi = 0.0, bdl = 0.0;
     for (int i = 0; i < K; i++) {
       if (R->Qp[i] <= 0) continue;

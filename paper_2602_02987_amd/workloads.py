@@ -22,7 +22,7 @@ from . import plan as _plan
 
 LAW_GEOMETRIC, LAW_LOGNORMAL, LAW_CONST, LAW_TABLE = 0, 1, 2, 3
 GATE_OCCUPANCY, GATE_PRIORITY, GATE_FCFS = 0, 1, 2
-ROUTE_SOLO_FIRST, ROUTE_RANDOM_SPLIT = 0, 1
+ROUTE_SOLO_FIRST, ROUTE_RANDOM_SPLIT, ROUTE_IMMEDIATE = 0, 1, 2
 
 
 @dataclass
