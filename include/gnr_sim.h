@@ -61,8 +61,13 @@ enum sim_gate { SIM_GATE_OCCUPANCY = 0, SIM_GATE_PRIORITY = 1, SIM_GATE_FCFS = 2
  * has its own FIFO buffer (capacity dbuf_cap each) that feeds that group only; within the group the placement
  * rule is the same as for SOLO_FIRST (least-loaded feasible server, lowest index). The draw is word 1 of block
  * (step, stream 10, server of the prefill, replication): solo iff word < floor(p_s,i * 2^32) (clamped to
- * 2^32 - 1, so p_s,i = 1 sends one request in 2^32 to the mixed group). */
-enum sim_route { SIM_ROUTE_SOLO_FIRST = 0, SIM_ROUTE_RANDOM_SPLIT = 1 };
+ * 2^32 - 1, so p_s,i = 1 sends one request in 2^32 to the mixed group).
+ * IMMEDIATE: no decoupled router (the "I" decode rule of the paper's ablation study, policies GI-WSP and FI-WSP):
+ * a request whose prefill completes goes on decoding on the same server, in the slot it already holds, and joins
+ * the batch at the restart that follows; a server holds at most B requests, its prefill included, so the gate
+ * admits only to servers with no prefill in service and fewer than B decodes; the decode buffer stays empty.
+ * ("WSP", without static planning, is a configuration with M = N.) */
+enum sim_route { SIM_ROUTE_SOLO_FIRST = 0, SIM_ROUTE_RANDOM_SPLIT = 1, SIM_ROUTE_IMMEDIATE = 2 };
 
 /* Per-class cumulative tallies (uint64), in this order. Counting processes as in Sec. 2.3:
  * A arrivals, U_P admissions to prefill, S_P prefill completions, U_DM/U_DS admissions to a

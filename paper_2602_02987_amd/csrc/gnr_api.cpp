@@ -120,7 +120,7 @@ int validate(const sim_config *c, int max_reps, Ticks *t)
   if (c->queue_cap < 1 || c->queue_cap > (int64_t(1) << 30) || c->dbuf_cap < 1 || c->dbuf_cap > (int64_t(1) << 30))
     return SIM_EINVAL;
   if (c->gate_mode < SIM_GATE_OCCUPANCY || c->gate_mode > SIM_GATE_FCFS) return SIM_EINVAL;
-  if (c->route_mode != SIM_ROUTE_SOLO_FIRST && c->route_mode != SIM_ROUTE_RANDOM_SPLIT) return SIM_EINVAL;
+  if (c->route_mode < SIM_ROUTE_SOLO_FIRST || c->route_mode > SIM_ROUTE_IMMEDIATE) return SIM_EINVAL;
   if (c->route_mode == SIM_ROUTE_RANDOM_SPLIT) {
     if (!c->p_solo) return SIM_EINVAL;
     for (int k = 0; k < c->K; ++k)

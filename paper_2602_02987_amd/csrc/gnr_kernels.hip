@@ -430,7 +430,10 @@ struct StepArrays {
 // RR: the variant with the randomized decode router: every completed prefill is sent to the solo or to the
 // mixed group by a random word, each group has its own buffer ring and is fed from that ring only. A routing
 // pass then takes jobs from both rings: the staged list holds the solo ring's jobs first.
-template <int MAXT, bool AB, bool RR>
+// IM: the variant with immediate same-slot decode (no router): a request whose prefill ends goes on decoding on
+// its own server, placed there by the lane that finishes the server; a server is offered to the gate while it
+// holds no prefill and fewer than B decodes.
+template <int MAXT, bool AB, bool RR, bool IM>
 __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict__ params, const StepArrays a,
                                                         const uint32_t key0, const uint32_t key1,
                                                         const uint32_t step_begin, const uint32_t n_steps)
@@ -515,7 +518,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
     if (valid && g < Mp) {   // the prefill word stays in LDS during the launch: tokens left, and whether a chunk runs
       const uint32_t pk = remptok[g];
       L.rem[g] = static_cast<uint16_t>(pk_rem(pk));
-      idle_slot = pk_rem(pk) == 0;
+      idle_slot = pk_rem(pk) == 0 && (!IM || static_cast<int>(byte_sum(n_cls[g])) < B);
       chunk = pk_ptok(pk) > 0;
     }
     const uint64_t bi = __ballot(idle_slot), bb = __ballot(busy), bj = __ballot(joined), bc = __ballot(chunk);
@@ -698,6 +701,9 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
               const int hb = g < M ? kLoadBins : 0;
               atomicSub(&L.lh[hb + nd_before], 1u);
               atomicAdd(&L.lh[hb + nd], 1u);
+              if constexpr (IM) {   // a full server (it holds no prefill then) has a slot again
+                if (nd_before == B && g < Mp) atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_idle[g >> 6]), bit);
+              }
             }
           }
           // the prefill advances by the chunk frozen at the start of the iteration
@@ -713,8 +719,30 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
               pe.P = (static_cast<uint32_t>(jw >> 32) & 0xFFFFu) + 1;
               pe.ttft = tn - (static_cast<int64_t>(stamp) + 1) * p.dt;
               atomicAdd(reinterpret_cast<unsigned long long *>(&hist[(0 * K + k) * kNBin + hbin(pe.ttft)]), 1ull);
+              if constexpr (IM) {
+                // the request keeps its slot: it joins the batch at the restart that follows this completion
+                // (the gate admits only where a slot is left, so nd < B here; were it not, the request is dropped)
+                if (nd >= B) {
+                  lds_add64(&L.tl[k * kNTally + SIM_T_DROP_D], 1);
+                  L.tl[kMaxK * kNTally + SIM_G_OVERFLOW] = 1;
+                } else {
+                const uint32_t Dl = static_cast<uint32_t>(jw >> 48) + 1;
+                fin[static_cast<size_t>(g) * BS + nd] = it + Dl;
+                job[static_cast<size_t>(g) * BS + nd] = jw;
+                n_cls[g] = nc + (1ull << (8 * k));
+                const int hb = g < M ? kLoadBins : 0;
+                atomicSub(&L.lh[hb + nd], 1u);
+                atomicAdd(&L.lh[hb + nd + 1], 1u);
+                ++nd;
+                L.loads[g] = static_cast<uint8_t>(nd);
+                lds_add64(&L.tl[k * kNTally + SIM_T_U_DS], 1);
+                atomicAdd(&L.cs[CS_YS + k], 1);
+                if (nd < B) atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_idle[g >> 6]), bit);
+                }
+              } else {
               atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_comp[g >> 6]), bit);
               atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_idle[g >> 6]), bit);
+              }
             }
           }
           if (joined) {
@@ -852,7 +880,8 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           o_nd = nd;
           o_pend = pend;
         }
-        const bool prefill_here = g < Mp && !(idle_word & lbit);
+        // (with immediate decode the bitmap marks the servers the gate may admit to: a full one is not in it)
+        const bool prefill_here = IM ? rem_v != 0 : (g < Mp && !(idle_word & lbit));
         o_must = o_due && ((join_word & lbit) || prefill_here || o_pend >= kMaxPend);
         o_scan = o_due && o_nd > 0;
         o_big = o_scan && o_nd > 64;   // the row's second half holds decodes too
@@ -1941,14 +1970,19 @@ int launch_reset(const Params &p, int reps, void *stream)
 int launch_steps(const Params &p, int reps, int threads, size_t lds_bytes, uint32_t step_begin, uint32_t n_steps,
                  void *stream)
 {
-  auto kernel =
-      p.ab_classes && p.route_mode == SIM_ROUTE_RANDOM_SPLIT
-          ? (threads > 768 ? gnr_step_kernel<1024, true, true> : threads > 512 ? gnr_step_kernel<768, true, true> : gnr_step_kernel<512, true, true>)
-      : p.ab_classes
-          ? (threads > 768 ? gnr_step_kernel<1024, true, false> : threads > 512 ? gnr_step_kernel<768, true, false> : gnr_step_kernel<512, true, false>)
-      : p.route_mode == SIM_ROUTE_RANDOM_SPLIT
-          ? (threads > 768 ? gnr_step_kernel<1024, false, true> : threads > 512 ? gnr_step_kernel<768, false, true> : gnr_step_kernel<512, false, true>)
-          : (threads > 768 ? gnr_step_kernel<1024, false, false> : threads > 512 ? gnr_step_kernel<768, false, false> : gnr_step_kernel<512, false, false>);
+  using StepKernel = void (*)(const Params *, StepArrays, uint32_t, uint32_t, uint32_t, uint32_t);
+  const int size = threads > 768 ? 2 : threads > 512 ? 1 : 0;
+  const bool ab = p.ab_classes != 0;
+  static const StepKernel table[3][2][3] = {
+      // [workgroup size][abandonment][router: solo-first, randomized, immediate]
+      {{gnr_step_kernel<512, false, false, false>, gnr_step_kernel<512, false, true, false>, gnr_step_kernel<512, false, false, true>},
+       {gnr_step_kernel<512, true, false, false>, gnr_step_kernel<512, true, true, false>, gnr_step_kernel<512, true, false, true>}},
+      {{gnr_step_kernel<768, false, false, false>, gnr_step_kernel<768, false, true, false>, gnr_step_kernel<768, false, false, true>},
+       {gnr_step_kernel<768, true, false, false>, gnr_step_kernel<768, true, true, false>, gnr_step_kernel<768, true, false, true>}},
+      {{gnr_step_kernel<1024, false, false, false>, gnr_step_kernel<1024, false, true, false>, gnr_step_kernel<1024, false, false, true>},
+       {gnr_step_kernel<1024, true, false, false>, gnr_step_kernel<1024, true, true, false>, gnr_step_kernel<1024, true, false, true>}}};
+  if (p.route_mode < 0 || p.route_mode > 2) return SIM_EINVAL;
+  const StepKernel kernel = table[size][ab ? 1 : 0][p.route_mode];
   if (lds_bytes > 64 * 1024) {   // more than the default dynamic LDS limit has to be asked for
     const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes));
