@@ -1266,15 +1266,25 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
               const uint32_t hd = static_cast<uint32_t>(L.cs[CS_QHEAD + k]);
               const uint32_t *dlr = qdl + static_cast<size_t>(k) * p.queue_cap;
               uint32_t found = 0;
-              for (uint32_t off = 0; off < qlen && found < need; off += 64) {   // wave-uniform
-                const uint32_t i = off + lane;
-                uint32_t pos = hd + i;
-                if (pos >= p.queue_cap) pos -= p.queue_cap;
-                const bool live = i < qlen && dlr[pos] > s;
-                const uint64_t bal = __ballot(live);
-                const uint32_t rk = found + static_cast<uint32_t>(__popcll(bal & lanes_below()));
-                if (live && rk < need) L.live_off[k * kAdmChunk + rk] = i;
-                found += static_cast<uint32_t>(__popcll(bal));
+              // four chunks of 64 entries per round: their deadlines are loaded together, one trip to memory
+              for (uint32_t off = 0; off < qlen && found < need; off += 256) {   // wave-uniform
+                uint32_t dl4[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                  const uint32_t i = off + 64u * u + lane;
+                  uint32_t pos = hd + i;
+                  if (pos >= p.queue_cap) pos -= p.queue_cap;
+                  dl4[u] = i < qlen ? dlr[pos] : 0u;   // (beyond the ring: counts as dead)
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                  const uint32_t i = off + 64u * u + lane;
+                  const bool live = dl4[u] > s;
+                  const uint64_t bal = __ballot(live);
+                  const uint32_t rk = found + static_cast<uint32_t>(__popcll(bal & lanes_below()));
+                  if (live && rk < need) L.live_off[k * kAdmChunk + rk] = i;
+                  found += static_cast<uint32_t>(__popcll(bal));
+                }
               }
               // (the ring holds as many live entries as the class counter says; if it ever did not, the
               // candidates beyond them would point at the head entry)
@@ -1532,24 +1542,34 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
             auto stage_ring = [&](const uint64_t *ring, const uint32_t *dlr, uint32_t *calr, uint32_t hd, uint32_t len,
                                   int scan_word, uint32_t need, int first_job) __attribute__((always_inline)) {
               uint32_t off = static_cast<uint32_t>(L.sc[scan_word]), found = 0, stop = off;
-              for (; off < len && found < need; off += 64) {   // wave-uniform
-                const uint32_t i = off + lane;
-                uint32_t pos = hd + i;
-                if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
-                const uint32_t dl = i < len ? dlr[pos] : 0u;
-                const bool live = i < len && dl > s;
-                const uint64_t bal = __ballot(live);
-                const uint32_t rk = found + static_cast<uint32_t>(__popcll(bal & lanes_below()));
-                const bool mine = live && rk < need;
-                if (mine) {
-                  const uint64_t jw = ring[pos];
-                  L.jobs[first_job + rk] = jw;
-                  if (dl != kNever)
-                    atomicSub(&calr[static_cast<size_t>((jw >> 29) & 7u) * cal_n + (dl & p.cal_mask)], 1u);
+              // four chunks of 64 entries per round: deadlines and requests are loaded together
+              for (; off < len && found < need; off += 256) {   // wave-uniform
+                uint32_t dl4[4];
+                uint64_t jw4[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                  const uint32_t i = off + 64u * u + lane;
+                  uint32_t pos = hd + i;
+                  if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
+                  dl4[u] = i < len ? dlr[pos] : 0u;   // (beyond the ring: counts as dead)
+                  jw4[u] = i < len ? ring[pos] : 0ull;
                 }
-                const uint64_t last = __ballot(mine && rk + 1 == need);
-                if (last) stop = off + static_cast<uint32_t>(__ffsll(static_cast<long long>(last)));   // one past the last staged entry
-                found += static_cast<uint32_t>(__popcll(bal));
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                  const uint32_t dl = dl4[u];
+                  const bool live = dl > s;
+                  const uint64_t bal = __ballot(live);
+                  const uint32_t rk = found + static_cast<uint32_t>(__popcll(bal & lanes_below()));
+                  const bool mine = live && rk < need;
+                  if (mine) {
+                    L.jobs[first_job + rk] = jw4[u];
+                    if (dl != kNever)
+                      atomicSub(&calr[static_cast<size_t>((jw4[u] >> 29) & 7u) * cal_n + (dl & p.cal_mask)], 1u);
+                  }
+                  const uint64_t last = __ballot(mine && rk + 1 == need);
+                  if (last) stop = off + 64u * u + static_cast<uint32_t>(__ffsll(static_cast<long long>(last)));   // one past the last staged entry
+                  found += static_cast<uint32_t>(__popcll(bal));
+                }
               }
               if (lane == 0) L.sc[scan_word] = static_cast<int32_t>(found >= need ? stop : len);   // (found < need: see the gate's scan)
             };
