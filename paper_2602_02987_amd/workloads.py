@@ -75,7 +75,11 @@ def with_plan(cfg: SimConfig, lam_plan=None, objective="bundled", **kw) -> SimCo
     """Fill x*, q_p* and M from the fluid LP solved for planning arrivals `lam_plan`."""
     lam = [c.lam for c in cfg.classes] if lam_plan is None else lam_plan
     p = _plan.solve_lp(cfg, lam, objective=objective, **kw)
-    out = replace(cfg, M=p.M, x_star=[float(v) for v in p.x], qp_star=[0.0] * cfg.K)
+    # prefill-backlog targets (the gate's tie-break): with a patience rate the unserved flow of a class abandons,
+    # lambda_i = mu_p,i x_i + theta_i q_p,i (paper Sec. 3.2 flow balance), so q_p,i* = (lambda_i - mu_p,i x_i*) / theta_i;
+    # without one the relaxed plan carries no backlog target
+    qp = [max(float(l) - float(sv), 0.0) / c.theta if c.theta > 0.0 else 0.0 for l, sv, c in zip(lam, p.served, cfg.classes)]
+    out = replace(cfg, M=p.M, x_star=[float(v) for v in p.x], qp_star=qp)
     out.notes = dict(cfg.notes, lp_value=p.value, tau_mix=p.tau_mix, tau_solo=p.tau_solo,
                      sum_x=float(p.x.sum()))
     return out

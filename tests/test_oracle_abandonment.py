@@ -212,7 +212,9 @@ def test_overloaded_network_with_abandonment_sits_at_the_fluid_point(oracle_mod)
     cfg = _lp_instance(512, 1, 60000, (1024, 3072), (400, 160))
     for c in cfg.classes:
         c.theta = theta
+    cfg = W.with_plan(cfg)                                     # the plan now carries backlog targets q_p*
     pl = P.solve_lp(cfg, [c.lam for c in cfg.classes])
+    assert np.allclose(cfg.qp_star, (np.array([c.lam for c in cfg.classes]) - pl.served) / theta, rtol=1e-9, atol=1e-12)
     o = oracle_mod.Oracle(cfg)
     o.run(20000); s0 = o.stats()
     o.run(40000); s1 = o.stats()
