@@ -1,0 +1,76 @@
+"""GPU parity on seeded random small configurations: every gate, every decode rule, with and without patience,
+random sizes, caps, chunk lengths, ring capacities, targets and split moves. Each case runs a few hundred steps
+through the C ABI and is compared with the oracle bit by bit."""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+
+from paper_2602_02987_amd import workloads as W
+from parity import assert_replication_equal, assert_stats_equal
+from test_gpu_parity import B  # noqa: F401  (fixture)
+
+pytestmark = pytest.mark.gpu
+
+
+def _random_config(rng, idx):
+    K = int(rng.integers(1, 9))
+    N = int(rng.choice([1, 2, 3, 7, 33, 64, 65, 130, 400, 1100, 2600, 5200, 9000]))
+    Bcap = int(rng.choice([1, 2, 3, 5, 16, 64, 65, 128]))
+    M = int(rng.integers(0, N + 1))
+    route = int(rng.choice([W.ROUTE_SOLO_FIRST, W.ROUTE_RANDOM_SPLIT, W.ROUTE_IMMEDIATE]))
+    if route == W.ROUTE_IMMEDIATE and rng.random() < 0.7:
+        M = N
+    laws = [W.LAW_GEOMETRIC, W.LAW_LOGNORMAL, W.LAW_CONST]
+    total = float(rng.uniform(0.5, 4.5))
+    share = rng.dirichlet(np.ones(K))
+    cls = []
+    for k in range(K):
+        in_law, out_law = int(rng.choice(laws)), int(rng.choice(laws))
+        cls.append(W.SimClass(lam=float(total * share[k]), in_law=in_law, in_p0=float(rng.uniform(20, 900)), in_p1=0.8,
+                              out_law=out_law, out_p0=float(rng.uniform(2, 400)), out_p1=1.0,
+                              price_in=float(rng.uniform(0.5, 4)), price_out=float(rng.uniform(0.5, 4)),
+                              bundled=int(rng.integers(0, 2)), priority=float(rng.uniform(0, 3)),
+                              theta=float(rng.choice([0.0, 0.0, 0.5, 5.0, 30.0]))))
+    x = rng.uniform(0.0, 0.4, K)
+    x[rng.random(K) < 0.15] = 0.0        # classes the occupancy gate never admits
+    return W.SimConfig(name=f"random-{idx}", K=K, N=N, B=Bcap, C=int(rng.choice([16, 64, 256, 1000])), c0=0.010,
+                       c_pre=float(rng.choice([0.0, 0.00005])), c_dec=float(rng.choice([0.0, 0.0002])), classes=cls, M=M,
+                       x_star=[float(v) for v in x], qp_star=[float(v) for v in rng.uniform(0, 2, K)],
+                       dt=float(rng.choice([0.0, 0.007])), gate_mode=int(rng.integers(0, 3)), route_mode=route,
+                       mod_amp=float(rng.choice([0.0, 0.5])), mod_period=int(rng.choice([0, 97, 400])),
+                       queue_cap=int(rng.choice([6, 50, 4096])), dbuf_cap=int(rng.choice([4, 40, 4096])),
+                       replications=int(rng.integers(1, 4)), steps=0, seed=int(rng.integers(1, 2**40)),
+                       p_solo=[float(v) for v in rng.choice([0.0, 0.3, 0.7, 1.0], K)])
+
+
+@pytest.mark.parametrize("batch", range(16))
+def test_random_configurations(B, oracle_mod, batch):
+    rng = np.random.default_rng(1000 + batch)
+    for i in range(12):
+        cfg = _random_config(rng, 100 * batch + i)
+        if cfg.mod_period == 0:
+            cfg = replace(cfg, mod_amp=0.0)
+        steps = int(rng.integers(150, 700)) if cfg.N <= 400 else int(rng.integers(60, 200)) if cfg.N <= 2600 else int(rng.integers(30, 80))
+        try:
+            sim = B.Sim(cfg)
+        except B.SimError:
+            # (too many arrivals per server and step for the truncated sampler): both sides refuse it
+            with pytest.raises(ValueError):
+                oracle_mod.Oracle(cfg)
+            continue
+        orc = oracle_mod.Oracle(cfg)
+        done = 0
+        for part in range(3):
+            n = steps // 3 + (part == 0)
+            if part == 1 and rng.random() < 0.5:
+                m = int(rng.integers(0, cfg.N + 1))
+                sim.set_split(m); orc.set_split(m)
+            if part == 2 and rng.random() < 0.5:
+                x = [float(v) for v in rng.uniform(0.0, 0.4, cfg.K)]
+                sim.set_targets(x, cfg.qp_star); orc.set_targets(x, cfg.qp_star)
+            sim.run(n); orc.run(n)
+            done += n
+            for r in range(cfg.replications):
+                assert_replication_equal(sim, orc, r, what=f"{cfg.name} ({cfg}) after {done} steps")
+        assert_stats_equal(sim.stats(), orc.stats())
