@@ -33,7 +33,8 @@
  * sampler tables against closed-form pmfs, a hand-traced worked example,
  * flow-balance / capacity / token-conservation invariants, Little's law as an
  * exact integer identity, the exact stationary law of the discrete M/Geo/c
- * chain and its Erlang-C limit, convergence of revenue to the fluid-LP optimum;
+ * chain and its Erlang-C limit, convergence of revenue to the fluid-LP optimum,
+ * the gate and router rules replayed step by step from an independent statement;
  * abandonment: the patience table against the geometric law, queues that nobody
  * leaves by service rebuilt job by job from the patience blocks, the exact
  * stationary law of the discrete chain with abandonment (Erlang-A).
