@@ -46,3 +46,38 @@ def test_clocks_replayed_step_by_step(oracle_mod, over):
                 restarts += int(due); starts += int(not due)
         prev = cur
     assert restarts > 2000 and starts > 5 and (joins > 0 or cfg.B <= 2)
+
+
+def test_every_decode_runs_exactly_its_output_length(oracle_mod):
+    """A request with D output tokens leaves its server when the server has completed exactly D iterations
+    that had it in the batch: iterations are counted from the restart that follows the placement (one more
+    if the server was in mid-iteration when the request arrived)."""
+    cfg = _heavy(queue_cap=100000, dbuf_cap=100000, replications=1)
+    dt = int(round(cfg.c0 * 1e9))
+    o = oracle_mod.Oracle(cfg)
+    prev_jobs = {g: [] for g in range(cfg.N)}
+    prev_t = np.full(cfg.N, IDLE, dtype=np.int64)
+    born = {}
+    checked = mid_seen = 0
+    for s in range(2500):
+        o.run(1)
+        sv, sl = o.servers(0), o.slots(0)
+        T = (s + 1) * dt
+        for g in range(cfg.N):
+            now = [int(v) for v in sl["job"][g, :sl["n_dec"][g]]]
+            was_mid = prev_t[g] != IDLE and prev_t[g] > T
+            a, b = list(prev_jobs[g]), list(now)
+            for jw in list(a):
+                if jw in b:
+                    a.remove(jw); b.remove(jw)
+            for jw in a:                                    # left in this step
+                it0, mid = born.pop((g, jw))
+                D = (jw >> 48) + 1
+                assert int(sv["iter"][g]) == it0 + D + mid, (s, g, jw)
+                checked += 1
+            for jw in b:                                    # placed in this step
+                born[(g, jw)] = (int(sv["iter"][g]), int(was_mid))
+                mid_seen += int(was_mid)
+            prev_jobs[g] = now
+        prev_t = sv["t_next"].copy()
+    assert checked > 500 and mid_seen > 5
