@@ -63,16 +63,25 @@ def measured_traffic():
     return TRAFFIC["bytes_per_launch"] if TRAFFIC["kernel_sha256"] == sha else None
 
 
+def policy_variant(W, cfg, theta, split, immediate):
+    """The configuration with the optional policy switches of the command line applied."""
+    if split:
+        cfg = W.with_random_split(cfg, lam_plan=[c.lam / 0.95 for c in cfg.classes])
+    if immediate:
+        cfg.route_mode = W.ROUTE_IMMEDIATE   # as in the paper's ablation: no static partition, every server may prefill
+        cfg.M = cfg.N
+    if theta:
+        for c in cfg.classes:
+            c.theta = theta
+    return cfg
+
+
 def _oracle_worker(args):
-    n, N, rep, steps, theta, split = args
+    n, N, rep, steps, theta, split, immediate = args
     sys.path.insert(0, ROOT)
     from oracle import binding as ob
     from paper_2602_02987_amd import workloads as W
-    cfg = W.config(n, N=N)
-    if split:
-        cfg = W.with_random_split(cfg, lam_plan=[c.lam / 0.95 for c in cfg.classes])
-    for c in cfg.classes:
-        c.theta = theta or c.theta
+    cfg = policy_variant(W, W.config(n, N=N), theta, split, immediate)
     o = ob.Oracle(cfg, max_reps=cfg.replications)
     o.select([rep])
     t = time.perf_counter()
@@ -80,7 +89,7 @@ def _oracle_worker(args):
     return time.perf_counter() - t
 
 
-def cpu_baseline(n, N, steps, theta=0.0, split=False):
+def cpu_baseline(n, N, steps, theta=0.0, split=False, immediate=False):
     """The oracle as it stands, one replication per host process, on a bounded sample."""
     import multiprocessing as mp
     from oracle import binding as ob
@@ -88,7 +97,7 @@ def cpu_baseline(n, N, steps, theta=0.0, split=False):
     cores = min(16, os.cpu_count() or 1)
     t = time.perf_counter()
     with mp.get_context("spawn").Pool(cores) as pool:
-        pool.map(_oracle_worker, [(n, N, r, steps, theta, split) for r in range(cores)])
+        pool.map(_oracle_worker, [(n, N, r, steps, theta, split, immediate) for r in range(cores)])
     wall = time.perf_counter() - t
     return dict(value=cores * N * steps / wall, unit="server-steps/s", cores=cores, kind="oracle",
                 sample=f"replications 0..{cores - 1} of the workload, first {steps} steps from the empty system, "
@@ -109,6 +118,9 @@ def main():
                     help="patience rate given to every class (abandonment; 0 = the configuration's own, none)")
     ap.add_argument("--random-split", action="store_true",
                     help="route decodes with the randomized router, solo probabilities from the configuration's plan")
+    ap.add_argument("--immediate", action="store_true",
+                    help="decode on the server that ran the prefill, no static partition (the ablation without a decode "
+                         "router: M = N)")
     ap.add_argument("--oracle-steps", type=int, default=1500, help="0 skips the CPU baseline")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run one device-to-device copy of this size before the timed region "
@@ -124,7 +136,7 @@ def main():
     base = None
     if args.oracle_steps > 0:
         n_servers = args.servers if args.servers else W.config(args.config).N
-        base = cpu_baseline(args.config, n_servers, args.oracle_steps, args.theta, args.random_split)
+        base = cpu_baseline(args.config, n_servers, args.oracle_steps, args.theta, args.random_split, args.immediate)
 
     import torch
     from paper_2602_02987_amd import binding
@@ -133,12 +145,11 @@ def main():
         over["N"] = args.servers
     if args.replications:
         over["replications"] = args.replications
-    cfg = W.config(args.config, **over)
-    if args.random_split:
-        cfg = W.with_random_split(cfg, lam_plan=[c.lam / 0.95 for c in cfg.classes])
-    if args.theta:
-        for c in cfg.classes:
-            c.theta = args.theta
+    if args.random_split and args.immediate:
+        ap.error("--random-split and --immediate are two different decode rules")
+    cfg = policy_variant(W, W.config(args.config, **over), args.theta, args.random_split, args.immediate)
+    default_run = (args.config == 5 and not over and not args.theta and not args.random_split and not args.immediate
+                   and args.sim_steps == 1000 and args.preload == 30000)
     slots_per_step = cfg.N * cfg.replications * args.sim_steps
 
     sim = binding.Sim(cfg)
@@ -184,13 +195,14 @@ def main():
         "dtype": "int64", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: K={cfg.K} N={cfg.N} R={cfg.replications} B={cfg.B} C={cfg.C} M={cfg.M}"
                                + (f" theta={args.theta}" if args.theta else "")
-                               + (" randomized router" if args.random_split else "") + ", "
+                               + (" randomized router" if args.random_split else "")
+                               + (" immediate decode" if args.immediate else "") + ", "
                                f"{args.sim_steps} simulation steps per bench step after {args.preload + args.warmup * args.sim_steps} untimed steps",
                    "server_step_slots_per_bench_step": slots_per_step,
                    "executed_iterations_per_s": iters / wall,
                    "overflow": bool(st1["overflow"])},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(),
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic() if default_run else None,
                      "kernel": "gnr_step_kernel", "launches": launches, "avg_launch_ms": per_launch_ms,
                      "algorithmic_bytes_per_launch": total_bytes / max(launches, 1), **shape},
     }
