@@ -167,3 +167,31 @@ def config(n: int, **over) -> SimConfig:
         # every period, so prefill queues swing widely); the plan is made for full capacity
         return _scaled_to_load(cfg, mix, 0.95)
     raise ValueError("config index must be 1..5")
+
+
+def convergence_instance(n: int, seeds: int = 5, B: int = 6, random_split: bool = False, bundled: bool = False,
+                         **over) -> SimConfig:
+    """The two-class instance of the paper's convergence analysis (EC, "Convergence Analysis") at scale n.
+
+    As printed there: class 0 decode-heavy (P=300, D=1000), class 1 prefill-heavy (P=3000, D=400), arrival rates
+    (0.5, 0.5) per server, patience rates (0.1, 0.1), separate charging with prices 0.1 per prompt token and 0.2
+    per output token, one replication per seed. Lengths are geometric with those means (the discrete counterpart
+    of the paper's exponential service requirements). Iteration times follow the paper's calibration (Sec. 6.1):
+    a solo iteration takes 8.9 ms and a mixed one with a full chunk of 256 tokens 33.3 ms; the small KV-cache
+    slope is left out. The paper does not print the batch size of this experiment: B = 6 is chosen here so that
+    decode capacity binds at these arrival rates (requests abandon, the plan keeps a prefill backlog).
+    `bundled=True` recognises the same prices at completion instead (the setting of the paper's Theorem 2).
+    """
+    cls = [SimClass(lam=0.5, in_p0=300.0, out_p0=1000.0, price_in=0.1, price_out=0.2, bundled=0, theta=0.1,
+                    priority=1000.0 / 300.0),
+           SimClass(lam=0.5, in_p0=3000.0, out_p0=400.0, price_in=0.1, price_out=0.2, bundled=0, theta=0.1,
+                    priority=400.0 / 3000.0)]
+    tau_solo, tau_mix, C = 0.0089, 0.0174 + 6.2e-5 * 256, 256
+    cfg = SimConfig(name=f"convergence-n{n}", K=2, N=n, B=B, C=C, c0=tau_solo, c_pre=(tau_mix - tau_solo) / C,
+                    c_dec=0.0, classes=cls, replications=seeds, steps=60_000, seed=1, queue_cap=4096 + 4 * n,
+                    dbuf_cap=4096 + 2 * n)
+    objective = "bundled" if bundled else "separate"
+    for c in cls:
+        c.bundled = int(bundled)
+    cfg = with_plan(replace(cfg, **over), objective=objective)
+    return with_random_split(cfg, objective=objective) if random_split else cfg
