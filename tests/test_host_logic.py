@@ -109,3 +109,25 @@ def test_plan_of_config_1_matches_its_closed_forms():
     # E ceil(P/C) of a geometric P: 1 / (1 - (1-p)^C)
     assert r["ECH"] == pytest.approx([1.0 / (1.0 - (1.0 - 1.0 / m) ** 256) for m in (512.0, 128.0)], rel=1e-4)
     assert cfg.M == pl.M == 1 and W.config(2).M == int(np.ceil(256 * pl.x.sum()))
+
+
+def test_ablation_policies_are_switches_on_one_instance():
+    """The five policies of the component ablation differ only in gate rule, decode rule and split; the instances
+    stay within the ranges the paper states and are the same on every call."""
+    from paper_2602_02987_amd import ablation as A
+    a, b = A.instances(3, n=100), A.instances(3, n=100)
+    for x, y in zip(a, b):
+        assert x.M == y.M and x.x_star == y.x_star and [c.lam for c in x.classes] == [c.lam for c in y.classes]
+    for cfg in a:
+        assert 10.0 <= 1.0 / cfg.c0 <= 50.0 and 0.0 < cfg.dt <= cfg.c0 and cfg.c_pre >= 0.0
+        assert 0.02 + 256e-5 <= cfg.c0 + cfg.c_pre * 256 <= 0.15 + 0.256 + 1e-12
+        assert all(0.25 <= c.lam <= 0.5 and 200 <= c.in_p0 <= 3000 and 200 <= c.out_p0 <= 3000 for c in cfg.classes)
+        assert sum(c.lam for c in cfg.classes) * cfg.dt <= 0.04 + 1e-12
+        pol = A.policies(cfg)
+        assert tuple(pol) == A.POLICIES
+        want = {"GG-SP": (W.GATE_OCCUPANCY, W.ROUTE_SOLO_FIRST, cfg.M), "FG-SP": (W.GATE_FCFS, W.ROUTE_SOLO_FIRST, cfg.M),
+                "GF-WSP": (W.GATE_OCCUPANCY, W.ROUTE_SOLO_FIRST, cfg.N), "GI-WSP": (W.GATE_OCCUPANCY, W.ROUTE_IMMEDIATE, cfg.N),
+                "FI-WSP": (W.GATE_FCFS, W.ROUTE_IMMEDIATE, cfg.N)}
+        for name, c in pol.items():
+            assert (c.gate_mode, c.route_mode, c.M) == want[name]
+            assert c.x_star == cfg.x_star and c.classes is cfg.classes and c.seed == cfg.seed
