@@ -1034,7 +1034,19 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
     }
     if (tid < 64) {
       const uint32_t ncomp = rank_bitmap(L.bm_comp, L.pre_c, nwords_m, Mp);
-      if (tid == 0) L.sc[SC_NCOMP] = static_cast<int32_t>(ncomp);
+      if (tid == 0) {
+        L.sc[SC_NCOMP] = static_cast<int32_t>(ncomp);
+        if constexpr (AB) {
+          // a buffer ring that cannot hold this step's completions behind its dead entries is compacted first
+          // (this wave has already taken the step's abandonments off the counters above)
+          const uint32_t room = p.dbuf_cap - static_cast<uint32_t>(L.cs[CS_DCOUNT]);
+          if (static_cast<uint32_t>(L.sc[SC_DLEN]) + (ncomp < room ? ncomp : room) > p.dbuf_cap) atomicOr(&L.sc[SC_COMPACT], 256);
+          if constexpr (RR) {   // how the completions split between the two rings is not known yet: either may get all
+            const uint32_t room_m = p.dbuf_cap - static_cast<uint32_t>(L.cs[CS_DCOUNT_M]);
+            if (static_cast<uint32_t>(L.sc[SC_DLEN_M]) + (ncomp < room_m ? ncomp : room_m) > p.dbuf_cap) atomicOr(&L.sc[SC_COMPACT], 512);
+          }
+        }
+      }
     }
     if (NT == 64 ? tid < 64 : (tid >= 64 && tid < 128)) {
       const uint32_t nidle = rank_bitmap(L.bm_idle, L.pre, nwords_m, M);   // idle prefill slots of the mixed group
@@ -1043,16 +1055,6 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
     __syncthreads();
     if constexpr (AB) {
       // a ring that cannot hold this step's appends behind its dead entries is compacted first
-      if (tid == 0) {
-        const uint32_t ncp = static_cast<uint32_t>(L.sc[SC_NCOMP]);
-        const uint32_t room = p.dbuf_cap - static_cast<uint32_t>(L.cs[CS_DCOUNT]);
-        if (static_cast<uint32_t>(L.sc[SC_DLEN]) + (ncp < room ? ncp : room) > p.dbuf_cap) atomicOr(&L.sc[SC_COMPACT], 256);
-        if constexpr (RR) {   // how the completions split between the two rings is not known yet: either may get all
-          const uint32_t room_m = p.dbuf_cap - static_cast<uint32_t>(L.cs[CS_DCOUNT_M]);
-          if (static_cast<uint32_t>(L.sc[SC_DLEN_M]) + (ncp < room_m ? ncp : room_m) > p.dbuf_cap) atomicOr(&L.sc[SC_COMPACT], 512);
-        }
-      }
-      __syncthreads();
       const int flags = L.sc[SC_COMPACT];   // cleared at the end of the step
       if (flags) {   // the same for every thread
         for (int k = wave; k < K; k += nwaves)
@@ -1256,7 +1258,8 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           nadm = ncand < limit ? ncand : limit;
           if constexpr (AB) {
             // where the candidates sit in their rings: a wave per class walks from the head past the dead entries
-            for (int k = wave; k < K; k += nwaves) {   // wave-uniform
+            // (the last waves take this: the first ones rank the candidates below)
+            for (int k = nwaves - 1 - wave; k < K; k += nwaves) {   // wave-uniform
               uint32_t need = 0;
 #pragma unroll
               for (int kk = 0; kk < kMaxK; ++kk)
@@ -1291,8 +1294,11 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
               for (uint32_t rk = found + lane; rk < need; rk += 64) L.live_off[k * kAdmChunk + rk] = 0;
               if (lane == 0) L.sc[SC_LEAD + k] = (need > 0 && found > 0) ? 1 : 0;
             }
-            __syncthreads();
+            // only the FCFS gate reads the offsets while it ranks the candidates; the other gates first use them
+            // after the barrier that ends this segment
+            if (p.gate_mode == SIM_GATE_FCFS) __syncthreads();
           }
+          PROF(26)
           // The admissions take the first nadm idle prefill slots, whatever their order: the slot bitmaps are
           // updated here a word at a time (no atomics).
           // A wave takes a word, a lane a slot; the slot of every admission rank goes into a table.
@@ -1312,6 +1318,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
               }
             }
           }
+          PROF(27)
           for (int c0 = wave_base; c0 < ncand; c0 += NT) {   // wave-uniform trip count
             const int c = c0 + lane;
             bool admitted = false;
@@ -1360,6 +1367,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
             }
           }
         }
+        PROF(28)
         // routing pass: up to kRouteLevels levels, first of the solo group (servers M..N-1), then, if that group
         // is full by then, of the mixed group (servers 0..M-1, one slot less). Level t of group G holds the
         // servers of G with at most lminG + (t - firstG) decodes.
