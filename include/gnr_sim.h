@@ -172,7 +172,9 @@ int sim_workspace_bytes(const sim_config *cfg, int max_replications, size_t *out
  * handle). SIM_EINVAL: bad sizes, negative target, M outside [0,N], dt > c0, negative theta, p_solo outside
  * [0,1] or missing under RANDOM_SPLIT, total
  * arrival mean per server-step above 0.05 (the per-step count is truncated at 3).
- * SIM_ENOMEM: workspace too small. The library never allocates device memory itself. */
+ * SIM_ENOMEM: workspace too small. The library never allocates device memory itself.
+ * The handle belongs to the device that is current at this call: every later call on it must be made
+ * with the same device current (SIM_EINVAL otherwise). */
 int sim_create(const sim_config *cfg, int max_replications, void *dev_workspace, size_t bytes, sim_t **out);
 
 /* Advances `replications` replications by `steps` steps, asynchronously on `hip_stream`

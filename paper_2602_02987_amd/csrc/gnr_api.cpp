@@ -26,9 +26,7 @@ struct sim_t {
   unsigned char *ws;
   size_t ws_bytes;
   int device;
-  // kernel timing
-  hipEvent_t ev0, ev1;
-  bool ev_ok;
+  // kernel timing: one pair of events per launch, read out and destroyed by drain_events
   std::vector<std::pair<hipEvent_t, hipEvent_t>> pending;
   int64_t launches;
   double kernel_ms;
@@ -169,6 +167,13 @@ int patience_tables(const sim_config &c, const Ticks &t, std::vector<uint16_t> *
   return SIM_OK;
 }
 
+// The workspace lives on the device that was current at sim_create: later calls must be made with it current.
+bool on_device(const sim_t *h)
+{
+  int d = -1;
+  return hipGetDevice(&d) == hipSuccess && d == h->device;
+}
+
 int sync(sim_t *, void *stream)
 {
   return hipStreamSynchronize(static_cast<hipStream_t>(stream)) == hipSuccess ? SIM_OK : SIM_EHIP;
@@ -253,7 +258,7 @@ int sim_create(const sim_config *cfg, int max_replications, void *dev_workspace,
   h->rows = rows;
   h->ws = static_cast<unsigned char *>(dev_workspace);
   h->ws_bytes = bytes;
-  h->launches = 0; h->kernel_ms = 0.0; h->ev_ok = true;
+  h->launches = 0; h->kernel_ms = 0.0;
   if (hipGetDevice(&h->device) != hipSuccess) { delete h; return SIM_EHIP; }
 
   // sampler tables
@@ -346,7 +351,7 @@ int sim_create(const sim_config *cfg, int max_replications, void *dev_workspace,
 
 int sim_run(sim_t *h, int64_t steps, int replications, uint64_t seed, void *hip_stream)
 {
-  if (!h || steps < 0 || replications < 1 || replications > h->max_reps) return SIM_EINVAL;
+  if (!h || steps < 0 || replications < 1 || replications > h->max_reps || !on_device(h)) return SIM_EINVAL;
   if (!h->started || replications != h->reps || seed != h->seed) {
     const int rc = launch_reset(h->p, h->max_reps, hip_stream);
     if (rc != SIM_OK) return rc;
@@ -360,7 +365,8 @@ int sim_run(sim_t *h, int64_t steps, int replications, uint64_t seed, void *hip_
   while (left > 0) {
     const uint32_t n = static_cast<uint32_t>(left < kStepsPerLaunch ? left : kStepsPerLaunch);
     hipEvent_t e0 = nullptr, e1 = nullptr;
-    const bool timed = h->ev_ok && hipEventCreate(&e0) == hipSuccess && hipEventCreate(&e1) == hipSuccess;
+    bool timed = hipEventCreate(&e0) == hipSuccess;
+    if (timed && hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); timed = false; }
     if (timed) (void)hipEventRecord(e0, st);
     const int rc = launch_steps(h->p, replications, h->threads, h->lds_bytes, static_cast<uint32_t>(h->steps_done), n, hip_stream);
     if (timed) { (void)hipEventRecord(e1, st); h->pending.emplace_back(e0, e1); }
@@ -378,7 +384,7 @@ int sim_run(sim_t *h, int64_t steps, int replications, uint64_t seed, void *hip_
 
 int sim_set_targets(sim_t *h, const double *x_star, const double *qp_star, void *hip_stream)
 {
-  if (!h || !x_star || !qp_star) return SIM_EINVAL;
+  if (!h || !x_star || !qp_star || !on_device(h)) return SIM_EINVAL;
   for (int k = 0; k < h->p.K; ++k)
     if (!(x_star[k] >= 0.0) || !std::isfinite(x_star[k]) || !std::isfinite(qp_star[k])) return SIM_EINVAL;
   for (int k = 0; k < h->p.K; ++k) {
@@ -397,7 +403,7 @@ int sim_set_targets(sim_t *h, const double *x_star, const double *qp_star, void 
 
 int sim_set_split(sim_t *h, int M, void *hip_stream)
 {
-  if (!h || M < 0 || M > h->p.N) return SIM_EINVAL;
+  if (!h || M < 0 || M > h->p.N || !on_device(h)) return SIM_EINVAL;
   Params q = h->p;
   q.M = M;
   if (M > q.Mp) q.Mp = M;   // never lowered: a server that turns solo may still hold a prefill
@@ -414,7 +420,7 @@ int sim_set_split(sim_t *h, int M, void *hip_stream)
 
 int sim_kernel_time(sim_t *h, int64_t *launches, double *milliseconds, int reset, void *hip_stream)
 {
-  if (!h) return SIM_EINVAL;
+  if (!h || !on_device(h)) return SIM_EINVAL;
   const int rc = sync(h, hip_stream);
   if (rc != SIM_OK) return rc;
   drain_events(h);
@@ -426,7 +432,7 @@ int sim_kernel_time(sim_t *h, int64_t *launches, double *milliseconds, int reset
 
 int sim_stats(sim_t *h, sim_stats_t *st, void *hip_stream)
 {
-  if (!h || !st || !h->started) return SIM_EINVAL;
+  if (!h || !st || !h->started || !on_device(h)) return SIM_EINVAL;
   int rc = launch_reduce(h->p, h->reps, hip_stream);
   if (rc != SIM_OK) return rc;
   rc = sync(h, hip_stream);
@@ -501,7 +507,7 @@ int sim_stats(sim_t *h, sim_stats_t *st, void *hip_stream)
 
 int sim_tallies(sim_t *h, int r, uint64_t *out, void *hip_stream)
 {
-  if (!h || !out || !h->started || r < 0 || r >= h->reps) return SIM_EINVAL;
+  if (!h || !out || !h->started || r < 0 || r >= h->reps || !on_device(h)) return SIM_EINVAL;
   int rc = sync(h, hip_stream);
   if (rc != SIM_OK) return rc;
   std::vector<uint64_t> buf(kTallyWords);
@@ -516,7 +522,7 @@ int sim_tallies(sim_t *h, int r, uint64_t *out, void *hip_stream)
 
 int sim_hist(sim_t *h, int r, int which, uint64_t *out, void *hip_stream)
 {
-  if (!h || !out || !h->started || r < 0 || r >= h->reps || which < 0 || which > 2) return SIM_EINVAL;
+  if (!h || !out || !h->started || r < 0 || r >= h->reps || which < 0 || which > 2 || !on_device(h)) return SIM_EINVAL;
   const int rc = sync(h, hip_stream);
   if (rc != SIM_OK) return rc;
   const int K = h->cfg.K;
@@ -525,7 +531,7 @@ int sim_hist(sim_t *h, int r, int which, uint64_t *out, void *hip_stream)
 
 int sim_digest(sim_t *h, int r, uint64_t *out, void *hip_stream)
 {
-  if (!h || !out || !h->started || r < 0 || r >= h->reps) return SIM_EINVAL;
+  if (!h || !out || !h->started || r < 0 || r >= h->reps || !on_device(h)) return SIM_EINVAL;
   int rc = launch_digest(h->p, h->reps, hip_stream);
   if (rc != SIM_OK) return rc;
   rc = sync(h, hip_stream);
@@ -535,7 +541,7 @@ int sim_digest(sim_t *h, int r, uint64_t *out, void *hip_stream)
 
 int sim_snapshot(sim_t *h, int r, sim_state_t *out, void *hip_stream)
 {
-  if (!h || !out || !h->started || r < 0 || r >= h->reps) return SIM_EINVAL;
+  if (!h || !out || !h->started || r < 0 || r >= h->reps || !on_device(h)) return SIM_EINVAL;
   int rc = sync(h, hip_stream);
   if (rc != SIM_OK) return rc;
   const int K = h->cfg.K, N = h->cfg.N, B = h->cfg.B;
