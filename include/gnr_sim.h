@@ -49,7 +49,8 @@ extern "C" {
 
 #define SIM_MAXK 8      /* classes */
 #define SIM_MAXB 128    /* decode slots per server */
-#define SIM_MAXN 12288  /* servers per replication */
+#define SIM_MAXN 12288  /* servers per replication: no configuration may have more; how many fit depends on the
+                           on-chip memory they need (see sim_onchip_bytes) */
 #define SIM_NBIN 720    /* latency histogram bins: exact below 16 ns, then 16 bins per octave */
 
 enum sim_err { SIM_OK = 0, SIM_EINVAL = -1, SIM_ENOMEM = -2, SIM_EHIP = -3, SIM_EOVERFLOW = -4 };
@@ -228,6 +229,13 @@ int sim_length_table(int law, double p0, double p1, uint16_t *out);
 int sim_patience_table(double theta, double dt, uint16_t *out);
 int sim_philox(uint64_t seed, uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t *out4);
 int sim_thresholds(const sim_config *cfg, int64_t rows, uint32_t *arr_thr, uint32_t *cls_thr);
+/* On-chip memory (LDS bytes of one compute unit) the step kernel needs for `cfg`, and the limit it must stay
+ * within. The clocks, iteration counters and decode counts of all N servers of a replication stay on chip for
+ * a whole launch (about 11.4 bytes per server, 2 more per mixed-group server, 6 KB more with abandonment, on top
+ * of about 28 KB): sim_workspace_bytes and sim_create return SIM_EINVAL for a configuration above the limit, and
+ * sim_set_split for a split that would exceed it. Host only; reads K, N, M, B, C, c0, c_pre, c_dec and the
+ * classes' theta. `out_limit` may be NULL. */
+int sim_onchip_bytes(const sim_config *cfg, size_t *out_bytes, size_t *out_limit);
 /* sizeof of the four ABI structs, in the order class, config, stats, state (for binding checks). */
 int sim_abi_sizes(size_t *out4);
 

@@ -79,6 +79,7 @@ def lib():
         L = C.CDLL(lib_path())
         L.sim_strerror.restype = C.c_char_p
         L.sim_workspace_bytes.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_size_t)]
+        L.sim_onchip_bytes.argtypes = [C.c_void_p, C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
         L.sim_create.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.POINTER(C.c_void_p)]
         L.sim_run.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_uint64, C.c_void_p]
         L.sim_stats.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
@@ -141,6 +142,14 @@ def marshal_config(cfg):
                     p_solo=C.addressof(ps))
     keep += [cls, xs, qs, ps]
     return cc, keep
+
+
+def sim_onchip_bytes(cfg):
+    """(bytes needed, limit) of on-chip memory for `cfg`; host only."""
+    cc, _keep = marshal_config(cfg)
+    n, lim = C.c_size_t(0), C.c_size_t(0)
+    _check(lib().sim_onchip_bytes(C.byref(cc), C.byref(n), C.byref(lim)), "sim_onchip_bytes")
+    return n.value, lim.value
 
 
 def sim_workspace_bytes(cfg, max_replications):

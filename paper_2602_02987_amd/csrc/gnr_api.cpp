@@ -110,6 +110,22 @@ int64_t host_hedge(int b)
   return static_cast<int64_t>(16 + b % 16) << (b / 16 - 1);
 }
 
+constexpr size_t kOnChipLimit = 160 * 1024;   // LDS of a compute unit; a replication's workgroup runs there alone
+
+// On-chip bytes the step kernel needs for a configuration with the mixed group at servers 0..M-1.
+size_t on_chip_bytes(const sim_config &c, const Ticks &t, int M)
+{
+  Params q;
+  std::memset(&q, 0, sizeof q);
+  q.K = c.K; q.N = c.N; q.Mp = M;
+  q.tbt_w = host_hbin(t.c0 + t.cpre * c.C + t.cdec * c.B) - host_hbin(t.c0) + 1;
+  q.nwords = (c.N + 63) / 64;
+  q.threads = step_threads(c.N);
+  for (int k = 0; k < c.K; ++k)
+    if (c.cls[k].theta > 0.0) q.ab_classes |= 1u << k;
+  return step_lds_bytes(q);
+}
+
 int validate(const sim_config *c, int max_reps, Ticks *t)
 {
   if (!c || max_reps < 1 || !c->cls || !c->x_star || !c->qp_star) return SIM_EINVAL;
@@ -143,6 +159,8 @@ int validate(const sim_config *c, int max_reps, Ticks *t)
   if (hi - lo + 1 > kMaxTbtBins) return SIM_EINVAL;
   // clocks are compared modulo 2^32 ns on the device: the longest iteration must stay far below 2^31 ns
   if (t->c0 + t->cpre * c->C + t->cdec * c->B > 2000000000ll) return SIM_EINVAL;
+  // the per-server records of a replication stay on chip for a whole launch
+  if (on_chip_bytes(*c, *t, c->M) > kOnChipLimit) return SIM_EINVAL;
   return SIM_OK;
 }
 
@@ -336,7 +354,7 @@ int sim_create(const sim_config *cfg, int max_replications, void *dev_workspace,
   h->threads = step_threads(cfg->N);
   p.threads = h->threads;
   h->lds_bytes = step_lds_bytes(p);
-  if (h->lds_bytes > 160 * 1024) { delete h; return SIM_EINVAL; }
+  if (h->lds_bytes > kOnChipLimit) { delete h; return SIM_EINVAL; }
   if (hipMemcpy(w + L.arr_thr, arr.data(), arr.size() * sizeof(uint32_t), hipMemcpyHostToDevice) != hipSuccess ||
       hipMemcpy(w + L.len_tab, tab.data(), tab.size() * sizeof(uint16_t), hipMemcpyHostToDevice) != hipSuccess ||
       hipMemcpy(w + L.params, &p, sizeof(Params), hipMemcpyHostToDevice) != hipSuccess ||
@@ -408,7 +426,7 @@ int sim_set_split(sim_t *h, int M, void *hip_stream)
   q.M = M;
   if (M > q.Mp) q.Mp = M;   // never lowered: a server that turns solo may still hold a prefill
   const size_t lds = step_lds_bytes(q);
-  if (lds > 160 * 1024) return SIM_EINVAL;
+  if (lds > kOnChipLimit) return SIM_EINVAL;
   h->p = q;
   h->cfg.M = M;
   h->lds_bytes = lds;
@@ -692,6 +710,20 @@ int sim_thresholds(const sim_config *cfg, int64_t rows, uint32_t *arr_thr, uint3
   if (arr_thr)
     for (int64_t j = 0; j < rows; ++j) build_arrival_row(lam, t.dt, cfg->mod_amp, cfg->mod_period, j, arr_thr + 3 * j);
   if (cls_thr) build_class_thresholds(cfg->cls, cfg->K, cls_thr);
+  return SIM_OK;
+}
+
+int sim_onchip_bytes(const sim_config *cfg, size_t *out_bytes, size_t *out_limit)
+{
+  Ticks t;
+  if (!cfg || !out_bytes || !cfg->cls || cfg->K < 1 || cfg->K > kMaxK || cfg->N < 1 || cfg->N > kMaxN || cfg->M < 0 ||
+      cfg->M > cfg->N || cfg->B < 1 || cfg->B > kMaxB || cfg->C < 1 || cfg->C > kMaxChunk || !(cfg->c0 > 0.0) ||
+      !(cfg->c_pre >= 0.0) || !(cfg->c_dec >= 0.0))
+    return SIM_EINVAL;
+  t.c0 = std::llround(cfg->c0 * 1e9); t.cpre = std::llround(cfg->c_pre * 1e9); t.cdec = std::llround(cfg->c_dec * 1e9);
+  t.dt = t.c0;
+  *out_bytes = on_chip_bytes(*cfg, t, cfg->M);
+  if (out_limit) *out_limit = kOnChipLimit;
   return SIM_OK;
 }
 

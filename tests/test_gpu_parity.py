@@ -226,3 +226,33 @@ def test_degenerate_runs(B, oracle_mod):
         sim.run(10, 5)                        # more than the workspace was sized for
     cfg = _heavy(N=1, M=0, B=1)
     run_both(B, oracle_mod, cfg, 800)
+
+
+def test_maximum_sizes(B, oracle_mod):
+    """The documented limits: the most servers a replication of this shape may have (11696 with 1500 mixed ones:
+    the on-chip records fill a compute unit's LDS to the last few bytes) and one more refused, the largest chunk
+    (8191 tokens) with the longest prompts and outputs the tables hold (32768 tokens)."""
+    from paper_2602_02987_amd.binding import TALLY
+    ti = {n: i for i, n in enumerate(TALLY)}
+    cls = [_limits_class(lam=2.0, in_p0=300.0, out_p0=40.0), _limits_class(lam=1.5, in_p0=90.0, out_p0=15.0)]
+    cfg = _limits_cfg("most-servers", cls, N=11696, M=1500, B=8, steps=120, replications=1, queue_cap=8192)
+    need, limit = B.sim_onchip_bytes(cfg)
+    assert limit - 64 < need <= limit
+    sim, orc = run_both(B, oracle_mod, cfg, 120, checkpoints=2)
+    assert orc.tallies(0)[0][:, ti["S_DS"]].sum() > 1000
+    for n_bad in (11697, 12289):
+        with pytest.raises(B.SimError):
+            B.Sim(_limits_cfg("too-many-servers", cls, N=n_bad, M=1500, B=8, steps=1))
+    # every prompt 32768 tokens long, prefilled in chunks of 8191 + 8191 + 8191 + 8191 + 4; outputs of the same length
+    cls = [_limits_class(lam=0.8, in_law=W.LAW_CONST, in_p0=32768.0, out_law=W.LAW_CONST, out_p0=32768.0)]
+    cfg = _limits_cfg("longest-requests", cls, N=6, M=2, B=4, steps=70000, x_star=[0.3], replications=1)
+    cfg.C = 8191
+    cfg.c_pre = 1e-7
+    sim, orc = run_both(B, oracle_mod, cfg, 70000, checkpoints=2)
+    t = orc.tallies(0)[0]
+    assert t[0, ti["S_P"]] > 20 and t[0, ti["TOKP_PRE"]] == 32768 * t[0, ti["S_P"]]
+    assert t[0, ti["S_DS"]] + t[0, ti["S_DM"]] > 5
+    with pytest.raises(B.SimError):
+        bad = _limits_cfg("chunk-too-large", cls, N=6, M=2, B=4, steps=1, x_star=[0.3])
+        bad.C = 8192
+        B.Sim(bad)

@@ -131,3 +131,23 @@ def test_ablation_policies_are_switches_on_one_instance():
         for name, c in pol.items():
             assert (c.gate_mode, c.route_mode, c.M) == want[name]
             assert c.x_star == cfg.x_star and c.classes is cfg.classes and c.seed == cfg.seed
+
+
+def test_on_chip_memory_bounds_the_number_of_servers():
+    """The library refuses, on the host, a configuration whose per-server records do not fit a compute unit's
+    on-chip memory, and says how much a configuration needs."""
+    from paper_2602_02987_amd import binding as B
+    need5, limit = B.sim_onchip_bytes(W.config(5))
+    assert limit == 160 * 1024 and 140_000 < need5 < limit
+    cfg = W.config(5, replications=1)
+    small = replace(cfg, N=2000, M=400)
+    assert B.sim_onchip_bytes(small)[0] < need5 - 80_000           # about 11.4 bytes per server
+    ab = W.config(5, replications=1)
+    for c in ab.classes:
+        c.theta = 0.1
+    assert B.sim_onchip_bytes(ab)[0] == need5 + 6 * 256 * 4         # the gate's table of waiting requests
+    B.sim_workspace_bytes(replace(cfg, N=11000, M=2377), 1)
+    with pytest.raises(B.SimError):
+        B.sim_workspace_bytes(replace(cfg, N=12200, M=2377), 1)
+    with pytest.raises(B.SimError):
+        B.sim_workspace_bytes(replace(cfg, N=12289, M=0), 1)
