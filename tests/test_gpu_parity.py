@@ -224,6 +224,10 @@ def test_degenerate_runs(B, oracle_mod):
     assert_replication_equal(sim, orc, 0, what="one of four")
     with pytest.raises(B.SimError):
         sim.run(10, 5)                        # more than the workspace was sized for
+    with pytest.raises(B.SimError):
+        sim.run(2 ** 29 - 700, 1)             # arrival stamps are kept in 29 bits: a run ends before step 2^29
+    sim.run(1, 1); orc.run(1, 1)              # the refused call changed nothing
+    assert_replication_equal(sim, orc, 0, what="after a refused run")
     cfg = _heavy(N=1, M=0, B=1)
     run_both(B, oracle_mod, cfg, 800)
 
