@@ -165,6 +165,7 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    sim.run(0)   # (with no preload and no warm-up this is what puts the empty system in place)
     torch.cuda.synchronize()
     sim.kernel_time(reset=True)
     K = cfg.K
