@@ -260,3 +260,14 @@ def test_maximum_sizes(B, oracle_mod):
         bad = _limits_cfg("chunk-too-large", cls, N=6, M=2, B=4, steps=1, x_star=[0.3])
         bad.C = 8192
         B.Sim(bad)
+
+
+def test_configs_2_to_4_at_their_full_length(B, oracle_mod):
+    """Configs 2, 3 and 4 exactly as specified — every replication, all 100000 steps — on the GPU; the oracle
+    recomputes sampled replications over the whole length (launch boundaries, clock wrap-arounds and ring
+    wrap-arounds of a long run included)."""
+    for n, sample in ((2, [0, 511, 1023]), (3, [2047]), (4, [512])):
+        cfg = W.config(n)
+        assert cfg.steps == 100_000
+        sim, orc = run_both(B, oracle_mod, cfg, cfg.steps, oracle_reps=sample)
+        assert not sim.stats()["overflow"]
