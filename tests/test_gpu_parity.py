@@ -1,6 +1,7 @@
 """GPU parity: the HIP library against the CPU oracle on the same seeded inputs, through the C ABI.
 Integer state, tallies, histograms and digests are compared bit-exactly; derived fp64 figures
 (rates, revenue, latency means) within 1e-12 relative."""
+import os
 from dataclasses import replace
 
 import numpy as np
@@ -271,3 +272,13 @@ def test_configs_2_to_4_at_their_full_length(B, oracle_mod):
         assert cfg.steps == 100_000
         sim, orc = run_both(B, oracle_mod, cfg, cfg.steps, oracle_reps=sample)
         assert not sim.stats()["overflow"]
+
+
+@pytest.mark.skipif(os.environ.get("GNR_LONG_TESTS") != "1",
+                    reason="about 150 s of oracle time on one host core; set GNR_LONG_TESTS=1 to run")
+def test_config5_over_a_whole_modulation_period(B, oracle_mod):
+    """Config 5 at its full size over 100000 steps (one period of the arrival modulation: the empty system, the
+    load peak with queues of thousands and every solo server full, and the trough); the oracle follows the last
+    replication."""
+    cfg = W.config(5)
+    run_both(B, oracle_mod, cfg, 100_000, oracle_reps=[cfg.replications - 1], checkpoints=10)
