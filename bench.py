@@ -121,7 +121,7 @@ def main():
     ap.add_argument("--immediate", action="store_true",
                     help="decode on the server that ran the prefill, no static partition (the ablation without a decode "
                          "router: M = N)")
-    ap.add_argument("--oracle-steps", type=int, default=1500, help="0 skips the CPU baseline")
+    ap.add_argument("--oracle-steps", type=int, default=4000, help="0 skips the CPU baseline")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run one device-to-device copy of this size before the timed region "
                          "(a kernel of known traffic to scale hardware counters with)")
