@@ -53,7 +53,7 @@
 
 enum { LAW_GEOMETRIC = 0, LAW_LOGNORMAL = 1, LAW_CONST = 2, LAW_TABLE = 3 };
 enum { GATE_OCCUPANCY = 0, GATE_PRIORITY = 1, GATE_FCFS = 2 };
-enum { ROUTE_SOLO_FIRST = 0, ROUTE_RANDOM_SPLIT = 1, ROUTE_IMMEDIATE = 2 };
+enum { ROUTE_SOLO_FIRST = 0, ROUTE_RANDOM_SPLIT = 1, ROUTE_IMMEDIATE = 2, ROUTE_WEIGHTED_SPLIT = 3 };
 
 /* per-class tally indices */
 enum {
@@ -86,7 +86,10 @@ typedef struct {
   double mod_amp;
   int64_t mod_period;
   int64_t queue_cap, dbuf_cap;
-  const double *p_solo;       /* ROUTE_RANDOM_SPLIT: probability p_s,i that a class-i decode is sent to the solo group */
+  const double *p_solo;       /* ROUTE_RANDOM_SPLIT, ROUTE_WEIGHTED_SPLIT: probability p_s,i that a class-i decode is
+                                 sent to the solo group */
+  const double *w_solo, *w_mixed; /* ROUTE_WEIGHTED_SPLIT: class selection weights of the two pools (the paper's
+                                     varpi_s,i and varpi_m,i, EC "General SLI-aware Extension") */
 } oracle_config;
 
 typedef struct { int used; uint32_t fin; int cls, P, D; uint32_t stamp; } slot_t;
@@ -128,6 +131,8 @@ typedef struct oracle_t {
   oracle_class cls[MAXK];
   double x_star[MAXK], qp_star[MAXK], p_solo[MAXK];
   uint32_t solo_thr[MAXK];   /* a decode goes to the solo group when its random word is below this */
+  double w_pool[2][MAXK];    /* ROUTE_WEIGHTED_SPLIT: selection weights as given, [0] solo pool, [1] mixed pool */
+  uint32_t wsel[2][MAXK];    /* ... and as integers in units of 2^-20, at least 1 */
   int64_t c0_ns, cpre_ns, cdec_ns, dt_ns;
   double nx[MAXK], invx[MAXK], nq[MAXK];
   uint32_t *arr_thr;      /* [rows][3] */
@@ -183,6 +188,16 @@ static uint32_t thr32(double p)
   double v = floor(p * 4294967296.0);
   if (v < 0.0) v = 0.0;
   if (v > 4294967295.0) v = 4294967295.0;
+  return (uint32_t)v;
+}
+
+/* A class selection weight in units of 2^-20, never below one unit: a class with weight zero is still served
+ * when it is the only one waiting, so each pool stays work-conserving. */
+static uint32_t weight_units(double w)
+{
+  double v = floor(w * 1048576.0 + 0.5);
+  if (v < 1.0) v = 1.0;
+  if (v > 1048576.0) v = 1048576.0;
   return (uint32_t)v;
 }
 
@@ -320,8 +335,18 @@ int oracle_create(const oracle_config *cfg, int max_reps, oracle_t **out)
     if (!(cfg->cls[k].theta >= 0.0) || !isfinite(cfg->cls[k].theta) || !(cfg->cls[k].lambda >= 0.0) ||
         cfg->x_star[k] < 0.0) { free(o); return -1; }
   }
-  if (cfg->route_mode < ROUTE_SOLO_FIRST || cfg->route_mode > ROUTE_IMMEDIATE) { free(o); return -1; }
-  if (cfg->route_mode == ROUTE_RANDOM_SPLIT) {
+  if (cfg->route_mode < ROUTE_SOLO_FIRST || cfg->route_mode > ROUTE_WEIGHTED_SPLIT) { free(o); return -1; }
+  if (cfg->route_mode == ROUTE_WEIGHTED_SPLIT) {
+    if (!cfg->w_solo || !cfg->w_mixed) { free(o); return -1; }
+    for (int k = 0; k < cfg->K; k++) {
+      if (!(cfg->w_solo[k] >= 0.0) || !(cfg->w_solo[k] <= 1.0) || !(cfg->w_mixed[k] >= 0.0) || !(cfg->w_mixed[k] <= 1.0)) {
+        free(o); return -1;
+      }
+      o->w_pool[0][k] = cfg->w_solo[k]; o->w_pool[1][k] = cfg->w_mixed[k];
+      o->wsel[0][k] = weight_units(cfg->w_solo[k]); o->wsel[1][k] = weight_units(cfg->w_mixed[k]);
+    }
+  }
+  if (cfg->route_mode == ROUTE_RANDOM_SPLIT || cfg->route_mode == ROUTE_WEIGHTED_SPLIT) {
     if (!cfg->p_solo) { free(o); return -1; }
     for (int k = 0; k < cfg->K; k++) {
       if (!(cfg->p_solo[k] >= 0.0) || !(cfg->p_solo[k] <= 1.0)) { free(o); return -1; }
@@ -329,6 +354,7 @@ int oracle_create(const oracle_config *cfg, int max_reps, oracle_t **out)
     }
   }
   o->cfg.cls = o->cls; o->cfg.x_star = o->x_star; o->cfg.qp_star = o->qp_star; o->cfg.p_solo = o->p_solo;
+  o->cfg.w_solo = o->w_pool[0]; o->cfg.w_mixed = o->w_pool[1];
   o->c0_ns = llround(cfg->c0 * 1e9);
   o->cpre_ns = llround(cfg->c_pre * 1e9);
   o->cdec_ns = llround(cfg->c_dec * 1e9);
@@ -663,7 +689,7 @@ static void step_rep(oracle_t *o, int r, uint32_t s)
           goto prefill_done;
         }
         fifojob *buf = &R->dbuf;
-        if (o->cfg.route_mode == ROUTE_RANDOM_SPLIT) {
+        if (o->cfg.route_mode == ROUTE_RANDOM_SPLIT || o->cfg.route_mode == ROUTE_WEIGHTED_SPLIT) {
           draw(o, r, g, s, 10u, w);
           if (!(w[1] < o->solo_thr[k])) buf = &R->dbuf_m;
         }
@@ -721,10 +747,18 @@ static void step_rep(oracle_t *o, int r, uint32_t s)
   /*    Under the randomized router each component of the buffer feeds its own group only: first the
    *    solo component to the solo group, then the mixed component to the mixed group (the two do not
    *    interact); within the group the same least-loaded rule. */
+  /*    General SLI-aware router (EC "General SLI-aware Extension"): the two pools as above, but whenever a slot of
+   *    a pool is filled the class is drawn with the pool's selection weights restricted to the classes that wait
+   *    in the pool's buffer, and the head-of-line job of that class is taken (FCFS within a class). The j-th
+   *    placement of the step in a pool uses word 0 of block (step, stream 11 for solo / 12 for mixed, j,
+   *    replication): with W the sum of the weights (in units of 2^-20) of the waiting classes, x = (word * W) >> 32
+   *    falls into the weight interval of the chosen class, classes in ascending order. */
   for (int pass = 0; pass < 2; pass++) {
-  const int split = o->cfg.route_mode == ROUTE_RANDOM_SPLIT;
+  const int weighted = o->cfg.route_mode == ROUTE_WEIGHTED_SPLIT;
+  const int split = o->cfg.route_mode == ROUTE_RANDOM_SPLIT || weighted;
   fifojob *buf = (split && pass == 1) ? &R->dbuf_m : &R->dbuf;
   if (!split && pass == 1) break;
+  uint32_t placed = 0;
   while (buf->len > 0) {
     int dst = -1, bl = 0;
     if (!split || pass == 0)
@@ -732,7 +766,31 @@ static void step_rep(oracle_t *o, int r, uint32_t s)
     if (dst < 0 && (!split || pass == 1))
       for (int g = 0; g < M; g++) { int l = R->sv[g].n_dec; if (l < B - 1 && (dst < 0 || l < bl)) { dst = g; bl = l; } }
     if (dst < 0) break;
-    job_t jb = fj_pop(buf);
+    job_t jb;
+    if (weighted) {
+      int64_t first[MAXK];
+      uint64_t total = 0;
+      for (int k = 0; k < K; k++) first[k] = -1;
+      for (int64_t i = 0; i < buf->len; i++) {
+        int c = buf->v[buf->head + i].cls;
+        if (first[c] < 0) first[c] = i;
+      }
+      for (int k = 0; k < K; k++) if (first[k] >= 0) total += o->wsel[pass][k];
+      draw(o, r, (int)placed, s, 11u + (uint32_t)pass, w);
+      uint64_t x = ((uint64_t)w[0] * total) >> 32, cum = 0;
+      int c = -1;
+      for (int k = 0; k < K && c < 0; k++) {
+        if (first[k] < 0) continue;
+        cum += o->wsel[pass][k];
+        if (x < cum) c = k;
+      }
+      jb = buf->v[buf->head + first[c]];
+      for (int64_t i = first[c]; i + 1 < buf->len; i++) buf->v[buf->head + i] = buf->v[buf->head + i + 1];
+      buf->len--;
+    } else {
+      jb = fj_pop(buf);
+    }
+    placed++;
     server_t *sv = &R->sv[dst];
     R->Qd[jb.cls]--;
     int j = 0; while (sv->slot[j].used) j++;

@@ -147,6 +147,15 @@ def solo_probabilities(plan: Plan) -> np.ndarray:
     return np.where(a + b > 0.0, a / np.where(a + b > 0.0, a + b, 1.0), 1.0)
 
 
+def selection_weights(plan: Plan):
+    """(varpi_s, varpi_m): the class shares of the planned decode completion rate of the solo and of the mixed pool,
+    varpi_s,i = mu_s,i y_s,i* / sum_j mu_s,j y_s,j* and likewise for the mixed pool, 0/0 = 0 (paper EC, "General
+    SLI-aware Extension")."""
+    a = plan.mu_s * plan.ys
+    b = plan.mu_m * plan.ym
+    return (a / a.sum() if a.sum() > 0.0 else np.zeros_like(a)), (b / b.sum() if b.sum() > 0.0 else np.zeros_like(b))
+
+
 def capacity_scale(cfg, mix, tbt_mixed_share=None, **kw) -> float:
     """Largest s such that arrivals s*mix are served in full by the fluid LP (all classes at 100 %),
     under the optional per-class bound on the share of decode tokens emitted in mixed iterations."""

@@ -22,7 +22,7 @@ from . import plan as _plan
 
 LAW_GEOMETRIC, LAW_LOGNORMAL, LAW_CONST, LAW_TABLE = 0, 1, 2, 3
 GATE_OCCUPANCY, GATE_PRIORITY, GATE_FCFS = 0, 1, 2
-ROUTE_SOLO_FIRST, ROUTE_RANDOM_SPLIT, ROUTE_IMMEDIATE = 0, 1, 2
+ROUTE_SOLO_FIRST, ROUTE_RANDOM_SPLIT, ROUTE_IMMEDIATE, ROUTE_WEIGHTED_SPLIT = 0, 1, 2, 3
 
 
 @dataclass
@@ -68,7 +68,9 @@ class SimConfig:
     steps: int = 1000
     seed: int = 1
     notes: dict = field(default_factory=dict)
-    p_solo: List[float] = field(default_factory=list)   # ROUTE_RANDOM_SPLIT: Pr(a class-i decode goes to the solo group)
+    p_solo: List[float] = field(default_factory=list)   # ROUTE_RANDOM_SPLIT, ROUTE_WEIGHTED_SPLIT: Pr(a class-i decode goes to the solo group)
+    w_solo: List[float] = field(default_factory=list)   # ROUTE_WEIGHTED_SPLIT: class selection weights of the solo pool
+    w_mixed: List[float] = field(default_factory=list)  # ... and of the mixed pool
 
 
 def with_plan(cfg: SimConfig, lam_plan=None, objective="bundled", **kw) -> SimConfig:
@@ -100,6 +102,16 @@ def with_random_split(cfg: SimConfig, lam_plan=None, **kw) -> SimConfig:
     lam = [c.lam for c in cfg.classes] if lam_plan is None else lam_plan
     p = _plan.solve_lp(cfg, lam, **kw)
     return replace(cfg, route_mode=ROUTE_RANDOM_SPLIT, p_solo=[float(v) for v in _plan.solo_probabilities(p)])
+
+
+def with_weighted_split(cfg: SimConfig, lam_plan=None, **kw) -> SimConfig:
+    """The general SLI-aware router (paper EC, "General SLI-aware Extension"): solo probabilities and the two pools'
+    class selection weights from the plan."""
+    lam = [c.lam for c in cfg.classes] if lam_plan is None else lam_plan
+    p = _plan.solve_lp(cfg, lam, **kw)
+    ws, wm = _plan.selection_weights(p)
+    return replace(cfg, route_mode=ROUTE_WEIGHTED_SPLIT, p_solo=[float(v) for v in _plan.solo_probabilities(p)],
+                   w_solo=[float(v) for v in ws], w_mixed=[float(v) for v in wm])
 
 
 def _scaled_to_load(cfg: SimConfig, mix, rho: float, **kw) -> SimConfig:

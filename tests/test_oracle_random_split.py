@@ -119,4 +119,4 @@ def test_bad_split_probabilities_are_rejected(oracle_mod):
     with pytest.raises(ValueError):
         oracle_mod.Oracle(cfg)
     with pytest.raises(ValueError):
-        oracle_mod.Oracle(replace(_heavy(), route_mode=3))
+        oracle_mod.Oracle(replace(_heavy(), route_mode=4))
