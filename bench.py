@@ -63,10 +63,12 @@ def measured_traffic():
     return TRAFFIC["bytes_per_launch"] if TRAFFIC["kernel_sha256"] == sha else None
 
 
-def policy_variant(W, cfg, theta, split, immediate):
+def policy_variant(W, cfg, theta, split, immediate, weighted=False):
     """The configuration with the optional policy switches of the command line applied."""
     if split:
         cfg = W.with_random_split(cfg, lam_plan=[c.lam / 0.95 for c in cfg.classes])
+    if weighted:
+        cfg = W.with_weighted_split(cfg, lam_plan=[c.lam / 0.95 for c in cfg.classes])
     if immediate:
         cfg.route_mode = W.ROUTE_IMMEDIATE   # as in the paper's ablation: no static partition, every server may prefill
         cfg.M = cfg.N
@@ -77,11 +79,11 @@ def policy_variant(W, cfg, theta, split, immediate):
 
 
 def _oracle_worker(args):
-    n, N, rep, steps, theta, split, immediate = args
+    n, N, rep, steps, theta, split, immediate, weighted = args
     sys.path.insert(0, ROOT)
     from oracle import binding as ob
     from paper_2602_02987_amd import workloads as W
-    cfg = policy_variant(W, W.config(n, N=N), theta, split, immediate)
+    cfg = policy_variant(W, W.config(n, N=N), theta, split, immediate, weighted)
     o = ob.Oracle(cfg, max_reps=cfg.replications)
     o.select([rep])
     t = time.perf_counter()
@@ -89,7 +91,7 @@ def _oracle_worker(args):
     return time.perf_counter() - t
 
 
-def cpu_baseline(n, N, steps, theta=0.0, split=False, immediate=False):
+def cpu_baseline(n, N, steps, theta=0.0, split=False, immediate=False, weighted=False):
     """The oracle as it stands, one replication per host process, on a bounded sample."""
     import multiprocessing as mp
     from oracle import binding as ob
@@ -97,7 +99,7 @@ def cpu_baseline(n, N, steps, theta=0.0, split=False, immediate=False):
     cores = min(16, os.cpu_count() or 1)
     t = time.perf_counter()
     with mp.get_context("spawn").Pool(cores) as pool:
-        pool.map(_oracle_worker, [(n, N, r, steps, theta, split, immediate) for r in range(cores)])
+        pool.map(_oracle_worker, [(n, N, r, steps, theta, split, immediate, weighted) for r in range(cores)])
     wall = time.perf_counter() - t
     return dict(value=cores * N * steps / wall, unit="server-steps/s", cores=cores, kind="oracle",
                 sample=f"replications 0..{cores - 1} of the workload, first {steps} steps from the empty system, "
@@ -118,6 +120,9 @@ def main():
                     help="patience rate given to every class (abandonment; 0 = the configuration's own, none)")
     ap.add_argument("--random-split", action="store_true",
                     help="route decodes with the randomized router, solo probabilities from the configuration's plan")
+    ap.add_argument("--weighted-split", action="store_true",
+                    help="route decodes with the general SLI-aware router: solo probabilities and class selection "
+                         "weights from the configuration's plan")
     ap.add_argument("--immediate", action="store_true",
                     help="decode on the server that ran the prefill, no static partition (the ablation without a decode "
                          "router: M = N)")
@@ -136,7 +141,8 @@ def main():
     base = None
     if args.oracle_steps > 0:
         n_servers = args.servers if args.servers else W.config(args.config).N
-        base = cpu_baseline(args.config, n_servers, args.oracle_steps, args.theta, args.random_split, args.immediate)
+        base = cpu_baseline(args.config, n_servers, args.oracle_steps, args.theta, args.random_split, args.immediate,
+                            args.weighted_split)
 
     import torch
     from paper_2602_02987_amd import binding
@@ -145,10 +151,11 @@ def main():
         over["N"] = args.servers
     if args.replications:
         over["replications"] = args.replications
-    if args.random_split and args.immediate:
-        ap.error("--random-split and --immediate are two different decode rules")
-    cfg = policy_variant(W, W.config(args.config, **over), args.theta, args.random_split, args.immediate)
+    if args.random_split + args.immediate + args.weighted_split > 1:
+        ap.error("--random-split, --weighted-split and --immediate are different decode rules")
+    cfg = policy_variant(W, W.config(args.config, **over), args.theta, args.random_split, args.immediate, args.weighted_split)
     default_run = (args.config == 5 and not over and not args.theta and not args.random_split and not args.immediate
+                   and not args.weighted_split
                    and args.sim_steps == 1000 and args.preload == 30000)
     slots_per_step = cfg.N * cfg.replications * args.sim_steps
 
@@ -197,6 +204,7 @@ def main():
         "config": {"workload": f"{cfg.name}: K={cfg.K} N={cfg.N} R={cfg.replications} B={cfg.B} C={cfg.C} M={cfg.M}"
                                + (f" theta={args.theta}" if args.theta else "")
                                + (" randomized router" if args.random_split else "")
+                               + (" weighted router" if args.weighted_split else "")
                                + (" immediate decode" if args.immediate else "") + ", "
                                f"{args.sim_steps} simulation steps per bench step after {args.preload + args.warmup * args.sim_steps} untimed steps",
                    "server_step_slots_per_bench_step": slots_per_step,

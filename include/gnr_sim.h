@@ -67,8 +67,18 @@ enum sim_gate { SIM_GATE_OCCUPANCY = 0, SIM_GATE_PRIORITY = 1, SIM_GATE_FCFS = 2
  * a request whose prefill completes goes on decoding on the same server, in the slot it already holds, and joins
  * the batch at the restart that follows; a server holds at most B requests, its prefill included, so the gate
  * admits only to servers with no prefill in service and fewer than B decodes; the decode buffer stays empty.
- * ("WSP", without static planning, is a configuration with M = N.) */
-enum sim_route { SIM_ROUTE_SOLO_FIRST = 0, SIM_ROUTE_RANDOM_SPLIT = 1, SIM_ROUTE_IMMEDIATE = 2 };
+ * ("WSP", without static planning, is a configuration with M = N.)
+ * WEIGHTED_SPLIT: the general SLI-aware router (EC, "General SLI-aware Extension"): requests are sent to the
+ * solo or the mixed pool's buffer as under RANDOM_SPLIT; whenever a slot of a pool is filled, the class is drawn
+ * with the pool's selection weights (w_solo = varpi_s, w_mixed = varpi_m) restricted to the classes that wait in
+ * that pool's buffer, and the head-of-line request of that class is taken (FCFS within a class). Weights are
+ * used in units of 2^-20, rounded to nearest and never below one unit (a class of weight zero is served when no
+ * other class waits, so a pool stays work-conserving). The j-th placement of a step in a pool draws word 0 of
+ * block (step, stream 11 for the solo / 12 for the mixed pool, j, replication): with W the sum of the units of
+ * the waiting classes, x = (word * W) >> 32 falls into the interval of the chosen class, classes in ascending
+ * order. The server is the least-loaded feasible one of the pool, as for the other routers. */
+enum sim_route { SIM_ROUTE_SOLO_FIRST = 0, SIM_ROUTE_RANDOM_SPLIT = 1, SIM_ROUTE_IMMEDIATE = 2,
+                 SIM_ROUTE_WEIGHTED_SPLIT = 3 };
 
 /* Per-class cumulative tallies (uint64), in this order. Counting processes as in Sec. 2.3:
  * A arrivals, U_P admissions to prefill, S_P prefill completions, U_DM/U_DS admissions to a
@@ -119,7 +129,9 @@ typedef struct {
   double mod_amp;                /* arrival modulation lambda(s) = lambda*(1 + amp*sin(2*pi*(s mod period)/period)) */
   int64_t mod_period;            /* in steps; 0 = homogeneous */
   int64_t queue_cap, dbuf_cap;   /* ring capacities: per class prefill queue, decode buffer */
-  const double *p_solo;          /* RANDOM_SPLIT: K probabilities p_s,i in [0,1], copied; else unused, may be NULL */
+  const double *p_solo;          /* RANDOM_SPLIT, WEIGHTED_SPLIT: K probabilities p_s,i in [0,1], copied; else unused, may be NULL */
+  const double *w_solo;          /* WEIGHTED_SPLIT: K class selection weights of the solo pool in [0,1] (varpi_s,i), copied */
+  const double *w_mixed;         /* WEIGHTED_SPLIT: ... of the mixed pool (varpi_m,i); both unused otherwise, may be NULL */
 } sim_config;
 
 /* Totals over replications plus derived fp64 figures (rates per server per unit time). */

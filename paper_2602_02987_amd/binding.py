@@ -34,7 +34,7 @@ class SimConfigC(C.Structure):
                 ("cls", C.c_void_p), ("M", C.c_int), ("x_star", C.c_void_p), ("qp_star", C.c_void_p),
                 ("gate_mode", C.c_int), ("route_mode", C.c_int), ("mod_amp", C.c_double),
                 ("mod_period", C.c_int64), ("queue_cap", C.c_int64), ("dbuf_cap", C.c_int64),
-                ("p_solo", C.c_void_p)]
+                ("p_solo", C.c_void_p), ("w_solo", C.c_void_p), ("w_mixed", C.c_void_p)]
 
 
 _D8 = C.c_double * MAXK
@@ -135,12 +135,14 @@ def marshal_config(cfg):
     xs = (C.c_double * K)(*cfg.x_star)
     qs = (C.c_double * K)(*cfg.qp_star)
     ps = (C.c_double * K)(*(list(getattr(cfg, "p_solo", [])) or [1.0] * K))
+    ws = (C.c_double * K)(*(list(getattr(cfg, "w_solo", [])) or [1.0 / K] * K))
+    wm = (C.c_double * K)(*(list(getattr(cfg, "w_mixed", [])) or [1.0 / K] * K))
     cc = SimConfigC(K=K, N=cfg.N, B=cfg.B, C=cfg.C, c0=cfg.c0, c_pre=cfg.c_pre, c_dec=cfg.c_dec, dt=cfg.dt,
                     cls=C.addressof(cls), M=cfg.M, x_star=C.addressof(xs), qp_star=C.addressof(qs),
                     gate_mode=cfg.gate_mode, route_mode=cfg.route_mode, mod_amp=cfg.mod_amp,
                     mod_period=cfg.mod_period, queue_cap=cfg.queue_cap, dbuf_cap=cfg.dbuf_cap,
-                    p_solo=C.addressof(ps))
-    keep += [cls, xs, qs, ps]
+                    p_solo=C.addressof(ps), w_solo=C.addressof(ws), w_mixed=C.addressof(wm))
+    keep += [cls, xs, qs, ps, ws, wm]
     return cc, keep
 
 

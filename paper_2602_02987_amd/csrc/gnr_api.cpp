@@ -13,7 +13,7 @@ using namespace gnr;
 struct sim_t {
   sim_config cfg;
   sim_class cls[kMaxK];
-  double x_star[kMaxK], qp_star[kMaxK], p_solo[kMaxK];
+  double x_star[kMaxK], qp_star[kMaxK], p_solo[kMaxK], w_solo[kMaxK], w_mixed[kMaxK];
   Params p;
   int max_reps;
   int reps;
@@ -83,7 +83,7 @@ Layout make_layout(const sim_config &c, int R, int64_t rows, size_t cal_entries)
     L.cal = take(static_cast<size_t>(R) * c.K * cal_entries * sizeof(uint32_t));
     L.dcal = take(static_cast<size_t>(R) * c.K * cal_entries * sizeof(uint32_t));
   }
-  if (c.route_mode == SIM_ROUTE_RANDOM_SPLIT) {
+  if (c.route_mode == SIM_ROUTE_RANDOM_SPLIT || c.route_mode == SIM_ROUTE_WEIGHTED_SPLIT) {
     L.dring_m = take(static_cast<size_t>(R) * c.dbuf_cap * sizeof(uint64_t));
     if (cal_entries) {
       L.ddl_m = take(static_cast<size_t>(R) * c.dbuf_cap * sizeof(uint32_t));
@@ -123,6 +123,7 @@ size_t on_chip_bytes(const sim_config &c, const Ticks &t, int M)
   q.threads = step_threads(c.N);
   for (int k = 0; k < c.K; ++k)
     if (c.cls[k].theta > 0.0) q.ab_classes |= 1u << k;
+  q.dl_rings = q.ab_classes != 0 || c.route_mode == SIM_ROUTE_WEIGHTED_SPLIT;
   return step_lds_bytes(q);
 }
 
@@ -134,8 +135,14 @@ int validate(const sim_config *c, int max_reps, Ticks *t)
   if (c->queue_cap < 1 || c->queue_cap > (int64_t(1) << 30) || c->dbuf_cap < 1 || c->dbuf_cap > (int64_t(1) << 30))
     return SIM_EINVAL;
   if (c->gate_mode < SIM_GATE_OCCUPANCY || c->gate_mode > SIM_GATE_FCFS) return SIM_EINVAL;
-  if (c->route_mode < SIM_ROUTE_SOLO_FIRST || c->route_mode > SIM_ROUTE_IMMEDIATE) return SIM_EINVAL;
-  if (c->route_mode == SIM_ROUTE_RANDOM_SPLIT) {
+  if (c->route_mode < SIM_ROUTE_SOLO_FIRST || c->route_mode > SIM_ROUTE_WEIGHTED_SPLIT) return SIM_EINVAL;
+  if (c->route_mode == SIM_ROUTE_WEIGHTED_SPLIT) {
+    if (!c->w_solo || !c->w_mixed) return SIM_EINVAL;
+    for (int k = 0; k < c->K; ++k)
+      if (!(c->w_solo[k] >= 0.0) || !(c->w_solo[k] <= 1.0) || !(c->w_mixed[k] >= 0.0) || !(c->w_mixed[k] <= 1.0))
+        return SIM_EINVAL;
+  }
+  if (c->route_mode == SIM_ROUTE_RANDOM_SPLIT || c->route_mode == SIM_ROUTE_WEIGHTED_SPLIT) {
     if (!c->p_solo) return SIM_EINVAL;
     for (int k = 0; k < c->K; ++k)
       if (!(c->p_solo[k] >= 0.0) || !(c->p_solo[k] <= 1.0)) return SIM_EINVAL;
@@ -165,11 +172,13 @@ int validate(const sim_config *c, int max_reps, Ticks *t)
 }
 
 // Patience tables of the classes that have a rate (others zero-filled) and the calendar size they need:
-// the power of two above the longest patience. Returns 0 entries when no class abandons.
+// the power of two above the longest patience. Returns 0 entries when no class abandons, unless the weighted
+// router is on: it needs the deadline rings (it marks the entries it takes out of a buffer as expired), so it
+// gets the smallest calendars even when nobody abandons.
 int patience_tables(const sim_config &c, const Ticks &t, std::vector<uint16_t> *tab, size_t *cal_entries)
 {
   *cal_entries = 0;
-  if (!any_patience(c)) return SIM_OK;
+  if (!any_patience(c) && c.route_mode != SIM_ROUTE_WEIGHTED_SPLIT) return SIM_OK;
   tab->assign(static_cast<size_t>(c.K) * kTableSize, 0);
   uint32_t longest = 1;
   for (int k = 0; k < c.K; ++k) {
@@ -269,7 +278,13 @@ int sim_create(const sim_config *cfg, int max_replications, void *dev_workspace,
     h->x_star[k] = cfg->x_star[k];
     h->qp_star[k] = cfg->qp_star[k];
   }
-  for (int k = 0; k < cfg->K; ++k) h->p_solo[k] = cfg->route_mode == SIM_ROUTE_RANDOM_SPLIT ? cfg->p_solo[k] : 1.0;
+  const bool split = cfg->route_mode == SIM_ROUTE_RANDOM_SPLIT || cfg->route_mode == SIM_ROUTE_WEIGHTED_SPLIT;
+  for (int k = 0; k < cfg->K; ++k) {
+    h->p_solo[k] = split ? cfg->p_solo[k] : 1.0;
+    h->w_solo[k] = cfg->route_mode == SIM_ROUTE_WEIGHTED_SPLIT ? cfg->w_solo[k] : 0.0;
+    h->w_mixed[k] = cfg->route_mode == SIM_ROUTE_WEIGHTED_SPLIT ? cfg->w_mixed[k] : 0.0;
+  }
+  h->cfg.w_solo = h->w_solo; h->cfg.w_mixed = h->w_mixed;
   h->cfg.cls = h->cls; h->cfg.x_star = h->x_star; h->cfg.qp_star = h->qp_star; h->cfg.p_solo = h->p_solo;
   h->max_reps = max_replications;
   h->reps = 0; h->seed = 0; h->steps_done = 0; h->started = false;
@@ -300,7 +315,11 @@ int sim_create(const sim_config *cfg, int max_replications, void *dev_workspace,
   p.BS = (cfg->B + 3) & ~3;
   p.gate_mode = cfg->gate_mode;
   p.route_mode = cfg->route_mode;
-  for (int k = 0; k < cfg->K; ++k) p.solo_thr[k] = probability_threshold(h->p_solo[k]);
+  for (int k = 0; k < cfg->K; ++k) {
+    p.solo_thr[k] = probability_threshold(h->p_solo[k]);
+    p.wsel[0][k] = selection_weight_units(h->w_solo[k]);
+    p.wsel[1][k] = selection_weight_units(h->w_mixed[k]);
+  }
   p.tbt_lo = host_hbin(t.c0);
   p.tbt_w = host_hbin(t.c0 + t.cpre * cfg->C + t.cdec * cfg->B) - p.tbt_lo + 1;
   p.nwords = (cfg->N + 63) / 64;
@@ -334,7 +353,7 @@ int sim_create(const sim_config *cfg, int max_replications, void *dev_workspace,
   p.hist = reinterpret_cast<uint64_t *>(w + L.hist);
   p.digest = reinterpret_cast<uint64_t *>(w + L.digest);
   p.reduced = reinterpret_cast<uint64_t *>(w + L.reduced);
-  if (cfg->route_mode == SIM_ROUTE_RANDOM_SPLIT) p.dring_m = reinterpret_cast<uint64_t *>(w + L.dring_m);
+  if (split) p.dring_m = reinterpret_cast<uint64_t *>(w + L.dring_m);
   if (cal_entries) {
     for (int k = 0; k < cfg->K; ++k)
       if (cfg->cls[k].theta > 0.0) p.ab_classes |= 1u << k;
@@ -344,7 +363,8 @@ int sim_create(const sim_config *cfg, int max_replications, void *dev_workspace,
     p.ddl = reinterpret_cast<uint32_t *>(w + L.ddl);
     p.cal = reinterpret_cast<uint32_t *>(w + L.cal);
     p.dcal = reinterpret_cast<uint32_t *>(w + L.dcal);
-    if (cfg->route_mode == SIM_ROUTE_RANDOM_SPLIT) {
+    p.dl_rings = 1;
+    if (split) {
       p.ddl_m = reinterpret_cast<uint32_t *>(w + L.ddl_m);
       p.dcal_m = reinterpret_cast<uint32_t *>(w + L.dcal_m);
     }
@@ -635,7 +655,7 @@ int sim_snapshot(sim_t *h, int r, sim_state_t *out, void *hip_stream)
     if (rc != SIM_OK) return rc;
     for (int64_t i = 0; i < cs[CS_DCOUNT]; ++i) out->dbuf[i] = ring[(static_cast<uint32_t>(cs[CS_DHEAD]) + i) % p.dbuf_cap];
   }
-  out->dbuf_m_len = p.route_mode == SIM_ROUTE_RANDOM_SPLIT ? cs[CS_DCOUNT_M] : 0;
+  out->dbuf_m_len = (p.route_mode == SIM_ROUTE_RANDOM_SPLIT || p.route_mode == SIM_ROUTE_WEIGHTED_SPLIT) ? cs[CS_DCOUNT_M] : 0;
   if (out->dbuf_m && out->dbuf_m_len > 0) {
     std::vector<uint64_t> ring(p.dbuf_cap);
     rc = copy_out(ring.data(), p.dring_m + static_cast<size_t>(r) * p.dbuf_cap, ring.size() * sizeof(uint64_t));

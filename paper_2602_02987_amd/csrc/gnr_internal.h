@@ -27,11 +27,13 @@ constexpr int kMaxTbtBins = 256;  // width of the on-chip time-between-tokens hi
 enum ClassStateWord {
   CS_QP = 0, CS_X = 8, CS_QD = 16, CS_YM = 24, CS_YS = 32, CS_QHEAD = 40, CS_DHEAD = 48, CS_DCOUNT = 49,
   CS_DHEAD_M = 50, CS_DCOUNT_M = 51,   // the mixed group's buffer under the randomized router
+  CS_QDS = 52,                         // [8] weighted router: waiting requests per class in the solo group's buffer
   CS_WORDS = 64
 };
 constexpr uint32_t kNever = 0xFFFFFFFFu;   // deadline of a request that never abandons
 constexpr int kStreamPatienceP = 2;        // random streams: 0 arrivals, 1 lengths, 2+k prefill-queue patience of class k,
-constexpr int kStreamPatienceD = 10;       // 10 decode-buffer patience
+constexpr int kStreamPatienceD = 10;       // 10 decode-buffer patience (word 0) and group of the randomized routers (word 1)
+constexpr int kStreamSelect = 11;          // 11, 12: class selection of the weighted router in the solo / mixed pool
 
 // Everything a kernel needs, passed by value.
 struct Params {
@@ -51,9 +53,14 @@ struct Params {
   // abandonment: classes with a patience rate (bit k), mask of the deadline calendars (entries - 1, a power of two
   // above the longest patience in steps)
   uint32_t ab_classes, cal_mask;
+  // deadline rings and calendars are in use: some class has a patience rate, or the weighted router is on (it
+  // takes requests out of the middle of a buffer and marks their entries with a deadline that has passed)
+  uint32_t dl_rings;
   // randomized router: a decode of class k goes to the solo group when its random word is below solo_thr[k]
   int route_mode;
   uint32_t solo_thr[kMaxK];
+  // weighted router: class selection weights of the solo [0] and the mixed [1] pool in units of 2^-20, at least 1
+  uint32_t wsel[2][kMaxK];
   // tables (device)
   const uint32_t *arr_thr;    // [rows][3]
   const uint16_t *len_tab;    // [K][2][65536]: in, out
@@ -94,6 +101,7 @@ double total_rate(const sim_class *cls, int K);
 void build_arrival_row(double lam, int64_t dt_ns, double amp, int64_t period, int64_t row, uint32_t thr[3]);
 void build_class_thresholds(const sim_class *cls, int K, uint32_t *thr);
 uint32_t probability_threshold(double p);   // floor(p * 2^32) clamped to [0, 2^32 - 1]
+uint32_t selection_weight_units(double w);  // round(w * 2^20) clamped to [1, 2^20]
 
 // kernel launchers (gnr_kernels.hip); stream is a hipStream_t
 int launch_reset(const Params &p, int reps, void *stream);

@@ -176,6 +176,10 @@ struct Lds {
   uint8_t *pend;      // [N] completed iterations not yet tallied (all with the server's current batch)
   uint16_t *rem;      // [Mp] prompt tokens left of the prefill a server has in service (0: none)
   uint32_t *live_off; // [K][kAdmChunk] abandonment only: ring offset from the head of the m-th waiting request of a class
+  // weighted router only: the class selections of a routing pass
+  uint32_t *sel_u;    // [kJobsLds] random word of each selection
+  uint16_t *sel_co;   // [kJobsLds] class | (how many selections before it chose the same class) << 3
+  uint16_t *sel_j;    // [kJobsLds] list position of each selection, ordered by class, then by order within the class
 };
 
 // Carves the dynamic LDS block; 8-byte granules, 64-bit arrays first.
@@ -217,7 +221,10 @@ __host__ __device__ __forceinline__ Lds lds_carve(const Params &p, unsigned char
   GNR_TAKE(pend, uint8_t, p.N)
   GNR_TAKE(rem, uint16_t, p.Mp)
   GNR_TAKE(stage, uint16_t, 2 * p.threads)
-  GNR_TAKE(live_off, uint32_t, p.ab_classes ? p.K * kAdmChunk : 0)
+  GNR_TAKE(live_off, uint32_t, p.dl_rings ? p.K * kAdmChunk : 0)
+  GNR_TAKE(sel_u, uint32_t, p.route_mode == SIM_ROUTE_WEIGHTED_SPLIT ? kJobsLds : 0)
+  GNR_TAKE(sel_co, uint16_t, p.route_mode == SIM_ROUTE_WEIGHTED_SPLIT ? kJobsLds : 0)
+  GNR_TAKE(sel_j, uint16_t, p.route_mode == SIM_ROUTE_WEIGHTED_SPLIT ? kJobsLds : 0)
 #undef GNR_TAKE
   if (total) *total = off;
   return L;
@@ -1005,6 +1012,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           L.cs[CS_QD + k] -= static_cast<int32_t>(n_leave_d);
           L.tl[k * kNTally + SIM_T_AB_D] += n_leave_d;
           atomicSub(&L.cs[CS_DCOUNT], static_cast<int32_t>(n_leave_d));
+          if constexpr (RR) L.cs[CS_QDS + k] -= static_cast<int32_t>(n_leave_d);   // (read by the weighted router only)
         }
         if constexpr (RR) {
           if (n_leave_dm) {
@@ -1129,6 +1137,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
             }
           }
           wave_count_by_class_i32(kept, k, K, &L.cs[CS_QD], 1);
+          if constexpr (AB) wave_count_by_class_i32(kept && solo, k, K, &L.cs[CS_QDS], 1);   // (read by the weighted router only)
           if (__ballot(active && !kept)) {
             wave_count_by_class(active && !kept, k, K, &L.tl[SIM_T_DROP_D], kNTally);
             if (lane == 0) L.tl[kMaxK * kNTally + SIM_G_OVERFLOW] = 1;
@@ -1581,12 +1590,146 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
               }
               if (lane == 0) L.sc[scan_word] = static_cast<int32_t>(found >= need ? stop : len);   // (found < need: see the gate's scan)
             };
+            // Weighted router: the pass's `need` placements in a pool each draw a class among those that still
+            // wait in the pool's buffer (one after the other: a class that runs out drops from the later draws) and
+            // take that class's requests in their order of arrival. The ring keeps the others where they are: an
+            // entry that is taken gets a deadline that has passed, like an abandoned one.
+            auto select_and_stage = [&](int pool, uint64_t *ring, uint32_t *dlr, uint32_t *calr, uint32_t hd, uint32_t len,
+                                        int scan_word, int need, int first_job, int placed_before,
+                                        int (&nsel)[kMaxK]) __attribute__((always_inline)) {
+              for (int j = lane; j < need; j += 64) {
+                uint32_t w[4];
+                philox4x32_10(key0, key1, s, static_cast<uint32_t>(kStreamSelect + pool), static_cast<uint32_t>(placed_before + j),
+                              static_cast<uint32_t>(r), w);
+                L.sel_u[j] = w[0];
+              }
+              int cnt[kMaxK];
+              uint32_t wt[kMaxK];
+#pragma unroll
+              for (int c = 0; c < kMaxK; ++c) {
+                const int solo_c = c < K ? L.cs[CS_QDS + c] : 0, all_c = c < K ? L.cs[CS_QD + c] : 0;
+                cnt[c] = __builtin_amdgcn_readfirstlane(pool == 0 ? solo_c : all_c - solo_c);
+                wt[c] = p.wsel[pool][c];
+                nsel[c] = 0;
+              }
+              __builtin_amdgcn_wave_barrier();
+              for (int j = 0; j < need; ++j) {   // wave-uniform: every lane follows the same draws
+                uint32_t total = 0;
+#pragma unroll
+                for (int c = 0; c < kMaxK; ++c) total += cnt[c] > 0 ? wt[c] : 0u;
+                const uint32_t u = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(L.sel_u[j])));
+                const uint32_t x = static_cast<uint32_t>((static_cast<uint64_t>(u) * total) >> 32);
+                int pick = -1;
+                uint32_t cum = 0;
+#pragma unroll
+                for (int c = 0; c < kMaxK; ++c) {
+                  if (cnt[c] > 0) {
+                    cum += wt[c];
+                    if (pick < 0 && x < cum) pick = c;
+                  }
+                }
+                if (pick < 0) pick = 0;   // (no class waits: cannot happen, the pass takes no more than wait)
+                int ord = 0;
+#pragma unroll
+                for (int c = 0; c < kMaxK; ++c)
+                  if (c == pick) { ord = nsel[c]; nsel[c] += 1; cnt[c] -= 1; }
+                if (lane == 0) L.sel_co[j] = static_cast<uint16_t>(pick | (ord << 3));
+              }
+              int base[kMaxK];
+              {
+                int run = 0;
+#pragma unroll
+                for (int c = 0; c < kMaxK; ++c) { base[c] = run; run += nsel[c]; }
+              }
+              __builtin_amdgcn_wave_barrier();
+              for (int j = lane; j < need; j += 64) {
+                const int co = L.sel_co[j], c = co & 7;
+                int b = 0;
+#pragma unroll
+                for (int cc = 0; cc < kMaxK; ++cc)
+                  if (cc == c) b = base[cc];
+                L.sel_j[b + (co >> 3)] = static_cast<uint16_t>(j);
+              }
+              __builtin_amdgcn_wave_barrier();
+              // walk the ring from the first entry that may still wait; the o-th waiting request of class c met on
+              // the way is taken if the pass selected that class more than o times
+              uint32_t off = static_cast<uint32_t>(L.sc[scan_word]), stop = off, first_left = 0xFFFFFFFFu;
+              int left = need;
+              int seen[kMaxK];
+#pragma unroll
+              for (int c = 0; c < kMaxK; ++c) seen[c] = 0;
+              for (; off < len && left > 0; off += 256) {   // wave-uniform
+                uint32_t dl4[4], pos4[4];
+                uint64_t jw4[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                  const uint32_t i = off + 64u * u + lane;
+                  uint32_t pos = hd + i;
+                  if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
+                  pos4[u] = pos;
+                  dl4[u] = i < len ? dlr[pos] : 0u;   // (beyond the ring: counts as gone)
+                  jw4[u] = i < len ? ring[pos] : 0ull;
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                  if (left > 0) {   // wave-uniform
+                    const uint32_t dl = dl4[u];
+                    const bool live = dl > s;
+                    const int c = static_cast<int>(jw4[u] >> 29) & 7;
+                    int ord = 0, quota = 0, b = 0;
+#pragma unroll
+                    for (int cc = 0; cc < kMaxK; ++cc) {
+                      if (cc < K) {   // wave-uniform
+                        const uint64_t bal = __ballot(live && c == cc);
+                        if (c == cc) { ord = seen[cc] + __popcll(bal & lanes_below()); quota = nsel[cc]; b = base[cc]; }
+                        seen[cc] += __popcll(bal);
+                      }
+                    }
+                    const bool mine = live && ord < quota;
+                    if (mine) {
+                      L.jobs[first_job + L.sel_j[b + ord]] = jw4[u];
+                      dlr[pos4[u]] = 0u;   // gone from the buffer
+                      if (dl != kNever) atomicSub(&calr[static_cast<size_t>(c) * cal_n + (dl & p.cal_mask)], 1u);
+                    }
+                    const uint64_t stay = __ballot(live && !mine), took = __ballot(mine);
+                    if (first_left == 0xFFFFFFFFu && stay)
+                      first_left = off + 64u * u + static_cast<uint32_t>(__ffsll(static_cast<long long>(stay))) - 1u;
+                    if (took) {
+                      left -= __popcll(took);
+                      stop = off + 64u * u + 64u - static_cast<uint32_t>(__clzll(static_cast<long long>(took)));   // one past the last taken entry
+                    }
+                  }
+                }
+              }
+              // the next pass (and the head, at the end of the step) starts at the first entry that still waits
+              if (lane == 0)
+                L.sc[scan_word] = static_cast<int32_t>(first_left != 0xFFFFFFFFu ? first_left : (left > 0 ? len : stop));
+            };
             if (wave == 0) {
               if constexpr (RR) {
+                if (p.route_mode == SIM_ROUTE_WEIGHTED_SPLIT) {
+                  int nsel_s[kMaxK], nsel_m[kMaxK];
+#pragma unroll
+                  for (int c = 0; c < kMaxK; ++c) nsel_s[c] = 0;
+                  if (takenL[0] > 0)
+                    select_and_stage(0, dring, ddl, dcal, dheadL[0], dlen_all, SC_DSCAN, takenL[0], 0, nextL[0], nsel_s);
+                  if (takenL[1] > 0)
+                    select_and_stage(1, dring_m, ddl_m, dcal_m, dheadL[1], dlen_all_m, SC_DSCAN_M, takenL[1], takenL[0], nextL[1], nsel_m);
+                  // (the per-class counts of both buffers were read above: what waits in the mixed group's buffer is
+                  // the class total less the solo buffer's share, and the total follows the placements later)
+                  if (lane < K) {
+                    int mine = 0;
+#pragma unroll
+                    for (int c = 0; c < kMaxK; ++c)
+                      if (c == lane) mine = nsel_s[c];
+                    L.cs[CS_QDS + lane] -= mine;
+                  }
+                } else {
                 if (takenL[0] > 0)
                   stage_ring(dring, ddl, dcal, dheadL[0], dlen_all, SC_DSCAN, static_cast<uint32_t>(takenL[0]), 0);
                 if (takenL[1] > 0)
                   stage_ring(dring_m, ddl_m, dcal_m, dheadL[1], dlen_all_m, SC_DSCAN_M, static_cast<uint32_t>(takenL[1]), takenL[0]);
+                }
               } else {
                 stage_ring(dring, ddl, dcal, dhead0, dlen_all, SC_DSCAN, static_cast<uint32_t>(total), 0);
               }
@@ -1871,7 +2014,7 @@ __global__ void gnr_reset_kernel(const Params p, const int reps)
   for (size_t i = t0; i < static_cast<size_t>(reps) * CS_WORDS; i += stride) p.cstate[i] = 0;
   for (size_t i = t0; i < static_cast<size_t>(reps) * kTallyWords; i += stride) p.tally[i] = 0;
   for (size_t i = t0; i < static_cast<size_t>(reps) * 3 * p.K * kNBin; i += stride) p.hist[i] = 0;
-  if (p.ab_classes)
+  if (p.dl_rings)
     for (size_t i = t0; i < static_cast<size_t>(reps) * p.K * (p.cal_mask + 1u); i += stride) {
       p.cal[i] = 0; p.dcal[i] = 0;
       if (p.dcal_m) p.dcal_m[i] = 0;
@@ -1951,7 +2094,7 @@ __global__ void gnr_digest_kernel(const Params p)
       d += h;
     }
   }
-  if (p.route_mode == SIM_ROUTE_RANDOM_SPLIT) {   // the mixed group's buffer
+  if (p.route_mode == SIM_ROUTE_RANDOM_SPLIT || p.route_mode == SIM_ROUTE_WEIGHTED_SPLIT) {   // the mixed group's buffer
     const uint32_t head = static_cast<uint32_t>(cs[CS_DHEAD_M]), len = static_cast<uint32_t>(cs[CS_DCOUNT_M]);
     const uint64_t *ring = p.dring_m + static_cast<size_t>(r) * p.dbuf_cap;
     const uint32_t *dlr = p.ab_classes ? p.ddl_m + static_cast<size_t>(r) * p.dbuf_cap : nullptr;
@@ -2000,7 +2143,7 @@ int launch_steps(const Params &p, int reps, int threads, size_t lds_bytes, uint3
 {
   using StepKernel = void (*)(const Params *, StepArrays, uint32_t, uint32_t, uint32_t, uint32_t);
   const int size = threads > 768 ? 2 : threads > 512 ? 1 : 0;
-  const bool ab = p.ab_classes != 0;
+  const bool ab = p.dl_rings != 0;
   static const StepKernel table[3][2][3] = {
       // [workgroup size][abandonment][router: solo-first, randomized, immediate]
       {{gnr_step_kernel<512, false, false, false>, gnr_step_kernel<512, false, true, false>, gnr_step_kernel<512, false, false, true>},
@@ -2009,8 +2152,9 @@ int launch_steps(const Params &p, int reps, int threads, size_t lds_bytes, uint3
        {gnr_step_kernel<768, true, false, false>, gnr_step_kernel<768, true, true, false>, gnr_step_kernel<768, true, false, true>}},
       {{gnr_step_kernel<1024, false, false, false>, gnr_step_kernel<1024, false, true, false>, gnr_step_kernel<1024, false, false, true>},
        {gnr_step_kernel<1024, true, false, false>, gnr_step_kernel<1024, true, true, false>, gnr_step_kernel<1024, true, false, true>}}};
-  if (p.route_mode < 0 || p.route_mode > 2) return SIM_EINVAL;
-  const StepKernel kernel = table[size][ab ? 1 : 0][p.route_mode];
+  if (p.route_mode < 0 || p.route_mode > 3) return SIM_EINVAL;
+  // (the weighted router is a run-time switch of the randomized router's variant with deadline rings)
+  const StepKernel kernel = table[size][ab ? 1 : 0][p.route_mode == SIM_ROUTE_WEIGHTED_SPLIT ? 1 : p.route_mode];
   if (lds_bytes > 64 * 1024) {   // more than the default dynamic LDS limit has to be asked for
     const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes));

@@ -88,6 +88,14 @@ int build_length_table(int law, double p0, double p1, const uint16_t *user, uint
 
 uint32_t probability_threshold(double p) { return quantise32(p); }
 
+// A class selection weight as an integer: the nearest multiple of 2^-20, but never zero, so that a class whose
+// weight is zero is still served when no other class waits (each pool stays work-conserving).
+uint32_t selection_weight_units(double w)
+{
+  const double v = std::floor(w * 1048576.0 + 0.5);
+  return v < 1.0 ? 1u : (v > 1048576.0 ? 1048576u : static_cast<uint32_t>(v));
+}
+
 int build_patience_table(double theta, double dt_seconds, uint16_t *out)
 {
   if (!(theta > 0.0) || !(dt_seconds > 0.0) || !std::isfinite(theta)) return SIM_EINVAL;

@@ -44,11 +44,21 @@ def _random_config(rng, idx):
                        p_solo=[float(v) for v in rng.choice([0.0, 0.3, 0.7, 1.0], K)])
 
 
-@pytest.mark.parametrize("batch", range(16))
+def _random_weights(rng, K):
+    w = rng.dirichlet(np.ones(K))
+    w[rng.random(K) < 0.2] = 0.0          # classes a pool serves only when no other class waits
+    return [float(v) for v in w]
+
+
+@pytest.mark.parametrize("batch", range(24))
 def test_random_configurations(B, oracle_mod, batch):
+    """Batches 0 to 15: the base, randomized and immediate-decode routers; 16 to 23: the weighted router."""
     rng = np.random.default_rng(1000 + batch)
     for i in range(12):
         cfg = _random_config(rng, 100 * batch + i)
+        if batch >= 16:
+            cfg = replace(cfg, route_mode=W.ROUTE_WEIGHTED_SPLIT, w_solo=_random_weights(rng, cfg.K),
+                          w_mixed=_random_weights(rng, cfg.K))
         if cfg.mod_period == 0:
             cfg = replace(cfg, mod_amp=0.0)
         steps = int(rng.integers(150, 700)) if cfg.N <= 400 else int(rng.integers(60, 200)) if cfg.N <= 2600 else int(rng.integers(30, 80))

@@ -22,6 +22,8 @@ def test_rings_of_one_or_two_entries(B, oracle_mod, caps):
                     impatient,
                     replace(base, route_mode=W.ROUTE_RANDOM_SPLIT, p_solo=[0.8, 0.3, 0.55]),
                     replace(impatient, route_mode=W.ROUTE_RANDOM_SPLIT, p_solo=[0.8, 0.3, 0.55]),
+                    replace(base, route_mode=W.ROUTE_WEIGHTED_SPLIT, p_solo=[0.8, 0.3, 0.55], w_solo=[0.5, 0.3, 0.2], w_mixed=[0.1, 0.6, 0.3]),
+                    replace(impatient, route_mode=W.ROUTE_WEIGHTED_SPLIT, p_solo=[0.8, 0.3, 0.55], w_solo=[0.5, 0.0, 0.5], w_mixed=[0.1, 0.6, 0.3]),
                     replace(base, route_mode=W.ROUTE_IMMEDIATE),
                     replace(impatient, M=base.N, route_mode=W.ROUTE_IMMEDIATE)):
             sim, orc = run_both(B, oracle_mod, cfg, 1500, checkpoints=3)

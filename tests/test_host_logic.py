@@ -61,7 +61,7 @@ def test_invalid_configurations_are_rejected(B):
     assert B.sim_workspace_bytes(good, 16) > 0
     bad = [replace(good, K=9), replace(good, N=0), replace(good, N=20000), replace(good, B=129), replace(good, B=0),
            replace(good, C=0), replace(good, M=9), replace(good, M=-1), replace(good, dt=0.02), replace(good, c0=0.0),
-           replace(good, queue_cap=0), replace(good, dbuf_cap=0), replace(good, gate_mode=7), replace(good, route_mode=3),
+           replace(good, queue_cap=0), replace(good, dbuf_cap=0), replace(good, gate_mode=7), replace(good, route_mode=4),
            replace(good, route_mode=1, p_solo=[0.5, 1.2]), replace(good, route_mode=1, p_solo=[-0.1, 0.5]),
            replace(good, x_star=[-0.1, 0.1]), replace(good, mod_amp=2.0)]
     heavy = W.config(1); heavy.classes[0].lam = 6.0
