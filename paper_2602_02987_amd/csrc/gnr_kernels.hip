@@ -177,7 +177,6 @@ struct Lds {
   uint16_t *rem;      // [Mp] prompt tokens left of the prefill a server has in service (0: none)
   uint32_t *live_off; // [K][kAdmChunk] abandonment only: ring offset from the head of the m-th waiting request of a class
   // weighted router only: the class selections of a routing pass
-  uint32_t *sel_u;    // [kJobsLds] random word of each selection
   uint16_t *sel_co;   // [kJobsLds] class | (how many selections before it chose the same class) << 3
   uint16_t *sel_j;    // [kJobsLds] list position of each selection, ordered by class, then by order within the class
 };
@@ -222,7 +221,6 @@ __host__ __device__ __forceinline__ Lds lds_carve(const Params &p, unsigned char
   GNR_TAKE(rem, uint16_t, p.Mp)
   GNR_TAKE(stage, uint16_t, 2 * p.threads)
   GNR_TAKE(live_off, uint32_t, p.dl_rings ? p.K * kAdmChunk : 0)
-  GNR_TAKE(sel_u, uint32_t, p.route_mode == SIM_ROUTE_WEIGHTED_SPLIT ? kJobsLds : 0)
   GNR_TAKE(sel_co, uint16_t, p.route_mode == SIM_ROUTE_WEIGHTED_SPLIT ? kJobsLds : 0)
   GNR_TAKE(sel_j, uint16_t, p.route_mode == SIM_ROUTE_WEIGHTED_SPLIT ? kJobsLds : 0)
 #undef GNR_TAKE
@@ -1597,44 +1595,49 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
             auto select_and_stage = [&](int pool, uint64_t *ring, uint32_t *dlr, uint32_t *calr, uint32_t hd, uint32_t len,
                                         int scan_word, int need, int first_job, int placed_before,
                                         int (&nsel)[kMaxK]) __attribute__((always_inline)) {
-              for (int j = lane; j < need; j += 64) {
-                uint32_t w[4];
-                philox4x32_10(key0, key1, s, static_cast<uint32_t>(kStreamSelect + pool), static_cast<uint32_t>(placed_before + j),
-                              static_cast<uint32_t>(r), w);
-                L.sel_u[j] = w[0];
-              }
-              int cnt[kMaxK];
-              uint32_t wt[kMaxK];
+              // the random word of selection j stays in a register of lane j % 64 (read below with a lane index:
+              // no trip to memory inside the sequential loop)
+              uint32_t ureg[kJobsLds / 64];
 #pragma unroll
-              for (int c = 0; c < kMaxK; ++c) {
-                const int solo_c = c < K ? L.cs[CS_QDS + c] : 0, all_c = c < K ? L.cs[CS_QD + c] : 0;
-                cnt[c] = __builtin_amdgcn_readfirstlane(pool == 0 ? solo_c : all_c - solo_c);
-                wt[c] = p.wsel[pool][c];
-                nsel[c] = 0;
-              }
-              __builtin_amdgcn_wave_barrier();
-              for (int j = 0; j < need; ++j) {   // wave-uniform: every lane follows the same draws
-                uint32_t total = 0;
-#pragma unroll
-                for (int c = 0; c < kMaxK; ++c) total += cnt[c] > 0 ? wt[c] : 0u;
-                const uint32_t u = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(L.sel_u[j])));
-                const uint32_t x = static_cast<uint32_t>((static_cast<uint64_t>(u) * total) >> 32);
-                int pick = -1;
-                uint32_t cum = 0;
-#pragma unroll
-                for (int c = 0; c < kMaxK; ++c) {
-                  if (cnt[c] > 0) {
-                    cum += wt[c];
-                    if (pick < 0 && x < cum) pick = c;
-                  }
+              for (int q = 0; q < kJobsLds / 64; ++q) {
+                ureg[q] = 0;
+                if (64 * q < need) {   // wave-uniform
+                  uint32_t w[4];
+                  philox4x32_10(key0, key1, s, static_cast<uint32_t>(kStreamSelect + pool),
+                                static_cast<uint32_t>(placed_before + 64 * q + lane), static_cast<uint32_t>(r), w);
+                  ureg[q] = w[0];
                 }
-                if (pick < 0) pick = 0;   // (no class waits: cannot happen, the pass takes no more than wait)
-                int ord = 0;
-#pragma unroll
-                for (int c = 0; c < kMaxK; ++c)
-                  if (c == pick) { ord = nsel[c]; nsel[c] += 1; cnt[c] -= 1; }
-                if (lane == 0) L.sel_co[j] = static_cast<uint16_t>(pick | (ord << 3));
               }
+              // lane c keeps class c's state: requests that wait in this buffer, selection weight, selections so far,
+              // and the running sum of the weights of the classes that still wait (recomputed when one runs out)
+              int cntv = 0, nselv = 0;
+              uint32_t wtv = 0;
+              if (lane < K) {
+                const int solo_c = L.cs[CS_QDS + lane];
+                cntv = pool == 0 ? solo_c : L.cs[CS_QD + lane] - solo_c;
+                wtv = p.wsel[pool][lane];
+              }
+              uint32_t cumv = wave_incl_scan(cntv > 0 ? wtv : 0u);
+              uint32_t total = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(cumv), 63));
+#pragma unroll
+              for (int q = 0; q < kJobsLds / 64; ++q)
+              for (int jj = 0; jj < 64 && 64 * q + jj < need; ++jj) {   // wave-uniform: every lane follows the same draws
+                const int j = 64 * q + jj;
+                const uint32_t u = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(ureg[q]), jj));
+                const uint32_t x = static_cast<uint32_t>((static_cast<uint64_t>(u) * total) >> 32);
+                const uint64_t hit = __ballot(cntv > 0 && x < cumv);
+                // (no class waits: cannot happen, the pass takes no more than wait)
+                const int pick = hit ? __ffsll(static_cast<long long>(hit)) - 1 : 0;
+                const int ord = __builtin_amdgcn_readlane(nselv, pick);
+                if (lane == pick) { nselv += 1; cntv -= 1; }
+                if (lane == 0) L.sel_co[j] = static_cast<uint16_t>(pick | (ord << 3));
+                if (__builtin_amdgcn_readlane(cntv, pick) == 0) {   // wave-uniform: the class has run out
+                  cumv = wave_incl_scan(cntv > 0 ? wtv : 0u);
+                  total = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(cumv), 63));
+                }
+              }
+#pragma unroll
+              for (int c = 0; c < kMaxK; ++c) nsel[c] = __builtin_amdgcn_readlane(nselv, c);
               int base[kMaxK];
               {
                 int run = 0;
