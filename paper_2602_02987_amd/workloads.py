@@ -182,7 +182,7 @@ def config(n: int, **over) -> SimConfig:
 
 
 def convergence_instance(n: int, seeds: int = 5, B: int = 6, random_split: bool = False, bundled: bool = False,
-                         **over) -> SimConfig:
+                         weighted_split: bool = False, **over) -> SimConfig:
     """The two-class instance of the paper's convergence analysis (EC, "Convergence Analysis") at scale n.
 
     As printed there: class 0 decode-heavy (P=300, D=1000), class 1 prefill-heavy (P=3000, D=400), arrival rates
@@ -206,4 +206,6 @@ def convergence_instance(n: int, seeds: int = 5, B: int = 6, random_split: bool 
     for c in cls:
         c.bundled = int(bundled)
     cfg = with_plan(replace(cfg, **over), objective=objective)
+    if weighted_split:
+        return with_weighted_split(cfg, objective=objective)
     return with_random_split(cfg, objective=objective) if random_split else cfg

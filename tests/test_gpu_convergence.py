@@ -81,7 +81,17 @@ def test_randomized_router_brings_class_occupancies_to_the_plan(B):
     assert err_split < 0.5 * err_plain, (err_split, err_plain)
 
 
+def test_weighted_router_brings_class_occupancies_to_the_plan(B):
+    """The general form of the router (weights = the plan's class shares of each pool's decode completions) reaches
+    the same class-wise occupancies."""
+    cfg, pl, rev, occ = _measure(B, 8000, weighted_split=True)
+    assert cfg.route_mode == W.ROUTE_WEIGHTED_SPLIT and abs(sum(cfg.w_solo) - 1.0) < 1e-9
+    assert np.allclose(occ["YM"], pl.ym, rtol=0.03, atol=0.005), (occ["YM"], pl.ym)
+    assert np.allclose(occ["YS"], pl.ys, rtol=0.06), (occ["YS"], pl.ys)
+    assert abs(rev.mean() / pl.value - 1.0) < 0.004
+
+
 def test_one_scale_bit_by_bit(B, oracle_mod):
-    for kw in (dict(), dict(random_split=True), dict(bundled=True)):
+    for kw in (dict(), dict(random_split=True), dict(bundled=True), dict(weighted_split=True)):
         cfg = W.convergence_instance(50, seeds=3, **kw)
         run_both(B, oracle_mod, cfg, 12_000, checkpoints=2)
