@@ -438,7 +438,7 @@ struct StepArrays {
 // IM: the variant with immediate same-slot decode (no router): a request whose prefill ends goes on decoding on
 // its own server, placed there by the lane that finishes the server; a server is offered to the gate while it
 // holds no prefill and fewer than B decodes.
-template <int MAXT, bool AB, bool RR, bool IM>
+template <int MAXT, bool AB, bool RR, bool IM, bool WS = false>
 __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict__ params, const StepArrays a,
                                                         const uint32_t key0, const uint32_t key1,
                                                         const uint32_t step_begin, const uint32_t n_steps)
@@ -1010,7 +1010,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           L.cs[CS_QD + k] -= static_cast<int32_t>(n_leave_d);
           L.tl[k * kNTally + SIM_T_AB_D] += n_leave_d;
           atomicSub(&L.cs[CS_DCOUNT], static_cast<int32_t>(n_leave_d));
-          if constexpr (RR) L.cs[CS_QDS + k] -= static_cast<int32_t>(n_leave_d);   // (read by the weighted router only)
+          if constexpr (WS) L.cs[CS_QDS + k] -= static_cast<int32_t>(n_leave_d);
         }
         if constexpr (RR) {
           if (n_leave_dm) {
@@ -1135,7 +1135,9 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
             }
           }
           wave_count_by_class_i32(kept, k, K, &L.cs[CS_QD], 1);
-          if constexpr (AB) wave_count_by_class_i32(kept && solo, k, K, &L.cs[CS_QDS], 1);   // (read by the weighted router only)
+          if constexpr (AB) {   // the weighted router also counts what waits in the solo group's buffer per class
+            if constexpr (WS) wave_count_by_class_i32(kept && solo, k, K, &L.cs[CS_QDS], 1);
+          }
           if (__ballot(active && !kept)) {
             wave_count_by_class(active && !kept, k, K, &L.tl[SIM_T_DROP_D], kNTally);
             if (lane == 0) L.tl[kMaxK * kNTally + SIM_G_OVERFLOW] = 1;
@@ -1710,7 +1712,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
             };
             if (wave == 0) {
               if constexpr (RR) {
-                if (p.route_mode == SIM_ROUTE_WEIGHTED_SPLIT) {
+                if constexpr (WS) {
                   int nsel_s[kMaxK], nsel_m[kMaxK];
 #pragma unroll
                   for (int c = 0; c < kMaxK; ++c) nsel_s[c] = 0;
@@ -2156,8 +2158,11 @@ int launch_steps(const Params &p, int reps, int threads, size_t lds_bytes, uint3
       {{gnr_step_kernel<1024, false, false, false>, gnr_step_kernel<1024, false, true, false>, gnr_step_kernel<1024, false, false, true>},
        {gnr_step_kernel<1024, true, false, false>, gnr_step_kernel<1024, true, true, false>, gnr_step_kernel<1024, true, false, true>}}};
   if (p.route_mode < 0 || p.route_mode > 3) return SIM_EINVAL;
-  // (the weighted router is a run-time switch of the randomized router's variant with deadline rings)
-  const StepKernel kernel = table[size][ab ? 1 : 0][p.route_mode == SIM_ROUTE_WEIGHTED_SPLIT ? 1 : p.route_mode];
+  static const StepKernel weighted[3] = {gnr_step_kernel<512, true, true, false, true>, gnr_step_kernel<768, true, true, false, true>,
+                                         gnr_step_kernel<1024, true, true, false, true>};
+  // (the weighted router is the randomized router's variant with deadline rings plus the class draws)
+  if (p.route_mode == SIM_ROUTE_WEIGHTED_SPLIT && !ab) return SIM_EINVAL;
+  const StepKernel kernel = p.route_mode == SIM_ROUTE_WEIGHTED_SPLIT ? weighted[size] : table[size][ab ? 1 : 0][p.route_mode];
   if (lds_bytes > 64 * 1024) {   // more than the default dynamic LDS limit has to be asked for
     const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes));
