@@ -21,10 +21,11 @@ HBM_PEAK_GBS = 8000.0
 
 
 # HBM traffic of one step-kernel launch of the default run, from hardware counters (FETCH_SIZE + WRITE_SIZE,
-# each scaled by what the same counter reads for a device copy of known size). Valid only for the kernel source
-# it was measured on: the hash below is compared with the current source and the figure dropped on a mismatch.
+# each scaled by what the same counter reads for a device copy of known size), and the occupancy rocprofv3 derives
+# for it. Valid only for the kernel source they were measured on: the hash below is compared with the current
+# source and the figures dropped on a mismatch.
 TRAFFIC = {"kernel_sha256": "55a273d356670aefcef904678914f183f376580642861c559ce0b84aeffdad11",
-           "bytes_per_launch": 412165632449.2818}
+           "bytes_per_launch": 412165632449.2818, "occupancy_percent": 49.17}
 
 
 def algorithmic_bytes(t0, g0, t1, g1, slots):
@@ -55,12 +56,26 @@ def algorithmic_bytes(t0, g0, t1, g1, slots):
                        bytes_per_slot_with_records_in_lds=on_chip_records / slots)
 
 
-def measured_traffic():
+def measured(key):
+    """A figure from the hardware-counter runs, or None when the kernel source is no longer the one they ran on."""
     import hashlib
     src = os.path.join(ROOT, "paper_2602_02987_amd", "csrc", "gnr_kernels.hip")
     with open(src, "rb") as fh:
         sha = hashlib.sha256(fh.read()).hexdigest()
-    return TRAFFIC["bytes_per_launch"] if TRAFFIC["kernel_sha256"] == sha else None
+    return TRAFFIC[key] if TRAFFIC["kernel_sha256"] == sha else None
+
+
+def occupancy(sim, replications, measured_percent):
+    """Waves per SIMD the launch shape allows (256 compute units of 4 SIMDs, 160 KB of LDS, 8 waves per SIMD)."""
+    threads, lds = sim.launch_shape()
+    waves = threads // 64
+    per_cu = min(160 * 1024 // max(lds, 1), 32 // waves, -(-replications // 256))
+    return {"threads_per_workgroup": threads, "lds_bytes_per_workgroup": lds, "workgroups_per_cu": per_cu,
+            "waves_per_simd": waves * per_cu / 4.0, "simd_capacity": 8, "measured_percent": measured_percent}
+
+
+def measured_traffic():
+    return measured("bytes_per_launch")
 
 
 def policy_variant(W, cfg, theta, split, immediate, weighted=False):
@@ -212,6 +227,7 @@ def main():
                    "overflow": bool(st1["overflow"])},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic() if default_run else None,
+                     "occupancy": occupancy(sim, cfg.replications, measured("occupancy_percent") if default_run else None),
                      "kernel": "gnr_step_kernel", "launches": launches, "avg_launch_ms": per_launch_ms,
                      "algorithmic_bytes_per_launch": total_bytes / max(launches, 1), **shape},
     }

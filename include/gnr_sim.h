@@ -229,6 +229,9 @@ int sim_digest(sim_t *h, int replication, uint64_t *out, void *hip_stream);
 /* Step-kernel launches and their accumulated device time (HIP events on the run's stream) since
  * the handle was created or this was last called with reset != 0. Synchronises the stream. */
 int sim_kernel_time(sim_t *h, int64_t *launches, double *milliseconds, int reset, void *hip_stream);
+/* Launch shape of the step kernel for this handle: threads per workgroup (one workgroup per replication) and
+ * dynamic LDS bytes per workgroup; what occupancy follows from. Host only; either pointer may be NULL. */
+int sim_launch_shape(sim_t *h, int *threads, size_t *lds_bytes);
 
 int sim_destroy(sim_t *h);
 const char *sim_strerror(int err);

@@ -80,6 +80,7 @@ def lib():
         L.sim_strerror.restype = C.c_char_p
         L.sim_workspace_bytes.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_size_t)]
         L.sim_onchip_bytes.argtypes = [C.c_void_p, C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
+        L.sim_launch_shape.argtypes = [C.c_void_p, C.POINTER(C.c_int), C.POINTER(C.c_size_t)]
         L.sim_create.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.POINTER(C.c_void_p)]
         L.sim_run.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_uint64, C.c_void_p]
         L.sim_stats.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
@@ -262,6 +263,12 @@ class Sim:
         d = _stats_dict(st)
         d["overflow"] = rc == SIM_EOVERFLOW
         return d
+
+    def launch_shape(self):
+        """(threads per workgroup, dynamic LDS bytes per workgroup) of the step kernel."""
+        t, n = C.c_int(0), C.c_size_t(0)
+        _check(lib().sim_launch_shape(self.h, C.byref(t), C.byref(n)), "sim_launch_shape")
+        return t.value, n.value
 
     def kernel_time(self, reset=False):
         n = C.c_int64(0)

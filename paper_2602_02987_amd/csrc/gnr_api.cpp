@@ -468,6 +468,14 @@ int sim_kernel_time(sim_t *h, int64_t *launches, double *milliseconds, int reset
   return SIM_OK;
 }
 
+int sim_launch_shape(sim_t *h, int *threads, size_t *lds_bytes)
+{
+  if (!h) return SIM_EINVAL;
+  if (threads) *threads = h->threads;
+  if (lds_bytes) *lds_bytes = h->lds_bytes;
+  return SIM_OK;
+}
+
 int sim_stats(sim_t *h, sim_stats_t *st, void *hip_stream)
 {
   if (!h || !st || !h->started || !on_device(h)) return SIM_EINVAL;
