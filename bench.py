@@ -147,7 +147,7 @@ def main():
                          "(a kernel of known traffic to scale hardware counters with)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (replications are independent and would shard "
+        print("bench.py: the simulator runs on one GPU only (replications are independent and would shard "
               "across GPUs without communication, but no multi-GPU path is built); use --gpus 1", file=sys.stderr)
         sys.exit(2)
 
