@@ -1,6 +1,7 @@
 """GPU parity on seeded random small configurations: every gate, every decode rule, with and without patience,
 random sizes, caps, chunk lengths, ring capacities, targets and split moves. Each case runs a few hundred steps
 through the C ABI and is compared with the oracle bit by bit."""
+import os
 from dataclasses import replace
 
 import numpy as np
@@ -50,13 +51,19 @@ def _random_weights(rng, K):
     return [float(v) for v in w]
 
 
-@pytest.mark.parametrize("batch", range(24))
+# More batches on request: GNR_RANDOM_BATCHES=400 runs batches 0..399 (about 4800 configurations, a few minutes);
+# the kernel as committed passed 400.
+_BATCHES = max(24, int(os.environ.get("GNR_RANDOM_BATCHES", "24")))
+
+
+@pytest.mark.parametrize("batch", range(_BATCHES))
 def test_random_configurations(B, oracle_mod, batch):
-    """Batches 0 to 15: the base, randomized and immediate-decode routers; 16 to 23: the weighted router."""
+    """Batches 0 to 15: the base, randomized and immediate-decode routers; 16 to 23: the weighted router; beyond
+    (opt-in), every third batch the weighted router."""
     rng = np.random.default_rng(1000 + batch)
     for i in range(12):
         cfg = _random_config(rng, 100 * batch + i)
-        if batch >= 16:
+        if 16 <= batch < 24 or (batch >= 24 and batch % 3 == 2):
             cfg = replace(cfg, route_mode=W.ROUTE_WEIGHTED_SPLIT, w_solo=_random_weights(rng, cfg.K),
                           w_mixed=_random_weights(rng, cfg.K))
         if cfg.mod_period == 0:
@@ -75,7 +82,12 @@ def test_random_configurations(B, oracle_mod, batch):
             n = steps // 3 + (part == 0)
             if part == 1 and rng.random() < 0.5:
                 m = int(rng.integers(0, cfg.N + 1))
-                sim.set_split(m); orc.set_split(m)
+                try:
+                    sim.set_split(m)
+                except B.SimError:      # (a split whose on-chip records do not fit is refused and changes nothing)
+                    m = None
+                if m is not None:
+                    orc.set_split(m)
             if part == 2 and rng.random() < 0.5:
                 x = [float(v) for v in rng.uniform(0.0, 0.4, cfg.K)]
                 sim.set_targets(x, cfg.qp_star); orc.set_targets(x, cfg.qp_star)
