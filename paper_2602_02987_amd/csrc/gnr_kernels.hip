@@ -177,6 +177,7 @@ struct Lds {
   uint16_t *rem;      // [Mp] prompt tokens left of the prefill a server has in service (0: none)
   uint32_t *live_off; // [K][kAdmChunk] abandonment only: ring offset from the head of the m-th waiting request of a class
   // weighted router only: the class selections of a routing pass
+  uint32_t *sel_u;    // [kJobsLds] random word of each selection
   uint16_t *sel_co;   // [kJobsLds] class | (how many selections before it chose the same class) << 3
   uint16_t *sel_j;    // [kJobsLds] list position of each selection, ordered by class, then by order within the class
 };
@@ -221,6 +222,7 @@ __host__ __device__ __forceinline__ Lds lds_carve(const Params &p, unsigned char
   GNR_TAKE(rem, uint16_t, p.Mp)
   GNR_TAKE(stage, uint16_t, 2 * p.threads)
   GNR_TAKE(live_off, uint32_t, p.dl_rings ? p.K * kAdmChunk : 0)
+  GNR_TAKE(sel_u, uint32_t, p.route_mode == SIM_ROUTE_WEIGHTED_SPLIT ? kJobsLds : 0)
   GNR_TAKE(sel_co, uint16_t, p.route_mode == SIM_ROUTE_WEIGHTED_SPLIT ? kJobsLds : 0)
   GNR_TAKE(sel_j, uint16_t, p.route_mode == SIM_ROUTE_WEIGHTED_SPLIT ? kJobsLds : 0)
 #undef GNR_TAKE
@@ -1597,49 +1599,98 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
             auto select_and_stage = [&](int pool, uint64_t *ring, uint32_t *dlr, uint32_t *calr, uint32_t hd, uint32_t len,
                                         int scan_word, int need, int first_job, int placed_before,
                                         int (&nsel)[kMaxK]) __attribute__((always_inline)) {
-              // the random word of selection j stays in a register of lane j % 64 (read below with a lane index:
-              // no trip to memory inside the sequential loop)
-              uint32_t ureg[kJobsLds / 64];
-#pragma unroll
-              for (int q = 0; q < kJobsLds / 64; ++q) {
-                ureg[q] = 0;
-                if (64 * q < need) {   // wave-uniform
-                  uint32_t w[4];
-                  philox4x32_10(key0, key1, s, static_cast<uint32_t>(kStreamSelect + pool),
-                                static_cast<uint32_t>(placed_before + 64 * q + lane), static_cast<uint32_t>(r), w);
-                  ureg[q] = w[0];
-                }
+              for (int j = lane; j < need; j += 64) {
+                uint32_t w[4];
+                philox4x32_10(key0, key1, s, static_cast<uint32_t>(kStreamSelect + pool), static_cast<uint32_t>(placed_before + j),
+                              static_cast<uint32_t>(r), w);
+                L.sel_u[j] = w[0];
               }
-              // lane c keeps class c's state: requests that wait in this buffer, selection weight, selections so far,
-              // and the running sum of the weights of the classes that still wait (recomputed when one runs out)
-              int cntv = 0, nselv = 0;
+              // Lane c knows class c's selection weight; what each class still has waiting (a pass takes at most
+              // 256, larger counts are capped), which classes wait, and the running sums of their weights are
+              // wave-uniform. The draws do not depend on one another until a class runs out, so they are evaluated
+              // 64 at a time, one per lane: a draw's class is the number of running sums it has reached. If the
+              // draws of a round would take more of a class than waits, the round ends with the draw that takes the
+              // last one, the sums are recomputed without that class, and the next round starts behind it.
+              int cntv = 0;
               uint32_t wtv = 0;
               if (lane < K) {
                 const int solo_c = L.cs[CS_QDS + lane];
                 cntv = pool == 0 ? solo_c : L.cs[CS_QD + lane] - solo_c;
                 wtv = p.wsel[pool][lane];
               }
+              cntv = cntv < 0 ? 0 : (cntv > 0xFFFF ? 0xFFFF : cntv);
+              uint64_t waits = __ballot(cntv > 0);
               uint32_t cumv = wave_incl_scan(cntv > 0 ? wtv : 0u);
-              uint32_t total = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(cumv), 63));
+              int rem[kMaxK];
+              uint32_t cum[kMaxK];
 #pragma unroll
-              for (int q = 0; q < kJobsLds / 64; ++q)
-              for (int jj = 0; jj < 64 && 64 * q + jj < need; ++jj) {   // wave-uniform: every lane follows the same draws
-                const int j = 64 * q + jj;
-                const uint32_t u = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(ureg[q]), jj));
-                const uint32_t x = static_cast<uint32_t>((static_cast<uint64_t>(u) * total) >> 32);
-                const uint64_t hit = __ballot(cntv > 0 && x < cumv);
-                // (no class waits: cannot happen, the pass takes no more than wait)
-                const int pick = hit ? __ffsll(static_cast<long long>(hit)) - 1 : 0;
-                const int ord = __builtin_amdgcn_readlane(nselv, pick);
-                if (lane == pick) { nselv += 1; cntv -= 1; }
-                if (lane == 0) L.sel_co[j] = static_cast<uint16_t>(pick | (ord << 3));
-                if (__builtin_amdgcn_readlane(cntv, pick) == 0) {   // wave-uniform: the class has run out
-                  cumv = wave_incl_scan(cntv > 0 ? wtv : 0u);
+              for (int c = 0; c < kMaxK; ++c) {
+                rem[c] = __builtin_amdgcn_readlane(cntv, c);
+                cum[c] = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(cumv), c));
+              }
+              uint32_t total = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(cumv), 63));
+              __builtin_amdgcn_wave_barrier();
+              for (int done = 0; done < need;) {   // wave-uniform
+                const int j = done + lane;
+                const bool valid = j < need;
+                const uint32_t u = valid ? L.sel_u[j] : 0u;
+                const uint32_t x = __umulhi(u, total);
+                int pick = 0;
+#pragma unroll
+                for (int c = 0; c < kMaxK; ++c)
+                  if (c < K) pick += x >= cum[c] ? 1 : 0;
+                if (pick > K - 1) pick = K - 1;   // (no class waits: cannot happen, the pass takes no more than wait)
+                int last = 64;   // lane of the first draw that takes the last waiting request of its class
+#pragma unroll
+                for (int c = 0; c < kMaxK; ++c) {
+                  if (c < K && rem[c] > 0) {   // wave-uniform
+                    const uint64_t bal = __ballot(valid && pick == c);
+                    if (__popcll(bal) >= rem[c]) {
+                      const int pos = nth_set_bit(bal, rem[c] - 1);
+                      last = pos < last ? pos : last;
+                    }
+                  }
+                }
+                const int n_valid = need - done < 64 ? need - done : 64;
+                const int n_acc = last < 64 ? last + 1 : n_valid;
+                const bool mine = lane < n_acc;
+                if (mine) L.sel_co[j] = static_cast<uint16_t>(pick);
+                bool ran_out = false;
+#pragma unroll
+                for (int c = 0; c < kMaxK; ++c) {
+                  if (c < K && rem[c] > 0) {   // wave-uniform
+                    const int took = __popcll(__ballot(mine && pick == c));
+                    rem[c] -= took;
+                    if (rem[c] == 0) { waits &= ~(1ull << c); ran_out = true; }
+                  }
+                }
+                if (ran_out) {   // wave-uniform
+                  cumv = wave_incl_scan(((waits >> lane) & 1ull) ? wtv : 0u);
+#pragma unroll
+                  for (int c = 0; c < kMaxK; ++c) cum[c] = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(cumv), c));
                   total = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(cumv), 63));
                 }
+                done += n_acc;
               }
+              PROF(29)
+              __builtin_amdgcn_wave_barrier();
+              // how many earlier selections of the pass chose the same class: counted over the lanes, 64 at a time
 #pragma unroll
-              for (int c = 0; c < kMaxK; ++c) nsel[c] = __builtin_amdgcn_readlane(nselv, c);
+              for (int c = 0; c < kMaxK; ++c) nsel[c] = 0;
+              for (int j0 = 0; j0 < need; j0 += 64) {   // wave-uniform
+                const int j = j0 + lane;
+                const int c = j < need ? static_cast<int>(L.sel_co[j]) : -1;
+                int ord = 0;
+#pragma unroll
+                for (int cc = 0; cc < kMaxK; ++cc) {
+                  if (cc < K) {   // wave-uniform
+                    const uint64_t bal = __ballot(c == cc);
+                    if (c == cc) ord = nsel[cc] + __popcll(bal & lanes_below());
+                    nsel[cc] += __popcll(bal);
+                  }
+                }
+                if (j < need) L.sel_co[j] = static_cast<uint16_t>(c | (ord << 3));
+              }
               int base[kMaxK];
               {
                 int run = 0;
@@ -1656,6 +1707,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
                 L.sel_j[b + (co >> 3)] = static_cast<uint16_t>(j);
               }
               __builtin_amdgcn_wave_barrier();
+              PROF(30)
               // walk the ring from the first entry that may still wait; the o-th waiting request of class c met on
               // the way is taken if the pass selected that class more than o times
               uint32_t off = static_cast<uint32_t>(L.sc[scan_word]), stop = off, first_left = 0xFFFFFFFFu;
@@ -1706,6 +1758,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
                   }
                 }
               }
+              PROF(31)
               // the next pass (and the head, at the end of the step) starts at the first entry that still waits
               if (lane == 0)
                 L.sc[scan_word] = static_cast<int32_t>(first_left != 0xFFFFFFFFu ? first_left : (left > 0 ? len : stop));
