@@ -12,7 +12,9 @@ modulation (paper Sec. 6 and the EC's synthetic two-class instance).
 """
 from __future__ import annotations
 
+import json
 import math
+import os
 from dataclasses import dataclass, field, replace
 from typing import List, Optional
 
@@ -209,3 +211,44 @@ def convergence_instance(n: int, seeds: int = 5, B: int = 6, random_split: bool 
     if weighted_split:
         return with_weighted_split(cfg, objective=objective)
     return with_random_split(cfg, objective=objective) if random_split else cfg
+
+
+# ---------------------------------------------------------------- frozen copies of the five configurations ----
+# Every generated number (seeded hyper-parameters, rates scaled to the LP capacity, targets and split from the LP)
+# is also stored as text under configs/, so a run can be tied to the exact inputs of another machine or library
+# version: `frozen_config(n)` reads them back, `python -m paper_2602_02987_amd.workloads` rewrites them.
+_CONFIG_DIR = os.path.join(os.path.dirname(os.path.abspath(__file__)), "configs")
+_CLASS_FIELDS = ("lam", "in_law", "in_p0", "in_p1", "out_law", "out_p0", "out_p1", "price_in", "price_out", "bundled",
+                 "priority", "theta")
+_CONFIG_FIELDS = ("name", "K", "N", "B", "C", "c0", "c_pre", "c_dec", "M", "x_star", "qp_star", "dt", "gate_mode",
+                  "route_mode", "mod_amp", "mod_period", "queue_cap", "dbuf_cap", "replications", "steps", "seed",
+                  "p_solo", "w_solo", "w_mixed")
+
+
+def to_plain(cfg: SimConfig) -> dict:
+    """The configuration as plain numbers and lists (length tables given by array are not supported here)."""
+    d = {f: getattr(cfg, f) for f in _CONFIG_FIELDS}
+    d["classes"] = [{f: getattr(c, f) for f in _CLASS_FIELDS} for c in cfg.classes]
+    d["notes"] = {k: float(v) for k, v in cfg.notes.items()}
+    return d
+
+
+def from_plain(d: dict) -> SimConfig:
+    classes = [SimClass(**c) for c in d["classes"]]
+    kw = {f: d[f] for f in _CONFIG_FIELDS}
+    return SimConfig(classes=classes, notes=dict(d.get("notes", {})), **kw)
+
+
+def frozen_config(n: int) -> SimConfig:
+    """Configuration n as stored under configs/ (no random draws, no LP solve)."""
+    with open(os.path.join(_CONFIG_DIR, f"cfg{n}.json")) as fh:
+        return from_plain(json.load(fh))
+
+
+if __name__ == "__main__":
+    os.makedirs(_CONFIG_DIR, exist_ok=True)
+    for _n in range(1, 6):
+        with open(os.path.join(_CONFIG_DIR, f"cfg{_n}.json"), "w") as _fh:
+            json.dump(to_plain(config(_n)), _fh, indent=1)
+            _fh.write("\n")
+        print("wrote", os.path.join(_CONFIG_DIR, f"cfg{_n}.json"))

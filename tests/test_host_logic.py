@@ -151,3 +151,27 @@ def test_on_chip_memory_bounds_the_number_of_servers():
         B.sim_workspace_bytes(replace(cfg, N=12200, M=2377), 1)
     with pytest.raises(B.SimError):
         B.sim_workspace_bytes(replace(cfg, N=12289, M=0), 1)
+
+
+def test_frozen_configurations_are_the_generated_ones():
+    """The text copies under configs/ hold what workloads.config(n) generates here: seeded hyper-parameters and
+    sizes exactly, rates and LP outputs to the solver's reproducibility; a run from the frozen copy of config 1 is
+    the run from the generated one, bit for bit."""
+    for n in range(1, 6):
+        a, b = W.config(n), W.frozen_config(n)
+        for f in ("name", "K", "N", "B", "C", "c0", "c_pre", "c_dec", "M", "gate_mode", "route_mode", "mod_amp",
+                  "mod_period", "queue_cap", "dbuf_cap", "replications", "steps", "seed"):
+            assert getattr(a, f) == getattr(b, f), (n, f)
+        assert np.allclose(a.x_star, b.x_star, rtol=1e-9, atol=1e-15) and np.allclose(a.qp_star, b.qp_star, rtol=1e-9, atol=1e-15)
+        for ca, cb in zip(a.classes, b.classes):
+            for f in ("in_law", "in_p0", "in_p1", "out_law", "out_p0", "out_p1", "price_in", "price_out", "bundled", "priority", "theta"):
+                assert getattr(ca, f) == getattr(cb, f), (n, f)
+            assert ca.lam == pytest.approx(cb.lam, rel=1e-9)
+    assert W.to_plain(W.from_plain(W.to_plain(W.config(4)))) == W.to_plain(W.config(4))
+
+
+def test_frozen_config1_runs_like_the_generated_one(oracle_mod):
+    a = oracle_mod.Oracle(W.config(1)); a.run(3000)
+    b = oracle_mod.Oracle(W.frozen_config(1)); b.run(3000)
+    for r in range(16):
+        assert a.digest(r) == b.digest(r)
