@@ -24,6 +24,13 @@ def build(force: bool = False) -> str:
     return LIB
 
 
+def build_checked(path: str) -> str:
+    """A copy of the oracle built with the compiler's undefined-behaviour checks (any finding aborts the process)."""
+    subprocess.check_call(["gcc", "-O1", "-g", "-ffp-contract=off", "-fPIC", "-shared", "-Wall", "-Wextra",
+                           "-fsanitize=undefined", "-fno-sanitize-recover=all", SRC, "-o", path, "-lm"])
+    return path
+
+
 class _Class(C.Structure):
     _fields_ = [("lam", C.c_double), ("in_law", C.c_int), ("out_law", C.c_int),
                 ("in_p0", C.c_double), ("in_p1", C.c_double), ("out_p0", C.c_double), ("out_p1", C.c_double),

@@ -175,3 +175,12 @@ def test_frozen_config1_runs_like_the_generated_one(oracle_mod):
     b = oracle_mod.Oracle(W.frozen_config(1)); b.run(3000)
     for r in range(16):
         assert a.digest(r) == b.digest(r)
+
+
+def test_every_configuration_is_in_the_regime_without_a_decode_buffer():
+    """Prop. 1 (decode-buffer elimination) needs gamma * tau >= (B-1)/B, i.e. tau_mix / tau_solo >= (B-1)/B: true of
+    the five configurations, the convergence instance and the ablation instances, whose plans all set q_d* = 0."""
+    from paper_2602_02987_amd import ablation as A
+    cfgs = [W.config(n) for n in range(1, 6)] + [W.convergence_instance(50)] + A.instances(4, n=50)
+    for cfg in cfgs:
+        assert cfg.notes["tau_mix"] / cfg.notes["tau_solo"] >= (cfg.B - 1) / cfg.B, cfg.name
