@@ -184,3 +184,31 @@ def test_every_configuration_is_in_the_regime_without_a_decode_buffer():
     cfgs = [W.config(n) for n in range(1, 6)] + [W.convergence_instance(50)] + A.instances(4, n=50)
     for cfg in cfgs:
         assert cfg.notes["tau_mix"] / cfg.notes["tau_solo"] >= (cfg.B - 1) / cfg.B, cfg.name
+
+
+def test_null_handles_and_null_outputs_are_refused():
+    """Every entry point that takes a handle returns SIM_EINVAL for a null one (before it touches the GPU), the
+    host helpers for null outputs; sim_strerror names every code."""
+    from paper_2602_02987_amd import binding as B
+    L = B.lib()
+    null = None
+    EINVAL = -1
+    assert L.sim_run(null, ctypes.c_int64(1), 1, ctypes.c_uint64(1), null) == EINVAL
+    assert L.sim_stats(null, null, null) == EINVAL
+    assert L.sim_set_targets(null, null, null, null) == EINVAL
+    assert L.sim_set_split(null, 0, null) == EINVAL
+    assert L.sim_snapshot(null, 0, null, null) == EINVAL
+    assert L.sim_tallies(null, 0, null, null) == EINVAL
+    assert L.sim_hist(null, 0, 0, null, null) == EINVAL
+    assert L.sim_digest(null, 0, null, null) == EINVAL
+    assert L.sim_kernel_time(null, null, null, 0, null) == EINVAL
+    assert L.sim_launch_shape(null, null, null) == EINVAL
+    assert L.sim_destroy(null) == EINVAL
+    assert L.sim_workspace_bytes(null, 1, null) == EINVAL
+    assert L.sim_onchip_bytes(null, null, null) == EINVAL
+    assert L.sim_length_table(0, ctypes.c_double(10.0), ctypes.c_double(0.0), null) == EINVAL
+    assert L.sim_patience_table(ctypes.c_double(1.0), ctypes.c_double(0.01), null) == EINVAL
+    assert L.sim_abi_sizes(null) == EINVAL
+    L.sim_strerror.restype = ctypes.c_char_p
+    names = {L.sim_strerror(c) for c in (0, -1, -2, -3, -4)}
+    assert len(names) == 5 and L.sim_strerror(-99) not in names
