@@ -52,7 +52,7 @@ def _random_weights(rng, K):
 
 
 # More batches on request: GNR_RANDOM_BATCHES=400 runs batches 0..399 (about 4800 configurations, a few minutes);
-# the kernel as committed passed 400.
+# the kernel as committed passed 1200.
 _BATCHES = max(24, int(os.environ.get("GNR_RANDOM_BATCHES", "24")))
 
 
