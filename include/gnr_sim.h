@@ -12,6 +12,8 @@
  * occupancy-deviation prefill gate, solo-first work-conserving decode router.
  * Revenue is recognised as in Sec. 2.3 (bundled: at request completion; separate: prompt
  * tokens at prefill completion, output tokens at decode completion).
+ * Other gates (static priority, FCFS) and routers (SLI-aware randomized and weighted routers, immediate
+ * decode on the prefill's server) are selected by gate_mode and route_mode: see enum sim_gate, enum sim_route.
  *
  * Time advances in fixed steps of length dt. Every server keeps an exact clock (integer ns) for
  * the end of its running iteration; in step s (boundary time T_s = (s+1)*dt) the library
