@@ -24,8 +24,8 @@ HBM_PEAK_GBS = 8000.0
 # each scaled by what the same counter reads for a device copy of known size), and the occupancy rocprofv3 derives
 # for it. Valid only for the kernel source they were measured on: the hash below is compared with the current
 # source and the figures dropped on a mismatch.
-TRAFFIC = {"kernel_sha256": "100f7e60103055aa875d694cbb73ee2405bbe6e0f69252f673f70aeef0fa832c",
-           "bytes_per_launch": 412118136013.86597, "occupancy_percent": 49.33}
+TRAFFIC = {"kernel_sha256": "3b8827f4caa4827b96c147ba5642282c59170d3a5d3d58a689efbb06df7d0392",
+           "bytes_per_launch": 412187551206.458, "occupancy_percent": 49.32}
 
 
 def algorithmic_bytes(t0, g0, t1, g1, slots):

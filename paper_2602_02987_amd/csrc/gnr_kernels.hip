@@ -1763,7 +1763,9 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
               if (lane == 0)
                 L.sc[scan_word] = static_cast<int32_t>(first_left != 0xFFFFFFFFu ? first_left : (left > 0 ? len : stop));
             };
-            if (wave == 0) {
+            // (a wave in the middle of the workgroup: the first waves assign the admissions above, the last ones
+            // turn the level counts into ranks below)
+            if (wave == (nwaves >= 8 ? nwaves / 2 : 0)) {
               if constexpr (RR) {
                 if constexpr (WS) {
                   int nsel_s[kMaxK], nsel_m[kMaxK];
