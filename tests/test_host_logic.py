@@ -212,3 +212,14 @@ def test_null_handles_and_null_outputs_are_refused():
     L.sim_strerror.restype = ctypes.c_char_p
     names = {L.sim_strerror(c) for c in (0, -1, -2, -3, -4)}
     assert len(names) == 5 and L.sim_strerror(-99) not in names
+
+
+def test_phase_profile_names_every_mark_once():
+    """The phase-profile tool names each cycle mark of the step kernel exactly once, and every mark the kernel
+    source sets has a name."""
+    from paper_2602_02987_amd import phase_profile as P
+    ids = [i for i, _ in P.PHASES]
+    assert len(ids) == len(set(ids)) and all(0 <= i < 32 for i in ids)
+    src = open(os.path.join(ROOT, "paper_2602_02987_amd", "csrc", "gnr_kernels.hip")).read()
+    marks = {int(m) for m in re.findall(r"PROF\((\d+)\)", src)}
+    assert marks <= set(ids), marks - set(ids)
