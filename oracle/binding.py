@@ -66,6 +66,7 @@ def lib():
         _lib.oracle_run.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_uint64]
         _lib.oracle_set_targets.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         _lib.oracle_patience_table.argtypes = [C.c_double, C.c_double, C.c_void_p]
+        _lib.oracle_poke.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int64]
     return _lib
 
 
@@ -212,6 +213,20 @@ class Oracle:
 
     def check(self):
         return int(self.L.oracle_check(self.h))
+
+    def poke(self, r, what, i, delta):
+        """Test hook: adds `delta` to one number of replication r's state (see oracle_poke)."""
+        if self.L.oracle_poke(self.h, int(r), int(what), int(i), C.c_int64(int(delta))):
+            raise RuntimeError("oracle_poke: nothing to perturb there")
+
+    def clear_violations(self):
+        self.L.oracle_clear_violations(self.h)
+
+    def violation_codes(self):
+        """The distinct codes the checker has reported since the last clear."""
+        out = (C.c_int * 64)()
+        n = self.L.oracle_violation_codes(self.h, out, 64)
+        return sorted(out[i] for i in range(min(n, 64)))
 
     def steps_done(self):
         return int(self.L.oracle_steps_done(self.h))

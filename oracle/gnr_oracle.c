@@ -23,8 +23,6 @@
  *  - revenue recognition events (Sec. 2.3, bundled and separate charging);
  *  - abandonment (Sec. 2.3): a job waiting in a prefill queue or in the decode
  *    buffer leaves when its exponential patience, rate theta of its class, ends;
- *  - abandonment (Sec. 2.3): a job waiting in a prefill queue or in the decode buffer leaves when its
- *    exponential patience, rate theta of its class, runs out;
  *  - balance equations and capacity constraints (Sec. 2.3) are checked by
  *    oracle_check(), recomputing every aggregate from the per-server state.
  *  Readings (time stepping, tie orders, samplers) are listed where they occur.
@@ -150,6 +148,7 @@ typedef struct oracle_t {
   int check_every;
   int64_t violations;
   int first_violation;
+  int codes[64], ncodes;  /* the distinct violation codes seen so far */
 } oracle_t;
 
 /* ---------------------------------------------------------------- Philox ---- */
@@ -446,7 +445,19 @@ int64_t oracle_violations(const oracle_t *o) { return o->violations; }
 int oracle_first_violation(const oracle_t *o) { return o->first_violation; }
 
 /* ------------------------------------------------------------ invariants ---- */
-static void viol(oracle_t *o, int code) { if (!o->violations) o->first_violation = code; o->violations++; }
+static void viol(oracle_t *o, int code)
+{
+  if (!o->violations) o->first_violation = code;
+  o->violations++;
+  for (int i = 0; i < o->ncodes; i++) if (o->codes[i] == code) return;
+  if (o->ncodes < 64) o->codes[o->ncodes++] = code;
+}
+/* The distinct codes seen so far (at most cap of them are written); returns how many there are. */
+int oracle_violation_codes(const oracle_t *o, int *out, int cap)
+{
+  for (int i = 0; i < o->ncodes && i < cap; i++) out[i] = o->codes[i];
+  return o->ncodes;
+}
 
 /* Recompute every aggregate from per-server state and compare with the running
  * counters: capacity constraints and balance equations of Sec. 2.3, token
@@ -554,6 +565,50 @@ int64_t oracle_check(oracle_t *o)
   for (int r = 0; r < o->reps; r++) if (o->rep[r].inited) n += check_rep(o, r);
   return n;
 }
+
+/* TEST HOOKS (used by the tests of the checker itself, never by a simulation): oracle_poke adds `delta` to one
+ * number of replication r's state so that a test can show which relation of check_rep() notices it.
+ * what: 0 Q_p,i  1 X_i  2 Q_d,i  3 Y_m,i  4 Y_s,i (i = class); 5 tally word (i = class * NTALLY + word);
+ * 6 decode count of server i; 7 prompt tokens left of server i's prefill; 8 end time of server i's iteration;
+ * 9 finish index of server i's first occupied slot; 10 (delta ignored) server i's first free slot becomes a copy of
+ * its first occupied one, counters untouched. oracle_clear_violations forgets what was found so far. */
+int oracle_poke(oracle_t *o, int r, int what, int i, int64_t delta)
+{
+  if (!o || r < 0 || r >= o->reps || !o->rep[r].inited || i < 0) return -1;
+  rep_t *R = &o->rep[r];
+  const int K = o->cfg.K, N = o->cfg.N;
+  if (what >= 0 && what <= 4 && i >= K) return -1;
+  if (what == 5 && i >= K * NTALLY) return -1;
+  if (what >= 6 && i >= N) return -1;
+  switch (what) {
+    case 0: R->Qp[i] += delta; break;
+    case 1: R->X[i] += delta; break;
+    case 2: R->Qd[i] += delta; break;
+    case 3: R->Ym[i] += delta; break;
+    case 4: R->Ys[i] += delta; break;
+    case 5: R->tally[i / NTALLY][i % NTALLY] += (uint64_t)delta; break;
+    case 6: R->sv[i].n_dec += (int)delta; break;
+    case 7: R->sv[i].pf_rem += (int)delta; break;
+    case 8: R->sv[i].t_next += delta; break;
+    case 9:
+      for (int j = 0; j < o->cfg.B; j++)
+        if (R->sv[i].slot[j].used) { R->sv[i].slot[j].fin += (uint32_t)delta; return 0; }
+      return -1;
+    case 10: {
+      slot_t *src = NULL, *dst = NULL;
+      for (int j = 0; j < o->cfg.B; j++) {
+        if (R->sv[i].slot[j].used && !src) src = &R->sv[i].slot[j];
+        if (!R->sv[i].slot[j].used && !dst) dst = &R->sv[i].slot[j];
+      }
+      if (!src || !dst) return -1;
+      *dst = *src;
+      break;
+    }
+    default: return -1;
+  }
+  return 0;
+}
+int oracle_clear_violations(oracle_t *o) { o->violations = 0; o->first_violation = 0; o->ncodes = 0; return 0; }
 
 /* ------------------------------------------------------------------ step ---- */
 static int64_t iter_time(const oracle_t *o, int ptok, int n)

@@ -214,12 +214,22 @@ def test_null_handles_and_null_outputs_are_refused():
     assert len(names) == 5 and L.sim_strerror(-99) not in names
 
 
-def test_phase_profile_names_every_mark_once():
-    """The phase-profile tool names each cycle mark of the step kernel exactly once, and every mark the kernel
-    source sets has a name."""
-    from paper_2602_02987_amd import phase_profile as P
-    ids = [i for i, _ in P.PHASES]
-    assert len(ids) == len(set(ids)) and all(0 <= i < 32 for i in ids)
-    src = open(os.path.join(ROOT, "paper_2602_02987_amd", "csrc", "gnr_kernels.hip")).read()
-    marks = {int(m) for m in re.findall(r"PROF\((\d+)\)", src)}
-    assert marks <= set(ids), marks - set(ids)
+def test_modulation_period_is_bounded_and_the_weighted_router_counts_its_tables():
+    """A modulation period beyond what a run can reach is refused (not a host allocation of its size); the on-chip
+    need reported for the weighted router includes its selection tables."""
+    from dataclasses import replace
+    from paper_2602_02987_amd import binding as B, workloads as W
+    cfg = W.config(5, N=300, replications=1)
+    assert B.sim_workspace_bytes(cfg, 1) > 0
+    with pytest.raises(B.SimError):
+        B.sim_workspace_bytes(replace(cfg, mod_period=(1 << 29) + 1), 1)
+    with pytest.raises(B.SimError):
+        B.sim_workspace_bytes(replace(cfg, mod_period=1 << 60), 1)
+    base, _ = B.sim_onchip_bytes(cfg)
+    ws = W.with_weighted_split(W.config(5, N=300, replications=1), lam_plan=[c.lam / 0.95 for c in cfg.classes])
+    rr = W.with_random_split(W.config(5, N=300, replications=1), lam_plan=[c.lam / 0.95 for c in cfg.classes])
+    need_ws, _ = B.sim_onchip_bytes(ws)
+    need_rr, _ = B.sim_onchip_bytes(rr)
+    assert need_rr == base
+    # deadline rings' candidate table (K x 256 words) plus 256 x (4 + 2 + 2) bytes of class selections
+    assert need_ws == base + cfg.K * 256 * 4 + 256 * 8

@@ -1,7 +1,8 @@
-"""The oracle built with the compiler's undefined-behaviour checks (signed overflow, shifts, out-of-range
+"""Sanitizer builds of the oracle (CPU only). First: the oracle built with the compiler's undefined-behaviour checks (signed overflow, shifts, out-of-range
 conversions, misaligned or null accesses abort the process) runs every policy variant on the overloaded small
 instance and two of the benchmark configurations. CPU only; runs in a child process so that an abort is a test
-failure, not the end of the test session."""
+failure, not the end of the test session. Second: every policy variant in a program of its own built with
+AddressSanitizer as well (heap and stack overruns, use after free, leaks abort it)."""
 import os
 import subprocess
 import sys
@@ -40,3 +41,12 @@ def test_oracle_runs_clean_under_the_undefined_behaviour_checks(tmp_path):
         """)
     res = subprocess.run([sys.executable, "-c", script], capture_output=True, text=True, timeout=600)
     assert res.returncode == 0 and "clean" in res.stdout and "runtime error" not in res.stderr, res.stderr[-2000:]
+
+
+def test_oracle_runs_clean_under_address_sanitizer(tmp_path):
+    exe = str(tmp_path / "oracle_asan")
+    subprocess.check_call(["gcc", "-O1", "-g", "-ffp-contract=off", "-Wall", "-fsanitize=address,undefined",
+                           "-fno-sanitize-recover=all", "-fno-omit-frame-pointer",
+                           os.path.join(ROOT, "tests", "oracle_asan_driver.c"), "-o", exe, "-lm"])
+    res = subprocess.run([exe], capture_output=True, text=True, timeout=600)
+    assert res.returncode == 0 and "clean" in res.stdout and "ERROR" not in res.stderr, (res.stdout[-1000:], res.stderr[-3000:])

@@ -98,14 +98,81 @@ def test_invariants_hold_every_step(oracle_mod, gate):
             assert g[GI["OVERFLOW"]] == 1 and t[:, TI["DROP_P"]].sum() > 0
 
 
+# What oracle_poke can perturb (first argument after the replication) and the checker's codes: 130-134 recount of
+# X, Y_m, Y_s, Q_d, Q_p from the servers and queues; 140-144 the balance equations of Sec. 2.3 (eq:bal-Qp, eq:bal-X,
+# eq:bal-Qd, eq:bal-Ym, eq:bal-Ys); 150/151 token conservation; 103 decode count of a server; 106 a mixed-group
+# server holds at most B-1 decodes; 121 the aggregate form of it, Y_m <= (B-1) X (eq:cap-Ym); 108/109 prefill state;
+# 112 a running iteration ends after the current boundary; 101 finish index of a decode.
+_POKE = dict(Qp=0, X=1, Qd=2, Ym=3, Ys=4, tally=5, n_dec=6, pf_rem=7, t_next=8, fin=9, extra_slot=10)
+
+
 def test_checker_detects_a_planted_imbalance(oracle_mod):
-    """The invariant checker is not vacuous: a second handle with another seed has other aggregates,
-    and totals cross-checked between the two differ (sanity of the comparison itself)."""
-    cfg = _heavy()
-    a = oracle_mod.Oracle(cfg); a.run(500)
-    b = oracle_mod.Oracle(cfg); b.run(500, seed=12)
-    assert a.digest(0) != b.digest(0)
-    assert not np.array_equal(a.tallies(0)[0], b.tallies(0)[0])
+    """The invariant checker fires, with the code of the violated relation, when one number of a consistent state
+    is perturbed: each balance equation, each recounted aggregate, token conservation, the per-server capacity
+    constraint and its aggregate form. Every "invariants hold" pin rests on this."""
+    cfg = _heavy(queue_cap=100000, dbuf_cap=100000, replications=1)
+    K, NT = cfg.K, len(TI)
+
+    def fresh(steps):
+        o = oracle_mod.Oracle(cfg)
+        o.run(steps)
+        assert o.check() == 0 and o.violations() == (0, 0)
+        return o
+
+    def planted(o, what, i, delta, expect, also=()):
+        o.clear_violations()
+        o.poke(0, _POKE[what], i, delta)
+        n = o.check()
+        codes = o.violation_codes()
+        assert n > 0 and o.violations()[1] == expect and set(also) <= set(codes), (what, i, delta, n, codes)
+        o.poke(0, _POKE[what], i, -delta)          # undo: the state is consistent again
+        o.clear_violations()
+        assert o.check() == 0, (what, i, "undo")
+
+    o = fresh(700)
+    for k in range(K):
+        # counting processes: each perturbs exactly the balance equations it appears in (the first one is reported first)
+        planted(o, "tally", k * NT + TI["A"], 1, 140)
+        planted(o, "tally", k * NT + TI["U_P"], 1, 140, also=(141,))
+        planted(o, "tally", k * NT + TI["S_P"], 1, 141, also=(142,))
+        planted(o, "tally", k * NT + TI["U_DS"], 1, 142, also=(144,))
+        planted(o, "tally", k * NT + TI["U_DM"], 1, 142, also=(143,))
+        planted(o, "tally", k * NT + TI["S_DM"], 1, 143)
+        planted(o, "tally", k * NT + TI["S_DS"], 1, 144)
+        planted(o, "tally", k * NT + TI["M_SM"], 1, 143, also=(144,))
+        planted(o, "tally", k * NT + TI["M_MS"], -1, 143, also=(144,))
+        planted(o, "tally", k * NT + TI["TOK_EMIT"], 1, 150)
+        planted(o, "tally", k * NT + TI["TOKD_DEC"], 1, 150)
+        planted(o, "tally", k * NT + TI["TOK_PREF"], -1, 151)
+        # state counters against the recount from the servers and queues, and against the balance equations
+        planted(o, "X", k, 1, 130, also=(141,))
+        planted(o, "Ym", k, -1, 131, also=(143,))
+        planted(o, "Ys", k, 1, 132, also=(144,))
+        planted(o, "Qd", k, 1, 133, also=(142,))
+        planted(o, "Qp", k, -1, 134, also=(140,))
+    sl, sv = o.slots(0), o.servers(0)
+    g_busy = int(np.nonzero(sl["n_dec"] > 0)[0][0])
+    planted(o, "n_dec", g_busy, 1, 103)
+    planted(o, "fin", g_busy, 40000, 101)                       # a decode that would outlive its D tokens
+    planted(o, "t_next", g_busy, -10**12, 112)                  # an iteration that should already have completed
+    g_pf = int(np.nonzero(sv["rem"] > 0)[0][0])
+    planted(o, "pf_rem", g_pf, 40000, 109, also=(151,))         # more prompt tokens left than the prompt has
+    g_solo = cfg.M + int(np.nonzero(sl["n_dec"][cfg.M:] > 0)[0][0])
+    planted(o, "pf_rem", g_solo, 1, 108, also=(130,))           # a prefill on a solo-group server
+    # capacity (Sec. 2.3): a mixed-group server with B decodes beside its prefill; with every mixed server full,
+    # the aggregate constraint Y_m <= (B-1) X fails too
+    o = oracle_mod.Oracle(cfg)
+    for _ in range(3000):
+        o.run(1)
+        sl, sv = o.slots(0), o.servers(0)
+        if np.all(sv["rem"][:cfg.M] > 0) and np.all(sl["n_dec"][:cfg.M] == cfg.B - 1):
+            break
+    else:
+        raise AssertionError("the mixed group never filled up")
+    assert o.check() == 0
+    o.poke(0, _POKE["extra_slot"], 0, 0)
+    assert o.check() > 0
+    assert {103, 106, 121} <= set(o.violation_codes()), o.violation_codes()
 
 
 def test_little_law_exact_identity(oracle_mod):
