@@ -79,6 +79,16 @@ __device__ __forceinline__ int select_bit(const uint64_t *bm, const uint32_t *pr
   return lo * 64 + nth_set_bit(bm[lo], static_cast<int>(j - pre[lo]));
 }
 
+// A wave-uniform value pinned in a scalar register. Without this the compiler, short of registers, re-reads
+// parameters from memory through the scalar cache wherever they are used (a round trip of hundreds of cycles in
+// the middle of a hot loop) instead of keeping them.
+__device__ __forceinline__ uint32_t pinned(uint32_t v)
+{
+  v = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(v)));
+  asm volatile("" : "+s"(v));
+  return v;
+}
+
 __device__ __forceinline__ uint64_t lanes_below() { return (1ull << (threadIdx.x & 63)) - 1ull; }
 
 // Inclusive prefix sum over the wave with data-parallel-primitive adds: shifts by 1, 2, 4 and 8 inside each
@@ -427,6 +437,17 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
   // Mp is the largest M the run has had (a prefill in service stays when its server turns solo).
   const int Mp = p.Mp;
   const int nwords_m = (Mp + 63) >> 6;   // bitmap words that hold servers with prefill state
+  // Iteration-time coefficients, chunk size and step length in ns (each below 2^31: the longest iteration is),
+  // window of the on-chip time-between-tokens histogram, class thresholds of the arrival draw: used in every block.
+  const uint32_t c0_ns = pinned(static_cast<uint32_t>(p.c0)), cpre_ns = pinned(static_cast<uint32_t>(p.cpre));
+  const uint32_t cdec_ns = pinned(static_cast<uint32_t>(p.cdec)), dt_ns = pinned(static_cast<uint32_t>(p.dt));
+  const int chunk_max = static_cast<int>(pinned(static_cast<uint32_t>(p.C)));
+  const int tbt_w = static_cast<int>(pinned(static_cast<uint32_t>(p.tbt_w))), tbt_lo = static_cast<int>(pinned(static_cast<uint32_t>(p.tbt_lo)));
+  // an arrival's class is the number of thresholds its random word has reached; classes beyond K-1 do not exist:
+  // their thresholds are the largest word, and the count is capped
+  uint32_t cthr[kMaxK - 1];
+#pragma unroll
+  for (int c = 0; c + 1 < kMaxK; ++c) cthr[c] = pinned(c + 1 < K ? p.cls_thr[c] : 0xFFFFFFFFu);
 
   int64_t *t_next = a.t_next + static_cast<size_t>(r) * N;
   uint32_t *iter_g = a.iter + static_cast<size_t>(r) * N;
@@ -560,9 +581,9 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
   // one more pass over the blocks does only that, and tallies every iteration still untallied.
   for (uint32_t s = step_begin; s <= step_begin + n_steps; ++s) {
     const bool final_pass = s == step_begin + n_steps;
-    T = (static_cast<int64_t>(s) + 1) * p.dt;
+    T = (static_cast<int64_t>(s) + 1) * dt_ns;
     const uint32_t T32 = static_cast<uint32_t>(T);
-    const int64_t Tp = T - p.dt;   // the boundary of the previous step: restarts refer to it
+    const int64_t Tp = T - dt_ns;   // the boundary of the previous step: restarts refer to it
     const uint32_t Tp32 = static_cast<uint32_t>(Tp);
     if (tid < 8) L.acc[tid] = 0;
     // abandonment only: how many waiting requests of class `tid` leave at the start of this step (asked for
@@ -576,7 +597,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
       }
     }
     const uint32_t *thr = a.arr_thr + 3 * (p.mod_period > 0 ? static_cast<int64_t>(s % static_cast<uint64_t>(p.mod_period)) : 0);
-    const uint32_t thr0 = thr[0], thr1 = thr[1], thr2 = thr[2];
+    const uint32_t thr0 = pinned(thr[0]), thr1 = pinned(thr[1]), thr2 = pinned(thr[2]);
     __syncthreads();
 
     // ---- 1. arrivals of one server: one random block, word 0 -> count, words 1.. -> classes
@@ -590,8 +611,8 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           if (j >= a) break;
           int k = 0;
 #pragma unroll
-          for (int c = 0; c + 1 < kMaxK; ++c) k += (c + 1 < K && w[1 + j] >= p.cls_thr[c]);
-          atomicAdd(&L.acc[k], 1u);
+          for (int c = 0; c + 1 < kMaxK; ++c) k += w[1 + j] >= cthr[c];
+          atomicAdd(&L.acc[k < K ? k : K - 1], 1u);
         }
       }
     };
@@ -619,10 +640,10 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           const uint32_t it = L.iter[g];
           int nd = L.loads[g];
           int rem = g < Mp ? static_cast<int>(L.rem[g]) : 0;
-          const int ptok = has_chunk ? (rem < p.C ? rem : p.C) : 0;   // the chunk frozen at the start of the iteration
+          const int ptok = has_chunk ? (rem < chunk_max ? rem : chunk_max) : 0;   // the chunk frozen at the start of the iteration
           const int64_t tn = T + static_cast<int64_t>(static_cast<int32_t>(L.t32[g] - T32));   // exact completion time
           comp = nc - nj;   // bytewise: no class joins more decodes than it holds
-          d = p.c0 + p.cpre * ptok + p.cdec * static_cast<int64_t>(byte_sum(comp));
+          d = static_cast<int64_t>(c0_ns + cpre_ns * static_cast<uint32_t>(ptok) + cdec_ns * byte_sum(comp));
           chunk = ptok > 0;
           m = static_cast<uint32_t>(L.pend[g]) + 1u;
           L.pend[g] = 0;
@@ -645,7 +666,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
                   const int k = static_cast<int>(jw >> 29) & 7;
                   const uint32_t stamp = static_cast<uint32_t>(jw) & 0x1FFFFFFFu;
                   const uint32_t Pl = (static_cast<uint32_t>(jw >> 32) & 0xFFFFu) + 1, Dl = static_cast<uint32_t>(jw >> 48) + 1;
-                  const int64_t e2e = tn - (static_cast<int64_t>(stamp) + 1) * p.dt;
+                  const int64_t e2e = tn - (static_cast<int64_t>(stamp) + 1) * dt_ns;
                   lds_add64(&L.tl[k * kNTally + (mixed_now ? SIM_T_S_DM : SIM_T_S_DS)], 1);
                   atomicSub(&L.cs[(mixed_now ? CS_YM : CS_YS) + k], 1);
                   lds_add64(&L.tl[k * kNTally + SIM_T_TOKP_DEC], Pl);
@@ -681,7 +702,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
               const uint32_t stamp = static_cast<uint32_t>(jw) & 0x1FFFFFFFu;
               pe.done = true; pe.k = k; pe.nc = nc;
               pe.P = (static_cast<uint32_t>(jw >> 32) & 0xFFFFu) + 1;
-              pe.ttft = tn - (static_cast<int64_t>(stamp) + 1) * p.dt;
+              pe.ttft = tn - (static_cast<int64_t>(stamp) + 1) * dt_ns;
               atomicAdd(reinterpret_cast<unsigned long long *>(&hist[(0 * K + k) * kNBin + hbin(pe.ttft)]), 1ull);
               if constexpr (IM) {
                 // the request keeps its slot: it joins the batch at the restart that follows this completion
@@ -714,7 +735,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
             atomicAnd(reinterpret_cast<unsigned long long *>(&L.bm_join[g >> 6]), ~bit);
           }
         }
-        tally_iterations(L.tl, L.tbth, p.tbt_w, p.tbt_lo, K, m, d, chunk, comp);
+        tally_iterations(L.tl, L.tbth, tbt_w, tbt_lo, K, m, d, chunk, comp);
         // a prefill that ended: completion count, recognised prompt tokens, time to first token; the
         // co-resident decodes switch mixed -> solo
         if (pe.done) {
@@ -786,14 +807,14 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
             const bool joined = join_word & lbit;
             const uint64_t nj = joined ? n_join[g] : 0ull;
             comp = nc - nj;   // bytewise: no class joins more decodes than it holds
-            d = p.c0 + p.cdec * static_cast<int64_t>(byte_sum(comp));   // untallied iterations never hold a chunk
+            d = static_cast<int64_t>(c0_ns + cdec_ns * byte_sum(comp));   // untallied iterations never hold a chunk
             m = static_cast<uint32_t>(pend);
             pend = 0;
             L.pend[g] = 0;
             unjoin = (flush_prev & lbit) && joined;   // the decodes placed at the boundary joined the batch there
             if (unjoin) n_join[g] = 0;
           }
-          tally_iterations(L.tl, L.tbth, p.tbt_w, p.tbt_lo, K, m, d, false, comp);
+          tally_iterations(L.tl, L.tbth, tbt_w, tbt_lo, K, m, d, false, comp);
           const uint64_t unjoin_m = __ballot(unjoin);
           if (unjoin_m) {   // this wave alone works on the block's words
             join_word &= ~unjoin_m;
@@ -805,15 +826,14 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
         if (todo) {
           bool chunk_now = false;
           if (todo & lbit) {
-            const int ptok = rem_v > 0 ? (rem_v < p.C ? rem_v : p.C) : 0;
+            const int ptok = rem_v > 0 ? (rem_v < chunk_max ? rem_v : chunk_max) : 0;
             chunk_now = ptok > 0;
             if (ptok == 0 && nd == 0) {
               busy = false;
             } else {
               // back-to-back after a completion, otherwise from the step boundary; only the low 32 bits of the
               // clock are kept and an iteration lasts less than 2^31 ns, so 32-bit arithmetic is exact here
-              const uint32_t dur = static_cast<uint32_t>(p.c0) + static_cast<uint32_t>(p.cpre) * static_cast<uint32_t>(ptok) +
-                                   static_cast<uint32_t>(p.cdec) * static_cast<uint32_t>(nd);
+              const uint32_t dur = c0_ns + cpre_ns * static_cast<uint32_t>(ptok) + cdec_ns * static_cast<uint32_t>(nd);
               t32v = ((due_prev & lbit) ? t32v : Tp32) + dur;
               L.t32[g] = t32v;
               busy = true;
@@ -2000,3 +2020,4 @@ using StepKernel = void (*)(const Params *, StepArrays, uint32_t, uint32_t, uint
 
 }  // namespace gnr
 #endif
+

@@ -101,6 +101,30 @@ def test_full_size_configs_on_sampled_replications(B, oracle_mod):
         run_both(B, oracle_mod, cfg, steps, oracle_reps=sample)
 
 
+def test_config5_full_size_in_the_state_the_benchmark_times(B, oracle_mod):
+    """Config 5 unmodified (N = 10000, 256 replications, modulation period 100000 steps) advanced in 1000-step
+    runs as the benchmark issues them, through the peak of the arrival rate (step 25000) into the state the
+    benchmark times: it starts its timed region after 31000 steps and ends it, with its default flags, at 36000.
+    The oracle follows one replication all the way (about a minute on one host core); state, tallies, histograms
+    and digest are compared at 10000, 25000, 31000 and 36000 steps."""
+    cfg = W.config(5)
+    assert (cfg.N, cfg.replications, cfg.mod_period) == (10000, 256, 100000)
+    rep = 137
+    sim = B.Sim(cfg)
+    orc = oracle_mod.Oracle(cfg, max_reps=cfg.replications)
+    orc.select([rep])
+    done = 0
+    for stop in (10000, 25000, 31000, 36000):
+        while done < stop:
+            sim.run(1000)
+            done += 1000
+        orc.run(stop - int(orc.steps_done()), cfg.replications, cfg.seed)
+        assert_replication_equal(sim, orc, rep, what=f"config 5 after {stop} steps")
+    sn = sim.snapshot(rep)
+    assert sn["Qp"].sum() > 1000 and sn["n_dec"][cfg.M:].mean() > cfg.B - 2      # the loaded state: long queues, solo servers full
+    assert not sim.stats()["overflow"]
+
+
 def _limits_class(**kw):
     base = dict(lam=1.0, in_law=W.LAW_CONST, in_p0=64.0, out_law=W.LAW_GEOMETRIC, out_p0=4.0)
     base.update(kw)
