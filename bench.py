@@ -20,12 +20,13 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 
 
-# HBM traffic of one step-kernel launch of the default run, from hardware counters (FETCH_SIZE + WRITE_SIZE,
-# each scaled by what the same counter reads for a device copy of known size), and the occupancy rocprofv3 derives
-# for it. Valid only for the kernel source they were measured on: the hash below is compared with the current
-# source and the figures dropped on a mismatch.
-TRAFFIC = {"kernel_sha256": "3b8827f4caa4827b96c147ba5642282c59170d3a5d3d58a689efbb06df7d0392",
-           "bytes_per_launch": 412187551206.458, "occupancy_percent": 49.32}
+# HBM traffic of one step-kernel launch of the default run, from hardware counters (two rocprofv3 --pmc runs:
+# FETCH_SIZE, then WRITE_SIZE, each scaled by what the same counter reads for a device copy of known size), and the
+# occupancy rocprofv3 derives for it. These are STORED figures, not taken in this run: they hold for the kernel
+# sources whose hash is given (compared with the current sources; on a mismatch the figures read null) and for the
+# state named in `state`. The line says so in `roofline.traffic_source` / `roofline.occupancy.source`.
+TRAFFIC = {"sources_sha256": "", "bytes_per_launch": None, "occupancy_percent": None,
+           "state": "", "profile": ""}
 
 
 def algorithmic_bytes(t0, g0, t1, g1, slots):
@@ -56,13 +57,20 @@ def algorithmic_bytes(t0, g0, t1, g1, slots):
                        bytes_per_slot_with_records_in_lds=on_chip_records / slots)
 
 
-def measured(key):
-    """A figure from the hardware-counter runs, or None when the kernel source is no longer the one they ran on."""
+def sources_hash():
+    """sha256 over the library's kernel and host sources, in a fixed order."""
     import hashlib
-    src = os.path.join(ROOT, "paper_2602_02987_amd", "csrc", "gnr_kernels.hip")
-    with open(src, "rb") as fh:
-        sha = hashlib.sha256(fh.read()).hexdigest()
-    return TRAFFIC[key] if TRAFFIC["kernel_sha256"] == sha else None
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_2602_02987_amd", "csrc")
+    for name in sorted(os.listdir(d)):
+        with open(os.path.join(d, name), "rb") as fh:
+            h.update(name.encode() + b"\0" + fh.read())
+    return h.hexdigest()
+
+
+def measured(key):
+    """A stored figure of the hardware-counter runs, or None when the sources are no longer the ones they ran on."""
+    return TRAFFIC[key] if TRAFFIC["sources_sha256"] == sources_hash() else None
 
 
 def occupancy(sim, replications, measured_percent):
@@ -71,7 +79,10 @@ def occupancy(sim, replications, measured_percent):
     waves = threads // 64
     per_cu = min(160 * 1024 // max(lds, 1), 32 // waves, -(-replications // 256))
     return {"threads_per_workgroup": threads, "lds_bytes_per_workgroup": lds, "workgroups_per_cu": per_cu,
-            "waves_per_simd": waves * per_cu / 4.0, "simd_capacity": 8, "measured_percent": measured_percent}
+            "waves_per_simd": waves * per_cu / 4.0, "simd_capacity": 8, "measured_percent": measured_percent,
+            "source": "launch shape from the library; measured_percent " +
+                      (f"stored: rocprofv3 counters, {TRAFFIC['state']}, {TRAFFIC['profile']}" if measured_percent is not None
+                       else "not available for these sources (null)")}
 
 
 def measured_traffic():
@@ -119,6 +130,21 @@ def cpu_baseline(n, N, steps, theta=0.0, split=False, immediate=False, weighted=
     return dict(value=cores * N * steps / wall, unit="server-steps/s", cores=cores, kind="oracle",
                 sample=f"replications 0..{cores - 1} of the workload, first {steps} steps from the empty system, "
                        f"one process per replication, wall {wall:.1f} s incl. table build")
+
+
+def gpu_on_the_baseline_sample(binding, torch, cfg, steps):
+    """The library on the CPU baseline's sample (the first `steps` steps from the empty system; all replications,
+    since a launch runs them side by side), so that the two figures can be compared like for like."""
+    sim = binding.Sim(cfg)
+    sim.run(0)                       # the reset kernel
+    torch.cuda.synchronize()
+    t = time.perf_counter()
+    sim.run(steps)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t
+    sim.close()
+    return dict(value=cfg.N * cfg.replications * steps / wall, unit="server-steps/s",
+                sample=f"all {cfg.replications} replications, first {steps} steps from the empty system, wall {wall * 1e3:.0f} ms")
 
 
 def main():
@@ -206,6 +232,9 @@ def main():
     total_bytes, shape = algorithmic_bytes(tt0, st0["glob"], tt1, st1["glob"], slots)
     per_launch_ms = kernel_ms / max(launches, 1)
     achieved = total_bytes / (kernel_ms * 1e-3) / 1e9 if kernel_ms > 0 else 0.0
+    own_bytes = shape["bytes_per_slot_with_records_in_lds"] * slots
+    achieved_own = own_bytes / (kernel_ms * 1e-3) / 1e9 if kernel_ms > 0 else 0.0
+    traffic = measured_traffic() if default_run else None
     iters = float(st1["glob"][0] + st1["glob"][1]) - float(st0["glob"][0] + st0["glob"][1])
 
     out = {
@@ -226,12 +255,23 @@ def main():
                    "executed_iterations_per_s": iters / wall,
                    "overflow": bool(st1["overflow"])},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic() if default_run else None,
+                     "frac": achieved / HBM_PEAK_GBS,
+                     # the same with the bytes this kernel has to move (server clocks, iteration counters and decode
+                     # counts stay in LDS for a whole launch and are not part of them)
+                     "achieved_own_bytes": achieved_own, "frac_own_bytes": achieved_own / HBM_PEAK_GBS,
+                     "traffic": traffic,
+                     "traffic_source": (f"stored: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, {TRAFFIC['state']}, sources sha256 "
+                                        f"{TRAFFIC['sources_sha256'][:12]}, {TRAFFIC['profile']}" if traffic is not None else
+                                        "none: no counter run on these sources and this workload (null)"),
                      "occupancy": occupancy(sim, cfg.replications, measured("occupancy_percent") if default_run else None),
                      "kernel": "gnr_step_kernel", "launches": launches, "avg_launch_ms": per_launch_ms,
                      "algorithmic_bytes_per_launch": total_bytes / max(launches, 1), **shape},
     }
     if base is not None:
+        sim.close()
+        del sim
+        torch.cuda.empty_cache()
+        base["gpu_same_sample"] = gpu_on_the_baseline_sample(binding, torch, cfg, args.oracle_steps)
         out["cpu_baseline"] = base
     print(json.dumps(out))
 

@@ -8,7 +8,8 @@ namespace gnr {
 size_t step_lds_bytes(const Params &p)
 {
   size_t total = 0;
-  lds_carve(p, nullptr, &total);
+  if (static_words(p.threads)) lds_carve<static_words(1024)>(p, nullptr, &total);
+  else lds_carve<0>(p, nullptr, &total);
   return total;
 }
 

@@ -145,6 +145,7 @@ constexpr int kMaxPend = 254;     // untallied iterations a server may accumulat
 struct Lds {
   int32_t *cs;        // [CS_WORDS]
   uint32_t *acc;      // [8]
+  double *gtab;       // [5][kMaxK] gate targets of the launch: n x*, 1/x*, x*, n q*, priority index
   int32_t *sc;        // [SC_WORDS]
   uint64_t *tl;       // [kTallyWords]
   uint64_t *tbth;     // [K][tbt_w]
@@ -178,42 +179,52 @@ struct Lds {
   uint16_t *sel_j;    // [kJobsLds] list position of each selection, ordered by class, then by order within the class
 };
 
-// Carves the dynamic LDS block; 8-byte granules, 64-bit arrays first.
+// Carves the dynamic LDS block; 8-byte granules. NWS > 0: the arrays indexed by 64-server word are sized for NWS
+// words and the per-wave arrays for sixteen waves, whatever the configuration has; every array but the per-server
+// ones and those behind them then sits at an offset the compiler knows (an immediate in the LDS instruction)
+// instead of one it has to keep in a register, or to spill and fetch back, at every access. Used for the
+// workgroups of sixteen waves (N up to 64 NWS servers). NWS = 0: everything sized by the configuration.
+constexpr int kStaticWords = kMaxN / 64;
+template <int NWS>
 __host__ __device__ __forceinline__ Lds lds_carve(const Params &p, unsigned char *base, size_t *total)
 {
   Lds L;
   size_t off = 0;
+  const size_t nw = NWS ? static_cast<size_t>(NWS) : static_cast<size_t>(p.nwords);
+  const size_t waves = NWS ? 16u : static_cast<size_t>(p.threads / 64);
 #define GNR_TAKE(field, type, count)                       \
   L.field = reinterpret_cast<type *>(base + off);          \
   off += (sizeof(type) * static_cast<size_t>(count) + 7) & ~size_t(7);
   GNR_TAKE(tl, uint64_t, kTallyWords)
-  GNR_TAKE(tbth, uint64_t, p.K * p.tbt_w)
-  GNR_TAKE(bm_idle, uint64_t, p.nwords)
-  GNR_TAKE(bm_comp, uint64_t, p.nwords)
-  GNR_TAKE(bm_busy, uint64_t, p.nwords)
-  GNR_TAKE(bm_join, uint64_t, p.nwords)
-  GNR_TAKE(bm_due, uint64_t, p.nwords)
-  GNR_TAKE(bm_touch, uint64_t, p.nwords)
-  GNR_TAKE(bm_flush, uint64_t, p.nwords)
-  GNR_TAKE(bm_chunk, uint64_t, p.nwords)
   GNR_TAKE(jobs, uint64_t, kJobsLds)
   GNR_TAKE(cs, int32_t, CS_WORDS)
   GNR_TAKE(acc, uint32_t, 8)
+  GNR_TAKE(gtab, double, 5 * kMaxK)
   GNR_TAKE(sc, int32_t, SC_WORDS)
-  GNR_TAKE(pre_lvl, uint32_t, kRouteLevels * p.nwords)
-  GNR_TAKE(pre_c, uint32_t, p.nwords + 1)
-  GNR_TAKE(pre, uint32_t, p.nwords + 1)
   GNR_TAKE(adm, uint32_t, kAdmChunk)
   GNR_TAKE(adm_slot, uint16_t, kAdmChunk)
   GNR_TAKE(lh, uint32_t, 2 * kLoadBins)
-  GNR_TAKE(ev_g, uint32_t, (p.threads / 64) * kEvPerWave)
-  GNR_TAKE(ev_q, uint32_t, (p.threads / 64) * kEvPerWave)
+  GNR_TAKE(ev_g, uint32_t, waves * kEvPerWave)
+  GNR_TAKE(ev_q, uint32_t, waves * kEvPerWave)
+  GNR_TAKE(stage, uint16_t, waves * 128)
+  GNR_TAKE(bm_idle, uint64_t, nw)
+  GNR_TAKE(bm_comp, uint64_t, nw)
+  GNR_TAKE(bm_busy, uint64_t, nw)
+  GNR_TAKE(bm_join, uint64_t, nw)
+  GNR_TAKE(bm_due, uint64_t, nw)
+  GNR_TAKE(bm_touch, uint64_t, nw)
+  GNR_TAKE(bm_flush, uint64_t, nw)
+  GNR_TAKE(bm_chunk, uint64_t, nw)
+  GNR_TAKE(pre_lvl, uint32_t, kRouteLevels * nw)
+  GNR_TAKE(pre_c, uint32_t, nw + 1)
+  GNR_TAKE(pre, uint32_t, nw + 1)
+  // from here on the offsets depend on the configuration
   GNR_TAKE(t32, uint32_t, p.N)
   GNR_TAKE(iter, uint32_t, p.N)
   GNR_TAKE(loads, uint8_t, p.N)
   GNR_TAKE(pend, uint8_t, p.N)
   GNR_TAKE(rem, uint16_t, p.Mp)
-  GNR_TAKE(stage, uint16_t, 2 * p.threads)
+  GNR_TAKE(tbth, uint64_t, p.K * p.tbt_w)
   GNR_TAKE(live_off, uint32_t, p.dl_rings ? p.K * kAdmChunk : 0)
   GNR_TAKE(sel_u, uint32_t, p.route_mode == SIM_ROUTE_WEIGHTED_SPLIT ? kJobsLds : 0)
   GNR_TAKE(sel_co, uint16_t, p.route_mode == SIM_ROUTE_WEIGHTED_SPLIT ? kJobsLds : 0)
@@ -222,6 +233,8 @@ __host__ __device__ __forceinline__ Lds lds_carve(const Params &p, unsigned char
   if (total) *total = off;
   return L;
 }
+// Words the word-indexed arrays are sized for, by workgroup size.
+__host__ __device__ constexpr int static_words(int threads) { return threads > 768 ? kStaticWords : 0; }
 
 // Bits of bitmap word w that belong to servers below `nbits`.
 __device__ __forceinline__ uint64_t bits_below(int w, int nbits)
@@ -343,21 +356,35 @@ __device__ __forceinline__ void tally_iterations(uint64_t *tl, uint64_t *tbth, i
 struct GateKey { double a, b; };
 
 // `live_off` (abandonment only, else null): ring offset of the m-th request of class k that still waits.
-__device__ __forceinline__ GateKey gate_key(const Params &p, const uint32_t *qring, const uint32_t *live_off,
-                                            const int (&xs)[kMaxK], const int (&qp)[kMaxK],
-                                            const uint32_t (&head)[kMaxK], int k, int m)
+// The gate's targets live in an LDS table for the launch, [5][kMaxK]: n x*, 1/x*, x*, n q*, priority index (a copy
+// of the parameter block's, which would be read through the scalar cache, a long round trip, at every comparison of
+// the ranking loops). The values of one class are fetched together, once, before they are used.
+enum GateTab { GT_NX = 0, GT_INVX = 1, GT_XSTAR = 2, GT_NQ = 3, GT_PRIO = 4 };
+struct ClassTargets { double nx, invx, xstar, nq, prio; };
+__device__ __forceinline__ ClassTargets load_targets(const double *tab, int k)
+{
+  ClassTargets t;
+  t.nx = tab[GT_NX * kMaxK + k]; t.invx = tab[GT_INVX * kMaxK + k]; t.xstar = tab[GT_XSTAR * kMaxK + k];
+  t.nq = tab[GT_NQ * kMaxK + k]; t.prio = tab[GT_PRIO * kMaxK + k];
+  return t;
+}
+// Key of the m-th waiting request of class k, of which X_k = xs_k are in prefill and Q_p,k = qp_k wait; head_k: ring
+// position of the class queue's head.
+__device__ __forceinline__ GateKey gate_key(const int gate_mode, const uint32_t queue_cap, const ClassTargets &t,
+                                            const uint32_t *qring, const uint32_t *live_off, int xs_k, int qp_k,
+                                            uint32_t head_k, int k, int m)
 {
   GateKey key;
-  if (p.gate_mode == SIM_GATE_OCCUPANCY) {
-    key.a = (static_cast<double>(xs[k] + m) - p.nx[k]) * p.invx[k];
-    key.b = static_cast<double>(qp[k] - m) - p.nq[k];
-  } else if (p.gate_mode == SIM_GATE_PRIORITY) {
-    key.a = -p.prio[k];
+  if (gate_mode == SIM_GATE_OCCUPANCY) {
+    key.a = (static_cast<double>(xs_k + m) - t.nx) * t.invx;
+    key.b = static_cast<double>(qp_k - m) - t.nq;
+  } else if (gate_mode == SIM_GATE_PRIORITY) {
+    key.a = -t.prio;
     key.b = 0.0;
   } else {
-    uint32_t pos = head[k] + (live_off ? live_off[k * kAdmChunk + m] : static_cast<uint32_t>(m));
-    if (pos >= p.queue_cap) pos -= p.queue_cap;
-    key.a = static_cast<double>(qring[static_cast<size_t>(k) * p.queue_cap + pos]);
+    uint32_t pos = head_k + (live_off ? live_off[k * kAdmChunk + m] : static_cast<uint32_t>(m));
+    if (pos >= queue_cap) pos -= queue_cap;
+    key.a = static_cast<double>(qring[static_cast<size_t>(k) * queue_cap + pos]);
     key.b = 0.0;
   }
   return key;
@@ -420,7 +447,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
 {
   const Params &p = *params;   // immutable after creation; read through the scalar cache on demand
   extern __shared__ __align__(16) unsigned char lds_raw[];
-  const Lds L = lds_carve(p, lds_raw, nullptr);
+  const Lds L = lds_carve<static_words(MAXT)>(p, lds_raw, nullptr);
 
   const int r = blockIdx.x;
   const int tid = threadIdx.x;
@@ -430,6 +457,14 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int nwaves = NT >> 6;
   const int wave_base = wave << 6;
+  // The instruction arbiter of a SIMD prefers its oldest wave: left alone, the first four waves of the workgroup
+  // finish every sweep early and the last four late, and the barrier waits for those. Raising the priority of the
+  // younger waves evens this out.
+  if (nwaves > 4) {
+    if (wave >= 12) __builtin_amdgcn_s_setprio(3);
+    else if (wave >= 8) __builtin_amdgcn_s_setprio(2);
+    else if (wave >= 4) __builtin_amdgcn_s_setprio(1);
+  }
   const int K = p.K, N = p.N, B = p.B, M = p.M, BS = p.BS;
   const int nper = (N + NT - 1) / NT;
   const int nwords = p.nwords;
@@ -448,6 +483,8 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
   uint32_t cthr[kMaxK - 1];
 #pragma unroll
   for (int c = 0; c + 1 < kMaxK; ++c) cthr[c] = pinned(c + 1 < K ? p.cls_thr[c] : 0xFFFFFFFFu);
+  const int gate_mode = static_cast<int>(pinned(static_cast<uint32_t>(p.gate_mode)));
+  const uint32_t queue_cap = pinned(p.queue_cap), dbuf_cap = pinned(p.dbuf_cap);
 
   int64_t *t_next = a.t_next + static_cast<size_t>(r) * N;
   uint32_t *iter_g = a.iter + static_cast<size_t>(r) * N;
@@ -457,20 +494,20 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
   uint64_t *n_join = a.n_join + static_cast<size_t>(r) * N;
   uint32_t *fin = a.fin + static_cast<size_t>(r) * N * BS;
   uint64_t *job = a.job + static_cast<size_t>(r) * N * BS;
-  uint32_t *qring = a.qring + static_cast<size_t>(r) * K * p.queue_cap;
-  uint64_t *dring = a.dring + static_cast<size_t>(r) * p.dbuf_cap;
+  uint32_t *qring = a.qring + static_cast<size_t>(r) * K * queue_cap;
+  uint64_t *dring = a.dring + static_cast<size_t>(r) * dbuf_cap;
   uint64_t *hist = a.hist + static_cast<size_t>(r) * 3 * K * kNBin;
   uint32_t *ev_g = L.ev_g + wave * kEvPerWave;
   uint32_t *ev_q = L.ev_q + wave * kEvPerWave;
   // abandonment only
   const uint32_t cal_n = p.cal_mask + 1u;
-  uint32_t *qdl = AB ? a.qdl + static_cast<size_t>(r) * K * p.queue_cap : nullptr;
-  uint32_t *ddl = AB ? a.ddl + static_cast<size_t>(r) * p.dbuf_cap : nullptr;
+  uint32_t *qdl = AB ? a.qdl + static_cast<size_t>(r) * K * queue_cap : nullptr;
+  uint32_t *ddl = AB ? a.ddl + static_cast<size_t>(r) * dbuf_cap : nullptr;
   uint32_t *cal = AB ? a.cal + static_cast<size_t>(r) * K * cal_n : nullptr;
   uint32_t *dcal = AB ? a.dcal + static_cast<size_t>(r) * K * cal_n : nullptr;
   const uint32_t *lo_tab = AB ? L.live_off : nullptr;
-  uint64_t *dring_m = RR ? a.dring_m + static_cast<size_t>(r) * p.dbuf_cap : nullptr;
-  uint32_t *ddl_m = AB && RR ? a.ddl_m + static_cast<size_t>(r) * p.dbuf_cap : nullptr;
+  uint64_t *dring_m = RR ? a.dring_m + static_cast<size_t>(r) * dbuf_cap : nullptr;
+  uint32_t *ddl_m = AB && RR ? a.ddl_m + static_cast<size_t>(r) * dbuf_cap : nullptr;
   uint32_t *dcal_m = AB && RR ? a.dcal_m + static_cast<size_t>(r) * K * cal_n : nullptr;
 
   // ---- load the replication's class state and rebuild the on-chip views of the server state
@@ -478,6 +515,13 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
   for (int i = tid; i < kTallyWords; i += NT) L.tl[i] = 0;
   for (int i = tid; i < K * p.tbt_w; i += NT) L.tbth[i] = 0;
   for (int i = tid; i < SC_WORDS; i += NT) L.sc[i] = 0;
+  if (tid < kMaxK) {
+    L.gtab[GT_NX * kMaxK + tid] = tid < K ? p.nx[tid] : 0.0;
+    L.gtab[GT_INVX * kMaxK + tid] = tid < K ? p.invx[tid] : 0.0;
+    L.gtab[GT_XSTAR * kMaxK + tid] = tid < K ? p.xstar[tid] : 0.0;
+    L.gtab[GT_NQ * kMaxK + tid] = tid < K ? p.nq[tid] : 0.0;
+    L.gtab[GT_PRIO * kMaxK + tid] = tid < K ? p.prio[tid] : 0.0;
+  }
   for (int i = tid; i < 2 * kLoadBins; i += NT) L.lh[i] = 0;
   __syncthreads();
   if constexpr (AB) {   // between launches the rings hold waiting requests only
@@ -522,52 +566,52 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
   //      dropped, the others keep their order and move towards the head (a lane never writes ahead of what
   //      the wave has read). `pending`: entries already counted in the ring length but not yet written.
   auto compact_queue = [&](int k, uint32_t now, uint32_t pending) __attribute__((always_inline)) {
-    uint32_t *ring = qring + static_cast<size_t>(k) * p.queue_cap;
-    uint32_t *dlr = qdl + static_cast<size_t>(k) * p.queue_cap;
+    uint32_t *ring = qring + static_cast<size_t>(k) * queue_cap;
+    uint32_t *dlr = qdl + static_cast<size_t>(k) * queue_cap;
     const uint32_t hd = static_cast<uint32_t>(L.cs[CS_QHEAD + k]);
     uint32_t n = static_cast<uint32_t>(L.sc[SC_QLEN + k]) - pending;
-    if (n > p.queue_cap) n = p.queue_cap;   // (a ring never holds more; keeps every access inside it regardless)
+    if (n > queue_cap) n = queue_cap;   // (a ring never holds more; keeps every access inside it regardless)
     uint32_t w = 0;
     for (uint32_t off = 0; off < n; off += 64) {   // wave-uniform
       const uint32_t i = off + lane;
       uint32_t pos = hd + i;
-      if (pos >= p.queue_cap) pos -= p.queue_cap;
+      if (pos >= queue_cap) pos -= queue_cap;
       const uint32_t st = i < n ? ring[pos] : 0u, dl = i < n ? dlr[pos] : 0u;
       const bool live = i < n && dl > now;
       const uint64_t bal = __ballot(live);
       if (live) {
         uint32_t wp = hd + w + static_cast<uint32_t>(__popcll(bal & lanes_below()));
-        if (wp >= p.queue_cap) wp -= p.queue_cap;
+        if (wp >= queue_cap) wp -= queue_cap;
         ring[wp] = st; dlr[wp] = dl;
       }
       w += static_cast<uint32_t>(__popcll(bal));
     }
     if (lane == 0) {
       uint32_t tail = hd + w;
-      if (tail >= p.queue_cap) tail -= p.queue_cap;
+      if (tail >= queue_cap) tail -= queue_cap;
       L.sc[SC_QLEN + k] = static_cast<int32_t>(w + pending);
       L.sc[SC_TAIL + k] = static_cast<int32_t>(tail);
     }
   };
   // (`mixed`: the mixed group's buffer ring of the randomized router)
   auto compact_buffer = [&](uint32_t now, bool mixed) __attribute__((always_inline)) {
-    uint64_t *dring = mixed ? dring_m : a.dring + static_cast<size_t>(r) * p.dbuf_cap;
-    uint32_t *ddl = mixed ? ddl_m : a.ddl + static_cast<size_t>(r) * p.dbuf_cap;
+    uint64_t *dring = mixed ? dring_m : a.dring + static_cast<size_t>(r) * dbuf_cap;
+    uint32_t *ddl = mixed ? ddl_m : a.ddl + static_cast<size_t>(r) * dbuf_cap;
     const uint32_t hd = static_cast<uint32_t>(L.cs[mixed ? CS_DHEAD_M : CS_DHEAD]);
     uint32_t n = static_cast<uint32_t>(L.sc[mixed ? SC_DLEN_M : SC_DLEN]);
-    if (n > p.dbuf_cap) n = p.dbuf_cap;
+    if (n > dbuf_cap) n = dbuf_cap;
     uint32_t w = 0;
     for (uint32_t off = 0; off < n; off += 64) {   // wave-uniform
       const uint32_t i = off + lane;
       uint32_t pos = hd + i;
-      if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
+      if (pos >= dbuf_cap) pos -= dbuf_cap;
       const uint64_t jw = i < n ? dring[pos] : 0ull;
       const uint32_t dl = i < n ? ddl[pos] : 0u;
       const bool live = i < n && dl > now;
       const uint64_t bal = __ballot(live);
       if (live) {
         uint32_t wp = hd + w + static_cast<uint32_t>(__popcll(bal & lanes_below()));
-        if (wp >= p.dbuf_cap) wp -= p.dbuf_cap;
+        if (wp >= dbuf_cap) wp -= dbuf_cap;
         dring[wp] = jw; ddl[wp] = dl;
       }
       w += static_cast<uint32_t>(__popcll(bal));
@@ -985,14 +1029,14 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
         }
       }
       const uint32_t a = L.acc[k];
-      const uint32_t room = p.queue_cap - static_cast<uint32_t>(L.cs[CS_QP + k]);
+      const uint32_t room = queue_cap - static_cast<uint32_t>(L.cs[CS_QP + k]);
       const uint32_t take = a < room ? a : room;
       // entries between head and tail: the waiting requests, with abandonment also the dead entries
       const uint32_t in_ring = static_cast<uint32_t>(AB ? L.sc[SC_QLEN + k] : L.cs[CS_QP + k]);
       uint32_t tail = static_cast<uint32_t>(L.cs[CS_QHEAD + k]) + in_ring;
-      if (tail >= p.queue_cap) tail -= p.queue_cap;
+      if (tail >= queue_cap) tail -= queue_cap;
       if constexpr (AB) {
-        if (in_ring + take > p.queue_cap) atomicOr(&L.sc[SC_COMPACT], 1 << k);
+        if (in_ring + take > queue_cap) atomicOr(&L.sc[SC_COMPACT], 1 << k);
         L.sc[SC_QLEN + k] = static_cast<int32_t>(in_ring + take);
       }
       L.sc[SC_TAKE + k] = static_cast<int32_t>(take);
@@ -1009,11 +1053,11 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
         if constexpr (AB) {
           // a buffer ring that cannot hold this step's completions behind its dead entries is compacted first
           // (this wave has already taken the step's abandonments off the counters above)
-          const uint32_t room = p.dbuf_cap - static_cast<uint32_t>(L.cs[CS_DCOUNT]);
-          if (static_cast<uint32_t>(L.sc[SC_DLEN]) + (ncomp < room ? ncomp : room) > p.dbuf_cap) atomicOr(&L.sc[SC_COMPACT], 256);
+          const uint32_t room = dbuf_cap - static_cast<uint32_t>(L.cs[CS_DCOUNT]);
+          if (static_cast<uint32_t>(L.sc[SC_DLEN]) + (ncomp < room ? ncomp : room) > dbuf_cap) atomicOr(&L.sc[SC_COMPACT], 256);
           if constexpr (RR) {   // how the completions split between the two rings is not known yet: either may get all
-            const uint32_t room_m = p.dbuf_cap - static_cast<uint32_t>(L.cs[CS_DCOUNT_M]);
-            if (static_cast<uint32_t>(L.sc[SC_DLEN_M]) + (ncomp < room_m ? ncomp : room_m) > p.dbuf_cap) atomicOr(&L.sc[SC_COMPACT], 512);
+            const uint32_t room_m = dbuf_cap - static_cast<uint32_t>(L.cs[CS_DCOUNT_M]);
+            if (static_cast<uint32_t>(L.sc[SC_DLEN_M]) + (ncomp < room_m ? ncomp : room_m) > dbuf_cap) atomicOr(&L.sc[SC_COMPACT], 512);
           }
         }
       }
@@ -1040,8 +1084,8 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
       const uint32_t take = static_cast<uint32_t>(L.sc[SC_TAKE + k]), tail = static_cast<uint32_t>(L.sc[SC_TAIL + k]);
       for (uint32_t j = tid; j < take; j += NT) {
         uint32_t pos = tail + j;
-        if (pos >= p.queue_cap) pos -= p.queue_cap;
-        qring[static_cast<size_t>(k) * p.queue_cap + pos] = s;
+        if (pos >= queue_cap) pos -= queue_cap;
+        qring[static_cast<size_t>(k) * queue_cap + pos] = s;
         if constexpr (AB) {
           // the accepted arrivals of a class are exchangeable: the j-th of this step draws its patience
           uint32_t dl = kNever;
@@ -1051,7 +1095,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
             dl = s + a.pat_tab[static_cast<size_t>(k) * kTableSize + (w[0] >> 16)];
             atomicAdd(&cal[static_cast<size_t>(k) * cal_n + (dl & p.cal_mask)], 1u);
           }
-          qdl[static_cast<size_t>(k) * p.queue_cap + pos] = dl;
+          qdl[static_cast<size_t>(k) * queue_cap + pos] = dl;
         }
       }
     }
@@ -1088,10 +1132,10 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           const uint64_t bal0 = __ballot(active && solo), bal1 = __ballot(active && !solo);
           const uint32_t idx = solo ? seen0 + static_cast<uint32_t>(__popcll(bal0 & lanes_below()))
                                     : seen1 + static_cast<uint32_t>(__popcll(bal1 & lanes_below()));
-          const bool kept = active && (solo ? dc0 : dc1) + idx < p.dbuf_cap;
+          const bool kept = active && (solo ? dc0 : dc1) + idx < dbuf_cap;
           if (kept) {
             uint32_t pos = (solo ? dh0 + fill0 : dh1 + fill1) + idx;
-            if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
+            if (pos >= dbuf_cap) pos -= dbuf_cap;
             (solo ? dring : dring_m)[pos] = jw;
             if constexpr (AB) {
               (solo ? ddl : ddl_m)[pos] = dl;
@@ -1110,7 +1154,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           seen1 += static_cast<uint32_t>(__popcll(bal1));
         }
         if (lane == 0) {   // what each ring accepted (a prefix of what it was sent)
-          const uint32_t room0 = p.dbuf_cap - dc0, room1 = p.dbuf_cap - dc1;
+          const uint32_t room0 = dbuf_cap - dc0, room1 = dbuf_cap - dc1;
           L.sc[SC_NCS] = static_cast<int32_t>(seen0 < room0 ? seen0 : room0);
           L.sc[SC_NCM] = static_cast<int32_t>(seen1 < room1 ? seen1 : room1);
         }
@@ -1129,10 +1173,10 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           const int g = select_bit(L.bm_comp, L.pre_c, nwords_m, j);
           const uint64_t jw = pf_job[g];
           k = static_cast<int>(jw >> 29) & 7;
-          kept = dcount + j < p.dbuf_cap;
+          kept = dcount + j < dbuf_cap;
           if (kept) {
             uint32_t pos = dhead + dfill + j;
-            if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
+            if (pos >= dbuf_cap) pos -= dbuf_cap;
             dring[pos] = jw;
             if constexpr (AB) {   // patience for the wait in the decode buffer
               uint32_t dl = kNever;
@@ -1176,7 +1220,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
       const int dcount0 = L.cs[CS_DCOUNT];
       int jrem, next = 0;
       {
-        const int ncp = L.sc[SC_NCOMP], room = static_cast<int>(p.dbuf_cap) - dcount0;
+        const int ncp = L.sc[SC_NCOMP], room = static_cast<int>(dbuf_cap) - dcount0;
         jrem = dcount0 + (ncp < room ? ncp : room);
       }
       const uint32_t dhead0 = static_cast<uint32_t>(L.cs[CS_DHEAD]);
@@ -1190,9 +1234,9 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
       }
       // abandonment only: ring entries of the decode buffer, this step's completions included
       uint32_t dlen_all = AB ? static_cast<uint32_t>(L.sc[SC_DLEN]) + static_cast<uint32_t>(RR ? L.sc[SC_NCS] : jrem - dcount0) : 0u;
-      if (dlen_all > p.dbuf_cap) dlen_all = p.dbuf_cap;   // (never more: the ring was compacted if it had to be)
+      if (dlen_all > dbuf_cap) dlen_all = dbuf_cap;   // (never more: the ring was compacted if it had to be)
       uint32_t dlen_all_m = AB && RR ? static_cast<uint32_t>(L.sc[SC_DLEN_M]) + static_cast<uint32_t>(L.sc[SC_NCM]) : 0u;
-      if (dlen_all_m > p.dbuf_cap) dlen_all_m = p.dbuf_cap;
+      if (dlen_all_m > dbuf_cap) dlen_all_m = dbuf_cap;
       if constexpr (AB) {
         if (tid == 0) {
           L.sc[SC_DSCAN] = 0;
@@ -1208,7 +1252,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           }
           __syncthreads();
         }
-        if ((AB || p.gate_mode == SIM_GATE_FCFS) && pass == 0) __syncthreads();   // ring entries written above are read below
+        if ((AB || gate_mode == SIM_GATE_FCFS) && pass == 0) __syncthreads();   // ring entries written above are read below
 
         // ---------------- segment A ----------------
         int nadm = 0, nidle = 0;
@@ -1217,13 +1261,14 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           const int limit = nidle < kAdmChunk ? nidle : kAdmChunk;
           int cnt[kMaxK], qp[kMaxK], xs[kMaxK], ncand = 0;
           uint32_t head[kMaxK];
+          const int cs_lane = L.cs[lane];   // the class state, one word per lane: one trip to LDS
 #pragma unroll
           for (int k = 0; k < kMaxK; ++k) {
             // wave-uniform values, kept in scalar registers
-            qp[k] = k < K ? __builtin_amdgcn_readfirstlane(L.cs[CS_QP + k]) : 0;
-            xs[k] = k < K ? __builtin_amdgcn_readfirstlane(L.cs[CS_X + k]) : 0;
-            head[k] = k < K ? static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(L.cs[CS_QHEAD + k])) : 0u;
-            const bool eligible = k < K && qp[k] > 0 && (p.gate_mode != SIM_GATE_OCCUPANCY || p.invx[k] > 0.0);
+            qp[k] = k < K ? __builtin_amdgcn_readlane(cs_lane, CS_QP + k) : 0;
+            xs[k] = k < K ? __builtin_amdgcn_readlane(cs_lane, CS_X + k) : 0;
+            head[k] = k < K ? static_cast<uint32_t>(__builtin_amdgcn_readlane(cs_lane, CS_QHEAD + k)) : 0u;
+            const bool eligible = k < K && qp[k] > 0 && (gate_mode != SIM_GATE_OCCUPANCY || L.gtab[GT_INVX * kMaxK + k] > 0.0);
             cnt[k] = eligible ? (qp[k] < limit ? qp[k] : limit) : 0;
             ncand += cnt[k];
           }
@@ -1237,9 +1282,9 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
               for (int kk = 0; kk < kMaxK; ++kk)
                 if (kk == k) need = static_cast<uint32_t>(cnt[kk]);
               uint32_t qlen = static_cast<uint32_t>(L.sc[SC_QLEN + k]);
-              if (qlen > p.queue_cap) qlen = p.queue_cap;
+              if (qlen > queue_cap) qlen = queue_cap;
               const uint32_t hd = static_cast<uint32_t>(L.cs[CS_QHEAD + k]);
-              const uint32_t *dlr = qdl + static_cast<size_t>(k) * p.queue_cap;
+              const uint32_t *dlr = qdl + static_cast<size_t>(k) * queue_cap;
               uint32_t found = 0;
               // four chunks of 64 entries per round: their deadlines are loaded together, one trip to memory
               for (uint32_t off = 0; off < qlen && found < need; off += 256) {   // wave-uniform
@@ -1248,7 +1293,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
                 for (int u = 0; u < 4; ++u) {
                   const uint32_t i = off + 64u * u + lane;
                   uint32_t pos = hd + i;
-                  if (pos >= p.queue_cap) pos -= p.queue_cap;
+                  if (pos >= queue_cap) pos -= queue_cap;
                   dl4[u] = i < qlen ? dlr[pos] : 0u;   // (beyond the ring: counts as dead)
                 }
 #pragma unroll
@@ -1268,7 +1313,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
             }
             // only the FCFS gate reads the offsets while it ranks the candidates; the other gates first use them
             // after the barrier that ends this segment
-            if (p.gate_mode == SIM_GATE_FCFS) __syncthreads();
+            if (gate_mode == SIM_GATE_FCFS) __syncthreads();
           }
           // The admissions take the first nadm idle prefill slots, whatever their order: the slot bitmaps are
           // updated here a word at a time (no atomics).
@@ -1297,33 +1342,35 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
 #pragma unroll
             for (int kk = 0; kk < kMaxK - 1; ++kk)
               if (k == kk && m >= cnt[kk]) { m -= cnt[kk]; k = kk + 1; }
-            GateKey key = {0.0, 0.0};
-#pragma unroll
-            for (int kk = 0; kk < kMaxK; ++kk)
-              if (k == kk) key = gate_key(p, qring, lo_tab, xs, qp, head, kk, m);
+            // this candidate's own key: its class's targets and counters, fetched by class (one trip to LDS)
+            const ClassTargets own = load_targets(L.gtab, k);
+            const int xs_own = L.cs[CS_X + k], qp_own = L.cs[CS_QP + k];
+            const uint32_t head_own = static_cast<uint32_t>(L.cs[CS_QHEAD + k]);
+            const GateKey key = gate_key(gate_mode, queue_cap, own, qring, lo_tab, xs_own, qp_own, head_own, k, m);
             int rank = m;
 #pragma unroll
             for (int k2 = 0; k2 < kMaxK; ++k2) {
               if (k2 == k || cnt[k2] == 0 || rank >= nadm) continue;
               // number of candidates of class k2 that sort before this one: they form a prefix of the class
+              const ClassTargets t2 = load_targets(L.gtab, k2);
               int lo = 0, hi = cnt[k2];
-              if (p.gate_mode == SIM_GATE_OCCUPANCY) {
+              if (gate_mode == SIM_GATE_OCCUPANCY) {
                 // the key is linear in the sequence number: bracket the crossing next to its estimate with two
                 // exact comparisons, so the search below runs over a few candidates only (or, if the
                 // estimate is off, over the side the comparisons point to)
-                const double est = key.a * p.xstar[k2] - (static_cast<double>(xs[k2]) - p.nx[k2]);
+                const double est = key.a * t2.xstar - (static_cast<double>(xs[k2]) - t2.nx);
                 const int g0 = est > 0.0 ? (est < static_cast<double>(hi) ? static_cast<int>(est) : hi) : 0;
                 const int l2 = g0 > 1 ? g0 - 1 : 0, h2 = g0 + 2 < hi ? g0 + 2 : hi;
                 if (l2 > 0) {
-                  if (gate_before(gate_key(p, qring, lo_tab, xs, qp, head, k2, l2 - 1), k2, key, k)) lo = l2; else hi = l2 - 1;
+                  if (gate_before(gate_key(gate_mode, queue_cap, t2, qring, lo_tab, xs[k2], qp[k2], head[k2], k2, l2 - 1), k2, key, k)) lo = l2; else hi = l2 - 1;
                 }
                 if (h2 < hi) {
-                  if (gate_before(gate_key(p, qring, lo_tab, xs, qp, head, k2, h2), k2, key, k)) lo = h2 + 1; else hi = h2;
+                  if (gate_before(gate_key(gate_mode, queue_cap, t2, qring, lo_tab, xs[k2], qp[k2], head[k2], k2, h2), k2, key, k)) lo = h2 + 1; else hi = h2;
                 }
               }
               while (lo < hi) {
                 const int mid = (lo + hi) >> 1;
-                if (gate_before(gate_key(p, qring, lo_tab, xs, qp, head, k2, mid), k2, key, k)) lo = mid + 1; else hi = mid;
+                if (gate_before(gate_key(gate_mode, queue_cap, t2, qring, lo_tab, xs[k2], qp[k2], head[k2], k2, mid), k2, key, k)) lo = mid + 1; else hi = mid;
               }
               rank += lo;
             }
@@ -1351,6 +1398,26 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           // (with abandonment a pass places no more jobs than are staged in LDS)
           const int jpass = AB && jrem > kJobsLds ? kJobsLds : jrem;
           int rem_jobs = jpass;
+          // The load histograms of both groups (servers per decode count below the cap) are read once, one bin per
+          // lane and register; the lowest non-empty level and the counts of the levels above it then come from
+          // ballots and lane reads instead of a chain of LDS round trips.
+          uint32_t hv[2][2];
+#pragma unroll
+          for (int gi = 0; gi < 2; ++gi) {
+            hv[gi][0] = L.lh[gi * kLoadBins + lane];
+            hv[gi][1] = L.lh[gi * kLoadBins + 64 + lane];
+          }
+          auto lowest_level = [&](int gi, int capg) __attribute__((always_inline)) -> int {
+            const uint64_t nz0 = __ballot(lane < capg && hv[gi][0] != 0);
+            if (nz0) return __ffsll(static_cast<long long>(nz0)) - 1;
+            const uint64_t nz1 = __ballot(64 + lane < capg && hv[gi][1] != 0);
+            return nz1 ? 63 + __ffsll(static_cast<long long>(nz1)) : -1;
+          };
+          auto level_count = [&](int gi, int level) __attribute__((always_inline)) -> uint32_t {   // level: wave-uniform, below 128
+            const int lo = __builtin_amdgcn_readlane(static_cast<int>(hv[gi][0]), level & 63);
+            const int hi = __builtin_amdgcn_readlane(static_cast<int>(hv[gi][1]), level & 63);
+            return static_cast<uint32_t>(level < 64 ? lo : hi);
+          };
           if constexpr (RR) {
             // each group takes jobs from its own ring; the pass's list holds the solo ring's jobs first and is
             // never longer than what is staged in LDS
@@ -1363,16 +1430,11 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
               int rem_g = jremL[gi] < kJobsLds - listed ? jremL[gi] : kJobsLds - listed;
               const int start_g = rem_g;
               if (glo >= ghi || nl >= kRouteLevels || rem_g <= 0 || (gi == 1 && gate_unfinished)) continue;   // wave-uniform
-              int lm = -1;
-              for (int base = 0; base < capg && lm < 0; base += 64) {
-                const int l = base + lane;
-                const uint64_t nz = __ballot(l < capg && L.lh[gi * kLoadBins + l] != 0);
-                if (nz) lm = base + __ffsll(static_cast<long long>(nz)) - 1;
-              }
+              const int lm = lowest_level(gi, capg);
               if (lm < 0) continue;   // no free slot in this group
               lminG[gi] = lm;
               for (int u = 0; nl < kRouteLevels && rem_g > 0 && lm + u < capg; ++u) {
-                csumG[gi] += static_cast<int>(L.lh[gi * kLoadBins + lm + u]);
+                csumG[gi] += static_cast<int>(level_count(gi, lm + u));
                 const int tk = csumG[gi] < rem_g ? csumG[gi] : rem_g;
                 if (lane == 0) { L.sc[SC_TAKE_T + nl] = tk; L.sc[SC_W_T + nl] = listed + (start_g - rem_g); }
                 rem_g -= tk;
@@ -1390,16 +1452,11 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
             const int glo = gi == 0 ? M : 0, ghi = gi == 0 ? N : M;
             const int capg = gi == 0 ? B : B - 1;
             if (glo >= ghi || nl >= kRouteLevels || rem_jobs <= 0 || (gi == 1 && gate_unfinished)) continue;   // wave-uniform
-            int lm = -1;
-            for (int base = 0; base < capg && lm < 0; base += 64) {
-              const int l = base + lane;
-              const uint64_t nz = __ballot(l < capg && L.lh[gi * kLoadBins + l] != 0);
-              if (nz) lm = base + __ffsll(static_cast<long long>(nz)) - 1;
-            }
+            const int lm = lowest_level(gi, capg);
             if (lm < 0) continue;   // no free slot in this group
             lminG[gi] = lm;
             for (int u = 0; nl < kRouteLevels && rem_jobs > 0 && lm + u < capg; ++u) {
-              csumG[gi] += static_cast<int>(L.lh[gi * kLoadBins + lm + u]);
+              csumG[gi] += static_cast<int>(level_count(gi, lm + u));
               const int tk = csumG[gi] < rem_jobs ? csumG[gi] : rem_jobs;
               if (lane == 0) { L.sc[SC_TAKE_T + nl] = tk; L.sc[SC_W_T + nl] = jpass - rem_jobs; }
               rem_jobs -= tk;
@@ -1466,10 +1523,10 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
               const uint32_t e = L.adm[j];
               k = static_cast<int>(e & 7u);
               uint32_t pos = static_cast<uint32_t>(L.cs[CS_QHEAD + k]) + (AB ? L.live_off[k * kAdmChunk + (e >> 3)] : (e >> 3));
-              if (pos >= p.queue_cap) pos -= p.queue_cap;
-              const uint32_t stamp = qring[static_cast<size_t>(k) * p.queue_cap + pos];
+              if (pos >= queue_cap) pos -= queue_cap;
+              const uint32_t stamp = qring[static_cast<size_t>(k) * queue_cap + pos];
               if constexpr (AB) {   // the request no longer waits: it leaves the calendar of its deadline
-                const uint32_t dl = qdl[static_cast<size_t>(k) * p.queue_cap + pos];
+                const uint32_t dl = qdl[static_cast<size_t>(k) * queue_cap + pos];
                 if (dl != kNever) atomicSub(&cal[static_cast<size_t>(k) * cal_n + (dl & p.cal_mask)], 1u);
               }
               if (L.loads[g]) nc = n_cls[g];
@@ -1502,7 +1559,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           }
           if (nadm == kAdmChunk && nidle > kAdmChunk) {   // rare: more idle slots than one pass serves
             for (int k = 0; k < K; ++k) {
-              const bool eligible = p.gate_mode != SIM_GATE_OCCUPANCY || p.invx[k] > 0.0;
+              const bool eligible = gate_mode != SIM_GATE_OCCUPANCY || L.gtab[GT_INVX * kMaxK + k] > 0.0;
               if (eligible && L.cs[CS_QP + k] - L.sc[SC_ADMK + k] > 0) gate_more = true;
             }
           }
@@ -1523,7 +1580,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
                 for (int u = 0; u < 4; ++u) {
                   const uint32_t i = off + 64u * u + lane;
                   uint32_t pos = hd + i;
-                  if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
+                  if (pos >= dbuf_cap) pos -= dbuf_cap;
                   dl4[u] = i < len ? dlr[pos] : 0u;   // (beyond the ring: counts as dead)
                   jw4[u] = i < len ? ring[pos] : 0ull;
                 }
@@ -1674,7 +1731,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
                 for (int u = 0; u < 4; ++u) {
                   const uint32_t i = off + 64u * u + lane;
                   uint32_t pos = hd + i;
-                  if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
+                  if (pos >= dbuf_cap) pos -= dbuf_cap;
                   pos4[u] = pos;
                   dl4[u] = i < len ? dlr[pos] : 0u;   // (beyond the ring: counts as gone)
                   jw4[u] = i < len ? ring[pos] : 0ull;
@@ -1749,15 +1806,15 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
             for (int j = tid; j < nstage; j += NT) {
               const int li = j < takenL[0] ? 0 : 1;
               uint32_t pos = dheadL[li] + static_cast<uint32_t>(nextL[li] + (li ? j - takenL[0] : j));
-              if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
-              if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
+              if (pos >= dbuf_cap) pos -= dbuf_cap;
+              if (pos >= dbuf_cap) pos -= dbuf_cap;
               L.jobs[j] = (li ? dring_m : dring)[pos];
             }
           } else {
           for (int j = tid; j < nstage; j += NT) {
             uint32_t pos = dhead0 + static_cast<uint32_t>(next + j);
-            if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
-            if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
+            if (pos >= dbuf_cap) pos -= dbuf_cap;
+            if (pos >= dbuf_cap) pos -= dbuf_cap;
             L.jobs[j] = dring[pos];
           }
           }
@@ -1788,14 +1845,14 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
               L.sc[SC_QLEN + k] -= static_cast<int32_t>(past);
               if (!adm_k) {
                 uint32_t h = static_cast<uint32_t>(L.cs[CS_QHEAD + k]) + past;
-                if (h >= p.queue_cap) h -= p.queue_cap;
+                if (h >= queue_cap) h -= queue_cap;
                 L.cs[CS_QHEAD + k] = static_cast<int32_t>(h);
               }
             }
           }
           if (adm_k) {
             uint32_t h = static_cast<uint32_t>(L.cs[CS_QHEAD + k]) + past;
-            if (h >= p.queue_cap) h -= p.queue_cap;
+            if (h >= queue_cap) h -= queue_cap;
             L.cs[CS_QHEAD + k] = static_cast<int32_t>(h);
             L.cs[CS_QP + k] -= adm_k;
             L.cs[CS_X + k] += adm_k;
@@ -1850,8 +1907,8 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
                       jw = L.jobs[j];
                     } else {
                       uint32_t pos = dhead0 + static_cast<uint32_t>(next + j);
-                      if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
-                      if (pos >= p.dbuf_cap) pos -= p.dbuf_cap;
+                      if (pos >= dbuf_cap) pos -= dbuf_cap;
+                      if (pos >= dbuf_cap) pos -= dbuf_cap;
                       jw = dring[pos];
                     }
                     const int k = static_cast<int>(jw >> 29) & 7;
@@ -1906,14 +1963,14 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
         if (tid == 0) {   // the head moves past everything the routing passes walked over
           const uint32_t past = static_cast<uint32_t>(L.sc[SC_DSCAN]);
           uint32_t h = dhead0 + past;
-          if (h >= p.dbuf_cap) h -= p.dbuf_cap;
+          if (h >= dbuf_cap) h -= dbuf_cap;
           L.cs[CS_DHEAD] = static_cast<int32_t>(h);
           L.cs[CS_DCOUNT] -= RR ? nextL[0] : next;
           L.sc[SC_DLEN] = static_cast<int32_t>(dlen_all - past);
           if constexpr (RR) {
             const uint32_t past_m = static_cast<uint32_t>(L.sc[SC_DSCAN_M]);
             h = dheadL[1] + past_m;
-            if (h >= p.dbuf_cap) h -= p.dbuf_cap;
+            if (h >= dbuf_cap) h -= dbuf_cap;
             L.cs[CS_DHEAD_M] = static_cast<int32_t>(h);
             L.cs[CS_DCOUNT_M] -= nextL[1];
             L.sc[SC_DLEN_M] = static_cast<int32_t>(dlen_all_m - past_m);
@@ -1923,18 +1980,18 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
       } else if constexpr (RR) {
         if (tid == 0 && next > 0) {
           uint32_t h = dheadL[0] + static_cast<uint32_t>(nextL[0]);
-          if (h >= p.dbuf_cap) h -= p.dbuf_cap;
+          if (h >= dbuf_cap) h -= dbuf_cap;
           L.cs[CS_DHEAD] = static_cast<int32_t>(h);
           L.cs[CS_DCOUNT] -= nextL[0];
           h = dheadL[1] + static_cast<uint32_t>(nextL[1]);
-          if (h >= p.dbuf_cap) h -= p.dbuf_cap;
+          if (h >= dbuf_cap) h -= dbuf_cap;
           L.cs[CS_DHEAD_M] = static_cast<int32_t>(h);
           L.cs[CS_DCOUNT_M] -= nextL[1];
         }
       } else {
       if (tid == 0 && next > 0) {
         uint32_t h = dhead0 + static_cast<uint32_t>(next);
-        if (h >= p.dbuf_cap) h -= p.dbuf_cap;
+        if (h >= dbuf_cap) h -= dbuf_cap;
         L.cs[CS_DHEAD] = static_cast<int32_t>(h);
         L.cs[CS_DCOUNT] -= next;
       }

@@ -258,18 +258,26 @@ def test_degenerate_runs(B, oracle_mod):
 
 
 def test_maximum_sizes(B, oracle_mod):
-    """The documented limits: the most servers a replication of this shape may have (11696 with 1500 mixed ones:
-    the on-chip records fill a compute unit's LDS to the last few bytes) and one more refused, the largest chunk
-    (8191 tokens) with the longest prompts and outputs the tables hold (32768 tokens)."""
+    """The documented limits: the most servers a replication of this shape may have (with 1500 mixed ones: found here
+    on the host as the largest N whose on-chip records fit a compute unit's LDS, more than 11500) and one more
+    refused, the largest chunk (8191 tokens) with the longest prompts and outputs the tables hold (32768 tokens)."""
     from paper_2602_02987_amd.binding import TALLY
     ti = {n: i for i, n in enumerate(TALLY)}
     cls = [_limits_class(lam=2.0, in_p0=300.0, out_p0=40.0), _limits_class(lam=1.5, in_p0=90.0, out_p0=15.0)]
-    cfg = _limits_cfg("most-servers", cls, N=11696, M=1500, B=8, steps=120, replications=1, queue_cap=8192)
+    shape = lambda n: _limits_cfg("most-servers", cls, N=n, M=1500, B=8, steps=120, replications=1, queue_cap=8192)  # noqa: E731
+    lo, hi = 8000, 12288                       # fits / does not fit
+    while hi - lo > 1:
+        mid = (lo + hi) // 2
+        need, limit = B.sim_onchip_bytes(shape(mid))
+        lo, hi = (mid, hi) if need <= limit else (lo, mid)
+    n_max = lo
+    assert n_max > 11500
+    cfg = shape(n_max)
     need, limit = B.sim_onchip_bytes(cfg)
     assert limit - 64 < need <= limit
     sim, orc = run_both(B, oracle_mod, cfg, 120, checkpoints=2)
     assert orc.tallies(0)[0][:, ti["S_DS"]].sum() > 1000
-    for n_bad in (11697, 12289):
+    for n_bad in (n_max + 1, 12289):
         with pytest.raises(B.SimError):
             B.Sim(_limits_cfg("too-many-servers", cls, N=n_bad, M=1500, B=8, steps=1))
     # every prompt 32768 tokens long, prefilled in chunks of 8191 + 8191 + 8191 + 8191 + 4; outputs of the same length
