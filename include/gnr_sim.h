@@ -192,6 +192,18 @@ int sim_workspace_bytes(const sim_config *cfg, int max_replications, size_t *out
  * with the same device current (SIM_EINVAL otherwise). */
 int sim_create(const sim_config *cfg, int max_replications, void *dev_workspace, size_t bytes, sim_t **out);
 
+/* sim_create for callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): the workspace is a device array inside the library, SIM_STATIC_WORKSPACE_BYTES
+ * large, that each GPU the library runs on holds until the process ends. Nothing is allocated: no hipMalloc,
+ * no hipFree, on no path. Arguments, checks and results are those of sim_create; SIM_ENOMEM when
+ * sim_workspace_bytes(cfg, max_replications) exceeds SIM_STATIC_WORKSPACE_BYTES. The handle is used and destroyed
+ * like any other (sim_run, sim_stats, the read-outs, sim_destroy). Every handle made by this call on one GPU shares
+ * that GPU's array, which keeps whatever the last one left: the call rewrites the tables and the first sim_run
+ * clears the state, so handles used one after the other are independent, but two that are alive on one GPU at the
+ * same time overwrite each other, and calls on them that overlap race. */
+#define SIM_STATIC_WORKSPACE_BYTES (32u << 20)
+int sim_create_static(const sim_config *cfg, int max_replications, sim_t **out);
+
 /* Advances `replications` replications by `steps` steps, asynchronously on `hip_stream`
  * (a hipStream_t, NULL = default stream). Repeating the same (replications, seed) resumes; another
  * pair restarts from the empty system. Results depend only on (config, replications, seed, total

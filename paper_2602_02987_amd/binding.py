@@ -82,6 +82,7 @@ def lib():
         L.sim_onchip_bytes.argtypes = [C.c_void_p, C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
         L.sim_launch_shape.argtypes = [C.c_void_p, C.POINTER(C.c_int), C.POINTER(C.c_size_t)]
         L.sim_create.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.POINTER(C.c_void_p)]
+        L.sim_create_static.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_void_p)]
         L.sim_run.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_uint64, C.c_void_p]
         L.sim_stats.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         L.sim_snapshot.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
@@ -204,7 +205,9 @@ def _stats_dict(st):
 class Sim:
     """sim_create / sim_run / sim_stats on the current CUDA(HIP) device and stream."""
 
-    def __init__(self, cfg, max_replications=None, device="cuda:0"):
+    def __init__(self, cfg, max_replications=None, device="cuda:0", static_workspace=False):
+        """`static_workspace`: use the library's own static device array (sim_create_static: nothing is allocated,
+        configurations up to 32 MiB of state) instead of a torch tensor."""
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("the simulator needs a GPU: no HIP device is visible")
@@ -217,10 +220,14 @@ class Sim:
         _check(lib().sim_workspace_bytes(C.byref(cc), self.max_reps, C.byref(nbytes)), "sim_workspace_bytes")
         self.workspace_bytes = nbytes.value
         with torch.cuda.device(self.device):
-            self.workspace = torch.empty(nbytes.value + 256, dtype=torch.uint8, device=self.device)
-            ptr = (self.workspace.data_ptr() + 255) & ~255
             h = C.c_void_p()
-            _check(lib().sim_create(C.byref(cc), self.max_reps, C.c_void_p(ptr), nbytes.value, C.byref(h)), "sim_create")
+            if static_workspace:
+                self.workspace = None
+                _check(lib().sim_create_static(C.byref(cc), self.max_reps, C.byref(h)), "sim_create_static")
+            else:
+                self.workspace = torch.empty(nbytes.value + 256, dtype=torch.uint8, device=self.device)
+                ptr = (self.workspace.data_ptr() + 255) & ~255
+                _check(lib().sim_create(C.byref(cc), self.max_reps, C.c_void_p(ptr), nbytes.value, C.byref(h)), "sim_create")
         self.h = h
 
     def _stream(self):

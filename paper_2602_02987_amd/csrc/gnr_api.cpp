@@ -243,6 +243,10 @@ double percentile(const uint64_t *hist, int pct)
 
 }  // namespace
 
+namespace {
+int create_in(const sim_config *cfg, int max_replications, void *dev_workspace, size_t bytes, sim_t **out);
+}
+
 extern "C" {
 
 int sim_workspace_bytes(const sim_config *cfg, int max_replications, size_t *out_bytes)
@@ -264,6 +268,23 @@ int sim_workspace_bytes(const sim_config *cfg, int max_replications, size_t *out
 }
 
 int sim_create(const sim_config *cfg, int max_replications, void *dev_workspace, size_t bytes, sim_t **out)
+{
+  return create_in(cfg, max_replications, dev_workspace, bytes, out);
+}
+
+int sim_create_static(const sim_config *cfg, int max_replications, sim_t **out)
+{
+  void *ws = nullptr;
+  size_t bytes = 0;
+  const int rc = static_workspace(&ws, &bytes);   // no allocation: the address of the library's own device array
+  if (rc != SIM_OK) return rc;
+  return create_in(cfg, max_replications, ws, bytes, out);
+}
+
+}  // extern "C"
+
+namespace {
+int create_in(const sim_config *cfg, int max_replications, void *dev_workspace, size_t bytes, sim_t **out)
 {
   try {
     Ticks t;
@@ -397,6 +418,10 @@ int sim_create(const sim_config *cfg, int max_replications, void *dev_workspace,
     return SIM_ENOMEM;
   }
 }
+
+}  // namespace
+
+extern "C" {
 
 int sim_run(sim_t *h, int64_t steps, int replications, uint64_t seed, void *hip_stream)
 {
@@ -725,7 +750,7 @@ const char *sim_strerror(int err)
   switch (err) {
     case SIM_OK: return "ok";
     case SIM_EINVAL: return "invalid argument or configuration";
-    case SIM_ENOMEM: return "workspace too small or out of host memory";
+    case SIM_ENOMEM: return "workspace too small (the static workspace holds 32 MiB) or out of host memory";
     case SIM_EHIP: return "HIP runtime error";
     case SIM_EOVERFLOW: return "a prefill queue or the decode buffer overflowed; requests were dropped";
     default: return "unknown error";

@@ -109,6 +109,8 @@ int launch_steps(const Params &p, int reps, int threads, size_t lds_bytes, uint3
                  void *stream);
 int launch_reduce(const Params &p, int reps, void *stream);
 int launch_digest(const Params &p, int reps, void *stream);
+// the library's static device workspace on the current device (address resolved once per device)
+int static_workspace(void **dev_ptr, size_t *bytes);
 size_t step_lds_bytes(const Params &p);
 int step_threads(int N);
 

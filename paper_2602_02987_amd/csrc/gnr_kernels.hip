@@ -1,6 +1,8 @@
 // Small kernels of the simulator (reset, totals over replications, state digest) and the launchers (gfx950).
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "gnr_step.h"
 
 namespace gnr {
@@ -152,6 +154,30 @@ __global__ void gnr_digest_kernel(const Params p)
   atomicAdd(&total, static_cast<unsigned long long>(d));
   __syncthreads();
   if (tid == 0) p.digest[r] = total;
+}
+
+// ------------------------------------------------------------------ static workspace ----
+// Device memory for handles whose caller cannot allocate any (sim_create_static). In host code the array's name
+// is only a stand-in for the symbol: its address on a device comes from hipGetSymbolAddress, asked once per device
+// with that device current, and that pointer is what the kernels are given.
+static __device__ __align__(256) unsigned char scratch[SIM_STATIC_WORKSPACE_BYTES];
+
+int static_workspace(void **dev_ptr, size_t *bytes)
+{
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static void *resolved[kMaxDevices] = {};
+  int d = -1;
+  if (hipGetDevice(&d) != hipSuccess || d < 0 || d >= kMaxDevices) return SIM_EHIP;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!resolved[d]) {
+    void *ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return SIM_EHIP;
+    resolved[d] = ptr;
+  }
+  *dev_ptr = resolved[d];
+  *bytes = sizeof(scratch);
+  return SIM_OK;
 }
 
 // ------------------------------------------------------------------ launchers ----
