@@ -10,8 +10,11 @@ namespace gnr {
 size_t step_lds_bytes(const Params &p)
 {
   size_t total = 0;
-  if (static_words(p.threads)) lds_carve<static_words(1024)>(p, nullptr, &total);
-  else lds_carve<0>(p, nullptr, &total);
+  switch (size_class(p.threads, p.nwords)) {
+    case 0: lds_carve<static_words(0)>(p, nullptr, &total); break;
+    case 1: lds_carve<static_words(1)>(p, nullptr, &total); break;
+    default: lds_carve<static_words(2)>(p, nullptr, &total); break;
+  }
   return total;
 }
 
@@ -201,7 +204,7 @@ int launch_reset(const Params &p, int reps, void *stream)
 int launch_steps(const Params &p, int reps, int threads, size_t lds_bytes, uint32_t step_begin, uint32_t n_steps,
                  void *stream)
 {
-  const int size = threads > 768 ? 2 : threads > 512 ? 1 : 0;
+  const int size = size_class(threads, p.nwords);
   const bool ab = p.dl_rings != 0;
   StepKernel kernel = nullptr;
   switch (p.route_mode) {

@@ -184,7 +184,8 @@ struct Lds {
 // ones and those behind them then sits at an offset the compiler knows (an immediate in the LDS instruction)
 // instead of one it has to keep in a register, or to spill and fetch back, at every access. Used for the
 // workgroups of sixteen waves (N up to 64 NWS servers). NWS = 0: everything sized by the configuration.
-constexpr int kStaticWords = kMaxN / 64;
+constexpr int kStaticWordsLarge = kMaxN / 64;   // any N the library accepts
+constexpr int kStaticWordsMedium = 160;          // N up to 10240: three kilobytes less
 template <int NWS>
 __host__ __device__ __forceinline__ Lds lds_carve(const Params &p, unsigned char *base, size_t *total)
 {
@@ -233,8 +234,16 @@ __host__ __device__ __forceinline__ Lds lds_carve(const Params &p, unsigned char
   if (total) *total = off;
   return L;
 }
-// Words the word-indexed arrays are sized for, by workgroup size.
-__host__ __device__ constexpr int static_words(int threads) { return threads > 768 ? kStaticWords : 0; }
+// Size classes of the step kernel: 0 workgroups of up to 512 threads (arrays sized by the configuration),
+// 1 and 2 sixteen waves with the word-indexed arrays sized for 160 words and for the largest N.
+__host__ __device__ constexpr int size_class(int threads, int nwords)
+{
+  return threads <= 512 ? 0 : (nwords <= kStaticWordsMedium ? 1 : 2);
+}
+__host__ __device__ constexpr int static_words(int size_class)
+{
+  return size_class == 0 ? 0 : (size_class == 1 ? kStaticWordsMedium : kStaticWordsLarge);
+}
 
 // Bits of bitmap word w that belong to servers below `nbits`.
 __device__ __forceinline__ uint64_t bits_below(int w, int nbits)
@@ -440,14 +449,14 @@ struct StepArrays {
 // IM: the variant with immediate same-slot decode (no router): a request whose prefill ends goes on decoding on
 // its own server, placed there by the lane that finishes the server; a server is offered to the gate while it
 // holds no prefill and fewer than B decodes.
-template <int MAXT, bool AB, bool RR, bool IM, bool WS = false>
+template <int MAXT, int NWS, bool AB, bool RR, bool IM, bool WS = false>
 __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict__ params, const StepArrays a,
                                                         const uint32_t key0, const uint32_t key1,
                                                         const uint32_t step_begin, const uint32_t n_steps)
 {
   const Params &p = *params;   // immutable after creation; read through the scalar cache on demand
   extern __shared__ __align__(16) unsigned char lds_raw[];
-  const Lds L = lds_carve<static_words(MAXT)>(p, lds_raw, nullptr);
+  const Lds L = lds_carve<NWS>(p, lds_raw, nullptr);
 
   const int r = blockIdx.x;
   const int tid = threadIdx.x;
@@ -2064,14 +2073,15 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
   if (tid < K) gt[tid * kNTally + SIM_T_TOK_PREF] = gt[tid * kNTally + SIM_T_TOKP_PRE] + L.acc[tid];
 }
 
-// The step kernel of one policy variant for a workgroup size class (0: up to 512 threads, 1: up to 768,
-// 2: up to 1024). Each variant is compiled in a translation unit of its own.
+// The step kernel of one policy variant for a size class (see size_class). Each variant is compiled in a
+// translation unit of its own.
 using StepKernel = void (*)(const Params *, StepArrays, uint32_t, uint32_t, uint32_t, uint32_t);
 #define GNR_STEP_VARIANT(name, AB, RR, IM, WS)                                                             \
   StepKernel name(int size_class)                                                                          \
   {                                                                                                        \
-    static const StepKernel table[3] = {gnr_step_kernel<512, AB, RR, IM, WS>, gnr_step_kernel<768, AB, RR, IM, WS>, \
-                                        gnr_step_kernel<1024, AB, RR, IM, WS>};                            \
+    static const StepKernel table[3] = {gnr_step_kernel<512, static_words(0), AB, RR, IM, WS>,             \
+                                        gnr_step_kernel<1024, static_words(1), AB, RR, IM, WS>,            \
+                                        gnr_step_kernel<1024, static_words(2), AB, RR, IM, WS>};           \
     return table[size_class];                                                                              \
   }
 
