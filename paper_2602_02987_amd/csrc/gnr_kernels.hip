@@ -11,9 +11,10 @@ size_t step_lds_bytes(const Params &p)
 {
   size_t total = 0;
   switch (size_class(p.threads, p.nwords)) {
-    case 0: lds_carve<static_words(0)>(p, nullptr, &total); break;
+    case 0: lds_carve<static_words(0), true>(p, nullptr, &total); break;
     case 1: lds_carve<static_words(1)>(p, nullptr, &total); break;
-    default: lds_carve<static_words(2)>(p, nullptr, &total); break;
+    case 2: lds_carve<static_words(2)>(p, nullptr, &total); break;
+    default: lds_carve<static_words(3)>(p, nullptr, &total); break;
   }
   return total;
 }

@@ -137,7 +137,12 @@ enum Scalar {
   SC_WORDS = 64
 };
 constexpr int kLoadBins = kMaxB + 1;
+// Table sizes. Workgroups of one or two waves (N up to 2560) share a compute unit with others of their kind and are
+// given smaller tables, so that eight of them fit its LDS: gate and routing passes then decide 64 admissions and stage
+// 64 requests at a time (more passes when a step brings more), and a wave finishes its queued servers when more than
+// 32 wait.
 constexpr int kEvPerWave = 128;   // servers a wave can queue for finishing; when full the queue is drained early
+constexpr int kEvPerWaveSmall = 96, kJobsLdsSmall = 64, kAdmChunkSmall = 64;
 constexpr int kRouteLevels = 4;
 constexpr int kJobsLds = 256;      // requests of a routing pass staged in LDS; later ones are read from the buffer
 constexpr int kMaxPend = 254;     // untallied iterations a server may accumulate (kept in a byte)
@@ -186,9 +191,12 @@ struct Lds {
 // workgroups of sixteen waves (N up to 64 NWS servers). NWS = 0: everything sized by the configuration.
 constexpr int kStaticWordsLarge = kMaxN / 64;   // any N the library accepts
 constexpr int kStaticWordsMedium = 160;          // N up to 10240: three kilobytes less
-template <int NWS>
+template <int NWS, bool SMALL = false>
 __host__ __device__ __forceinline__ Lds lds_carve(const Params &p, unsigned char *base, size_t *total)
 {
+  constexpr int kEvPerWave = SMALL ? kEvPerWaveSmall : gnr::kEvPerWave;       // (these shadow the large tables' sizes)
+  constexpr int kJobsLds = SMALL ? kJobsLdsSmall : gnr::kJobsLds;
+  constexpr int kAdmChunk = SMALL ? kAdmChunkSmall : gnr::kAdmChunk;
   Lds L;
   size_t off = 0;
   const size_t nw = NWS ? static_cast<size_t>(NWS) : static_cast<size_t>(p.nwords);
@@ -234,15 +242,16 @@ __host__ __device__ __forceinline__ Lds lds_carve(const Params &p, unsigned char
   if (total) *total = off;
   return L;
 }
-// Size classes of the step kernel: 0 workgroups of up to 512 threads (arrays sized by the configuration),
-// 1 and 2 sixteen waves with the word-indexed arrays sized for 160 words and for the largest N.
+// Size classes of the step kernel: 0 workgroups of one or two waves (small tables, arrays sized by the
+// configuration), 1 up to 512 threads (arrays sized by the configuration), 2 and 3 sixteen waves with the
+// word-indexed arrays sized for 160 words and for the largest N.
 __host__ __device__ constexpr int size_class(int threads, int nwords)
 {
-  return threads <= 512 ? 0 : (nwords <= kStaticWordsMedium ? 1 : 2);
+  return threads <= 128 ? 0 : threads <= 512 ? 1 : (nwords <= kStaticWordsMedium ? 2 : 3);
 }
 __host__ __device__ constexpr int static_words(int size_class)
 {
-  return size_class == 0 ? 0 : (size_class == 1 ? kStaticWordsMedium : kStaticWordsLarge);
+  return size_class <= 1 ? 0 : (size_class == 2 ? kStaticWordsMedium : kStaticWordsLarge);
 }
 
 // Bits of bitmap word w that belong to servers below `nbits`.
@@ -381,7 +390,7 @@ __device__ __forceinline__ ClassTargets load_targets(const double *tab, int k)
 // position of the class queue's head.
 __device__ __forceinline__ GateKey gate_key(const int gate_mode, const uint32_t queue_cap, const ClassTargets &t,
                                             const uint32_t *qring, const uint32_t *live_off, int xs_k, int qp_k,
-                                            uint32_t head_k, int k, int m)
+                                            uint32_t head_k, int k, int m, int adm_chunk)
 {
   GateKey key;
   if (gate_mode == SIM_GATE_OCCUPANCY) {
@@ -391,7 +400,7 @@ __device__ __forceinline__ GateKey gate_key(const int gate_mode, const uint32_t 
     key.a = -t.prio;
     key.b = 0.0;
   } else {
-    uint32_t pos = head_k + (live_off ? live_off[k * kAdmChunk + m] : static_cast<uint32_t>(m));
+    uint32_t pos = head_k + (live_off ? live_off[k * adm_chunk + m] : static_cast<uint32_t>(m));
     if (pos >= queue_cap) pos -= queue_cap;
     key.a = static_cast<double>(qring[static_cast<size_t>(k) * queue_cap + pos]);
     key.b = 0.0;
@@ -456,7 +465,11 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
 {
   const Params &p = *params;   // immutable after creation; read through the scalar cache on demand
   extern __shared__ __align__(16) unsigned char lds_raw[];
-  const Lds L = lds_carve<NWS>(p, lds_raw, nullptr);
+  constexpr bool SMALL = MAXT <= 128;
+  constexpr int kEvPerWave = SMALL ? kEvPerWaveSmall : gnr::kEvPerWave;       // (these shadow the large tables' sizes)
+  constexpr int kJobsLds = SMALL ? kJobsLdsSmall : gnr::kJobsLds;
+  constexpr int kAdmChunk = SMALL ? kAdmChunkSmall : gnr::kAdmChunk;
+  const Lds L = lds_carve<NWS, SMALL>(p, lds_raw, nullptr);
 
   const int r = blockIdx.x;
   const int tid = threadIdx.x;
@@ -1355,7 +1368,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
             const ClassTargets own = load_targets(L.gtab, k);
             const int xs_own = L.cs[CS_X + k], qp_own = L.cs[CS_QP + k];
             const uint32_t head_own = static_cast<uint32_t>(L.cs[CS_QHEAD + k]);
-            const GateKey key = gate_key(gate_mode, queue_cap, own, qring, lo_tab, xs_own, qp_own, head_own, k, m);
+            const GateKey key = gate_key(gate_mode, queue_cap, own, qring, lo_tab, xs_own, qp_own, head_own, k, m, kAdmChunk);
             int rank = m;
 #pragma unroll
             for (int k2 = 0; k2 < kMaxK; ++k2) {
@@ -1371,15 +1384,15 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
                 const int g0 = est > 0.0 ? (est < static_cast<double>(hi) ? static_cast<int>(est) : hi) : 0;
                 const int l2 = g0 > 1 ? g0 - 1 : 0, h2 = g0 + 2 < hi ? g0 + 2 : hi;
                 if (l2 > 0) {
-                  if (gate_before(gate_key(gate_mode, queue_cap, t2, qring, lo_tab, xs[k2], qp[k2], head[k2], k2, l2 - 1), k2, key, k)) lo = l2; else hi = l2 - 1;
+                  if (gate_before(gate_key(gate_mode, queue_cap, t2, qring, lo_tab, xs[k2], qp[k2], head[k2], k2, l2 - 1, kAdmChunk), k2, key, k)) lo = l2; else hi = l2 - 1;
                 }
                 if (h2 < hi) {
-                  if (gate_before(gate_key(gate_mode, queue_cap, t2, qring, lo_tab, xs[k2], qp[k2], head[k2], k2, h2), k2, key, k)) lo = h2 + 1; else hi = h2;
+                  if (gate_before(gate_key(gate_mode, queue_cap, t2, qring, lo_tab, xs[k2], qp[k2], head[k2], k2, h2, kAdmChunk), k2, key, k)) lo = h2 + 1; else hi = h2;
                 }
               }
               while (lo < hi) {
                 const int mid = (lo + hi) >> 1;
-                if (gate_before(gate_key(gate_mode, queue_cap, t2, qring, lo_tab, xs[k2], qp[k2], head[k2], k2, mid), k2, key, k)) lo = mid + 1; else hi = mid;
+                if (gate_before(gate_key(gate_mode, queue_cap, t2, qring, lo_tab, xs[k2], qp[k2], head[k2], k2, mid, kAdmChunk), k2, key, k)) lo = mid + 1; else hi = mid;
               }
               rank += lo;
             }
@@ -2079,9 +2092,10 @@ using StepKernel = void (*)(const Params *, StepArrays, uint32_t, uint32_t, uint
 #define GNR_STEP_VARIANT(name, AB, RR, IM, WS)                                                             \
   StepKernel name(int size_class)                                                                          \
   {                                                                                                        \
-    static const StepKernel table[3] = {gnr_step_kernel<512, static_words(0), AB, RR, IM, WS>,             \
-                                        gnr_step_kernel<1024, static_words(1), AB, RR, IM, WS>,            \
-                                        gnr_step_kernel<1024, static_words(2), AB, RR, IM, WS>};           \
+    static const StepKernel table[4] = {gnr_step_kernel<128, static_words(0), AB, RR, IM, WS>,             \
+                                        gnr_step_kernel<512, static_words(1), AB, RR, IM, WS>,             \
+                                        gnr_step_kernel<1024, static_words(2), AB, RR, IM, WS>,            \
+                                        gnr_step_kernel<1024, static_words(3), AB, RR, IM, WS>};           \
     return table[size_class];                                                                              \
   }
 
