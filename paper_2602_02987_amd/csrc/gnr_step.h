@@ -182,6 +182,7 @@ struct Lds {
   uint32_t *sel_u;    // [kJobsLds] random word of each selection
   uint16_t *sel_co;   // [kJobsLds] class | (how many selections before it chose the same class) << 3
   uint16_t *sel_j;    // [kJobsLds] list position of each selection, ordered by class, then by order within the class
+  int32_t *sel_n;     // [8] requests the pass takes from the solo group's buffer, per class
 };
 
 // Carves the dynamic LDS block; 8-byte granules. NWS > 0: the arrays indexed by 64-server word are sized for NWS
@@ -238,6 +239,7 @@ __host__ __device__ __forceinline__ Lds lds_carve(const Params &p, unsigned char
   GNR_TAKE(sel_u, uint32_t, p.route_mode == SIM_ROUTE_WEIGHTED_SPLIT ? kJobsLds : 0)
   GNR_TAKE(sel_co, uint16_t, p.route_mode == SIM_ROUTE_WEIGHTED_SPLIT ? kJobsLds : 0)
   GNR_TAKE(sel_j, uint16_t, p.route_mode == SIM_ROUTE_WEIGHTED_SPLIT ? kJobsLds : 0)
+  GNR_TAKE(sel_n, int32_t, p.route_mode == SIM_ROUTE_WEIGHTED_SPLIT ? 8 : 0)
 #undef GNR_TAKE
   if (total) *total = off;
   return L;
@@ -1102,22 +1104,45 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
         __syncthreads();
       }
     }
-    for (int k = 0; k < K; ++k) {
-      const uint32_t take = static_cast<uint32_t>(L.sc[SC_TAKE + k]), tail = static_cast<uint32_t>(L.sc[SC_TAIL + k]);
-      for (uint32_t j = tid; j < take; j += NT) {
-        uint32_t pos = tail + j;
+    if constexpr (AB) {
+      // One thread per accepted arrival of any class, so that the table reads of all classes are in flight together;
+      // the last waves take them, while the first ones move the completions below. The accepted arrivals of a class
+      // are exchangeable: the j-th of this step draws its patience.
+      uint32_t upto[kMaxK];   // accepted arrivals of the classes up to and including k
+      {
+        uint32_t run = 0;
+#pragma unroll
+        for (int k = 0; k < kMaxK; ++k) {
+          if (k < K) run += static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(L.sc[SC_TAKE + k]));
+          upto[k] = run;
+        }
+      }
+      for (uint32_t i = static_cast<uint32_t>((nwaves - 1 - wave) * 64 + lane); i < upto[kMaxK - 1]; i += NT) {
+        int k = 0;
+        uint32_t before = 0;
+#pragma unroll
+        for (int c = 0; c + 1 < kMaxK; ++c)
+          if (i >= upto[c]) { k = c + 1; before = upto[c]; }
+        const uint32_t j = i - before;
+        uint32_t pos = static_cast<uint32_t>(L.sc[SC_TAIL + k]) + j;
         if (pos >= queue_cap) pos -= queue_cap;
         qring[static_cast<size_t>(k) * queue_cap + pos] = s;
-        if constexpr (AB) {
-          // the accepted arrivals of a class are exchangeable: the j-th of this step draws its patience
-          uint32_t dl = kNever;
-          if ((p.ab_classes >> k) & 1u) {
-            uint32_t w[4];
-            philox4x32_10(key0, key1, s, static_cast<uint32_t>(kStreamPatienceP + k), j, static_cast<uint32_t>(r), w);
-            dl = s + a.pat_tab[static_cast<size_t>(k) * kTableSize + (w[0] >> 16)];
-            atomicAdd(&cal[static_cast<size_t>(k) * cal_n + (dl & p.cal_mask)], 1u);
-          }
-          qdl[static_cast<size_t>(k) * queue_cap + pos] = dl;
+        uint32_t dl = kNever;
+        if ((p.ab_classes >> k) & 1u) {
+          uint32_t w[4];
+          philox4x32_10(key0, key1, s, static_cast<uint32_t>(kStreamPatienceP + k), j, static_cast<uint32_t>(r), w);
+          dl = s + a.pat_tab[static_cast<size_t>(k) * kTableSize + (w[0] >> 16)];
+          atomicAdd(&cal[static_cast<size_t>(k) * cal_n + (dl & p.cal_mask)], 1u);
+        }
+        qdl[static_cast<size_t>(k) * queue_cap + pos] = dl;
+      }
+    } else {
+      for (int k = 0; k < K; ++k) {
+        const uint32_t take = static_cast<uint32_t>(L.sc[SC_TAKE + k]), tail = static_cast<uint32_t>(L.sc[SC_TAIL + k]);
+        for (uint32_t j = tid; j < take; j += NT) {
+          uint32_t pos = tail + j;
+          if (pos >= queue_cap) pos -= queue_cap;
+          qring[static_cast<size_t>(k) * queue_cap + pos] = s;
         }
       }
     }
@@ -1636,7 +1661,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
                 uint32_t w[4];
                 philox4x32_10(key0, key1, s, static_cast<uint32_t>(kStreamSelect + pool), static_cast<uint32_t>(placed_before + j),
                               static_cast<uint32_t>(r), w);
-                L.sel_u[j] = w[0];
+                L.sel_u[first_job + j] = w[0];
               }
               // Lane c knows class c's selection weight; what each class still has waiting (a pass takes at most
               // 256, larger counts are capped), which classes wait, and the running sums of their weights are
@@ -1666,7 +1691,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
               for (int done = 0; done < need;) {   // wave-uniform
                 const int j = done + lane;
                 const bool valid = j < need;
-                const uint32_t u = valid ? L.sel_u[j] : 0u;
+                const uint32_t u = valid ? L.sel_u[first_job + j] : 0u;
                 const uint32_t x = __umulhi(u, total);
                 int pick = 0;
 #pragma unroll
@@ -1687,7 +1712,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
                 const int n_valid = need - done < 64 ? need - done : 64;
                 const int n_acc = last < 64 ? last + 1 : n_valid;
                 const bool mine = lane < n_acc;
-                if (mine) L.sel_co[j] = static_cast<uint16_t>(pick);
+                if (mine) L.sel_co[first_job + j] = static_cast<uint16_t>(pick);
                 bool ran_out = false;
 #pragma unroll
                 for (int c = 0; c < kMaxK; ++c) {
@@ -1711,7 +1736,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
               for (int c = 0; c < kMaxK; ++c) nsel[c] = 0;
               for (int j0 = 0; j0 < need; j0 += 64) {   // wave-uniform
                 const int j = j0 + lane;
-                const int c = j < need ? static_cast<int>(L.sel_co[j]) : -1;
+                const int c = j < need ? static_cast<int>(L.sel_co[first_job + j]) : -1;
                 int ord = 0;
 #pragma unroll
                 for (int cc = 0; cc < kMaxK; ++cc) {
@@ -1721,7 +1746,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
                     nsel[cc] += __popcll(bal);
                   }
                 }
-                if (j < need) L.sel_co[j] = static_cast<uint16_t>(c | (ord << 3));
+                if (j < need) L.sel_co[first_job + j] = static_cast<uint16_t>(c | (ord << 3));
               }
               int base[kMaxK];
               {
@@ -1731,12 +1756,12 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
               }
               __builtin_amdgcn_wave_barrier();
               for (int j = lane; j < need; j += 64) {
-                const int co = L.sel_co[j], c = co & 7;
+                const int co = L.sel_co[first_job + j], c = co & 7;
                 int b = 0;
 #pragma unroll
                 for (int cc = 0; cc < kMaxK; ++cc)
                   if (cc == c) b = base[cc];
-                L.sel_j[b + (co >> 3)] = static_cast<uint16_t>(j);
+                L.sel_j[first_job + b + (co >> 3)] = static_cast<uint16_t>(j);
               }
               __builtin_amdgcn_wave_barrier();
               // walk the ring from the first entry that may still wait; the o-th waiting request of class c met on
@@ -1775,7 +1800,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
                     }
                     const bool mine = live && ord < quota;
                     if (mine) {
-                      L.jobs[first_job + L.sel_j[b + ord]] = jw4[u];
+                      L.jobs[first_job + L.sel_j[first_job + b + ord]] = jw4[u];
                       dlr[pos4[u]] = 0u;   // gone from the buffer
                       if (dl != kNever) atomicSub(&calr[static_cast<size_t>(c) * cal_n + (dl & p.cal_mask)], 1u);
                     }
@@ -1793,36 +1818,42 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
               if (lane == 0)
                 L.sc[scan_word] = static_cast<int32_t>(first_left != 0xFFFFFFFFu ? first_left : (left > 0 ? len : stop));
             };
-            // (a wave in the middle of the workgroup: the first waves assign the admissions above, the last ones
-            // turn the level counts into ranks below)
-            if (wave == (nwaves >= 8 ? nwaves / 2 : 0)) {
-              if constexpr (RR) {
+            // (waves in the middle of the workgroup: the first waves assign the admissions above, the last ones
+            // turn the level counts into ranks below; with two buffers each has a wave of its own, on another SIMD)
+            const int ring_wave = nwaves >= 8 ? nwaves / 2 : 0, ring_wave_m = nwaves >= 8 ? nwaves / 2 + 1 : 0;
+            if constexpr (RR) {
+              if (wave == ring_wave) {
                 if constexpr (WS) {
-                  int nsel_s[kMaxK], nsel_m[kMaxK];
+                  int nsel_s[kMaxK];
 #pragma unroll
                   for (int c = 0; c < kMaxK; ++c) nsel_s[c] = 0;
                   if (takenL[0] > 0)
                     select_and_stage(0, dring, ddl, dcal, dheadL[0], dlen_all, SC_DSCAN, takenL[0], 0, nextL[0], nsel_s);
-                  if (takenL[1] > 0)
-                    select_and_stage(1, dring_m, ddl_m, dcal_m, dheadL[1], dlen_all_m, SC_DSCAN_M, takenL[1], takenL[0], nextL[1], nsel_m);
-                  // (the per-class counts of both buffers were read above: what waits in the mixed group's buffer is
+                  // what the pass took from the solo group's buffer per class comes off that buffer's counts in
+                  // segment C: the other buffer's wave reads them meanwhile (what waits in the mixed group's buffer is
                   // the class total less the solo buffer's share, and the total follows the placements later)
                   if (lane < K) {
                     int mine = 0;
 #pragma unroll
                     for (int c = 0; c < kMaxK; ++c)
                       if (c == lane) mine = nsel_s[c];
-                    L.cs[CS_QDS + lane] -= mine;
+                    L.sel_n[lane] = mine;
                   }
                 } else {
-                if (takenL[0] > 0)
-                  stage_ring(dring, ddl, dcal, dheadL[0], dlen_all, SC_DSCAN, static_cast<uint32_t>(takenL[0]), 0);
-                if (takenL[1] > 0)
+                  if (takenL[0] > 0)
+                    stage_ring(dring, ddl, dcal, dheadL[0], dlen_all, SC_DSCAN, static_cast<uint32_t>(takenL[0]), 0);
+                }
+              }
+              if (wave == ring_wave_m && takenL[1] > 0) {
+                if constexpr (WS) {
+                  int nsel_m[kMaxK];
+                  select_and_stage(1, dring_m, ddl_m, dcal_m, dheadL[1], dlen_all_m, SC_DSCAN_M, takenL[1], takenL[0], nextL[1], nsel_m);
+                } else {
                   stage_ring(dring_m, ddl_m, dcal_m, dheadL[1], dlen_all_m, SC_DSCAN_M, static_cast<uint32_t>(takenL[1]), takenL[0]);
                 }
-              } else {
-                stage_ring(dring, ddl, dcal, dhead0, dlen_all, SC_DSCAN, static_cast<uint32_t>(total), 0);
               }
+            } else {
+              if (wave == ring_wave) stage_ring(dring, ddl, dcal, dhead0, dlen_all, SC_DSCAN, static_cast<uint32_t>(total), 0);
             }
           } else if constexpr (RR) {
             for (int j = tid; j < nstage; j += NT) {
@@ -1958,6 +1989,9 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
             }
             // every server below the last level of its group now holds that level, plus one if that level reached it
             if (tmin < tend) L.loads[g] = static_cast<uint8_t>(my_lmin + my_n - 1 + (got_last ? 1 : 0));
+          }
+          if constexpr (WS) {   // what the pass took from the solo group's buffer, per class
+            if (tid >= NT - 64 && lane < K) L.cs[CS_QDS + lane] -= L.sel_n[lane];
           }
           if (tid == 0) {
 #pragma unroll
