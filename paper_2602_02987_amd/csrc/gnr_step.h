@@ -1300,6 +1300,254 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           __syncthreads();
         }
         if ((AB || gate_mode == SIM_GATE_FCFS) && pass == 0) __syncthreads();   // ring entries written above are read below
+        // With abandonment the requests a routing pass places are first staged in LDS, by the waves that own the decode
+        // buffers (each buffer has a wave of its own, on different SIMDs).
+        const int ring_wave = nwaves >= 8 ? (WS ? 4 : nwaves / 2) : nwaves - 1;
+        const int ring_wave_m = nwaves >= 8 ? ring_wave + 1 : nwaves - 1;
+        // the weighted router's selection is long: it runs in segment A beside the gate's ranking, on waves that are
+        // given nothing else to do there; the plain walk of a ring runs in segment B
+        constexpr bool kStageEarly = AB && WS;
+        // one wave walks a ring from where the last pass stopped and stages the next `need` waiting jobs
+        auto stage_ring = [&](const uint64_t *ring, const uint32_t *dlr, uint32_t *calr, uint32_t hd, uint32_t len,
+                              int scan_word, uint32_t need, int first_job) __attribute__((always_inline)) {
+          uint32_t off = static_cast<uint32_t>(L.sc[scan_word]), found = 0, stop = off;
+          // four chunks of 64 entries per round: deadlines and requests are loaded together
+          for (; off < len && found < need; off += 256) {   // wave-uniform
+            uint32_t dl4[4];
+            uint64_t jw4[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+              const uint32_t i = off + 64u * u + lane;
+              uint32_t pos = hd + i;
+              if (pos >= dbuf_cap) pos -= dbuf_cap;
+              dl4[u] = i < len ? dlr[pos] : 0u;   // (beyond the ring: counts as dead)
+              jw4[u] = i < len ? ring[pos] : 0ull;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+              const uint32_t dl = dl4[u];
+              const bool live = dl > s;
+              const uint64_t bal = __ballot(live);
+              const uint32_t rk = found + static_cast<uint32_t>(__popcll(bal & lanes_below()));
+              const bool mine = live && rk < need;
+              if (mine) {
+                L.jobs[first_job + rk] = jw4[u];
+                if (dl != kNever)
+                  atomicSub(&calr[static_cast<size_t>((jw4[u] >> 29) & 7u) * cal_n + (dl & p.cal_mask)], 1u);
+              }
+              const uint64_t last = __ballot(mine && rk + 1 == need);
+              if (last) stop = off + 64u * u + static_cast<uint32_t>(__ffsll(static_cast<long long>(last)));   // one past the last staged entry
+              found += static_cast<uint32_t>(__popcll(bal));
+            }
+          }
+          if (lane == 0) L.sc[scan_word] = static_cast<int32_t>(found >= need ? stop : len);   // (found < need: see the gate's scan)
+        };
+        // Weighted router: the pass's `need` placements in a pool each draw a class among those that still
+        // wait in the pool's buffer (one after the other: a class that runs out drops from the later draws) and
+        // take that class's requests in their order of arrival. The ring keeps the others where they are: an
+        // entry that is taken gets a deadline that has passed, like an abandoned one.
+        auto select_and_stage = [&](int pool, uint64_t *ring, uint32_t *dlr, uint32_t *calr, uint32_t hd, uint32_t len,
+                                    int scan_word, int need, int first_job, int placed_before,
+                                    int (&nsel)[kMaxK]) __attribute__((always_inline)) {
+          for (int j = lane; j < need; j += 64) {
+            uint32_t w[4];
+            philox4x32_10(key0, key1, s, static_cast<uint32_t>(kStreamSelect + pool), static_cast<uint32_t>(placed_before + j),
+                          static_cast<uint32_t>(r), w);
+            L.sel_u[first_job + j] = w[0];
+          }
+          // Lane c knows class c's selection weight; what each class still has waiting (a pass takes at most
+          // 256, larger counts are capped), which classes wait, and the running sums of their weights are
+          // wave-uniform. The draws do not depend on one another until a class runs out, so they are evaluated
+          // 64 at a time, one per lane: a draw's class is the number of running sums it has reached. If the
+          // draws of a round would take more of a class than waits, the round ends with the draw that takes the
+          // last one, the sums are recomputed without that class, and the next round starts behind it.
+          int cntv = 0;
+          uint32_t wtv = 0;
+          if (lane < K) {
+            const int solo_c = L.cs[CS_QDS + lane];
+            cntv = pool == 0 ? solo_c : L.cs[CS_QD + lane] - solo_c;
+            wtv = p.wsel[pool][lane];
+          }
+          cntv = cntv < 0 ? 0 : (cntv > 0xFFFF ? 0xFFFF : cntv);
+          uint64_t waits = __ballot(cntv > 0);
+          uint32_t cumv = wave_incl_scan(cntv > 0 ? wtv : 0u);
+          int rem[kMaxK];
+          uint32_t cum[kMaxK];
+#pragma unroll
+          for (int c = 0; c < kMaxK; ++c) {
+            rem[c] = __builtin_amdgcn_readlane(cntv, c);
+            cum[c] = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(cumv), c));
+          }
+          uint32_t total = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(cumv), 63));
+          __builtin_amdgcn_wave_barrier();
+          for (int done = 0; done < need;) {   // wave-uniform
+            const int j = done + lane;
+            const bool valid = j < need;
+            const uint32_t u = valid ? L.sel_u[first_job + j] : 0u;
+            const uint32_t x = __umulhi(u, total);
+            int pick = 0;
+#pragma unroll
+            for (int c = 0; c < kMaxK; ++c)
+              if (c < K) pick += x >= cum[c] ? 1 : 0;
+            if (pick > K - 1) pick = K - 1;   // (no class waits: cannot happen, the pass takes no more than wait)
+            int last = 64;   // lane of the first draw that takes the last waiting request of its class
+#pragma unroll
+            for (int c = 0; c < kMaxK; ++c) {
+              if (c < K && rem[c] > 0) {   // wave-uniform
+                const uint64_t bal = __ballot(valid && pick == c);
+                if (__popcll(bal) >= rem[c]) {
+                  const int pos = nth_set_bit(bal, rem[c] - 1);
+                  last = pos < last ? pos : last;
+                }
+              }
+            }
+            const int n_valid = need - done < 64 ? need - done : 64;
+            const int n_acc = last < 64 ? last + 1 : n_valid;
+            const bool mine = lane < n_acc;
+            if (mine) L.sel_co[first_job + j] = static_cast<uint16_t>(pick);
+            bool ran_out = false;
+#pragma unroll
+            for (int c = 0; c < kMaxK; ++c) {
+              if (c < K && rem[c] > 0) {   // wave-uniform
+                const int took = __popcll(__ballot(mine && pick == c));
+                rem[c] -= took;
+                if (rem[c] == 0) { waits &= ~(1ull << c); ran_out = true; }
+              }
+            }
+            if (ran_out) {   // wave-uniform
+              cumv = wave_incl_scan(((waits >> lane) & 1ull) ? wtv : 0u);
+#pragma unroll
+              for (int c = 0; c < kMaxK; ++c) cum[c] = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(cumv), c));
+              total = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(cumv), 63));
+            }
+            done += n_acc;
+          }
+          __builtin_amdgcn_wave_barrier();
+          // how many earlier selections of the pass chose the same class: counted over the lanes, 64 at a time
+#pragma unroll
+          for (int c = 0; c < kMaxK; ++c) nsel[c] = 0;
+          for (int j0 = 0; j0 < need; j0 += 64) {   // wave-uniform
+            const int j = j0 + lane;
+            const int c = j < need ? static_cast<int>(L.sel_co[first_job + j]) : -1;
+            int ord = 0;
+#pragma unroll
+            for (int cc = 0; cc < kMaxK; ++cc) {
+              if (cc < K) {   // wave-uniform
+                const uint64_t bal = __ballot(c == cc);
+                if (c == cc) ord = nsel[cc] + __popcll(bal & lanes_below());
+                nsel[cc] += __popcll(bal);
+              }
+            }
+            if (j < need) L.sel_co[first_job + j] = static_cast<uint16_t>(c | (ord << 3));
+          }
+          int base[kMaxK];
+          {
+            int run = 0;
+#pragma unroll
+            for (int c = 0; c < kMaxK; ++c) { base[c] = run; run += nsel[c]; }
+          }
+          __builtin_amdgcn_wave_barrier();
+          for (int j = lane; j < need; j += 64) {
+            const int co = L.sel_co[first_job + j], c = co & 7;
+            int b = 0;
+#pragma unroll
+            for (int cc = 0; cc < kMaxK; ++cc)
+              if (cc == c) b = base[cc];
+            L.sel_j[first_job + b + (co >> 3)] = static_cast<uint16_t>(j);
+          }
+          __builtin_amdgcn_wave_barrier();
+          // walk the ring from the first entry that may still wait; the o-th waiting request of class c met on
+          // the way is taken if the pass selected that class more than o times
+          uint32_t off = static_cast<uint32_t>(L.sc[scan_word]), stop = off, first_left = 0xFFFFFFFFu;
+          int left = need;
+          int seen[kMaxK];
+#pragma unroll
+          for (int c = 0; c < kMaxK; ++c) seen[c] = 0;
+          for (; off < len && left > 0; off += 256) {   // wave-uniform
+            uint32_t dl4[4], pos4[4];
+            uint64_t jw4[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+              const uint32_t i = off + 64u * u + lane;
+              uint32_t pos = hd + i;
+              if (pos >= dbuf_cap) pos -= dbuf_cap;
+              pos4[u] = pos;
+              dl4[u] = i < len ? dlr[pos] : 0u;   // (beyond the ring: counts as gone)
+              jw4[u] = i < len ? ring[pos] : 0ull;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+              if (left > 0) {   // wave-uniform
+                const uint32_t dl = dl4[u];
+                const bool live = dl > s;
+                const int c = static_cast<int>(jw4[u] >> 29) & 7;
+                int ord = 0, quota = 0, b = 0;
+#pragma unroll
+                for (int cc = 0; cc < kMaxK; ++cc) {
+                  if (cc < K) {   // wave-uniform
+                    const uint64_t bal = __ballot(live && c == cc);
+                    if (c == cc) { ord = seen[cc] + __popcll(bal & lanes_below()); quota = nsel[cc]; b = base[cc]; }
+                    seen[cc] += __popcll(bal);
+                  }
+                }
+                const bool mine = live && ord < quota;
+                if (mine) {
+                  L.jobs[first_job + L.sel_j[first_job + b + ord]] = jw4[u];
+                  dlr[pos4[u]] = 0u;   // gone from the buffer
+                  if (dl != kNever) atomicSub(&calr[static_cast<size_t>(c) * cal_n + (dl & p.cal_mask)], 1u);
+                }
+                const uint64_t stay = __ballot(live && !mine), took = __ballot(mine);
+                if (first_left == 0xFFFFFFFFu && stay)
+                  first_left = off + 64u * u + static_cast<uint32_t>(__ffsll(static_cast<long long>(stay))) - 1u;
+                if (took) {
+                  left -= __popcll(took);
+                  stop = off + 64u * u + 64u - static_cast<uint32_t>(__clzll(static_cast<long long>(took)));   // one past the last taken entry
+                }
+              }
+            }
+          }
+          // the next pass (and the head, at the end of the step) starts at the first entry that still waits
+          if (lane == 0)
+            L.sc[scan_word] = static_cast<int32_t>(first_left != 0xFFFFFFFFu ? first_left : (left > 0 ? len : stop));
+        };
+        auto stage_pass = [&](int total_pass) __attribute__((always_inline)) {
+          // (each buffer has a wave of its own, on different SIMDs; in a large workgroup these waves leave the
+          // level counts below to the others)
+          if constexpr (RR) {
+            if (wave == ring_wave) {
+              if constexpr (WS) {
+                int nsel_s[kMaxK];
+#pragma unroll
+                for (int c = 0; c < kMaxK; ++c) nsel_s[c] = 0;
+                if (takenL[0] > 0)
+                  select_and_stage(0, dring, ddl, dcal, dheadL[0], dlen_all, SC_DSCAN, takenL[0], 0, nextL[0], nsel_s);
+                // what the pass took from the solo group's buffer per class comes off that buffer's counts in
+                // segment C: the other buffer's wave reads them meanwhile (what waits in the mixed group's buffer is
+                // the class total less the solo buffer's share, and the total follows the placements later)
+                if (lane < K) {
+                  int mine = 0;
+#pragma unroll
+                  for (int c = 0; c < kMaxK; ++c)
+                    if (c == lane) mine = nsel_s[c];
+                  L.sel_n[lane] = mine;
+                }
+              } else {
+                if (takenL[0] > 0)
+                  stage_ring(dring, ddl, dcal, dheadL[0], dlen_all, SC_DSCAN, static_cast<uint32_t>(takenL[0]), 0);
+              }
+            }
+            if (wave == ring_wave_m && takenL[1] > 0) {
+              if constexpr (WS) {
+                int nsel_m[kMaxK];
+                select_and_stage(1, dring_m, ddl_m, dcal_m, dheadL[1], dlen_all_m, SC_DSCAN_M, takenL[1], takenL[0], nextL[1], nsel_m);
+              } else {
+                stage_ring(dring_m, ddl_m, dcal_m, dheadL[1], dlen_all_m, SC_DSCAN_M, static_cast<uint32_t>(takenL[1]), takenL[0]);
+              }
+            }
+          } else {
+            if (wave == ring_wave) stage_ring(dring, ddl, dcal, dhead0, dlen_all, SC_DSCAN, static_cast<uint32_t>(total_pass), 0);
+          }
+        };
 
         // ---------------- segment A ----------------
         int nadm = 0, nidle = 0;
@@ -1518,12 +1766,25 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
             if (gate_unfinished) route_wait = true;
             else route_on = false;   // every slot is taken: the jobs stay in the buffer
           } else {
+            // Waves that count the servers of each level, and this wave's place among them. With abandonment the
+            // requests the pass places are first staged in LDS by the waves that own the decode buffers: a large
+            // workgroup gives them no counting to do, so that the staging runs beside the gate's ranking.
+            int cw = wave, cn = nwaves;
+            if constexpr (kStageEarly) {
+              stage_pass(total);
+              if (nwaves >= 8) {
+                constexpr int n_ring = RR ? 2 : 1;
+                cn = nwaves - n_ring;
+                cw = wave < ring_wave ? wave : wave - n_ring;   // (negative for the buffers' waves)
+                if (wave >= ring_wave && wave < ring_wave + n_ring) cw = nwords;   // nothing to count
+              }
+            }
             // four blocks per round: their decode counts are read together, then compared level by level
-            for (int w0 = wave; w0 < nwords; w0 += 4 * nwaves) {
+            for (int w0 = cw; w0 < nwords; w0 += 4 * cn) {
               int tmin4[4], tend4[4];
 #pragma unroll
               for (int u = 0; u < 4; ++u) {
-                const int wi = w0 + u * nwaves;
+                const int wi = w0 + u * cn;
                 const int g = (wi << 6) + lane;
                 tmin4[u] = 0; tend4[u] = 0;
                 if (wi < nwords && g < N) {
@@ -1536,7 +1797,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
               }
 #pragma unroll
               for (int u = 0; u < 4; ++u) {
-                const int wi = w0 + u * nwaves;
+                const int wi = w0 + u * cn;
                 if (wi < nwords) {   // wave-uniform
 #pragma unroll
                   for (int t = 0; t < kRouteLevels; ++t) {
@@ -1615,246 +1876,7 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
           // the requests this pass places are staged in LDS
           const int nstage = total < kJobsLds ? total : kJobsLds;
           if constexpr (AB) {
-            // one wave walks a ring from where the last pass stopped and stages the next `need` waiting jobs
-            auto stage_ring = [&](const uint64_t *ring, const uint32_t *dlr, uint32_t *calr, uint32_t hd, uint32_t len,
-                                  int scan_word, uint32_t need, int first_job) __attribute__((always_inline)) {
-              uint32_t off = static_cast<uint32_t>(L.sc[scan_word]), found = 0, stop = off;
-              // four chunks of 64 entries per round: deadlines and requests are loaded together
-              for (; off < len && found < need; off += 256) {   // wave-uniform
-                uint32_t dl4[4];
-                uint64_t jw4[4];
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                  const uint32_t i = off + 64u * u + lane;
-                  uint32_t pos = hd + i;
-                  if (pos >= dbuf_cap) pos -= dbuf_cap;
-                  dl4[u] = i < len ? dlr[pos] : 0u;   // (beyond the ring: counts as dead)
-                  jw4[u] = i < len ? ring[pos] : 0ull;
-                }
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                  const uint32_t dl = dl4[u];
-                  const bool live = dl > s;
-                  const uint64_t bal = __ballot(live);
-                  const uint32_t rk = found + static_cast<uint32_t>(__popcll(bal & lanes_below()));
-                  const bool mine = live && rk < need;
-                  if (mine) {
-                    L.jobs[first_job + rk] = jw4[u];
-                    if (dl != kNever)
-                      atomicSub(&calr[static_cast<size_t>((jw4[u] >> 29) & 7u) * cal_n + (dl & p.cal_mask)], 1u);
-                  }
-                  const uint64_t last = __ballot(mine && rk + 1 == need);
-                  if (last) stop = off + 64u * u + static_cast<uint32_t>(__ffsll(static_cast<long long>(last)));   // one past the last staged entry
-                  found += static_cast<uint32_t>(__popcll(bal));
-                }
-              }
-              if (lane == 0) L.sc[scan_word] = static_cast<int32_t>(found >= need ? stop : len);   // (found < need: see the gate's scan)
-            };
-            // Weighted router: the pass's `need` placements in a pool each draw a class among those that still
-            // wait in the pool's buffer (one after the other: a class that runs out drops from the later draws) and
-            // take that class's requests in their order of arrival. The ring keeps the others where they are: an
-            // entry that is taken gets a deadline that has passed, like an abandoned one.
-            auto select_and_stage = [&](int pool, uint64_t *ring, uint32_t *dlr, uint32_t *calr, uint32_t hd, uint32_t len,
-                                        int scan_word, int need, int first_job, int placed_before,
-                                        int (&nsel)[kMaxK]) __attribute__((always_inline)) {
-              for (int j = lane; j < need; j += 64) {
-                uint32_t w[4];
-                philox4x32_10(key0, key1, s, static_cast<uint32_t>(kStreamSelect + pool), static_cast<uint32_t>(placed_before + j),
-                              static_cast<uint32_t>(r), w);
-                L.sel_u[first_job + j] = w[0];
-              }
-              // Lane c knows class c's selection weight; what each class still has waiting (a pass takes at most
-              // 256, larger counts are capped), which classes wait, and the running sums of their weights are
-              // wave-uniform. The draws do not depend on one another until a class runs out, so they are evaluated
-              // 64 at a time, one per lane: a draw's class is the number of running sums it has reached. If the
-              // draws of a round would take more of a class than waits, the round ends with the draw that takes the
-              // last one, the sums are recomputed without that class, and the next round starts behind it.
-              int cntv = 0;
-              uint32_t wtv = 0;
-              if (lane < K) {
-                const int solo_c = L.cs[CS_QDS + lane];
-                cntv = pool == 0 ? solo_c : L.cs[CS_QD + lane] - solo_c;
-                wtv = p.wsel[pool][lane];
-              }
-              cntv = cntv < 0 ? 0 : (cntv > 0xFFFF ? 0xFFFF : cntv);
-              uint64_t waits = __ballot(cntv > 0);
-              uint32_t cumv = wave_incl_scan(cntv > 0 ? wtv : 0u);
-              int rem[kMaxK];
-              uint32_t cum[kMaxK];
-#pragma unroll
-              for (int c = 0; c < kMaxK; ++c) {
-                rem[c] = __builtin_amdgcn_readlane(cntv, c);
-                cum[c] = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(cumv), c));
-              }
-              uint32_t total = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(cumv), 63));
-              __builtin_amdgcn_wave_barrier();
-              for (int done = 0; done < need;) {   // wave-uniform
-                const int j = done + lane;
-                const bool valid = j < need;
-                const uint32_t u = valid ? L.sel_u[first_job + j] : 0u;
-                const uint32_t x = __umulhi(u, total);
-                int pick = 0;
-#pragma unroll
-                for (int c = 0; c < kMaxK; ++c)
-                  if (c < K) pick += x >= cum[c] ? 1 : 0;
-                if (pick > K - 1) pick = K - 1;   // (no class waits: cannot happen, the pass takes no more than wait)
-                int last = 64;   // lane of the first draw that takes the last waiting request of its class
-#pragma unroll
-                for (int c = 0; c < kMaxK; ++c) {
-                  if (c < K && rem[c] > 0) {   // wave-uniform
-                    const uint64_t bal = __ballot(valid && pick == c);
-                    if (__popcll(bal) >= rem[c]) {
-                      const int pos = nth_set_bit(bal, rem[c] - 1);
-                      last = pos < last ? pos : last;
-                    }
-                  }
-                }
-                const int n_valid = need - done < 64 ? need - done : 64;
-                const int n_acc = last < 64 ? last + 1 : n_valid;
-                const bool mine = lane < n_acc;
-                if (mine) L.sel_co[first_job + j] = static_cast<uint16_t>(pick);
-                bool ran_out = false;
-#pragma unroll
-                for (int c = 0; c < kMaxK; ++c) {
-                  if (c < K && rem[c] > 0) {   // wave-uniform
-                    const int took = __popcll(__ballot(mine && pick == c));
-                    rem[c] -= took;
-                    if (rem[c] == 0) { waits &= ~(1ull << c); ran_out = true; }
-                  }
-                }
-                if (ran_out) {   // wave-uniform
-                  cumv = wave_incl_scan(((waits >> lane) & 1ull) ? wtv : 0u);
-#pragma unroll
-                  for (int c = 0; c < kMaxK; ++c) cum[c] = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(cumv), c));
-                  total = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(cumv), 63));
-                }
-                done += n_acc;
-              }
-              __builtin_amdgcn_wave_barrier();
-              // how many earlier selections of the pass chose the same class: counted over the lanes, 64 at a time
-#pragma unroll
-              for (int c = 0; c < kMaxK; ++c) nsel[c] = 0;
-              for (int j0 = 0; j0 < need; j0 += 64) {   // wave-uniform
-                const int j = j0 + lane;
-                const int c = j < need ? static_cast<int>(L.sel_co[first_job + j]) : -1;
-                int ord = 0;
-#pragma unroll
-                for (int cc = 0; cc < kMaxK; ++cc) {
-                  if (cc < K) {   // wave-uniform
-                    const uint64_t bal = __ballot(c == cc);
-                    if (c == cc) ord = nsel[cc] + __popcll(bal & lanes_below());
-                    nsel[cc] += __popcll(bal);
-                  }
-                }
-                if (j < need) L.sel_co[first_job + j] = static_cast<uint16_t>(c | (ord << 3));
-              }
-              int base[kMaxK];
-              {
-                int run = 0;
-#pragma unroll
-                for (int c = 0; c < kMaxK; ++c) { base[c] = run; run += nsel[c]; }
-              }
-              __builtin_amdgcn_wave_barrier();
-              for (int j = lane; j < need; j += 64) {
-                const int co = L.sel_co[first_job + j], c = co & 7;
-                int b = 0;
-#pragma unroll
-                for (int cc = 0; cc < kMaxK; ++cc)
-                  if (cc == c) b = base[cc];
-                L.sel_j[first_job + b + (co >> 3)] = static_cast<uint16_t>(j);
-              }
-              __builtin_amdgcn_wave_barrier();
-              // walk the ring from the first entry that may still wait; the o-th waiting request of class c met on
-              // the way is taken if the pass selected that class more than o times
-              uint32_t off = static_cast<uint32_t>(L.sc[scan_word]), stop = off, first_left = 0xFFFFFFFFu;
-              int left = need;
-              int seen[kMaxK];
-#pragma unroll
-              for (int c = 0; c < kMaxK; ++c) seen[c] = 0;
-              for (; off < len && left > 0; off += 256) {   // wave-uniform
-                uint32_t dl4[4], pos4[4];
-                uint64_t jw4[4];
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                  const uint32_t i = off + 64u * u + lane;
-                  uint32_t pos = hd + i;
-                  if (pos >= dbuf_cap) pos -= dbuf_cap;
-                  pos4[u] = pos;
-                  dl4[u] = i < len ? dlr[pos] : 0u;   // (beyond the ring: counts as gone)
-                  jw4[u] = i < len ? ring[pos] : 0ull;
-                }
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                  if (left > 0) {   // wave-uniform
-                    const uint32_t dl = dl4[u];
-                    const bool live = dl > s;
-                    const int c = static_cast<int>(jw4[u] >> 29) & 7;
-                    int ord = 0, quota = 0, b = 0;
-#pragma unroll
-                    for (int cc = 0; cc < kMaxK; ++cc) {
-                      if (cc < K) {   // wave-uniform
-                        const uint64_t bal = __ballot(live && c == cc);
-                        if (c == cc) { ord = seen[cc] + __popcll(bal & lanes_below()); quota = nsel[cc]; b = base[cc]; }
-                        seen[cc] += __popcll(bal);
-                      }
-                    }
-                    const bool mine = live && ord < quota;
-                    if (mine) {
-                      L.jobs[first_job + L.sel_j[first_job + b + ord]] = jw4[u];
-                      dlr[pos4[u]] = 0u;   // gone from the buffer
-                      if (dl != kNever) atomicSub(&calr[static_cast<size_t>(c) * cal_n + (dl & p.cal_mask)], 1u);
-                    }
-                    const uint64_t stay = __ballot(live && !mine), took = __ballot(mine);
-                    if (first_left == 0xFFFFFFFFu && stay)
-                      first_left = off + 64u * u + static_cast<uint32_t>(__ffsll(static_cast<long long>(stay))) - 1u;
-                    if (took) {
-                      left -= __popcll(took);
-                      stop = off + 64u * u + 64u - static_cast<uint32_t>(__clzll(static_cast<long long>(took)));   // one past the last taken entry
-                    }
-                  }
-                }
-              }
-              // the next pass (and the head, at the end of the step) starts at the first entry that still waits
-              if (lane == 0)
-                L.sc[scan_word] = static_cast<int32_t>(first_left != 0xFFFFFFFFu ? first_left : (left > 0 ? len : stop));
-            };
-            // (waves in the middle of the workgroup: the first waves assign the admissions above, the last ones
-            // turn the level counts into ranks below; with two buffers each has a wave of its own, on another SIMD)
-            const int ring_wave = nwaves >= 8 ? nwaves / 2 : 0, ring_wave_m = nwaves >= 8 ? nwaves / 2 + 1 : 0;
-            if constexpr (RR) {
-              if (wave == ring_wave) {
-                if constexpr (WS) {
-                  int nsel_s[kMaxK];
-#pragma unroll
-                  for (int c = 0; c < kMaxK; ++c) nsel_s[c] = 0;
-                  if (takenL[0] > 0)
-                    select_and_stage(0, dring, ddl, dcal, dheadL[0], dlen_all, SC_DSCAN, takenL[0], 0, nextL[0], nsel_s);
-                  // what the pass took from the solo group's buffer per class comes off that buffer's counts in
-                  // segment C: the other buffer's wave reads them meanwhile (what waits in the mixed group's buffer is
-                  // the class total less the solo buffer's share, and the total follows the placements later)
-                  if (lane < K) {
-                    int mine = 0;
-#pragma unroll
-                    for (int c = 0; c < kMaxK; ++c)
-                      if (c == lane) mine = nsel_s[c];
-                    L.sel_n[lane] = mine;
-                  }
-                } else {
-                  if (takenL[0] > 0)
-                    stage_ring(dring, ddl, dcal, dheadL[0], dlen_all, SC_DSCAN, static_cast<uint32_t>(takenL[0]), 0);
-                }
-              }
-              if (wave == ring_wave_m && takenL[1] > 0) {
-                if constexpr (WS) {
-                  int nsel_m[kMaxK];
-                  select_and_stage(1, dring_m, ddl_m, dcal_m, dheadL[1], dlen_all_m, SC_DSCAN_M, takenL[1], takenL[0], nextL[1], nsel_m);
-                } else {
-                  stage_ring(dring_m, ddl_m, dcal_m, dheadL[1], dlen_all_m, SC_DSCAN_M, static_cast<uint32_t>(takenL[1]), takenL[0]);
-                }
-              }
-            } else {
-              if (wave == ring_wave) stage_ring(dring, ddl, dcal, dhead0, dlen_all, SC_DSCAN, static_cast<uint32_t>(total), 0);
-            }
+            if constexpr (!kStageEarly) stage_pass(total);
           } else if constexpr (RR) {
             for (int j = tid; j < nstage; j += NT) {
               const int li = j < takenL[0] ? 0 : 1;
