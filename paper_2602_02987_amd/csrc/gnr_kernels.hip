@@ -1,6 +1,7 @@
 // Small kernels of the simulator (reset, totals over replications, state digest) and the launchers (gfx950).
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <mutex>
 
 #include "gnr_step.h"
@@ -186,15 +187,32 @@ int static_workspace(void **dev_ptr, size_t *bytes)
 
 // ------------------------------------------------------------------ launchers ----
 // The step kernel's policy variants, each compiled in a translation unit of its own (gnr_step_<variant>.hip).
-StepKernel step_kernel_plain(int size_class);
-StepKernel step_kernel_rr(int size_class);
-StepKernel step_kernel_im(int size_class);
-StepKernel step_kernel_ab(int size_class);
-StepKernel step_kernel_ab_rr(int size_class);
-StepKernel step_kernel_ab_im(int size_class);
-StepKernel step_kernel_ws(int size_class);
+StepKernel step_kernel_plain(int size_class, bool dense);
+StepKernel step_kernel_rr(int size_class, bool dense);
+StepKernel step_kernel_im(int size_class, bool dense);
+StepKernel step_kernel_ab(int size_class, bool dense);
+StepKernel step_kernel_ab_rr(int size_class, bool dense);
+StepKernel step_kernel_ab_im(int size_class, bool dense);
+StepKernel step_kernel_ws(int size_class, bool dense);
 
 static int hip_ok(hipError_t e) { return e == hipSuccess ? SIM_OK : SIM_EHIP; }
+
+constexpr size_t kLdsPerComputeUnit = 160 * 1024;
+
+// Compute units of the current device (asked once per device; 256 if the runtime does not say).
+static int compute_units()
+{
+  constexpr int kMaxDevices = 64;
+  static std::atomic<int> known[kMaxDevices] = {};
+  int d = 0;
+  if (hipGetDevice(&d) != hipSuccess || d < 0 || d >= kMaxDevices) return 256;
+  int n = known[d].load(std::memory_order_relaxed);
+  if (n == 0) {
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, d) != hipSuccess || n < 1) n = 256;
+    known[d].store(n, std::memory_order_relaxed);
+  }
+  return n;
+}
 
 int launch_reset(const Params &p, int reps, void *stream)
 {
@@ -207,13 +225,29 @@ int launch_steps(const Params &p, int reps, int threads, size_t lds_bytes, uint3
 {
   const int size = size_class(threads, p.nwords);
   const bool ab = p.dl_rings != 0;
+  // The roomy form of a small size class holds two waves per SIMD, the dense form four: the dense one is taken when
+  // the launch then needs fewer rounds of workgroups (every workgroup runs for the whole launch, so a workgroup
+  // that finds no place at first waits for another to end).
+  bool dense = false;
+  if (size <= 1) {
+    const int cus = compute_units();
+    const int waves = threads / 64;
+    const int by_lds = static_cast<int>(kLdsPerComputeUnit / (lds_bytes ? lds_bytes : 1));
+    auto rounds = [&](bool d) {
+      int wgs = 4 * waves_per_simd(threads, d) / waves;   // wave slots of the four SIMDs
+      wgs = wgs < by_lds ? wgs : by_lds;
+      wgs = wgs < 1 ? 1 : wgs;
+      return (reps + cus * wgs - 1) / (cus * wgs);
+    };
+    dense = rounds(true) < rounds(false);
+  }
   StepKernel kernel = nullptr;
   switch (p.route_mode) {
-    case SIM_ROUTE_SOLO_FIRST: kernel = ab ? step_kernel_ab(size) : step_kernel_plain(size); break;
-    case SIM_ROUTE_RANDOM_SPLIT: kernel = ab ? step_kernel_ab_rr(size) : step_kernel_rr(size); break;
-    case SIM_ROUTE_IMMEDIATE: kernel = ab ? step_kernel_ab_im(size) : step_kernel_im(size); break;
+    case SIM_ROUTE_SOLO_FIRST: kernel = ab ? step_kernel_ab(size, dense) : step_kernel_plain(size, dense); break;
+    case SIM_ROUTE_RANDOM_SPLIT: kernel = ab ? step_kernel_ab_rr(size, dense) : step_kernel_rr(size, dense); break;
+    case SIM_ROUTE_IMMEDIATE: kernel = ab ? step_kernel_ab_im(size, dense) : step_kernel_im(size, dense); break;
     // (the weighted router is the randomized router's variant with deadline rings plus the class draws)
-    case SIM_ROUTE_WEIGHTED_SPLIT: kernel = ab ? step_kernel_ws(size) : nullptr; break;
+    case SIM_ROUTE_WEIGHTED_SPLIT: kernel = ab ? step_kernel_ws(size, dense) : nullptr; break;
     default: break;
   }
   if (!kernel) return SIM_EINVAL;

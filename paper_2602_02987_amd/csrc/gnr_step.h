@@ -251,6 +251,15 @@ __host__ __device__ constexpr int size_class(int threads, int nwords)
 {
   return threads <= 128 ? 0 : threads <= 512 ? 1 : (nwords <= kStaticWordsMedium ? 2 : 3);
 }
+// Waves of an instantiation that are guaranteed to fit a SIMD together (the compiler keeps its registers within
+// 512 / this many). A workgroup of 1024 threads needs four; the smaller classes are compiled twice: roomy, with up
+// to 256 registers and two waves per SIMD, which is fastest while every workgroup of the launch finds a place at
+// that density, and dense, with 128 registers and four waves per SIMD, for launches that would otherwise run their
+// workgroups in more rounds.
+__host__ __device__ constexpr int waves_per_simd(int max_threads, bool dense)
+{
+  return max_threads > 512 || dense ? 4 : 2;
+}
 __host__ __device__ constexpr int static_words(int size_class)
 {
   return size_class <= 1 ? 0 : (size_class == 2 ? kStaticWordsMedium : kStaticWordsLarge);
@@ -460,8 +469,8 @@ struct StepArrays {
 // IM: the variant with immediate same-slot decode (no router): a request whose prefill ends goes on decoding on
 // its own server, placed there by the lane that finishes the server; a server is offered to the gate while it
 // holds no prefill and fewer than B decodes.
-template <int MAXT, int NWS, bool AB, bool RR, bool IM, bool WS = false>
-__global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict__ params, const StepArrays a,
+template <int MAXT, int NWS, bool AB, bool RR, bool IM, bool WS = false, bool DENSE = false>
+__global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(waves_per_simd(MAXT, DENSE)))) gnr_step_kernel(const Params *__restrict__ params, const StepArrays a,
                                                         const uint32_t key0, const uint32_t key1,
                                                         const uint32_t step_begin, const uint32_t n_steps)
 {
@@ -2142,17 +2151,19 @@ __global__ void __launch_bounds__(MAXT) gnr_step_kernel(const Params *__restrict
   if (tid < K) gt[tid * kNTally + SIM_T_TOK_PREF] = gt[tid * kNTally + SIM_T_TOKP_PRE] + L.acc[tid];
 }
 
-// The step kernel of one policy variant for a size class (see size_class). Each variant is compiled in a
-// translation unit of its own.
+// The step kernel of one policy variant for a size class (see size_class), in its roomy or, for the two smaller
+// classes, its dense form (see waves_per_simd). Each variant is compiled in a translation unit of its own.
 using StepKernel = void (*)(const Params *, StepArrays, uint32_t, uint32_t, uint32_t, uint32_t);
 #define GNR_STEP_VARIANT(name, AB, RR, IM, WS)                                                             \
-  StepKernel name(int size_class)                                                                          \
+  StepKernel name(int size_class, bool dense)                                                              \
   {                                                                                                        \
-    static const StepKernel table[4] = {gnr_step_kernel<128, static_words(0), AB, RR, IM, WS>,             \
+    static const StepKernel table[6] = {gnr_step_kernel<128, static_words(0), AB, RR, IM, WS>,             \
                                         gnr_step_kernel<512, static_words(1), AB, RR, IM, WS>,             \
                                         gnr_step_kernel<1024, static_words(2), AB, RR, IM, WS>,            \
-                                        gnr_step_kernel<1024, static_words(3), AB, RR, IM, WS>};           \
-    return table[size_class];                                                                              \
+                                        gnr_step_kernel<1024, static_words(3), AB, RR, IM, WS>,            \
+                                        gnr_step_kernel<128, static_words(0), AB, RR, IM, WS, true>,       \
+                                        gnr_step_kernel<512, static_words(1), AB, RR, IM, WS, true>};      \
+    return table[dense && size_class <= 1 ? 4 + size_class : size_class];                                  \
   }
 
 }  // namespace gnr
