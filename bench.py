@@ -76,12 +76,18 @@ def measured(key):
 
 
 def occupancy(sim, replications, measured_percent):
-    """Waves per SIMD the launch shape allows (256 compute units of 4 SIMDs, 160 KB of LDS, 8 waves per SIMD)."""
+    """Waves per SIMD of the launch (256 compute units of 4 SIMDs, 160 KB of LDS). The step kernel is compiled for four
+    waves per SIMD (128 registers a lane); workgroups of up to 512 threads also exist in a form for two (up to 256
+    registers), which the library launches when every workgroup still finds a place at once."""
     threads, lds = sim.launch_shape()
     waves = threads // 64
-    per_cu = min(160 * 1024 // max(lds, 1), 32 // waves, -(-replications // 256))
+    wanted = -(-replications // 256)
+    by_lds = 160 * 1024 // max(lds, 1)
+    roomy = threads <= 512 and wanted <= min(by_lds, max(8 // waves, 1))
+    per_cu = min(by_lds, max((8 if roomy else 16) // waves, 1), wanted)
     return {"threads_per_workgroup": threads, "lds_bytes_per_workgroup": lds, "workgroups_per_cu": per_cu,
-            "waves_per_simd": waves * per_cu / 4.0, "simd_capacity": 8, "measured_percent": measured_percent,
+            "waves_per_simd": waves * per_cu / 4.0, "waves_per_simd_the_registers_allow": 2 if roomy else 4,
+            "simd_capacity": 8, "measured_percent": measured_percent,
             "source": "launch shape from the library; measured_percent " +
                       (f"stored: rocprofv3 counters, {TRAFFIC['state']}, {TRAFFIC['profile']}" if measured_percent is not None
                        else "not available for these sources (null)")}

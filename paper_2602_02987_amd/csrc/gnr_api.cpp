@@ -113,19 +113,20 @@ int64_t host_hedge(int b)
 
 constexpr size_t kOnChipLimit = 160 * 1024;   // LDS of a compute unit; a replication's workgroup runs there alone
 
-// On-chip bytes the step kernel needs for a configuration with the mixed group at servers 0..M-1.
-size_t on_chip_bytes(const sim_config &c, const Ticks &t, int M)
+// On-chip bytes the step kernel needs for a configuration with the mixed group at servers 0..M-1, in the workgroup
+// size a launch of `reps` replications gets (few replications get the largest workgroups and need most).
+size_t on_chip_bytes(const sim_config &c, const Ticks &t, int M, int reps)
 {
   Params q;
   std::memset(&q, 0, sizeof q);
   q.K = c.K; q.N = c.N; q.Mp = M;
   q.tbt_w = host_hbin(t.c0 + t.cpre * c.C + t.cdec * c.B) - host_hbin(t.c0) + 1;
   q.nwords = (c.N + 63) / 64;
-  q.threads = step_threads(c.N);
   q.route_mode = c.route_mode;   // the weighted router keeps its class selections on chip
   for (int k = 0; k < c.K; ++k)
     if (c.cls[k].theta > 0.0) q.ab_classes |= 1u << k;
   q.dl_rings = q.ab_classes != 0 || c.route_mode == SIM_ROUTE_WEIGHTED_SPLIT;
+  q.threads = step_threads(q, reps);
   return step_lds_bytes(q);
 }
 
@@ -170,7 +171,7 @@ int validate(const sim_config *c, int max_reps, Ticks *t)
   // clocks are compared modulo 2^32 ns on the device: the longest iteration must stay far below 2^31 ns
   if (t->c0 + t->cpre * c->C + t->cdec * c->B > 2000000000ll) return SIM_EINVAL;
   // the per-server records of a replication stay on chip for a whole launch
-  if (on_chip_bytes(*c, *t, c->M) > kOnChipLimit) return SIM_EINVAL;
+  if (on_chip_bytes(*c, *t, c->M, max_reps) > kOnChipLimit) return SIM_EINVAL;
   return SIM_OK;
 }
 
@@ -401,7 +402,7 @@ int create_in(const sim_config *cfg, int max_replications, void *dev_workspace, 
     }
   
     p.self = reinterpret_cast<const Params *>(w + L.params);
-    h->threads = step_threads(cfg->N);
+    h->threads = step_threads(p, max_replications);
     p.threads = h->threads;
     h->lds_bytes = step_lds_bytes(p);
     if (h->lds_bytes > kOnChipLimit) return SIM_EINVAL;
@@ -810,7 +811,7 @@ int sim_onchip_bytes(const sim_config *cfg, size_t *out_bytes, size_t *out_limit
     return SIM_EINVAL;
   t.c0 = std::llround(cfg->c0 * 1e9); t.cpre = std::llround(cfg->c_pre * 1e9); t.cdec = std::llround(cfg->c_dec * 1e9);
   t.dt = t.c0;
-  *out_bytes = on_chip_bytes(*cfg, t, cfg->M);
+  *out_bytes = on_chip_bytes(*cfg, t, cfg->M, 1);
   if (out_limit) *out_limit = kOnChipLimit;
   return SIM_OK;
 }

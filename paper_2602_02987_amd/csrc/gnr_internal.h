@@ -112,7 +112,7 @@ int launch_digest(const Params &p, int reps, void *stream);
 // the library's static device workspace on the current device (address resolved once per device)
 int static_workspace(void **dev_ptr, size_t *bytes);
 size_t step_lds_bytes(const Params &p);
-int step_threads(int N);
+int step_threads(Params q, int reps);   // workgroup size for a launch of `reps` replications (q.threads is not read)
 
 }  // namespace gnr
 #endif

@@ -231,6 +231,6 @@ def test_modulation_period_is_bounded_and_the_weighted_router_counts_its_tables(
     need_ws, _ = B.sim_onchip_bytes(ws)
     need_rr, _ = B.sim_onchip_bytes(rr)
     assert need_rr == base
-    # a one- or two-wave workgroup decides 64 admissions and stages 64 requests per pass: the deadline rings'
-    # candidate table (K x 64 words), 64 x (4 + 2 + 2) bytes of class selections, 8 words of per-class counts
-    assert need_ws == base + cfg.K * 64 * 4 + 64 * 8 + 8 * 4
+    # (the figure is for the largest workgroup the library would launch, here 512 threads) the deadline rings'
+    # candidate table (K x 256 words), 256 x (4 + 2 + 2) bytes of class selections, 8 words of per-class counts
+    assert need_ws == base + cfg.K * 256 * 4 + 256 * 8 + 8 * 4
