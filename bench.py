@@ -25,8 +25,8 @@ HBM_PEAK_GBS = 8000.0
 # occupancy rocprofv3 derives for it. These are STORED figures, not taken in this run: they hold for the kernel
 # sources whose hash is given (compared with the current sources; on a mismatch the figures read null) and for the
 # state named in `state`. The line says so in `roofline.traffic_source` / `roofline.occupancy.source`.
-TRAFFIC = {"sources_sha256": "3f4b9bb724b84e0124ee2326cd11a58fb0f2e552bef3ae3775ea1eac74cc9a75",
-           "bytes_per_launch": 401866645071, "occupancy_percent": 49.10384,
+TRAFFIC = {"sources_sha256": "6bb855f1f358f801d2eea8c7e9a2bdebb5f285e59b1c4d81e8af30caa40ac5b7",
+           "bytes_per_launch": 401866586276, "occupancy_percent": 49.271994,
            "state": "config 5 after 30000 untimed steps, mean of 2 launches of 1000 steps",
            "profile": "profiles/gnr_step_kernel_cfg5_hbm_traffic.md"}
 
