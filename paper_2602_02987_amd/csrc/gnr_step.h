@@ -183,6 +183,8 @@ struct Lds {
   uint16_t *sel_co;   // [kJobsLds] class | (how many selections before it chose the same class) << 3
   uint16_t *sel_j;    // [kJobsLds] list position of each selection, ordered by class, then by order within the class
   int32_t *sel_n;     // [8] requests the pass takes from the solo group's buffer, per class
+  // two-buffer routers only:
+  uint64_t *solo_w;   // [4] per chunk of 64 completed prefills of a round: which of them go to the solo group
 };
 
 // Carves the dynamic LDS block; 8-byte granules. NWS > 0: the arrays indexed by 64-server word are sized for NWS
@@ -240,6 +242,7 @@ __host__ __device__ __forceinline__ Lds lds_carve(const Params &p, unsigned char
   GNR_TAKE(sel_co, uint16_t, p.route_mode == SIM_ROUTE_WEIGHTED_SPLIT ? kJobsLds : 0)
   GNR_TAKE(sel_j, uint16_t, p.route_mode == SIM_ROUTE_WEIGHTED_SPLIT ? kJobsLds : 0)
   GNR_TAKE(sel_n, int32_t, p.route_mode == SIM_ROUTE_WEIGHTED_SPLIT ? 8 : 0)
+  GNR_TAKE(solo_w, uint64_t, p.route_mode == SIM_ROUTE_RANDOM_SPLIT || p.route_mode == SIM_ROUTE_WEIGHTED_SPLIT ? 4 : 0)
 #undef GNR_TAKE
   if (total) *total = off;
   return L;
@@ -1079,8 +1082,10 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(waves
       L.tl[k * kNTally + SIM_T_DROP_P] += a - take;
       if (a > take) L.tl[kMaxK * kNTally + SIM_G_OVERFLOW] = 1;
     }
+    uint32_t ncomp_own = 0;   // (the first wave's count of completed prefills)
     if (tid < 64) {
       const uint32_t ncomp = rank_bitmap(L.bm_comp, L.pre_c, nwords_m, Mp);
+      ncomp_own = ncomp;
       if (tid == 0) {
         L.sc[SC_NCOMP] = static_cast<int32_t>(ncomp);
         if constexpr (AB) {
@@ -1098,6 +1103,42 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(waves
     if (NT == 64 ? tid < 64 : (tid >= 64 && tid < 128)) {
       const uint32_t nidle = rank_bitmap(L.bm_idle, L.pre, nwords_m, M);   // idle prefill slots of the mixed group
       if (lane == 0) L.sc[SC_NIDLE] = static_cast<int32_t>(nidle);
+    }
+    // Two-buffer routers: word 1 of a completed prefill's block picks its group, and its rank within the group's
+    // ring is the number of earlier completions (in server order) sent to the same group. Up to four waves take a
+    // chunk of 64 completions each: before the barrier they fetch the request, draw its block and publish which of
+    // their 64 go to the solo group; after it every chunk knows the counts before it and appends its requests.
+    // What a wave fetched stays in its registers across the barrier.
+    const int chunk_waves = nwaves < 4 ? nwaves : 4, chunk_first = nwaves >= 6 ? 2 : 0;
+    const int my_chunk = wave - chunk_first;
+    const bool chunk_wave = RR && my_chunk >= 0 && my_chunk < chunk_waves;
+    bool c_active = false, c_solo = false;
+    uint64_t c_jw = 0;
+    uint32_t c_dl = kNever;
+    int c_k = 0;
+    auto draw_chunk = [&](uint32_t first, uint32_t ncomp_all) __attribute__((always_inline)) {
+      const uint32_t j = first + 64u * static_cast<uint32_t>(my_chunk) + lane;
+      c_active = j < ncomp_all;
+      c_solo = false;
+      c_dl = kNever;
+      const int g = c_active ? select_bit(L.bm_comp, L.pre_c, nwords_m, j) : 0;
+      c_jw = pf_job[g];   // (slot 0 for the lanes past the end: read, not used)
+      uint32_t w[4];
+      philox4x32_10(key0, key1, s, static_cast<uint32_t>(kStreamPatienceD), static_cast<uint32_t>(g), static_cast<uint32_t>(r), w);
+      c_k = static_cast<int>(c_jw >> 29) & 7;
+      c_solo = c_active && w[1] < p.solo_thr[c_k];
+      if constexpr (AB) {
+        if (c_active && ((p.ab_classes >> c_k) & 1u)) c_dl = s + a.pat_tab[static_cast<size_t>(c_k) * kTableSize + (w[0] >> 16)];
+      }
+      const uint64_t to_solo = __ballot(c_solo);
+      if (lane == 0) L.solo_w[my_chunk] = to_solo;
+    };
+    if constexpr (RR) {
+      if (chunk_wave) {
+        // (each of these waves ranks the completion bitmap itself: the same values as the first wave writes)
+        const uint32_t ncomp_all = wave == 0 ? ncomp_own : rank_bitmap(L.bm_comp, L.pre_c, nwords_m, Mp);
+        draw_chunk(0u, ncomp_all);
+      }
     }
     __syncthreads();
     if constexpr (AB) {
@@ -1157,45 +1198,41 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(waves
     }
     // completed prefills join the decode buffer in ascending server order
     if constexpr (RR) {
-      // randomized router: word 1 of the completion's block picks the group; one wave takes the completions in
-      // order, so the rank of each within its group's ring follows from running counts
-      if (wave == 0) {
-        const uint32_t ncomp = static_cast<uint32_t>(L.sc[SC_NCOMP]);
-        const uint32_t dc0 = static_cast<uint32_t>(L.cs[CS_DCOUNT]), dc1 = static_cast<uint32_t>(L.cs[CS_DCOUNT_M]);
-        const uint32_t dh0 = static_cast<uint32_t>(L.cs[CS_DHEAD]), dh1 = static_cast<uint32_t>(L.cs[CS_DHEAD_M]);
-        // ring entries before the tail (with abandonment the dead entries count)
-        const uint32_t fill0 = AB ? static_cast<uint32_t>(L.sc[SC_DLEN]) : dc0, fill1 = AB ? static_cast<uint32_t>(L.sc[SC_DLEN_M]) : dc1;
-        uint32_t seen0 = 0, seen1 = 0;   // completions sent to either group so far
-        for (uint32_t j0 = 0; j0 < ncomp; j0 += 64) {   // wave-uniform
-          const uint32_t j = j0 + lane;
-          const bool active = j < ncomp;
-          int k = 0;
-          bool solo = false;
-          uint64_t jw = 0;
-          uint32_t dl = kNever;
-          if (active) {
-            const int g = select_bit(L.bm_comp, L.pre_c, nwords_m, j);
-            jw = pf_job[g];
-            k = static_cast<int>(jw >> 29) & 7;
-            uint32_t w[4];
-            philox4x32_10(key0, key1, s, static_cast<uint32_t>(kStreamPatienceD), static_cast<uint32_t>(g),
-                          static_cast<uint32_t>(r), w);
-            solo = w[1] < p.solo_thr[k];
-            if constexpr (AB) {
-              if ((p.ab_classes >> k) & 1u) dl = s + a.pat_tab[static_cast<size_t>(k) * kTableSize + (w[0] >> 16)];
-            }
-          }
+      const uint32_t ncomp = static_cast<uint32_t>(L.sc[SC_NCOMP]);
+      const uint32_t dc0 = static_cast<uint32_t>(L.cs[CS_DCOUNT]), dc1 = static_cast<uint32_t>(L.cs[CS_DCOUNT_M]);
+      const uint32_t dh0 = static_cast<uint32_t>(L.cs[CS_DHEAD]), dh1 = static_cast<uint32_t>(L.cs[CS_DHEAD_M]);
+      // ring entries before the tail (with abandonment the dead entries count)
+      const uint32_t fill0 = AB ? static_cast<uint32_t>(L.sc[SC_DLEN]) : dc0, fill1 = AB ? static_cast<uint32_t>(L.sc[SC_DLEN_M]) : dc1;
+      uint32_t seen0 = 0, seen1 = 0;   // completions sent to either group in the rounds before this one
+      const uint32_t per_round = 64u * static_cast<uint32_t>(chunk_waves);
+      for (uint32_t first = 0; first < ncomp; first += per_round) {   // wave-uniform; one round is the rule
+        if (first > 0) {
+          __syncthreads();   // every wave has read the words of the round before
+          if (chunk_wave) draw_chunk(first, ncomp);
+          __syncthreads();
+        }
+        uint32_t solo_before = 0, solo_round = 0;   // in the chunks before this wave's, in the whole round
+        for (int c = 0; c < chunk_waves; ++c) {
+          const uint32_t n = static_cast<uint32_t>(__popcll(L.solo_w[c]));
+          if (c < my_chunk) solo_before += n;
+          solo_round += n;
+        }
+        const uint32_t in_round = ncomp - first < per_round ? ncomp - first : per_round;
+        if (chunk_wave && 64u * static_cast<uint32_t>(my_chunk) < in_round) {   // wave-uniform
+          const bool active = c_active, solo = c_solo;
+          const int k = c_k;
           const uint64_t bal0 = __ballot(active && solo), bal1 = __ballot(active && !solo);
-          const uint32_t idx = solo ? seen0 + static_cast<uint32_t>(__popcll(bal0 & lanes_below()))
-                                    : seen1 + static_cast<uint32_t>(__popcll(bal1 & lanes_below()));
+          // (the chunks before this one are full)
+          const uint32_t idx = solo ? seen0 + solo_before + static_cast<uint32_t>(__popcll(bal0 & lanes_below()))
+                                    : seen1 + (64u * static_cast<uint32_t>(my_chunk) - solo_before) + static_cast<uint32_t>(__popcll(bal1 & lanes_below()));
           const bool kept = active && (solo ? dc0 : dc1) + idx < dbuf_cap;
           if (kept) {
             uint32_t pos = (solo ? dh0 + fill0 : dh1 + fill1) + idx;
             if (pos >= dbuf_cap) pos -= dbuf_cap;
-            (solo ? dring : dring_m)[pos] = jw;
+            (solo ? dring : dring_m)[pos] = c_jw;
             if constexpr (AB) {
-              (solo ? ddl : ddl_m)[pos] = dl;
-              if (dl != kNever) atomicAdd(&(solo ? dcal : dcal_m)[static_cast<size_t>(k) * cal_n + (dl & p.cal_mask)], 1u);
+              (solo ? ddl : ddl_m)[pos] = c_dl;
+              if (c_dl != kNever) atomicAdd(&(solo ? dcal : dcal_m)[static_cast<size_t>(k) * cal_n + (c_dl & p.cal_mask)], 1u);
             }
           }
           wave_count_by_class_i32(kept, k, K, &L.cs[CS_QD], 1);
@@ -1206,14 +1243,14 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(waves
             wave_count_by_class(active && !kept, k, K, &L.tl[SIM_T_DROP_D], kNTally);
             if (lane == 0) L.tl[kMaxK * kNTally + SIM_G_OVERFLOW] = 1;
           }
-          seen0 += static_cast<uint32_t>(__popcll(bal0));
-          seen1 += static_cast<uint32_t>(__popcll(bal1));
         }
-        if (lane == 0) {   // what each ring accepted (a prefix of what it was sent)
-          const uint32_t room0 = dbuf_cap - dc0, room1 = dbuf_cap - dc1;
-          L.sc[SC_NCS] = static_cast<int32_t>(seen0 < room0 ? seen0 : room0);
-          L.sc[SC_NCM] = static_cast<int32_t>(seen1 < room1 ? seen1 : room1);
-        }
+        seen0 += solo_round;
+        seen1 += in_round - solo_round;
+      }
+      if (tid == 0) {   // what each ring accepted (a prefix of what it was sent)
+        const uint32_t room0 = dbuf_cap - dc0, room1 = dbuf_cap - dc1;
+        L.sc[SC_NCS] = static_cast<int32_t>(seen0 < room0 ? seen0 : room0);
+        L.sc[SC_NCM] = static_cast<int32_t>(seen1 < room1 ? seen1 : room1);
       }
       __syncthreads();
     } else {
