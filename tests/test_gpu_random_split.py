@@ -50,9 +50,10 @@ def test_planned_split_on_the_binding_capacity_instance(B, oracle_mod):
 
 
 def test_every_workgroup_shape_with_the_randomized_router(B, oracle_mod):
-    """One, two, eight and sixteen waves; routing passes that take jobs from both rings, more jobs than a pass
+    """One, two, four, eight and sixteen waves; routing passes that take jobs from both rings, more jobs than a pass
     stages, several gate passes per step beside routing to the mixed group, full groups and long buffers."""
-    for N, M, Bcap, steps, lam, ps in ((60, 20, 8, 1500, (2.2, 1.8), (0.6, 0.4)), (700, 200, 8, 600, (2.2, 1.8), (0.6, 0.4)),
+    for N, M, Bcap, steps, lam, ps in ((60, 20, 8, 1500, (2.2, 1.8), (0.6, 0.4)), (100, 30, 8, 1200, (2.2, 1.8), (0.6, 0.4)),
+                                       (200, 60, 8, 1000, (2.2, 1.8), (0.6, 0.4)), (700, 200, 8, 600, (2.2, 1.8), (0.6, 0.4)),
                                        (4000, 1500, 8, 200, (2.4, 2.0), (0.7, 0.2)),
                                        (8192, 5000, 8, 60, (2.5, 2.0), (0.5, 0.5)),
                                        (8192, 300, 2, 300, (2.5, 2.0), (0.9, 0.8))):

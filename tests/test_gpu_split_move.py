@@ -90,3 +90,23 @@ def test_online_adaptive_loop_in_step_with_the_oracle(B, oracle_mod):
     for r in range(cfg.replications):
         assert_replication_equal(sim, orc, r, what="online loop")
     assert_stats_equal(sim.stats(), orc.stats())
+
+
+def test_a_burst_of_completed_prefills_larger_than_one_round(B, oracle_mod):
+    """The two-buffer routers take the completed prefills of a step 64 to a wave, in rounds of up to four waves.
+    Queues fill while no server admits (M = 0); then many servers turn mixed at once, admit in the same step (several
+    gate passes) and end their one-chunk prefills in the same step: 1200 completions in a step for eight-wave
+    workgroups (five rounds), 500 for two-wave workgroups (four rounds), also with a decode buffer too small for them,
+    with abandonment and with the weighted router."""
+    cls = [_limits_class(lam=2.4, out_p0=300.0), _limits_class(lam=2.0, in_p0=40.0, out_p0=500.0)]
+    base = _limits_cfg("burst", cls, N=1500, M=0, B=8, steps=100, replications=1, dbuf_cap=4096, queue_cap=8192)
+    rr = replace(base, route_mode=W.ROUTE_RANDOM_SPLIT, p_solo=[0.6, 0.3])
+    ab = replace(rr, classes=[replace(c, theta=th) for c, th in zip(rr.classes, (2.0, 0.5))])
+    ws = replace(ab, route_mode=W.ROUTE_WEIGHTED_SPLIT, w_solo=[0.7, 0.3], w_mixed=[0.2, 0.8])
+    moves = [(None, 40), (1200, 6), (100, 20), (1400, 8)]
+    for cfg in (rr, replace(rr, name="burst-small-buffer", dbuf_cap=512), ab, ws):
+        sim, orc = _run_moves(B, oracle_mod, cfg, moves)
+        t, _ = orc.tallies(0)
+        assert t[:, TI["S_P"]].sum() > 1500, cfg.name   # the bursts went through
+    many = replace(rr, name="burst-two-waves", N=600, replications=1500)
+    _run_moves(B, oracle_mod, many, [(None, 40), (500, 6), (50, 10)], oracle_reps=[0, 749, 1499])
