@@ -246,6 +246,13 @@ int sim_kernel_time(sim_t *h, int64_t *launches, double *milliseconds, int reset
 /* Launch shape of the step kernel for this handle: threads per workgroup (one workgroup per replication) and
  * dynamic LDS bytes per workgroup; what occupancy follows from. Host only; either pointer may be NULL. */
 int sim_launch_shape(sim_t *h, int *threads, size_t *lds_bytes);
+/* The launch shape the library gives `replications` replications of `cfg` (what sim_create(cfg, replications, ...)
+ * fixes for the handle): threads per workgroup, LDS bytes per workgroup, and the waves per SIMD the chosen form of
+ * the kernel is compiled for (4: 128 registers a lane; 2: up to 256, for workgroups of up to 512 threads when all of
+ * them find a place at once at that density). A replication is one workgroup that runs for the whole launch, so the
+ * shape is the largest workgroup that keeps the rounds of workgroups lowest on the current device (256 compute units
+ * are assumed when there is none). Host only; any out pointer may be NULL. SIM_EINVAL as for sim_create. */
+int sim_launch_plan(const sim_config *cfg, int replications, int *threads, size_t *lds_bytes, int *waves_per_simd);
 
 int sim_destroy(sim_t *h);
 const char *sim_strerror(int err);

@@ -80,6 +80,7 @@ def lib():
         L.sim_strerror.restype = C.c_char_p
         L.sim_workspace_bytes.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_size_t)]
         L.sim_onchip_bytes.argtypes = [C.c_void_p, C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
+        L.sim_launch_plan.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_size_t), C.POINTER(C.c_int)]
         L.sim_launch_shape.argtypes = [C.c_void_p, C.POINTER(C.c_int), C.POINTER(C.c_size_t)]
         L.sim_create.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.POINTER(C.c_void_p)]
         L.sim_create_static.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_void_p)]
@@ -154,6 +155,15 @@ def sim_onchip_bytes(cfg):
     n, lim = C.c_size_t(0), C.c_size_t(0)
     _check(lib().sim_onchip_bytes(C.byref(cc), C.byref(n), C.byref(lim)), "sim_onchip_bytes")
     return n.value, lim.value
+
+
+def sim_launch_plan(cfg, replications=None):
+    """(threads per workgroup, LDS bytes per workgroup, waves per SIMD of the kernel form) for a launch; host only."""
+    cc, _keep = marshal_config(cfg)
+    t, n, w = C.c_int(0), C.c_size_t(0), C.c_int(0)
+    _check(lib().sim_launch_plan(C.byref(cc), cfg.replications if replications is None else replications,
+                                 C.byref(t), C.byref(n), C.byref(w)), "sim_launch_plan")
+    return t.value, n.value, w.value
 
 
 def sim_workspace_bytes(cfg, max_replications):

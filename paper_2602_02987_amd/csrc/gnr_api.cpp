@@ -113,9 +113,9 @@ int64_t host_hedge(int b)
 
 constexpr size_t kOnChipLimit = 160 * 1024;   // LDS of a compute unit; a replication's workgroup runs there alone
 
-// On-chip bytes the step kernel needs for a configuration with the mixed group at servers 0..M-1, in the workgroup
-// size a launch of `reps` replications gets (few replications get the largest workgroups and need most).
-size_t on_chip_bytes(const sim_config &c, const Ticks &t, int M, int reps)
+// What decides the step kernel's launch shape, for a configuration with the mixed group at servers 0..M-1 and a
+// launch of `reps` replications (few replications get the largest workgroups, which need most on-chip bytes).
+Params shape_params(const sim_config &c, const Ticks &t, int M, int reps)
 {
   Params q;
   std::memset(&q, 0, sizeof q);
@@ -127,7 +127,12 @@ size_t on_chip_bytes(const sim_config &c, const Ticks &t, int M, int reps)
     if (c.cls[k].theta > 0.0) q.ab_classes |= 1u << k;
   q.dl_rings = q.ab_classes != 0 || c.route_mode == SIM_ROUTE_WEIGHTED_SPLIT;
   q.threads = step_threads(q, reps);
-  return step_lds_bytes(q);
+  return q;
+}
+
+size_t on_chip_bytes(const sim_config &c, const Ticks &t, int M, int reps)
+{
+  return step_lds_bytes(shape_params(c, t, M, reps));
 }
 
 int validate(const sim_config *c, int max_reps, Ticks *t)
@@ -814,6 +819,23 @@ int sim_onchip_bytes(const sim_config *cfg, size_t *out_bytes, size_t *out_limit
   *out_bytes = on_chip_bytes(*cfg, t, cfg->M, 1);
   if (out_limit) *out_limit = kOnChipLimit;
   return SIM_OK;
+}
+
+int sim_launch_plan(const sim_config *cfg, int replications, int *threads, size_t *lds_bytes, int *waves_per_simd)
+{
+  try {
+    Ticks t;
+    const int rc = validate(cfg, replications, &t);
+    if (rc != SIM_OK) return rc;
+    const Params q = shape_params(*cfg, t, cfg->M, replications);
+    const size_t lds = step_lds_bytes(q);
+    if (threads) *threads = q.threads;
+    if (lds_bytes) *lds_bytes = lds;
+    if (waves_per_simd) *waves_per_simd = q.threads > 512 || step_dense(replications, q.threads, lds) ? 4 : 2;
+    return SIM_OK;
+  } catch (...) {
+    return SIM_ENOMEM;
+  }
 }
 
 int sim_abi_sizes(size_t *out4)

@@ -112,7 +112,8 @@ int launch_digest(const Params &p, int reps, void *stream);
 // the library's static device workspace on the current device (address resolved once per device)
 int static_workspace(void **dev_ptr, size_t *bytes);
 size_t step_lds_bytes(const Params &p);
-int step_threads(Params q, int reps);   // workgroup size for a launch of `reps` replications (q.threads is not read)
+int step_threads(Params q, int reps);
+bool step_dense(int reps, int threads, size_t lds_bytes);   // whether such a launch takes the four-waves-per-SIMD form of a small size class   // workgroup size for a launch of `reps` replications (q.threads is not read)
 
 }  // namespace gnr
 #endif

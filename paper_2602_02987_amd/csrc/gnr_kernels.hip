@@ -49,6 +49,12 @@ static int launch_rounds(int reps, int threads, size_t lds_bytes, int per_simd)
   return (reps + at_once - 1) / at_once;
 }
 
+bool step_dense(int reps, int threads, size_t lds_bytes)
+{
+  return threads <= 512 && launch_rounds(reps, threads, lds_bytes, waves_per_simd(threads, true)) <
+                               launch_rounds(reps, threads, lds_bytes, waves_per_simd(threads, false));
+}
+
 int step_threads(Params q, int reps)
 {
   // A replication with many servers fills the LDS of a compute unit, runs alone there and wants all sixteen
@@ -246,8 +252,7 @@ int launch_steps(const Params &p, int reps, int threads, size_t lds_bytes, uint3
   // The roomy form of a small size class holds two waves per SIMD, the dense form four: the dense one is taken when
   // the launch then needs fewer rounds of workgroups (every workgroup runs for the whole launch, so a workgroup
   // that finds no place at first waits for another to end).
-  const bool dense = size <= 1 && launch_rounds(reps, threads, lds_bytes, waves_per_simd(threads, true)) <
-                                     launch_rounds(reps, threads, lds_bytes, waves_per_simd(threads, false));
+  const bool dense = step_dense(reps, threads, lds_bytes);
   StepKernel kernel = nullptr;
   switch (p.route_mode) {
     case SIM_ROUTE_SOLO_FIRST: kernel = ab ? step_kernel_ab(size, dense) : step_kernel_plain(size, dense); break;

@@ -230,7 +230,31 @@ def test_modulation_period_is_bounded_and_the_weighted_router_counts_its_tables(
     rr = W.with_random_split(W.config(5, N=300, replications=1), lam_plan=[c.lam / 0.95 for c in cfg.classes])
     need_ws, _ = B.sim_onchip_bytes(ws)
     need_rr, _ = B.sim_onchip_bytes(rr)
-    assert need_rr == base
+    assert need_rr == base + 4 * 8              # the group words of four chunks of completed prefills
     # (the figure is for the largest workgroup the library would launch, here 512 threads) the deadline rings'
     # candidate table (K x 256 words), 256 x (4 + 2 + 2) bytes of class selections, 8 words of per-class counts
-    assert need_ws == base + cfg.K * 256 * 4 + 256 * 8 + 8 * 4
+    assert need_ws == need_rr + cfg.K * 256 * 4 + 256 * 8 + 8 * 4
+
+
+def test_launch_shape_follows_the_replications():
+    """A replication is one workgroup that lives for the whole launch: the library takes the largest workgroup that
+    keeps the rounds of workgroups lowest (256 compute units, four waves a SIMD at most, LDS) and the roomy form of
+    the kernel (two waves a SIMD) unless the dense one saves a round. Without a device 256 compute units are assumed."""
+    from paper_2602_02987_amd import binding as B, workloads as W
+    plan = lambda n, **over: B.sim_launch_plan(W.config(n, **over))
+    assert plan(1)[0::2] == (64, 2)                        # 8 servers: one block, one wave
+    assert plan(2)[0::2] == (256, 4)                       # 4 blocks, 1024 replications: four per compute unit
+    assert plan(2, replications=2048)[0::2] == (128, 4)    # eight two-wave workgroups per compute unit
+    assert plan(2, replications=256)[0::2] == (256, 2)     # one per compute unit: room for the form with more registers
+    assert plan(3)[0::2] == (128, 4) and plan(3)[1] == 20112
+    assert plan(3, replications=1024)[0::2] == (256, 4)
+    assert plan(3, replications=512)[0::2] == (512, 4)
+    assert plan(3, replications=256)[0::2] == (512, 2)
+    assert plan(4)[0::2] == (256, 4)
+    assert plan(4, replications=2048)[0::2] == (256, 4)    # the LDS holds four per compute unit: two rounds either way
+    assert plan(5) == (1024, 148368, 4)
+    for n in (1, 2, 3, 4, 5):                              # eight of the smallest workgroups share a compute unit
+        t, lds, w = plan(n)
+        assert lds <= 160 * 1024 and t in (64, 128, 256, 512, 1024) and w in (2, 4)
+    # what a handle is created with is what the plan says (no device: compared through the on-chip need)
+    assert B.sim_onchip_bytes(W.config(3))[0] == B.sim_launch_plan(W.config(3), 1)[1]
