@@ -25,8 +25,8 @@ HBM_PEAK_GBS = 8000.0
 # occupancy rocprofv3 derives for it. These are STORED figures, not taken in this run: they hold for the kernel
 # sources whose hash is given (compared with the current sources; on a mismatch the figures read null) and for the
 # state named in `state`. The line says so in `roofline.traffic_source` / `roofline.occupancy.source`.
-TRAFFIC = {"sources_sha256": "6bb855f1f358f801d2eea8c7e9a2bdebb5f285e59b1c4d81e8af30caa40ac5b7",
-           "bytes_per_launch": 401866586276, "occupancy_percent": 49.271994,
+TRAFFIC = {"sources_sha256": "119b1700b68703b27f2fb2bfb70b17f4a34d34ce83a6cbf1ffe58280d60872bb",
+           "bytes_per_launch": 401846133144, "occupancy_percent": 49.352839,
            "state": "config 5 after 30000 untimed steps, mean of 2 launches of 1000 steps",
            "profile": "profiles/gnr_step_kernel_cfg5_hbm_traffic.md"}
 
@@ -75,20 +75,18 @@ def measured(key):
     return TRAFFIC[key] if TRAFFIC["sources_sha256"] == sources_hash() else None
 
 
-def occupancy(sim, replications, measured_percent):
-    """Waves per SIMD of the launch (256 compute units of 4 SIMDs, 160 KB of LDS). The step kernel is compiled for four
-    waves per SIMD (128 registers a lane); workgroups of up to 512 threads also exist in a form for two (up to 256
-    registers), which the library launches when every workgroup still finds a place at once."""
+def occupancy(binding, cfg, sim, replications, measured_percent):
+    """Waves per SIMD of the launch (256 compute units of 4 SIMDs, 160 KB of LDS). The library says which form of the
+    step kernel it launches: the one compiled for four waves per SIMD (128 registers a lane) or, for workgroups of up
+    to 512 threads that all find a place at once at that density, the one for two (up to 256 registers)."""
     threads, lds = sim.launch_shape()
+    _, _, per_simd = binding.sim_launch_plan(cfg, replications)
     waves = threads // 64
-    wanted = -(-replications // 256)
-    by_lds = 160 * 1024 // max(lds, 1)
-    roomy = threads <= 512 and wanted <= min(by_lds, max(8 // waves, 1))
-    per_cu = min(by_lds, max((8 if roomy else 16) // waves, 1), wanted)
+    per_cu = min(160 * 1024 // max(lds, 1), max(4 * per_simd // waves, 1), -(-replications // 256))
     return {"threads_per_workgroup": threads, "lds_bytes_per_workgroup": lds, "workgroups_per_cu": per_cu,
-            "waves_per_simd": waves * per_cu / 4.0, "waves_per_simd_the_registers_allow": 2 if roomy else 4,
+            "waves_per_simd": waves * per_cu / 4.0, "waves_per_simd_the_registers_allow": per_simd,
             "simd_capacity": 8, "measured_percent": measured_percent,
-            "source": "launch shape from the library; measured_percent " +
+            "source": "launch shape and kernel form from the library; measured_percent " +
                       (f"stored: rocprofv3 counters, {TRAFFIC['state']}, {TRAFFIC['profile']}" if measured_percent is not None
                        else "not available for these sources (null)")}
 
@@ -271,7 +269,7 @@ def main():
                      "traffic_source": (f"stored: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, {TRAFFIC['state']}, sources sha256 "
                                         f"{TRAFFIC['sources_sha256'][:12]}, {TRAFFIC['profile']}" if traffic is not None else
                                         "none: no counter run on these sources and this workload (null)"),
-                     "occupancy": occupancy(sim, cfg.replications, measured("occupancy_percent") if default_run else None),
+                     "occupancy": occupancy(binding, cfg, sim, cfg.replications, measured("occupancy_percent") if default_run else None),
                      "kernel": "gnr_step_kernel", "launches": launches, "avg_launch_ms": per_launch_ms,
                      "algorithmic_bytes_per_launch": total_bytes / max(launches, 1), **shape},
     }
