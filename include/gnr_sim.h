@@ -269,8 +269,9 @@ int sim_thresholds(const sim_config *cfg, int64_t rows, uint32_t *arr_thr, uint3
  * within. The clocks, iteration counters and decode counts of all N servers of a replication stay on chip for
  * a whole launch (about 11.4 bytes per server, 2 more per mixed-group server, 6 KB more with abandonment, on top
  * of about 28 KB): sim_workspace_bytes and sim_create return SIM_EINVAL for a configuration above the limit, and
- * sim_set_split for a split that would exceed it. Host only; reads K, N, M, B, C, c0, c_pre, c_dec and the
- * classes' theta. `out_limit` may be NULL. */
+ * sim_set_split for a split that would exceed it. The figure is for the largest workgroup the library would launch
+ * the configuration with (the one it takes for few replications; see sim_launch_plan for a given count). Host only;
+ * reads K, N, M, B, C, c0, c_pre, c_dec, route_mode and the classes' theta. `out_limit` may be NULL. */
 int sim_onchip_bytes(const sim_config *cfg, size_t *out_bytes, size_t *out_limit);
 /* sizeof of the four ABI structs, in the order class, config, stats, state (for binding checks). */
 int sim_abi_sizes(size_t *out4);
