@@ -1825,15 +1825,24 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(waves
                 if (wave >= ring_wave && wave < ring_wave + n_ring) cw = nwords;   // nothing to count
               }
             }
+            // In a sixteen-wave workgroup the first waves also rank the gate's candidates, the first four most of
+            // them: the words are dealt out in runs of unequal length (4 : 7 : 11 : 17 per wave of each quarter).
+            int w_lo = cw, w_hi = nwords, w_next = cn;
+            if (!kStageEarly && nwaves == 16 && gate_on) {
+              auto run_start = [](int i) { return i < 4 ? 4 * i : i < 8 ? 16 + 7 * (i - 4) : i < 12 ? 44 + 11 * (i - 8) : 88 + 17 * (i - 12); };
+              w_lo = nwords * run_start(wave) / 156;
+              w_hi = nwords * run_start(wave + 1) / 156;
+              w_next = 1;
+            }
             // four blocks per round: their decode counts are read together, then compared level by level
-            for (int w0 = cw; w0 < nwords; w0 += 4 * cn) {
+            for (int w0 = w_lo; w0 < w_hi; w0 += 4 * w_next) {
               int tmin4[4], tend4[4];
 #pragma unroll
               for (int u = 0; u < 4; ++u) {
-                const int wi = w0 + u * cn;
+                const int wi = w0 + u * w_next;
                 const int g = (wi << 6) + lane;
                 tmin4[u] = 0; tend4[u] = 0;
-                if (wi < nwords && g < N) {
+                if (wi < w_hi && g < N) {
                   const int gi = g >= M ? 0 : 1;
                   const int first = gi == 0 ? 0 : nG[0];
                   const int d = static_cast<int>(L.loads[g]) - (gi == 0 ? lminG[0] : lminG[1]);
@@ -1843,8 +1852,8 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(waves
               }
 #pragma unroll
               for (int u = 0; u < 4; ++u) {
-                const int wi = w0 + u * cn;
-                if (wi < nwords) {   // wave-uniform
+                const int wi = w0 + u * w_next;
+                if (wi < w_hi) {   // wave-uniform
 #pragma unroll
                   for (int t = 0; t < kRouteLevels; ++t) {
                     if (t < nl) {
