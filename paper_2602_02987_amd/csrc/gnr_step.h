@@ -1257,7 +1257,10 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(waves
       const uint32_t ncomp = static_cast<uint32_t>(L.sc[SC_NCOMP]);
       const uint32_t dcount = static_cast<uint32_t>(L.cs[CS_DCOUNT]), dhead = static_cast<uint32_t>(L.cs[CS_DHEAD]);
       const uint32_t dfill = AB ? static_cast<uint32_t>(L.sc[SC_DLEN]) : dcount;   // ring entries before the tail
-      for (uint32_t j0 = wave_base; j0 < ncomp; j0 += NT) {   // wave-uniform trip count
+      // (64 to a wave; in a large workgroup not the first waves, which have ranked the bitmaps and go on to rank the
+      // gate's candidates: the last waves, or with abandonment, whose arrivals the last two waves take, the ones before them)
+      const int comp_turn = nwaves < 8 ? wave : (AB ? (2 * nwaves - 3 - wave) % nwaves : nwaves - 1 - wave);
+      for (uint32_t j0 = static_cast<uint32_t>(comp_turn) * 64u; j0 < ncomp; j0 += NT) {   // wave-uniform trip count
         const uint32_t j = j0 + lane;
         const bool active = j < ncomp;
         int k = 0;
