@@ -1873,55 +1873,34 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(waves
 
         // ---------------- segment B ----------------
         bool gate_more = false;
+        bool a_active = false;   // this lane's admission of the pass: slot, class, arrival stamp, decodes beside it
+        int a_g = 0, a_k = 0;
+        uint32_t a_stamp = 0;
+        uint64_t a_nc = 0;
         if (gate_on) {
           if (pass == 0 && tid == 0) {   // the completions of this step are in the buffer
             if constexpr (RR) { L.cs[CS_DCOUNT] = jremL[0]; L.cs[CS_DCOUNT_M] = jremL[1]; }
             else L.cs[CS_DCOUNT] = jrem;
           }
-          // admission j goes to the idle prefill slot of rank j; one thread per admission
-          for (int j0 = wave_base; j0 < nadm; j0 += NT) {   // wave-uniform trip count
-            const int j = j0 + lane;
-            const bool active = j < nadm;
-            int k = 0;
-            uint64_t wait = 0, nc = 0;
-            if (active) {
-              const int g = L.adm_slot[j];
+          // Admission j goes to the idle prefill slot of rank j; one thread per admission (a pass admits no more than
+          // the workgroup has threads). Here the wave only reads what segment C changes (queue heads, decode
+          // counts of the servers) and asks memory for the request's stamp; the rest follows in segment C.
+          if (wave_base < nadm) {   // wave-uniform
+            const int j = wave_base + lane;
+            a_active = j < nadm;
+            if (a_active) {
+              a_g = L.adm_slot[j];
               const uint32_t e = L.adm[j];
-              k = static_cast<int>(e & 7u);
-              uint32_t pos = static_cast<uint32_t>(L.cs[CS_QHEAD + k]) + (AB ? L.live_off[k * kAdmChunk + (e >> 3)] : (e >> 3));
+              a_k = static_cast<int>(e & 7u);
+              uint32_t pos = static_cast<uint32_t>(L.cs[CS_QHEAD + a_k]) + (AB ? L.live_off[a_k * kAdmChunk + (e >> 3)] : (e >> 3));
               if (pos >= queue_cap) pos -= queue_cap;
-              const uint32_t stamp = qring[static_cast<size_t>(k) * queue_cap + pos];
+              a_stamp = qring[static_cast<size_t>(a_k) * queue_cap + pos];
               if constexpr (AB) {   // the request no longer waits: it leaves the calendar of its deadline
-                const uint32_t dl = qdl[static_cast<size_t>(k) * queue_cap + pos];
-                if (dl != kNever) atomicSub(&cal[static_cast<size_t>(k) * cal_n + (dl & p.cal_mask)], 1u);
+                const uint32_t dl = qdl[static_cast<size_t>(a_k) * queue_cap + pos];
+                if (dl != kNever) atomicSub(&cal[static_cast<size_t>(a_k) * cal_n + (dl & p.cal_mask)], 1u);
               }
-              if (L.loads[g]) nc = n_cls[g];
-              wait = static_cast<uint64_t>(s - stamp);
-              uint32_t w[4];
-              philox4x32_10(key0, key1, s, 1u, static_cast<uint32_t>(g), static_cast<uint32_t>(r), w);
-              const uint32_t Pl = a.len_tab[(static_cast<size_t>(k) * 2 + 0) * kTableSize + (w[0] >> 16)];
-              const uint32_t Dl = a.len_tab[(static_cast<size_t>(k) * 2 + 1) * kTableSize + (w[1] >> 16)];
-              pf_job[g] = static_cast<uint64_t>(stamp) | (static_cast<uint64_t>(k) << 29) |
-                          (static_cast<uint64_t>(Pl - 1) << 32) | (static_cast<uint64_t>(Dl - 1) << 48);
-              // an idle prefill slot implies that the running iteration holds no chunk
-              L.rem[g] = static_cast<uint16_t>(Pl);
-              const uint64_t bit = 1ull << (g & 63);
-              // at an iteration boundary the next iteration carries a chunk: tally the untallied ones first
-              if ((L.bm_busy[g >> 6] & bit) && (L.bm_due[g >> 6] & bit) && L.pend[g])
-                atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_flush[g >> 6]), bit);
+              if (L.loads[a_g]) a_nc = n_cls[a_g];   // (before this pass's placements on the server)
             }
-            wave_sum_by_class(active, k, K, wait, &L.tl[SIM_T_WAIT_STEPS], kNTally);
-            uint64_t even, odd;   // co-resident decodes switch solo -> mixed
-            wave_sum_bytes(nc, even, odd);
-            if (lane == 0 && (even | odd))
-              for (int c = 0; c < K; ++c) {
-                const int v = static_cast<int>(class_field(even, odd, c));
-                if (v) {
-                  lds_add64(&L.tl[c * kNTally + SIM_T_M_SM], static_cast<uint64_t>(v));
-                  atomicSub(&L.cs[CS_YS + c], v);
-                  atomicAdd(&L.cs[CS_YM + c], v);
-                }
-              }
           }
           if (nadm == kAdmChunk && nidle > kAdmChunk) {   // rare: more idle slots than one pass serves
             for (int k = 0; k < K; ++k) {
@@ -1967,6 +1946,37 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(waves
         __syncthreads();
 
         // ---------------- segment C ----------------
+        if (gate_on && wave_base < nadm) {   // wave-uniform: the admissions this wave began in segment B
+          uint64_t wait = 0;
+          if (a_active) {
+            const int g = a_g, k = a_k;
+            wait = static_cast<uint64_t>(s - a_stamp);
+            uint32_t w[4];
+            philox4x32_10(key0, key1, s, 1u, static_cast<uint32_t>(g), static_cast<uint32_t>(r), w);
+            const uint32_t Pl = a.len_tab[(static_cast<size_t>(k) * 2 + 0) * kTableSize + (w[0] >> 16)];
+            const uint32_t Dl = a.len_tab[(static_cast<size_t>(k) * 2 + 1) * kTableSize + (w[1] >> 16)];
+            pf_job[g] = static_cast<uint64_t>(a_stamp) | (static_cast<uint64_t>(k) << 29) |
+                        (static_cast<uint64_t>(Pl - 1) << 32) | (static_cast<uint64_t>(Dl - 1) << 48);
+            // an idle prefill slot implies that the running iteration holds no chunk
+            L.rem[g] = static_cast<uint16_t>(Pl);
+            const uint64_t bit = 1ull << (g & 63);
+            // at an iteration boundary the next iteration carries a chunk: tally the untallied ones first
+            if ((L.bm_busy[g >> 6] & bit) && (L.bm_due[g >> 6] & bit) && L.pend[g])
+              atomicOr(reinterpret_cast<unsigned long long *>(&L.bm_flush[g >> 6]), bit);
+          }
+          wave_sum_by_class(a_active, a_k, K, wait, &L.tl[SIM_T_WAIT_STEPS], kNTally);
+          uint64_t even, odd;   // co-resident decodes switch solo -> mixed
+          wave_sum_bytes(a_nc, even, odd);
+          if (lane == 0 && (even | odd))
+            for (int c = 0; c < K; ++c) {
+              const int v = static_cast<int>(class_field(even, odd, c));
+              if (v) {
+                lds_add64(&L.tl[c * kNTally + SIM_T_M_SM], static_cast<uint64_t>(v));
+                atomicSub(&L.cs[CS_YS + c], v);
+                atomicAdd(&L.cs[CS_YM + c], v);
+              }
+            }
+        }
         if (gate_on && tid < K) {   // class counters follow the admissions of this pass
           const int k = tid, adm_k = L.sc[SC_ADMK + k];
           // ring entries the head moves past: the admitted requests; with abandonment also the dead entries
