@@ -1599,7 +1599,7 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(waves
         };
 
         // ---------------- segment A ----------------
-        int nadm = 0, nidle = 0;
+        int nadm = 0, nidle = 0, ncand_pass = 0;
         if (gate_on) {
           nidle = __builtin_amdgcn_readfirstlane(L.sc[SC_NIDLE]);
           const int limit = nidle < kAdmChunk ? nidle : kAdmChunk;
@@ -1617,6 +1617,7 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(waves
             ncand += cnt[k];
           }
           nadm = ncand < limit ? ncand : limit;
+          ncand_pass = ncand;
           if constexpr (AB) {
             // where the candidates sit in their rings: a wave per class walks from the head past the dead entries
             // (the last waves take this: the first ones rank the candidates below)
@@ -1829,10 +1830,11 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(waves
               }
             }
             // In a sixteen-wave workgroup the first waves also rank the gate's candidates, the first four most of
-            // them: the words are dealt out in runs of unequal length (4 : 7 : 11 : 17 per wave of each quarter).
+            // them: when there are candidates for four waves or more, the words are dealt out in runs of unequal
+            // length (2 : 7 : 11 : 19 per wave of each quarter).
             int w_lo = cw, w_hi = nwords, w_next = cn;
-            if (!kStageEarly && nwaves == 16 && gate_on) {
-              auto run_start = [](int i) { return i < 4 ? 4 * i : i < 8 ? 16 + 7 * (i - 4) : i < 12 ? 44 + 11 * (i - 8) : 88 + 17 * (i - 12); };
+            if (!kStageEarly && nwaves == 16 && ncand_pass >= 256) {
+              auto run_start = [](int i) { return i < 4 ? 2 * i : i < 8 ? 8 + 7 * (i - 4) : i < 12 ? 36 + 11 * (i - 8) : 80 + 19 * (i - 12); };
               w_lo = nwords * run_start(wave) / 156;
               w_hi = nwords * run_start(wave + 1) / 156;
               w_next = 1;
@@ -2010,7 +2012,16 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(waves
             take_r[t] = __builtin_amdgcn_readfirstlane(L.sc[SC_TAKE_T + t]);
             w_r[t] = __builtin_amdgcn_readfirstlane(L.sc[SC_W_T + t]);
           }
-          for (int wi = wave; wi < nwords; wi += nwaves) {
+          // (sixteen waves, a pass with admissions: the first waves have just finished those, so they take shorter runs of
+          // words, and the later waves of a SIMD, which are served first, longer ones: 4, 4, 7, 9, then 9, 11 and 13 a wave)
+          int c_lo = wave, c_hi = nwords, c_next = nwaves;
+          if (nwaves == 16 && gate_on && nadm > 32) {
+            auto run_start = [](int i) { return i < 2 ? 4 * i : i == 2 ? 8 : i == 3 ? 15 : i < 8 ? 24 + 9 * (i - 4) : i < 12 ? 60 + 11 * (i - 8) : 104 + 13 * (i - 12); };
+            c_lo = nwords * run_start(wave) / 156;
+            c_hi = nwords * run_start(wave + 1) / 156;
+            c_next = 1;
+          }
+          for (int wi = c_lo; wi < c_hi; wi += c_next) {
             const int gw = wi << 6;
             const int g = gw + lane;
             const uint64_t bit = 1ull << lane;
