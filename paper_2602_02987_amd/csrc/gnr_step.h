@@ -1679,7 +1679,16 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(waves
               }
             }
           }
-          for (int c0 = wave_base; c0 < ncand; c0 += NT) {   // wave-uniform trip count
+          // (the waves that run the weighted router's selection in this segment rank no candidates)
+          int rank_first = wave_base, rank_step = NT;
+          if constexpr (kStageEarly) {
+            if (nwaves >= 8) {
+              rank_step = NT - 128;
+              rank_first = wave < ring_wave ? wave_base : wave_base - 128;
+            }
+          }
+          const bool ranks = !(kStageEarly && nwaves >= 8 && (wave == ring_wave || wave == ring_wave_m));   // wave-uniform
+          for (int c0 = rank_first; ranks && c0 < ncand; c0 += rank_step) {   // wave-uniform trip count
             const int c = c0 + lane;
             bool admitted = false;
             int k = 0, m = c;
@@ -1833,10 +1842,20 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(waves
             // them: when there are candidates for four waves or more, the words are dealt out in runs of unequal
             // length (2 : 7 : 11 : 19 per wave of each quarter).
             int w_lo = cw, w_hi = nwords, w_next = cn;
-            if (!kStageEarly && nwaves == 16 && ncand_pass >= 256) {
-              auto run_start = [](int i) { return i < 4 ? 2 * i : i < 8 ? 8 + 7 * (i - 4) : i < 12 ? 36 + 11 * (i - 8) : 80 + 19 * (i - 12); };
-              w_lo = nwords * run_start(wave) / 156;
-              w_hi = nwords * run_start(wave + 1) / 156;
+            if (nwaves == 16 && ncand_pass >= 256) {
+              // (halves of a word: with the weighted router waves 4 and 5 run the selection and the others take runs of
+              // 6, 6, 6, 6, 0, 0, then 11 a wave and 16.5 for the last four)
+              const int q = wave >> 2, o = wave & 3;   // quarter of the workgroup, place in it
+              int lo2, len2;   // start and length of the run, in halves of a word (312 in all)
+              if (kStageEarly) {
+                lo2 = q == 0 ? 12 * o : q == 1 ? (o < 2 ? 48 : 48 + 22 * (o - 2)) : q == 2 ? 92 + 22 * o : 180 + 33 * o;
+                len2 = q == 0 ? 12 : q == 1 ? (o < 2 ? 0 : 22) : q == 2 ? 22 : 33;
+              } else {
+                lo2 = q == 0 ? 4 * o : q == 1 ? 16 + 14 * o : q == 2 ? 72 + 22 * o : 160 + 38 * o;
+                len2 = q == 0 ? 4 : q == 1 ? 14 : q == 2 ? 22 : 38;
+              }
+              w_lo = nwords * lo2 / 312;
+              w_hi = nwords * (lo2 + len2) / 312;
               w_next = 1;
             }
             // four blocks per round: their decode counts are read together, then compared level by level
@@ -2016,7 +2035,12 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(waves
           // words, and the later waves of a SIMD, which are served first, longer ones: 4, 4, 7, 9, then 9, 11 and 13 a wave)
           int c_lo = wave, c_hi = nwords, c_next = nwaves;
           if (nwaves == 16 && gate_on && nadm > 32) {
-            auto run_start = [](int i) { return i < 2 ? 4 * i : i == 2 ? 8 : i == 3 ? 15 : i < 8 ? 24 + 9 * (i - 4) : i < 12 ? 60 + 11 * (i - 8) : 104 + 13 * (i - 12); };
+            // (with two buffers a word costs more, and the last waves gain less from being served first: 5, 5, 8, 10,
+            // then 10, 11, 11)
+            auto run_start = [](int i) {
+              if (RR) return i < 2 ? 5 * i : i == 2 ? 10 : i == 3 ? 18 : i < 8 ? 28 + 10 * (i - 4) : 68 + 11 * (i - 8);
+              return i < 2 ? 4 * i : i == 2 ? 8 : i == 3 ? 15 : i < 8 ? 24 + 9 * (i - 4) : i < 12 ? 60 + 11 * (i - 8) : 104 + 13 * (i - 12);
+            };
             c_lo = nwords * run_start(wave) / 156;
             c_hi = nwords * run_start(wave + 1) / 156;
             c_next = 1;
