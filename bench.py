@@ -25,8 +25,8 @@ HBM_PEAK_GBS = 8000.0
 # occupancy rocprofv3 derives for it. These are STORED figures, not taken in this run: they hold for the kernel
 # sources whose hash is given (compared with the current sources; on a mismatch the figures read null) and for the
 # state named in `state`. The line says so in `roofline.traffic_source` / `roofline.occupancy.source`.
-TRAFFIC = {"sources_sha256": "75933514b84add5ffb59edc42c0369c862aa66ee728e040faf90f6bba346b902",
-           "bytes_per_launch": 398386956884, "occupancy_percent": 49.186668,
+TRAFFIC = {"sources_sha256": "ff281d80f0e6ffd6d7e9b5aa63472772f827532354a0607625103d6964cb154e",
+           "bytes_per_launch": 398319604029, "occupancy_percent": 49.261507,
            "state": "config 5 after 30000 untimed steps, mean of 2 launches of 1000 steps",
            "profile": "profiles/gnr_step_kernel_cfg5_hbm_traffic.md"}
 
