@@ -243,7 +243,7 @@ def test_launch_shape_follows_the_replications():
     from paper_2602_02987_amd import binding as B, workloads as W
     plan = lambda n, **over: B.sim_launch_plan(W.config(n, **over))
     assert plan(1)[0::2] == (64, 2)                        # 8 servers: one block, one wave
-    assert plan(2)[0::2] == (256, 4)                       # 4 blocks, 1024 replications: four per compute unit
+    assert plan(2)[0::2] == (128, 2)                       # 4 blocks, 1024 replications: a block a wave would not pay for the dense form
     assert plan(2, replications=2048)[0::2] == (128, 4)    # eight two-wave workgroups per compute unit
     assert plan(2, replications=256)[0::2] == (256, 2)     # one per compute unit: room for the form with more registers
     assert plan(3)[0::2] == (128, 4) and plan(3)[1] == 20112
