@@ -63,16 +63,19 @@ int step_threads(Params q, int reps)
   // Smaller replications share a compute unit. A workgroup steps faster the more waves it has, as long as its
   // waves have blocks of servers to work on and all workgroups of the launch find a place at once (at most four
   // waves per SIMD): measured on 256, 1024 and 2048 servers with 128 to 2048 replications, the largest workgroup
-  // that keeps the number of rounds lowest was the fastest or within 3 % of it in every case.
+  // that keeps the number of rounds lowest was the fastest or within 3 % of it in every case; sixteen waves
+  // measured 4 to 26 % faster than eight on 2048 to 5000 servers with up to 256 replications.
   // With fewer than two blocks to a wave the larger workgroup only pays where it can still run in the roomy form
   // (256 servers, 1024 replications: 128 threads roomy 19.0 ms per 1000 steps, 256 threads dense 19.6).
   const int blocks = (q.N + 63) / 64;
   int best = 64, best_rounds = 0;
-  for (int t = 64; t <= 512 && t / 64 < 2 * blocks; t *= 2) {   // (a wave more than there are blocks only waits)
+  for (int t = 64; t <= 1024 && t / 64 < 2 * blocks; t *= 2) {   // (a wave more than there are blocks only waits)
     q.threads = t;
     const size_t lds = step_lds_bytes(q);
+    if (lds > kLdsPerComputeUnit) break;
     const int rounds = launch_rounds(reps, t, lds, 4);
-    const bool thin = blocks < 2 * (t / 64) && launch_rounds(reps, t, lds, 2) > rounds;   // few blocks a wave, and dense
+    // few blocks a wave, and dense (sixteen waves have no roomy form)
+    const bool thin = blocks < 2 * (t / 64) && (t > 512 || launch_rounds(reps, t, lds, 2) > rounds);
     if (best_rounds == 0 || rounds < best_rounds || (rounds == best_rounds && !thin)) { best = t; best_rounds = rounds; }
   }
   return best;

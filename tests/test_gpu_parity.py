@@ -104,15 +104,17 @@ def test_full_size_configs_on_sampled_replications(B, oracle_mod):
 def test_roomy_and_dense_forms_of_the_smaller_size_classes(B, oracle_mod):
     """The library compiles its one- to eight-wave workgroups twice, for two and for four waves per SIMD, and takes
     the denser form when the launch then needs fewer rounds of workgroups. Both forms of both classes against the
-    oracle on sampled replications: N = 3000 runs 512 threads (one workgroup per compute unit in the roomy form, so
-    more than 256 replications take the dense one); N = 600 runs 512 threads roomy with 64 replications and 128 threads
-    dense with 1500 (six two-wave workgroups per compute unit)."""
-    for N, M, reps, steps in ((3000, 800, 40, 400), (3000, 800, 300, 400), (600, 150, 64, 600), (600, 150, 1500, 600)):
+    oracle on sampled replications: N = 3000 runs sixteen waves while every replication has a compute unit of its own
+    and 512 threads in the dense form beyond that (two workgroups per compute unit); N = 1500 and N = 600 run 512
+    threads roomy with few replications; N = 600 with 1500 replications runs 128 threads dense (six workgroups per
+    compute unit)."""
+    for N, M, reps, steps in ((3000, 800, 40, 400), (3000, 800, 300, 400), (1500, 400, 40, 500), (600, 150, 64, 600), (600, 150, 1500, 600)):
         cfg = replace(W.config(3, N=N, replications=reps), M=M)
         sim, _ = run_both(B, oracle_mod, cfg, steps, oracle_reps=[0, reps // 2, reps - 1], checkpoints=2)
         threads, lds, per_simd = B.sim_launch_plan(cfg)
         assert sim.launch_shape() == (threads, lds)
-        assert (threads, per_simd) == {(3000, 40): (512, 2), (3000, 300): (512, 4), (600, 64): (512, 2), (600, 1500): (128, 4)}[(N, reps)]
+        assert (threads, per_simd) == {(3000, 40): (1024, 4), (3000, 300): (512, 4), (1500, 40): (512, 2), (600, 64): (512, 2),
+                                       (600, 1500): (128, 4)}[(N, reps)]
 
 
 def test_config5_full_size_in_the_state_the_benchmark_times(B, oracle_mod):

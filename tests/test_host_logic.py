@@ -252,6 +252,8 @@ def test_launch_shape_follows_the_replications():
     assert plan(3, replications=256)[0::2] == (512, 2)
     assert plan(4)[0::2] == (256, 4)
     assert plan(4, replications=2048)[0::2] == (256, 4)    # the LDS holds four per compute unit: two rounds either way
+    assert plan(4, replications=256)[0::2] == (1024, 4)    # a compute unit each: sixteen waves, two blocks a wave
+    assert plan(4, replications=257)[0::2] == (512, 4)
     assert plan(5) == (1024, 148368, 4)
     for n in (1, 2, 3, 4, 5):                              # eight of the smallest workgroups share a compute unit
         t, lds, w = plan(n)
