@@ -25,8 +25,8 @@ HBM_PEAK_GBS = 8000.0
 # occupancy rocprofv3 derives for it. These are STORED figures, not taken in this run: they hold for the kernel
 # sources whose hash is given (compared with the current sources; on a mismatch the figures read null) and for the
 # state named in `state`. The line says so in `roofline.traffic_source` / `roofline.occupancy.source`.
-TRAFFIC = {"sources_sha256": "7450eec1fdb9e53ca809613f80ca1bd2640354cbe338b5d697d30e0f598cc45d",
-           "bytes_per_launch": 398268269083, "occupancy_percent": 49.301468,
+TRAFFIC = {"sources_sha256": "36b1cdc446a435ea5d947a0f520aef396e99be5f854e2d565e668645875b45de",
+           "bytes_per_launch": 398303942132, "occupancy_percent": 49.174334,
            "state": "config 5 after 30000 untimed steps, mean of 2 launches of 1000 steps",
            "profile": "profiles/gnr_step_kernel_cfg5_hbm_traffic.md"}
 
