@@ -189,7 +189,8 @@ int sim_workspace_bytes(const sim_config *cfg, int max_replications, size_t *out
  * arrival mean per server-step above 0.05 (the per-step count is truncated at 3).
  * SIM_ENOMEM: workspace too small. The library never allocates device memory itself.
  * The handle belongs to the device that is current at this call: every later call on it must be made
- * with the same device current (SIM_EINVAL otherwise). */
+ * with the same device current (SIM_EINVAL otherwise). The launch shape of the handle (see sim_launch_plan) is
+ * fixed here for `max_replications` replications; runs with fewer use the same shape, results do not depend on it. */
 int sim_create(const sim_config *cfg, int max_replications, void *dev_workspace, size_t bytes, sim_t **out);
 
 /* sim_create for callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
