@@ -117,6 +117,24 @@ def test_roomy_and_dense_forms_of_the_smaller_size_classes(B, oracle_mod):
                                        (600, 1500): (128, 4)}[(N, reps)]
 
 
+def test_results_do_not_depend_on_the_launch_shape(B):
+    """The same replications under handles created for few and for many replications (other workgroup sizes and
+    kernel forms): identical digests, tallies and histograms."""
+    cfg = replace(W.config(3, N=600, replications=8), M=150)
+    shapes, outs = set(), []
+    for max_reps in (8, 600, 1500, 2400):
+        sim = B.Sim(cfg, max_replications=max_reps)
+        sim.run(700, 8)
+        shapes.add(sim.launch_shape())
+        outs.append(([sim.digest(r) for r in range(8)], [sim.tallies(r)[0].copy() for r in range(8)], [np.concatenate([sim.hist(r, w).ravel() for w in range(3)]) for r in range(8)]))
+        sim.close()
+    assert len(shapes) >= 3
+    for o in outs[1:]:
+        assert o[0] == outs[0][0]
+        assert all(np.array_equal(a, b) for a, b in zip(o[1], outs[0][1]))
+        assert all(np.array_equal(a, b) for a, b in zip(o[2], outs[0][2]))
+
+
 def test_config5_full_size_in_the_state_the_benchmark_times(B, oracle_mod):
     """Config 5 unmodified (N = 10000, 256 replications, modulation period 100000 steps) advanced in 1000-step
     runs as the benchmark issues them, through the peak of the arrival rate (step 25000) into the state the
