@@ -25,8 +25,8 @@ HBM_PEAK_GBS = 8000.0
 # occupancy rocprofv3 derives for it. These are STORED figures, not taken in this run: they hold for the kernel
 # sources whose hash is given (compared with the current sources; on a mismatch the figures read null) and for the
 # state named in `state`. The line says so in `roofline.traffic_source` / `roofline.occupancy.source`.
-TRAFFIC = {"sources_sha256": "36b1cdc446a435ea5d947a0f520aef396e99be5f854e2d565e668645875b45de",
-           "bytes_per_launch": 398303942132, "occupancy_percent": 49.174334,
+TRAFFIC = {"sources_sha256": "2deafb033583d2666eeff110af655d64ecb755e994a1361eddfdc361ac88b881",
+           "bytes_per_launch": 389799500740, "occupancy_percent": 49.201863,
            "state": "config 5 after 30000 untimed steps, mean of 2 launches of 1000 steps",
            "profile": "profiles/gnr_step_kernel_cfg5_hbm_traffic.md"}
 
@@ -60,13 +60,15 @@ def algorithmic_bytes(t0, g0, t1, g1, slots):
 
 
 def sources_hash():
-    """sha256 over the library's kernel and host sources, in a fixed order."""
+    """sha256 over the library's kernel and host sources, in a fixed order, and the compiler flags they are built with."""
     import hashlib
+    from paper_2602_02987_amd import build as _b
     h = hashlib.sha256()
     d = os.path.join(ROOT, "paper_2602_02987_amd", "csrc")
     for name in sorted(os.listdir(d)):
         with open(os.path.join(d, name), "rb") as fh:
             h.update(name.encode() + b"\0" + fh.read())
+    h.update(" ".join(_b.FLAGS).encode())
     return h.hexdigest()
 
 
