@@ -54,6 +54,7 @@ extern "C" {
 #define SIM_MAXN 12288  /* servers per replication: no configuration may have more; how many fit depends on the
                            on-chip memory they need (see sim_onchip_bytes) */
 #define SIM_NBIN 720    /* latency histogram bins: exact below 16 ns, then 16 bins per octave */
+#define SIM_MAXR (1 << 20) /* replications of one handle: keeps every size of the workspace layout far below 2^64 */
 
 enum sim_err { SIM_OK = 0, SIM_EINVAL = -1, SIM_ENOMEM = -2, SIM_EHIP = -3, SIM_EOVERFLOW = -4 };
 enum sim_law { SIM_GEOMETRIC = 0, SIM_LOGNORMAL = 1, SIM_CONST = 2, SIM_TABLE = 3 };
@@ -184,7 +185,7 @@ int sim_workspace_bytes(const sim_config *cfg, int max_replications, size_t *out
 
 /* Validates and deep-copies the config, builds the sampler tables on the host and uploads them
  * into `dev_workspace` (device pointer, 256-byte aligned, owned by the caller, must outlive the
- * handle). SIM_EINVAL: bad sizes, negative target, M outside [0,N], dt > c0, negative theta, p_solo outside
+ * handle). SIM_EINVAL: bad sizes (more than SIM_MAXR replications among them), negative target, M outside [0,N], dt > c0, negative theta, p_solo outside
  * [0,1] or missing under RANDOM_SPLIT, total
  * arrival mean per server-step above 0.05 (the per-step count is truncated at 3).
  * SIM_ENOMEM: workspace too small. The library never allocates device memory itself.

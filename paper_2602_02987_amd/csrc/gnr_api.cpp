@@ -137,7 +137,7 @@ size_t on_chip_bytes(const sim_config &c, const Ticks &t, int M, int reps)
 
 int validate(const sim_config *c, int max_reps, Ticks *t)
 {
-  if (!c || max_reps < 1 || !c->cls || !c->x_star || !c->qp_star) return SIM_EINVAL;
+  if (!c || max_reps < 1 || max_reps > SIM_MAXR || !c->cls || !c->x_star || !c->qp_star) return SIM_EINVAL;
   if (c->K < 1 || c->K > kMaxK || c->N < 1 || c->N > kMaxN || c->B < 1 || c->B > kMaxB) return SIM_EINVAL;
   if (c->C < 1 || c->C > kMaxChunk || c->M < 0 || c->M > c->N) return SIM_EINVAL;
   if (c->queue_cap < 1 || c->queue_cap > (int64_t(1) << 30) || c->dbuf_cap < 1 || c->dbuf_cap > (int64_t(1) << 30))
@@ -440,7 +440,7 @@ int sim_run(sim_t *h, int64_t steps, int replications, uint64_t seed, void *hip_
       h->p.key0 = static_cast<uint32_t>(seed);
       h->p.key1 = static_cast<uint32_t>(seed >> 32);
     }
-    if (h->steps_done + steps >= (int64_t(1) << 29)) return SIM_EINVAL;
+    if (steps >= (int64_t(1) << 29) - h->steps_done) return SIM_EINVAL;   // (written so that no sum can overflow)
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     int64_t left = steps;
     while (left > 0) {

@@ -89,6 +89,18 @@ __device__ __forceinline__ uint32_t pinned(uint32_t v)
   return v;
 }
 
+// Sixteen bytes of a slot row, read with the non-temporal hint: the rows stream through once per completed
+// iteration and are not needed again before they would have left the caches anyway, so they should not push out
+// the per-server records, ring entries and tables that the rest of the step reads (measured on 10000 servers x
+// 256 replications: 2.9 % faster; the same hint on the few slot and request words that are read again when a
+// decode leaves made it slower).
+__device__ __forceinline__ uint4 stream_load(const uint32_t *p)
+{
+  typedef uint32_t word4 __attribute__((ext_vector_type(4)));
+  const word4 x = __builtin_nontemporal_load(reinterpret_cast<const word4 *>(p));
+  return make_uint4(x.x, x.y, x.z, x.w);
+}
+
 __device__ __forceinline__ uint64_t lanes_below() { return (1ull << (threadIdx.x & 63)) - 1ull; }
 
 // Inclusive prefix sum over the wave with data-parallel-primitive adds: shifts by 1, 2, 4 and 8 inside each
@@ -978,8 +990,8 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(waves
           const uint32_t off = (gw + sid) * static_cast<uint32_t>(BS) + 4u * q0;
           // a register that is not loaded holds zeros, which no iteration index equals (the first is 1)
           v[t][0] = v[t][1] = make_uint4(0u, 0u, 0u, 0u);
-          if (4 * q0 < nds) v[t][0] = *reinterpret_cast<const uint4 *>(fin + off);
-          if (4 * q0 + 32 < nds) v[t][1] = *reinterpret_cast<const uint4 *>(fin + off + 32u);
+          if (4 * q0 < nds) v[t][0] = stream_load(fin + off);
+          if (4 * q0 + 32 < nds) v[t][1] = stream_load(fin + off + 32u);
         }
 #pragma unroll
         for (int t = 0; t < Q; ++t) {

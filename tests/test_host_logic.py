@@ -72,6 +72,15 @@ def test_invalid_configurations_are_rejected(B):
         assert e.value.code == -1
     with pytest.raises(B.SimError):
         B.sim_workspace_bytes(good, 0)
+    # replications are bounded, so that no size of the workspace layout can wrap around 2^64: a ring of 2^30
+    # entries for each of 2^31 - 1 replications would
+    with pytest.raises(B.SimError) as e:
+        B.sim_workspace_bytes(good, (1 << 20) + 1)
+    assert e.value.code == -1
+    with pytest.raises(B.SimError):
+        B.sim_workspace_bytes(replace(good, queue_cap=1 << 30), (1 << 31) - 1)
+    big = B.sim_workspace_bytes(replace(good, queue_cap=1 << 30, dbuf_cap=1 << 30), 1 << 20)   # the largest rings allowed
+    assert (1 << 20) * (good.K * 4 + 8) * (1 << 30) < big < (1 << 55)
 
 
 def test_patience_adds_deadline_rings_and_calendars_to_the_workspace(B):
