@@ -79,6 +79,28 @@ def test_modulated_arrivals_and_many_classes(B, oracle_mod):
     assert_stats_equal(sim.stats(), orc.stats())
 
 
+def test_two_handles_on_two_streams_at_once(B, oracle_mod):
+    """Two handles of different configurations (two variants of the step kernel) advance in turns, each on a stream
+    of its own with no synchronisation in between, so that their launches overlap on the device; every handle has
+    its own workspace and the library keeps no state between them: both match the oracle."""
+    import torch
+    cfgs = [W.config(3, N=300, replications=3), replace(_heavy(W.GATE_OCCUPANCY), name="heavy-beside")]
+    cfgs[0].classes[1].theta = 0.05
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    sims = [B.Sim(c, max_replications=c.replications) for c in cfgs]
+    for _ in range(6):
+        for sim, st in zip(sims, streams):
+            with torch.cuda.stream(st):
+                sim.run(250)
+    for sim, st, cfg in zip(sims, streams, cfgs):
+        orc = oracle_mod.Oracle(cfg, max_reps=cfg.replications)
+        orc.run(1500, cfg.replications, None)
+        with torch.cuda.stream(st):
+            for r in range(cfg.replications):
+                assert_replication_equal(sim, orc, r, what=cfg.name + " beside another handle")
+            assert_stats_equal(sim.stats(), orc.stats())
+
+
 def test_resume_and_restart(B, oracle_mod):
     cfg = _heavy()
     a = B.Sim(cfg); a.run(900)
