@@ -25,8 +25,8 @@ HBM_PEAK_GBS = 8000.0
 # occupancy rocprofv3 derives for it. These are STORED figures, not taken in this run: they hold for the kernel
 # sources whose hash is given (compared with the current sources; on a mismatch the figures read null) and for the
 # state named in `state`. The line says so in `roofline.traffic_source` / `roofline.occupancy.source`.
-TRAFFIC = {"sources_sha256": "569d0b78994e891521b9ebdfc284f6d5f4278532d4bdf56aeb7df9265f34d033",
-           "bytes_per_launch": 383863560335, "occupancy_percent": 48.982985,
+TRAFFIC = {"sources_sha256": "3abd042e65bae0a98324464102efade702e73527a7039320e997bf28af340194",
+           "bytes_per_launch": 383860798110, "occupancy_percent": 49.107249,
            "state": "config 5 after 30000 untimed steps, mean of 2 launches of 1000 steps",
            "profile": "profiles/gnr_step_kernel_cfg5_hbm_traffic.md"}
 

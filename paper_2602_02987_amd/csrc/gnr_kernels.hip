@@ -10,12 +10,16 @@ namespace gnr {
 
 size_t step_lds_bytes(const Params &p)
 {
+  // The layout is carved out of a host block that is never read or written: only the total is wanted, but the
+  // same code as on the device forms the pointers, and those stay inside a real object this way (the largest
+  // configuration the library accepts needs less than a fifth of it).
+  alignas(16) static unsigned char block[1 << 20];
   size_t total = 0;
   switch (size_class(p.threads, p.nwords)) {
-    case 0: lds_carve<static_words(0), true>(p, nullptr, &total); break;
-    case 1: lds_carve<static_words(1)>(p, nullptr, &total); break;
-    case 2: lds_carve<static_words(2)>(p, nullptr, &total); break;
-    default: lds_carve<static_words(3)>(p, nullptr, &total); break;
+    case 0: lds_carve<static_words(0), true>(p, block, &total); break;
+    case 1: lds_carve<static_words(1)>(p, block, &total); break;
+    case 2: lds_carve<static_words(2)>(p, block, &total); break;
+    default: lds_carve<static_words(3)>(p, block, &total); break;
   }
   return total;
 }
